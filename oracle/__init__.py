@@ -1,0 +1,35 @@
+"""CPU oracle for the LRQ-DiT quantized linear layer (numpy, fp64).
+
+TEST INFRASTRUCTURE ONLY.  This package is the slow, plain reference that the
+HIP path is checked against; it is imported by tests/, by the smoke check and by
+the benchmark's cpu_baseline leg, never by the product path.  It shares no code,
+table or constant with the HIP sources and does not import the GPU package.
+
+What follows the paper and where:
+
+* rotation.py  - Sylvester Hadamard matrix and its butterfly form
+                 (Preliminaries, "Rotation Transformation", Eq. hadamard), the
+                 dense rotation X.R used for the outlier-aware branch of the
+                 Adaptive Rotation Scheme (Method, ARS case equation).
+* actquant.py  - per-token dynamic uniform quantizer (Preliminaries, Eq. 1, in
+                 its symmetric absmax form; Experiment, "Implementation Details":
+                 per-token dynamic activations).
+* tlq.py       - Twin-Log Quantization: log2 transform, sign masks, twin
+                 clamp-round quantizers (Eq. log-based quantizer), search-based
+                 clipping (Eq. hyperparameters clip), dequantization (Eq. dequant),
+                 exponent split and integerisation ("Hardware Implementation").
+* qlinear.py   - the quantized linear layer Y = s_x * s_w * (I_x . I_w) assembled
+                 from the above (last equation of "Hardware Implementation").
+
+Pins (tests/test_oracle_*.py) and what is parity-unpinned by the paper: the int8
+normalisation of the level table and the [1, 2^(b-1)] clamp of the negative twin
+are this build's readings of points the paper leaves open; they are pinned only
+by their own stated definitions, everything else against closed forms, library
+special cases and brute force.
+"""
+from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits  # noqa: F401
+from .rotation import hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense  # noqa: F401
+from .actquant import quantize_per_token  # noqa: F401
+from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
+                  tlq_level_values, tlq_lut, pack_codes, unpack_codes)
+from .qlinear import ars_rotate_quant, qlinear, qlinear_from_parts, reference_linear  # noqa: F401

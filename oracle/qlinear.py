@@ -1,0 +1,68 @@
+"""The W-A-quantized linear layer assembled from the oracle's parts (test infrastructure, fp64).
+
+Y[t, n] = scale_t * wscale_n * sum_k q[t, k] * lut_n[code[n, k]]  (+ bias_n)
+
+which is the integer-times-scale form of the last equation of "Hardware Implementation"
+(I^X the activation integers, s^X their scale) with the per-channel int8 level table standing
+in for the shift datapath, and per-token / per-channel granularity as in Experiment,
+"Implementation Details".
+"""
+import numpy as np
+
+from .actquant import quantize_per_token
+from .bf16 import bf16_bits_to_f64
+from .rotation import rotate_dense, rotate_hadamard
+from .tlq import TLQParams, tlq_calibrate, tlq_encode, tlq_lut
+
+
+def ars_rotate_quant(X_bits, a_bits, rotation, had_block=None, R_bits=None):
+    """Rotate (per-layer choice) and quantize per token.
+    X_bits: bf16 bit patterns [M, K]; rotation: "none" | "hadamard" | "dense".
+    Returns (q int8 [M, K], scale fp32 [M])."""
+    x = bf16_bits_to_f64(X_bits)
+    if rotation == "hadamard":
+        u, norm = rotate_hadamard(x, had_block), np.sqrt(np.float64(had_block))
+    elif rotation == "dense":
+        u, norm = rotate_dense(x, bf16_bits_to_f64(R_bits)), 1.0
+    else:
+        assert rotation == "none"
+        u, norm = x, 1.0
+    return quantize_per_token(u, a_bits, norm)
+
+
+def qlinear_from_parts(q, scale, codes, lut, wscale, bits, bias=None):
+    """fp64 Y [M, N] from activation codes, weight codes and the per-channel level table.
+    The integer sum is taken by an fp64 matmul of integer-valued matrices: every partial sum is
+    an integer below 2^53, so the result is the exact integer whatever the summation order."""
+    idx = codes.astype(np.int64) & (2 ** bits - 1)
+    wv = np.take_along_axis(lut.astype(np.float64), idx, axis=1)          # [N, K] decoded int8 values
+    acc = q.astype(np.float64) @ wv.T                                      # exact integers
+    y = (acc * scale.astype(np.float64)[:, None]) * wscale.astype(np.float64)[None, :]
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y
+
+
+def qlinear(X_bits, W, w_bits, a_bits, rotation, had_block=None, R_bits=None, I=7,
+            alpha_grid=None, beta_grid=None, bias=None):
+    """Whole path: TLQ calibrate + encode the (already rotated) weights, rotate + quantize the
+    activations, integer GEMM, rescale.  Returns a dict with every intermediate."""
+    p = tlq_calibrate(W, w_bits, alpha_grid, beta_grid)
+    codes = tlq_encode(W, p)
+    lut, wscale = tlq_lut(p, I)
+    q, scale = ars_rotate_quant(X_bits, a_bits, rotation, had_block, R_bits)
+    y = qlinear_from_parts(q, scale, codes, lut, wscale, w_bits, bias)
+    return dict(params=p, codes=codes, lut=lut, wscale=wscale, q=q, scale=scale, y=y)
+
+
+def reference_linear(X_bits, W, rotation, had_block=None, R_bits=None):
+    """Unquantized product in the rotated basis, (X.Rot)(W)^T in fp64 with the normalised
+    rotation: the quantity the quantized layer approximates (diagnostic only)."""
+    x = bf16_bits_to_f64(X_bits)
+    if rotation == "hadamard":
+        u = rotate_hadamard(x, had_block) / np.sqrt(np.float64(had_block))
+    elif rotation == "dense":
+        u = x @ bf16_bits_to_f64(R_bits)
+    else:
+        u = x
+    return u @ np.asarray(W, dtype=np.float64).T
