@@ -1,0 +1,174 @@
+/*
+ * lrq.h - C ABI of the MI355X (gfx950) quantized-linear hot path of LRQ-DiT.
+ *
+ * The library implements one W-A-quantized linear layer of a Diffusion Transformer:
+ *   activations  -> Adaptive Rotation Scheme (Hadamard, or a dense outlier-aware rotation, chosen per
+ *                   layer) -> per-token uniform quantization to 4/8-bit codes
+ *   weights      -> packed 3/4-bit Twin-Log Quantization (TLQ) codes, decoded through a per-channel
+ *                   level table into int8 MFMA operands inside the GEMM
+ *   output       -> int32 accumulators rescaled per token x per channel.
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library neither frees nor keeps
+ *     it after the call returns.  Structs (lrq_rotation, lrq_tlq_weight) live in HOST memory and are
+ *     read during the call only; the pointers inside them are device pointers.
+ *   - Work is enqueued on the caller's stream (a hipStream_t passed as void*, NULL = default stream)
+ *     and is asynchronous: no entry point synchronises the device.
+ *   - Arrays are dense and row-major.  X[M,K] activations (tokens x hidden), W[N,K] weights (output
+ *     channel x hidden), Y[M,N].  bf16 buffers hold raw bfloat16 bit patterns (uint16).
+ *   - Return value: LRQ_OK (0) or a negative lrq_status.  All argument validation happens on the host
+ *     before anything is launched, so a failing call has enqueued nothing.
+ *   - Pointers must be aligned to 16 bytes (what any device allocator returns).
+ */
+#ifndef LRQ_H_
+#define LRQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LRQ_OK = 0,
+    LRQ_EINVAL = -1,       /* null pointer, non-positive size, misaligned pointer, inconsistent struct   */
+    LRQ_EUNSUPPORTED = -2, /* bit-width, block size or shape outside what the kernels implement          */
+    LRQ_EWORKSPACE = -3,   /* workspace pointer null or smaller than the *_workspace_bytes() answer      */
+    LRQ_EHIP = -4          /* the HIP runtime reported an error while launching                           */
+} lrq_status;
+
+typedef enum { LRQ_ROT_NONE = 0, LRQ_ROT_HADAMARD = 1, LRQ_ROT_DENSE = 2 } lrq_rotation_kind;
+typedef enum { LRQ_OUT_BF16 = 0, LRQ_OUT_FP32 = 1 } lrq_out_dtype;
+
+/*
+ * Per-layer rotation choice of the Adaptive Rotation Scheme (paper: Method, "Adaptive Rotation
+ * Scheme", case equation X.R_H if J < threshold, X.R1.P.R2 otherwise).
+ *   LRQ_ROT_HADAMARD  u = x . (I (x) H_h): block-diagonal Sylvester Hadamard of block size
+ *                     had_block = h, a power of two dividing K (Preliminaries, Eq. hadamard).  The
+ *                     transform is taken unnormalised (+-1 entries) and 1/sqrt(h) goes into the scale.
+ *   LRQ_ROT_DENSE     u = x . R with R a K x K bf16 matrix (row-major, device): any orthogonal matrix,
+ *                     e.g. the paper's greedy outlier-aware product R1.P.R2 materialised.
+ *   LRQ_ROT_NONE      u = x.
+ */
+typedef struct {
+    int kind;        /* lrq_rotation_kind                                   */
+    int had_block;   /* h for LRQ_ROT_HADAMARD, ignored otherwise           */
+    const void* R;   /* bf16 [K,K] device pointer for LRQ_ROT_DENSE or NULL */
+} lrq_rotation;
+
+/*
+ * A TLQ-quantized weight matrix (paper: Method, "Twin-Log Quantization for Weights").  The caller
+ * allocates every array (device memory, sizes below) and fills N, K, bits, I before the call to
+ * lrq_tlq_quantize_pack, which writes the arrays.
+ *   codes      uint8 [N, K*bits/8]  canonical packing of the signed b-bit codes W_q = W_q+ - W_q-
+ *              (Eq. log-based quantizer), each stored as its low b bits.
+ *              bits = 4: byte j = code[2j] | code[2j+1] << 4.
+ *              bits = 3: every 8 codes form a 24-bit little-endian group, code i at bits [3i, 3i+3).
+ *   s_pos/s_neg double [N], z_pos/z_neg int32 [N]: scales and zero-points of the two log-domain twins
+ *              (Eq. hyperparameters clip); alpha/beta float [N]: the clip factors the search picked.
+ *   lut        int8 [N, 16] (16 entries per channel for either bit-width, the first 2^bits used):
+ *              lut[n][c & (2^bits-1)] is the int8 MFMA operand of signed code c, i.e. the level
+ *              +-round(2^r 2^I) 2^(f-I) of "Hardware Implementation" divided by wscale[n] and rounded.
+ *   wscale     float [N]: max_c |level| / 127.
+ *   gemm_codes uint8 [lrq_tlq_gemm_codes_bytes()]: the same codes re-tiled for the GEMM's operand
+ *              loader (private layout, subject to change; only lrq_qlinear reads it).
+ */
+typedef struct {
+    int N, K;
+    int bits;            /* 3 | 4                                                              */
+    int I;               /* integerisation bits of 2^r ~ round(2^r 2^I) 2^-I; < 0: exact 2^e   */
+    uint8_t* codes;
+    double* s_pos;
+    double* s_neg;
+    int32_t* z_pos;
+    int32_t* z_neg;
+    float* alpha;
+    float* beta;
+    int8_t* lut;
+    float* wscale;
+    uint8_t* gemm_codes;
+} lrq_tlq_weight;
+
+/* Human-readable text of a status code (static storage). */
+const char* lrq_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int lrq_version(void);
+
+/* Sizes in bytes of the caller-allocated arrays of lrq_tlq_weight; 0 on invalid arguments. */
+size_t lrq_tlq_codes_bytes(int N, int K, int bits);
+size_t lrq_tlq_gemm_codes_bytes(int N, int K, int bits);
+
+/* Workspace of lrq_tlq_quantize_pack (bytes; 0 is a valid answer). */
+size_t lrq_tlq_workspace_bytes(int N, int K, int bits);
+
+/*
+ * lrq_tlq_quantize_pack - calibrate and pack weight codes for a bit-width.
+ * Paper: Method, "Twin-Log Quantization for Weights": Eq. log-based quantizer (codes), Eq.
+ * hyperparameters clip (search-based clipping, s+-, z+-), Eq. dequant (levels used by the search
+ * objective), "Hardware Implementation" (exponent split and integerisation -> lut, wscale).
+ *   W           float [N,K], the weights already smoothed and rotated into the activation basis.
+ *   bits        3 | 4.    I: see lrq_tlq_weight.
+ *   alpha_grid  float [n_alpha] device, candidate clip factors of the positive twin, scanned in order;
+ *   beta_grid   float [n_beta]  device, same for the negative twin.  1 <= n <= 64.
+ *   out         host struct whose device arrays are written (out->N/K/bits/I must equal the arguments).
+ *   ws          device workspace of at least lrq_tlq_workspace_bytes(N,K,bits) bytes (may be NULL if 0).
+ * Per output channel and per sign the first grid value minimising sum (W_f - W)^2 wins; a candidate
+ * whose clipped maximum does not exceed the minimum is skipped; exact zeros take code 0.
+ * Requires K % 64 == 0 and K <= 16384.  Errors: LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP.
+ */
+int lrq_tlq_quantize_pack(void* stream, const float* W, int N, int K, int bits, int I,
+                          const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
+                          lrq_tlq_weight* out, void* ws, size_t ws_bytes);
+
+/* Workspace of lrq_ars_rotate_quant (bytes). */
+size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bits);
+
+/*
+ * lrq_ars_rotate_quant - rotate and quantize an activation tile for a given per-layer rotation choice.
+ * Paper: Method, "Adaptive Rotation Scheme" (rotation choice), Preliminaries Eq. 1 in its symmetric
+ * per-token form (Experiment, "Implementation Details": per-token dynamic activation quantization).
+ *   X         bf16 [M,K].            rot: see lrq_rotation.       act_bits: 4 | 8.
+ *   q         int8 [M,K] out: codes in [-qmax, qmax], qmax = 2^(act_bits-1) - 1 (4-bit codes are held
+ *             in int8 containers), q = rint(u * (qmax / amax_t)), round-half-even, amax_t = max_k |u|.
+ *   scale     float [M] out: amax_t / (qmax * sqrt(h)) for Hadamard, amax_t / qmax otherwise, so that
+ *             q * scale approximates x . (normalised rotation).  An all-zero token gives q = 0, scale 0.
+ * The rotation, the maximum and the rounding decision are taken in fp64 on the exact bf16 values.
+ * Requires K % 8 == 0; Hadamard: had_block a power of two dividing K, K <= 16384.
+ */
+int lrq_ars_rotate_quant(void* stream, const void* X, int M, int K, const lrq_rotation* rot,
+                         int act_bits, int8_t* q, float* scale, void* ws, size_t ws_bytes);
+
+/* Workspace of lrq_qlinear (bytes): activation codes, scales and rotation scratch. */
+size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act_bits);
+
+/*
+ * lrq_qlinear - fused rotate, quantize, decode, GEMM and rescale:
+ *   Y[t,n] = scale_t * wscale_n * sum_k q[t,k] * lut_n[code[n,k]]  (+ bias_n)
+ * Paper: last equation of "Hardware Implementation" (integer product times activation scale), with
+ * the int8 level table in place of the shift datapath; "SpeedUp and Latency" (INT8 x INT8 GEMM with
+ * higher-precision accumulation).
+ *   X, M, K, rot, act_bits  as for lrq_ars_rotate_quant.
+ *   w          host struct written by lrq_tlq_quantize_pack (w->K must equal K).
+ *   bias       float [N] or NULL.
+ *   out_dtype  LRQ_OUT_BF16 (round-to-nearest-even) | LRQ_OUT_FP32.       Y: [M, N] out.
+ *   ws         device workspace of at least lrq_workspace_bytes(M, N, K, rot, act_bits) bytes.
+ * Runs as the rotate+quantize kernel(s) followed by the decode+MFMA GEMM kernel on the same stream.
+ * Requires K % 64 == 0.
+ */
+int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y,
+                void* ws, size_t ws_bytes);
+
+/*
+ * lrq_qgemm - the GEMM + rescale stage of lrq_qlinear alone, on activation codes already produced by
+ * lrq_ars_rotate_quant (q int8 [M,K], scale float [M]).  Same formula, same constraints; no workspace.
+ */
+int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K,
+              const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRQ_H_ */

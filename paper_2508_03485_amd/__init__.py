@@ -1,0 +1,218 @@
+"""Thin Python binding of liblrq (the C ABI declared in include/lrq.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  PyTorch is
+used for device memory and streams.  There is no CPU or eager fallback: if liblrq.so has not been
+built, loading fails with an error that says how to build it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblrq.so")
+
+LRQ_OK, LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP = 0, -1, -2, -3, -4
+LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE = 0, 1, 2
+LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
+
+EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes",
+           "lrq_tlq_workspace_bytes", "lrq_tlq_quantize_pack", "lrq_ars_workspace_bytes",
+           "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm")
+
+
+class LrqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class _Rotation(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("had_block", ctypes.c_int), ("R", ctypes.c_void_p)]
+
+
+class _TlqWeight(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int), ("K", ctypes.c_int), ("bits", ctypes.c_int), ("I", ctypes.c_int),
+                ("codes", ctypes.c_void_p), ("s_pos", ctypes.c_void_p), ("s_neg", ctypes.c_void_p),
+                ("z_pos", ctypes.c_void_p), ("z_neg", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+                ("beta", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("wscale", ctypes.c_void_p),
+                ("gemm_codes", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load liblrq.so (once) and declare the signatures of include/lrq.h."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2508_03485_amd.build` "
+                          "(hipcc, gfx950); there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.lrq_status_string.restype, L.lrq_status_string.argtypes = ctypes.c_char_p, [ci]
+    L.lrq_version.restype, L.lrq_version.argtypes = ci, []
+    for name in ("lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes", "lrq_tlq_workspace_bytes"):
+        f = getattr(L, name)
+        f.restype, f.argtypes = sz, [ci, ci, ci]
+    L.lrq_tlq_quantize_pack.restype = ci
+    L.lrq_tlq_quantize_pack.argtypes = [vp, vp, ci, ci, ci, ci, vp, ci, vp, ci, ctypes.POINTER(_TlqWeight), vp, sz]
+    L.lrq_ars_workspace_bytes.restype = sz
+    L.lrq_ars_workspace_bytes.argtypes = [ci, ci, ctypes.POINTER(_Rotation), ci]
+    L.lrq_ars_rotate_quant.restype = ci
+    L.lrq_ars_rotate_quant.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, vp, vp, vp, sz]
+    L.lrq_workspace_bytes.restype = sz
+    L.lrq_workspace_bytes.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
+    L.lrq_qlinear.restype = ci
+    L.lrq_qlinear.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, ctypes.POINTER(_TlqWeight), vp, ci,
+                              vp, vp, sz]
+    L.lrq_qgemm.restype = ci
+    L.lrq_qgemm.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().lrq_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != LRQ_OK:
+        raise LrqError(status, where)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+@dataclass
+class Rotation:
+    """Per-layer rotation choice: kind in {"none", "hadamard", "dense"}."""
+    kind: str = "hadamard"
+    had_block: int = 0
+    R: object = None        # torch bf16 [K, K] on the device for kind == "dense"
+
+    def c_struct(self) -> _Rotation:
+        kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE}
+        return _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R))
+
+
+class TLQWeight:
+    """Device arrays of one TLQ-quantized weight matrix (see lrq_tlq_weight in include/lrq.h)."""
+
+    def __init__(self, N: int, K: int, bits: int, I: int, device):
+        import torch
+        L = lib()
+        self.N, self.K, self.bits, self.I = N, K, bits, I
+        nb, ng = L.lrq_tlq_codes_bytes(N, K, bits), L.lrq_tlq_gemm_codes_bytes(N, K, bits)
+        if nb == 0 or ng == 0:
+            raise LrqError(LRQ_EUNSUPPORTED, "TLQWeight sizes")
+        kw = dict(device=device)
+        self.codes = torch.empty(nb, dtype=torch.uint8, **kw).view(N, nb // N)
+        self.s_pos = torch.empty(N, dtype=torch.float64, **kw)
+        self.s_neg = torch.empty(N, dtype=torch.float64, **kw)
+        self.z_pos = torch.empty(N, dtype=torch.int32, **kw)
+        self.z_neg = torch.empty(N, dtype=torch.int32, **kw)
+        self.alpha = torch.empty(N, dtype=torch.float32, **kw)
+        self.beta = torch.empty(N, dtype=torch.float32, **kw)
+        self.lut = torch.empty((N, 16), dtype=torch.int8, **kw)
+        self.wscale = torch.empty(N, dtype=torch.float32, **kw)
+        self.gemm_codes = torch.zeros(ng, dtype=torch.uint8, **kw)
+
+    def c_struct(self) -> _TlqWeight:
+        return _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
+                          _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
+                          _ptr(self.wscale), _ptr(self.gemm_codes))
+
+
+def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None, out: Optional[TLQWeight] = None):
+    """lrq_tlq_quantize_pack: W fp32 [N, K] on the device -> TLQWeight."""
+    import torch
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
+    N, K = W.shape
+    if alpha_grid is None:
+        alpha_grid = torch.tensor([1.0 + 0.05 * i for i in range(21)], dtype=torch.float32, device=W.device)
+    if beta_grid is None:
+        beta_grid = alpha_grid
+    w = out if out is not None else TLQWeight(N, K, bits, I, W.device)
+    cs = w.c_struct()
+    st = lib().lrq_tlq_quantize_pack(_stream(), _ptr(W), N, K, bits, I, _ptr(alpha_grid), alpha_grid.numel(),
+                                     _ptr(beta_grid), beta_grid.numel(), ctypes.byref(cs), None, 0)
+    _check(st, "lrq_tlq_quantize_pack")
+    return w
+
+
+def ars_workspace_bytes(M: int, K: int, rot: Rotation, act_bits: int) -> int:
+    r = rot.c_struct()
+    return lib().lrq_ars_workspace_bytes(M, K, ctypes.byref(r), act_bits)
+
+
+def workspace_bytes(M: int, N: int, K: int, rot: Rotation, act_bits: int) -> int:
+    r = rot.c_struct()
+    return lib().lrq_workspace_bytes(M, N, K, ctypes.byref(r), act_bits)
+
+
+def ars_rotate_quant(X, rot: Rotation, act_bits: int, q=None, scale=None, workspace=None) -> Tuple[object, object]:
+    """lrq_ars_rotate_quant: X bf16 [M, K] -> (q int8 [M, K], scale fp32 [M])."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    if q is None:
+        q = torch.empty((M, K), dtype=torch.int8, device=X.device)
+    if scale is None:
+        scale = torch.empty(M, dtype=torch.float32, device=X.device)
+    r = rot.c_struct()
+    need = lib().lrq_ars_workspace_bytes(M, K, ctypes.byref(r), act_bits)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    st = lib().lrq_ars_rotate_quant(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, _ptr(q), _ptr(scale),
+                                    _ptr(workspace), 0 if workspace is None else workspace.numel())
+    _check(st, "lrq_ars_rotate_quant")
+    return q, scale
+
+
+def _out_code(dtype) -> int:
+    import torch
+    return {torch.bfloat16: LRQ_OUT_BF16, torch.float32: LRQ_OUT_FP32}[dtype]
+
+
+def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=None, out=None, workspace=None):
+    """lrq_qlinear: fused rotate, quantize, decode, GEMM and rescale.  Returns Y [M, N]."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    out_dtype = out_dtype or (out.dtype if out is not None else torch.bfloat16)
+    if out is None:
+        out = torch.empty((M, w.N), dtype=out_dtype, device=X.device)
+    r, cs = rot.c_struct(), w.c_struct()
+    if workspace is None:
+        workspace = torch.empty(lib().lrq_workspace_bytes(M, w.N, K, ctypes.byref(r), act_bits), dtype=torch.uint8,
+                                device=X.device)
+    st = lib().lrq_qlinear(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
+                           _out_code(out_dtype), _ptr(out), _ptr(workspace), workspace.numel())
+    _check(st, "lrq_qlinear")
+    return out
+
+
+def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
+    """lrq_qgemm: the decode + GEMM + rescale stage on existing activation codes."""
+    import torch
+    assert q.is_cuda and q.dtype == torch.int8 and q.is_contiguous()
+    M, K = q.shape
+    out_dtype = out_dtype or (out.dtype if out is not None else torch.bfloat16)
+    if out is None:
+        out = torch.empty((M, w.N), dtype=out_dtype, device=q.device)
+    cs = w.c_struct()
+    st = lib().lrq_qgemm(_stream(), _ptr(q), _ptr(scale), M, K, ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
+                         _ptr(out))
+    _check(st, "lrq_qgemm")
+    return out

@@ -1,0 +1,183 @@
+// extern "C" entry points of liblrq: argument validation (host only, before any launch), workspace
+// carving and dispatch to the kernels.
+#include "lrq_internal.h"
+
+namespace {
+
+inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+constexpr int kMaxRowLds = 16384;   // a token row / weight row is staged in LDS as doubles
+
+int check_rotation(const lrq_rotation* rot, int K) {
+    if (!rot) return LRQ_EINVAL;
+    switch (rot->kind) {
+        case LRQ_ROT_NONE:
+            return K <= kMaxRowLds ? LRQ_OK : LRQ_EUNSUPPORTED;
+        case LRQ_ROT_HADAMARD:
+            if (rot->had_block <= 0) return LRQ_EINVAL;
+            if (!is_pow2(rot->had_block) || K % rot->had_block != 0) return LRQ_EUNSUPPORTED;
+            return K <= kMaxRowLds ? LRQ_OK : LRQ_EUNSUPPORTED;
+        case LRQ_ROT_DENSE:
+            if (!rot->R || !aligned16(rot->R)) return LRQ_EINVAL;
+            return K % 64 == 0 ? LRQ_OK : LRQ_EUNSUPPORTED;
+        default:
+            return LRQ_EINVAL;
+    }
+}
+
+int check_act(const void* X, int M, int K, const lrq_rotation* rot, int act_bits) {
+    if (!X || M <= 0 || K <= 0 || !aligned16(X)) return LRQ_EINVAL;
+    if (act_bits != 4 && act_bits != 8) return LRQ_EUNSUPPORTED;
+    if (K % 8 != 0) return LRQ_EUNSUPPORTED;
+    return check_rotation(rot, K);
+}
+
+int check_weight(const lrq_tlq_weight* w) {
+    if (!w || w->N <= 0 || w->K <= 0) return LRQ_EINVAL;
+    if (w->bits != 3 && w->bits != 4) return LRQ_EUNSUPPORTED;
+    if (!w->codes || !w->s_pos || !w->s_neg || !w->z_pos || !w->z_neg || !w->alpha || !w->beta || !w->lut ||
+        !w->wscale || !w->gemm_codes)
+        return LRQ_EINVAL;
+    if (!aligned16(w->codes) || !aligned16(w->lut) || !aligned16(w->gemm_codes)) return LRQ_EINVAL;
+    return LRQ_OK;
+}
+
+struct ArsWs {
+    size_t u_off, total;
+};
+ArsWs ars_layout(int M, int K, const lrq_rotation* rot) {
+    ArsWs l{0, 0};
+    if (rot && rot->kind == LRQ_ROT_DENSE) l.total = round256((size_t)M * K * sizeof(double));
+    return l;
+}
+
+int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                     int8_t* q, float* scale, void* ws) {
+    hipError_t e = hipSuccess;
+    const uint16_t* x = static_cast<const uint16_t*>(X);
+    switch (rot->kind) {
+        case LRQ_ROT_NONE:
+            e = lrq::launch_plain_quant(st, x, M, K, act_bits, q, scale);
+            break;
+        case LRQ_ROT_HADAMARD:
+            e = lrq::launch_hadamard_quant(st, x, M, K, rot->had_block, act_bits, q, scale);
+            break;
+        default:
+            e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
+                                               static_cast<double*>(ws), q, scale);
+            break;
+    }
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+const char* lrq_status_string(int status) {
+    switch (status) {
+        case LRQ_OK: return "ok";
+        case LRQ_EINVAL: return "invalid argument (null pointer, non-positive size, misaligned pointer or inconsistent struct)";
+        case LRQ_EUNSUPPORTED: return "unsupported bit-width, block size or shape";
+        case LRQ_EWORKSPACE: return "workspace missing or too small";
+        case LRQ_EHIP: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+int lrq_version(void) { return 100; }
+
+size_t lrq_tlq_codes_bytes(int N, int K, int bits) {
+    if (N <= 0 || K <= 0 || (bits != 3 && bits != 4) || K % 8 != 0) return 0;
+    return (size_t)N * K / 8 * bits;
+}
+
+size_t lrq_tlq_gemm_codes_bytes(int N, int K, int bits) {
+    if (N <= 0 || K <= 0 || (bits != 3 && bits != 4) || K % 8 != 0) return 0;
+    // K that is not a multiple of the GEMM's K block cannot be fed to lrq_qlinear; keep the buffer non-empty
+    const int Kp = (K + lrq::kGemmBlockK - 1) / lrq::kGemmBlockK * lrq::kGemmBlockK;
+    return lrq::gemm_codes_bytes(N, Kp, bits);
+}
+
+size_t lrq_tlq_workspace_bytes(int N, int K, int bits) {
+    (void)N; (void)K; (void)bits;
+    return 0;
+}
+
+int lrq_tlq_quantize_pack(void* stream, const float* W, int N, int K, int bits, int I, const float* alpha_grid,
+                          int n_alpha, const float* beta_grid, int n_beta, lrq_tlq_weight* out, void* ws,
+                          size_t ws_bytes) {
+    (void)ws; (void)ws_bytes;
+    if (!W || !alpha_grid || !beta_grid || !out || N <= 0 || K <= 0 || !aligned16(W)) return LRQ_EINVAL;
+    if (n_alpha < 1 || n_alpha > 64 || n_beta < 1 || n_beta > 64) return LRQ_EINVAL;
+    if (bits != 3 && bits != 4) return LRQ_EUNSUPPORTED;
+    if (out->N != N || out->K != K || out->bits != bits || out->I != I) return LRQ_EINVAL;
+    int st = check_weight(out);
+    if (st != LRQ_OK) return st;
+    if (K % 64 != 0 || K > kMaxRowLds || I > 20) return LRQ_EUNSUPPORTED;
+    hipError_t e = lrq::launch_tlq_quantize_pack(static_cast<hipStream_t>(stream), W, N, K, bits, I, alpha_grid,
+                                                 n_alpha, beta_grid, n_beta, *out);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bits) {
+    (void)act_bits;
+    if (M <= 0 || K <= 0) return 0;
+    return ars_layout(M, K, rot).total;
+}
+
+int lrq_ars_rotate_quant(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                         int8_t* q, float* scale, void* ws, size_t ws_bytes) {
+    int st = check_act(X, M, K, rot, act_bits);
+    if (st != LRQ_OK) return st;
+    if (!q || !scale || !aligned16(q)) return LRQ_EINVAL;
+    const size_t need = ars_layout(M, K, rot).total;
+    if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) return LRQ_EWORKSPACE;
+    return run_rotate_quant(static_cast<hipStream_t>(stream), X, M, K, rot, act_bits, q, scale, ws);
+}
+
+size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act_bits) {
+    (void)N; (void)act_bits;
+    if (M <= 0 || K <= 0) return 0;
+    return round256((size_t)M * K) + round256((size_t)M * sizeof(float)) + ars_layout(M, K, rot).total;
+}
+
+int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight* w,
+              const float* bias, int out_dtype, void* Y) {
+    if (!q || !scale || !Y || M <= 0 || K <= 0 || !aligned16(q) || !aligned16(Y)) return LRQ_EINVAL;
+    int st = check_weight(w);
+    if (st != LRQ_OK) return st;
+    if (w->K != K) return LRQ_EINVAL;
+    if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
+    if (K % lrq::kGemmBlockK != 0) return LRQ_EUNSUPPORTED;
+    hipError_t e = lrq::launch_qgemm(static_cast<hipStream_t>(stream), q, scale, M, K, *w, bias, out_dtype, Y);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+    int st = check_act(X, M, K, rot, act_bits);
+    if (st != LRQ_OK) return st;
+    st = check_weight(w);
+    if (st != LRQ_OK) return st;
+    if (!Y || !aligned16(Y) || w->K != K) return LRQ_EINVAL;
+    if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
+    if (K % lrq::kGemmBlockK != 0) return LRQ_EUNSUPPORTED;
+    const size_t need = lrq_workspace_bytes(M, w->N, K, rot, act_bits);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return LRQ_EWORKSPACE;
+    char* base = static_cast<char*>(ws);
+    int8_t* q = reinterpret_cast<int8_t*>(base);
+    float* scale = reinterpret_cast<float*>(base + round256((size_t)M * K));
+    void* rot_ws = base + round256((size_t)M * K) + round256((size_t)M * sizeof(float));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = run_rotate_quant(s, X, M, K, rot, act_bits, q, scale, rot_ws);
+    if (st != LRQ_OK) return st;
+    hipError_t e = lrq::launch_qgemm(s, q, scale, M, K, *w, bias, out_dtype, Y);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

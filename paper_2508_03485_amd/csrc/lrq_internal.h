@@ -1,0 +1,44 @@
+// Internal declarations shared by the HIP translation units of liblrq (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lrq.h"
+
+namespace lrq {
+
+// ---- launchers implemented in the .hip files; each returns hipGetLastError() after the launch ----
+
+// u = x.(I (x) H_h) in fp64, per-token absmax, round to codes.  K % 8 == 0, h | K, h power of two.
+hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
+                                 int8_t* q, float* scale);
+// u = x (no rotation), same quantizer.
+hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, int act_bits,
+                              int8_t* q, float* scale);
+// u = x.R in fp64 (k ascending), written to U [M,K] doubles, then quantized from U.
+hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
+                                     int act_bits, double* U, int8_t* q, float* scale);
+
+hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
+                                    const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
+                                    const lrq_tlq_weight& out);
+
+hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
+                        const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y);
+
+// ---- private GEMM weight layout ----
+// Channels are grouped in tiles of 32, K in blocks of 64.  One (channel tile, K block) unit holds, for
+// each of the 64 lanes of a wave, the codes that lane feeds to two consecutive 32x32x32 int8 MFMAs:
+// lane l owns channel (l % 32) of the tile and k = 32*s + 16*(l / 32) + [0, 16) for step s = 0, 1.
+// Units are stored [channel tile][K block][lane], 16 bytes (4-bit) or 12 bytes (3-bit) per lane.
+constexpr int kGemmTileN = 32;
+constexpr int kGemmBlockK = 64;
+
+inline size_t gemm_codes_bytes(int N, int K, int bits) {
+    size_t tiles = (size_t)(N + kGemmTileN - 1) / kGemmTileN;
+    size_t kblocks = (size_t)K / kGemmBlockK;
+    return tiles * kblocks * 64 * (bits == 4 ? 16 : 12);
+}
+
+}  // namespace lrq

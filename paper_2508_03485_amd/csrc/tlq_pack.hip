@@ -1,0 +1,233 @@
+// Twin-Log Quantization of a weight matrix: calibrate (search-based clipping), encode, build the
+// per-channel int8 level table and pack (Method, "Twin-Log Quantization for Weights").  Offline step:
+// one workgroup per output channel, fp64 throughout, written for clarity rather than speed.
+#include "lrq_internal.h"
+
+namespace lrq {
+namespace {
+
+constexpr int NT = 256;
+constexpr int kWave = 64;
+
+struct Red4 {
+    double pmax, pmin, nmax, nmin;
+};
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ double wave_maxd(double v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ double wave_mind(double v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v = fmin(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+__device__ __forceinline__ double block_sum(double v, double* red) {
+    v = wave_sum(v);
+    if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int i = 0; i < NT / kWave; ++i) r += red[i];
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ double clampd(double v, double lo, double hi) { return fmin(fmax(v, lo), hi); }
+
+// Grid search of one clip factor for one sign (Eq. hyperparameters clip); all threads return the
+// same (s, z, factor).  sgn = +1 scans the positive weights, -1 the negative ones.
+__device__ void search_side(const float* __restrict__ w, const double* __restrict__ ell, int K, double sgn,
+                            bool has, double wmax, double wmin, const float* __restrict__ grid, int ngrid,
+                            double nint, double qlo, double qhi, double* red, double& s_out, double& z_out,
+                            float& c_out) {
+    double best_err = INFINITY, best_s = 1.0, best_z = has ? rint(wmin) : 0.0;
+    float best_c = 1.0f;
+    for (int ci = 0; ci < ngrid; ++ci) {
+        const float c32 = grid[ci];
+        const double T = (double)c32 * wmax;
+        if (!(has && T > wmin)) continue;                    // uniform over the workgroup
+        const double s = (T - wmin) / nint;
+        const double z = rint(wmin / s);
+        double err = 0.0;
+        for (int k = threadIdx.x; k < K; k += NT) {
+            const double wk = (double)w[k];
+            if (wk * sgn > 0.0) {
+                const double qv = clampd(rint(ell[k] / s) - z, qlo, qhi);
+                const double d = exp2(s * (qv + z)) - fabs(wk);
+                err += d * d;
+            }
+        }
+        err = block_sum(err, red);
+        if (err < best_err) {
+            best_err = err;
+            best_s = s;
+            best_z = z;
+            best_c = c32;
+        }
+    }
+    s_out = best_s;
+    z_out = best_z;
+    c_out = best_c;
+}
+
+__global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
+    const float* __restrict__ W, int N, int K, int bits, int I, const float* __restrict__ agrid, int na,
+    const float* __restrict__ bgrid, int nb, uint8_t* __restrict__ codes_out, double* __restrict__ s_pos,
+    double* __restrict__ s_neg, int32_t* __restrict__ z_pos, int32_t* __restrict__ z_neg,
+    float* __restrict__ alpha, float* __restrict__ beta, int8_t* __restrict__ lut, float* __restrict__ wscale,
+    uint8_t* __restrict__ gemm_codes) {
+    extern __shared__ double sm[];
+    double* ell = sm;                                   // K doubles: log2|w|
+    double* red = sm + K;                               // 64 doubles of reduction scratch
+    int8_t* code = reinterpret_cast<int8_t*>(red + 64); // K signed codes
+    const int n = blockIdx.x, t = threadIdx.x;
+    const float* w = W + (size_t)n * K;
+    const int half = 1 << (bits - 1), nlev = 1 << bits;
+
+    // W' = log2|W| and the per-sign extrema over the masked positions
+    double pmax = -INFINITY, pmin = INFINITY, nmax = -INFINITY, nmin = INFINITY;
+    for (int k = t; k < K; k += NT) {
+        const double wk = (double)w[k];
+        const double l = wk != 0.0 ? log2(fabs(wk)) : 0.0;
+        ell[k] = l;
+        if (wk > 0.0) { pmax = fmax(pmax, l); pmin = fmin(pmin, l); }
+        if (wk < 0.0) { nmax = fmax(nmax, l); nmin = fmin(nmin, l); }
+    }
+    pmax = wave_maxd(pmax); pmin = wave_mind(pmin); nmax = wave_maxd(nmax); nmin = wave_mind(nmin);
+    Red4* r4 = reinterpret_cast<Red4*>(red);
+    if (t % kWave == 0) r4[t / kWave] = Red4{pmax, pmin, nmax, nmin};
+    __syncthreads();
+    for (int i = 0; i < NT / kWave; ++i) {
+        pmax = fmax(pmax, r4[i].pmax); pmin = fmin(pmin, r4[i].pmin);
+        nmax = fmax(nmax, r4[i].nmax); nmin = fmin(nmin, r4[i].nmin);
+    }
+    __syncthreads();
+    const bool has_p = pmax >= pmin, has_n = nmax >= nmin;   // +-inf sentinels survive on an empty side
+    if (!has_p) pmax = pmin = 0.0;
+    if (!has_n) nmax = nmin = 0.0;
+
+    double sp, zp, sn, zn;
+    float al, be;
+    search_side(w, ell, K, 1.0, has_p, pmax, pmin, agrid, na, (double)(half - 1), 0.0, (double)(half - 1), red, sp, zp, al);
+    search_side(w, ell, K, -1.0, has_n, nmax, nmin, bgrid, nb, (double)half, 1.0, (double)half, red, sn, zn, be);
+
+    if (t == 0) {
+        s_pos[n] = sp; s_neg[n] = sn; z_pos[n] = (int32_t)zp; z_neg[n] = (int32_t)zn;
+        alpha[n] = al; beta[n] = be;
+    }
+
+    // level table: e(c) = s+(c + z+) for c >= 0, s-(-c + z-) for c < 0; exponent split and integerisation
+    double v = 0.0;
+    if (t < nlev) {
+        const int c = t < half ? t : t - nlev;              // signed code whose low bits are t
+        const double e = c >= 0 ? sp * ((double)c + zp) : sn * ((double)(-c) + zn);
+        double mag;
+        if (I < 0) {
+            mag = exp2(e);
+        } else {
+            const double f = floor(e), r = e - f;
+            const double mant = rint(exp2(r) * (double)(1 << I));
+            mag = ldexp(mant, (int)f - I);
+        }
+        v = c >= 0 ? mag : -mag;
+        red[t] = fabs(v);
+    }
+    __syncthreads();
+    double vmax = 0.0;
+    for (int i = 0; i < nlev; ++i) vmax = fmax(vmax, red[i]);
+    const float ws = (float)(vmax / 127.0);
+    if (t < 16) {
+        int8_t entry = 0;
+        if (t < nlev) entry = (int8_t)(int)clampd(rint(v / (double)ws), -127.0, 127.0);
+        lut[(size_t)n * 16 + t] = entry;
+    }
+    if (t == 0) wscale[n] = ws;
+
+    // codes (Eq. log-based quantizer); the negative twin is clamped to [1, 2^(b-1)]
+    for (int k = t; k < K; k += NT) {
+        const double wk = (double)w[k];
+        int c = 0;
+        if (wk > 0.0) c = (int)clampd(rint(ell[k] / sp) - zp, 0.0, (double)(half - 1));
+        else if (wk < 0.0) c = -(int)clampd(rint(ell[k] / sn) - zn, 1.0, (double)half);
+        code[k] = (int8_t)c;
+    }
+    __syncthreads();
+
+    const unsigned mask = (unsigned)nlev - 1u;
+    if (bits == 4) {
+        // canonical: byte j = code[2j] | code[2j+1] << 4, written 4 bytes at a time
+        uint32_t* dst = reinterpret_cast<uint32_t*>(codes_out + (size_t)n * (K / 2));
+        for (int g = t; g < K / 8; g += NT) {
+            unsigned canon = 0, tiled = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) canon |= ((unsigned)code[g * 8 + i] & mask) << (4 * i);
+            dst[g] = canon;
+            // GEMM layout: byte j of the dword = code[k+j] | code[k+4+j] << 4
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                tiled |= (((unsigned)code[g * 8 + j] & mask) | (((unsigned)code[g * 8 + 4 + j] & mask) << 4)) << (8 * j);
+            const int kb = g / 8, r = g % 8, s = r / 4, hl = (r / 2) % 2, d = r % 2;
+            const size_t unit = (size_t)(n / kGemmTileN) * (K / kGemmBlockK) + kb;
+            const size_t off = (unit * 64 + (n % kGemmTileN) + 32 * hl) * 16 + (s * 2 + d) * 4;
+            *reinterpret_cast<uint32_t*>(gemm_codes + off) = tiled;
+        }
+    } else {
+        // canonical: 8 codes -> 24-bit little-endian group
+        uint8_t* dst = codes_out + (size_t)n * (K / 8 * 3);
+        for (int g = t; g < K / 8; g += NT) {
+            unsigned v24 = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v24 |= ((unsigned)code[g * 8 + i] & mask) << (3 * i);
+            dst[g * 3 + 0] = (uint8_t)(v24 & 255u);
+            dst[g * 3 + 1] = (uint8_t)((v24 >> 8) & 255u);
+            dst[g * 3 + 2] = (uint8_t)(v24 >> 16);
+        }
+        // GEMM layout: per lane and K block three dwords: d0/d1 = low two bits of the 16 codes of
+        // step 0/1 (code 4g+j at bits [8j+2g, 8j+2g+2)), d2 = third bits (step s, code 4g+j at bit 8j+4s+g)
+        for (int u = t; u < K / 32; u += NT) {
+            const int kb = u / 2, hl = u % 2;
+            unsigned d[3] = {0u, 0u, 0u};
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const unsigned c = (unsigned)code[kb * 64 + 32 * s + 16 * hl + i] & mask;
+                    const int g = i / 4, j = i % 4;
+                    d[s] |= (c & 3u) << (8 * j + 2 * g);
+                    d[2] |= (c >> 2) << (8 * j + 4 * s + g);
+                }
+            const size_t unit = (size_t)(n / kGemmTileN) * (K / kGemmBlockK) + kb;
+            uint32_t* o = reinterpret_cast<uint32_t*>(gemm_codes + (unit * 64 + (n % kGemmTileN) + 32 * hl) * 12);
+            o[0] = d[0]; o[1] = d[1]; o[2] = d[2];
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
+                                    const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
+                                    const lrq_tlq_weight& out) {
+    const size_t lds = (size_t)K * sizeof(double) + 64 * sizeof(double) + (size_t)K;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tlq_quantize_pack_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
+                       beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
+                       out.lut, out.wscale, out.gemm_codes);
+    return hipGetLastError();
+}
+
+}  // namespace lrq

@@ -1,0 +1,112 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments on the host before anything would be launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2508_03485_amd as lrq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(lrq.LIB_PATH):
+        from paper_2508_03485_amd.build import build
+        build()
+    return lrq.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "lrq.h")).read()
+    declared = set(re.findall(r"\b(lrq_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(lrq.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert L.lrq_version() >= 100
+    assert lrq.status_string(0) == "ok" and "workspace" in lrq.status_string(lrq.LRQ_EWORKSPACE)
+
+
+def test_sizes(L):
+    assert L.lrq_tlq_codes_bytes(1152, 1152, 4) == 1152 * 1152 // 2
+    assert L.lrq_tlq_codes_bytes(1152, 1152, 3) == 1152 * 1152 * 3 // 8
+    assert L.lrq_tlq_codes_bytes(8, 12, 4) == 0 and L.lrq_tlq_codes_bytes(8, 16, 5) == 0
+    assert L.lrq_tlq_gemm_codes_bytes(1152, 1152, 4) == 1152 * 1152 // 2
+    assert L.lrq_tlq_gemm_codes_bytes(33, 64, 3) == 64 * 64 * 3 // 8          # channels padded to 32
+    had = lrq.Rotation("hadamard", 128).c_struct()
+    assert L.lrq_ars_workspace_bytes(256, 1152, ctypes.byref(had), 8) == 0
+    dense = lrq._Rotation(lrq.LRQ_ROT_DENSE, 0, 4096)
+    assert L.lrq_ars_workspace_bytes(256, 1152, ctypes.byref(dense), 8) >= 256 * 1152 * 8
+    assert L.lrq_workspace_bytes(256, 64, 1152, ctypes.byref(had), 8) >= 256 * 1152 + 256 * 4
+
+
+def test_rotate_quant_rejects_bad_arguments_on_the_host(L):
+    P = 4096   # any aligned non-null value: validation must fail before the pointer is ever used
+    had = lambda h: ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_HADAMARD, h, None))
+    f = L.lrq_ars_rotate_quant
+    assert f(None, None, 4, 128, had(128), 8, P, P, None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 0, 128, had(128), 8, P, P, None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P + 2, 4, 128, had(128), 8, P, P, None, 0) == lrq.LRQ_EINVAL          # misaligned
+    assert f(None, P, 4, 128, None, 8, P, P, None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 4, 128, had(128), 6, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED        # act bits
+    assert f(None, P, 4, 132, had(4), 8, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED          # K % 8
+    assert f(None, P, 4, 1152, had(96), 8, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED        # not a power of two
+    assert f(None, P, 4, 1152, had(256), 8, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED       # does not divide K
+    assert f(None, P, 4, 1152, had(0), 8, P, P, None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 4, 1152, had(128), 8, None, P, None, 0) == lrq.LRQ_EINVAL
+    dense = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_DENSE, 0, P))
+    assert f(None, P, 4, 1152, dense, 8, P, P, None, 0) == lrq.LRQ_EWORKSPACE
+    assert f(None, P, 4, 1152, dense, 8, P, P, P, 16) == lrq.LRQ_EWORKSPACE
+    assert f(None, P, 4, 1152, ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_DENSE, 0, None)), 8, P, P, P, 1 << 30) == lrq.LRQ_EINVAL
+    assert f(None, P, 4, 1152, ctypes.byref(lrq._Rotation(7, 0, None)), 8, P, P, None, 0) == lrq.LRQ_EINVAL
+
+
+def _weight(N=64, K=128, bits=4, I=7, p=4096, **over):
+    kw = dict(N=N, K=K, bits=bits, I=I, codes=p, s_pos=p, s_neg=p, z_pos=p, z_neg=p, alpha=p, beta=p, lut=p,
+              wscale=p, gemm_codes=p)
+    kw.update(over)
+    return lrq._TlqWeight(**kw)
+
+
+def test_quantize_pack_rejects_bad_arguments_on_the_host(L):
+    P = 4096
+    f = L.lrq_tlq_quantize_pack
+    ok = _weight()
+    assert f(None, None, 64, 128, 4, 7, P, 21, P, 21, ctypes.byref(ok), None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 64, 128, 4, 7, P, 0, P, 21, ctypes.byref(ok), None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 64, 128, 4, 7, P, 65, P, 21, ctypes.byref(ok), None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 64, 128, 5, 7, P, 21, P, 21, ctypes.byref(_weight(bits=5)), None, 0) == lrq.LRQ_EUNSUPPORTED
+    assert f(None, P, 64, 128, 4, 7, P, 21, P, 21, ctypes.byref(_weight(N=32)), None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 64, 128, 4, 7, P, 21, P, 21, ctypes.byref(_weight(lut=None)), None, 0) == lrq.LRQ_EINVAL
+    assert f(None, P, 64, 72, 4, 7, P, 21, P, 21, ctypes.byref(_weight(K=72)), None, 0) == lrq.LRQ_EUNSUPPORTED
+    assert f(None, P, 64, 32768, 4, 7, P, 21, P, 21, ctypes.byref(_weight(K=32768)), None, 0) == lrq.LRQ_EUNSUPPORTED
+    assert f(None, P, 64, 128, 4, 7, P, 21, P, 21, None, None, 0) == lrq.LRQ_EINVAL
+
+
+def test_qlinear_rejects_bad_arguments_on_the_host(L):
+    P = 4096
+    had = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_HADAMARD, 128, None))
+    f = L.lrq_qlinear
+    w = ctypes.byref(_weight())
+    big = 1 << 30
+    assert f(None, P, 16, 128, had, 8, w, None, 0, None, P, big) == lrq.LRQ_EINVAL            # Y null
+    assert f(None, P, 16, 256, had, 8, w, None, 0, P, P, big) == lrq.LRQ_EINVAL               # K mismatch
+    assert f(None, P, 16, 128, had, 8, w, None, 3, P, P, big) == lrq.LRQ_EUNSUPPORTED         # out dtype
+    assert f(None, P, 16, 128, had, 8, w, None, 0, P, None, 0) == lrq.LRQ_EWORKSPACE
+    assert f(None, P, 16, 128, had, 8, w, None, 0, P, P, 100) == lrq.LRQ_EWORKSPACE
+    assert f(None, P, 16, 128, had, 8, None, None, 0, P, P, big) == lrq.LRQ_EINVAL
+    assert f(None, P, 16, 128, had, 8, ctypes.byref(_weight(bits=2)), None, 0, P, P, big) == lrq.LRQ_EUNSUPPORTED
+    g = L.lrq_qgemm
+    assert g(None, None, P, 16, 128, w, None, 0, P) == lrq.LRQ_EINVAL
+    assert g(None, P, P, 16, 128, w, None, 9, P) == lrq.LRQ_EUNSUPPORTED
+    w96 = ctypes.byref(_weight(K=96))
+    assert g(None, P, P, 16, 96, w96, None, 0, P) == lrq.LRQ_EUNSUPPORTED                    # K % 64
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(lrq, "_lib", None)
+    monkeypatch.setattr(lrq, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError, match="no fallback"):
+        lrq.lib()

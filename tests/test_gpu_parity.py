@@ -1,0 +1,183 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+Bar: bit-exact packed weight codes and activation codes; relative Frobenius error <= 1e-3 on
+outputs (bf16 outputs are compared with the oracle output rounded to bf16, since rounding to 8
+significant bits alone costs about 1.5e-3)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import bf16_bits_from_dev, bf16_to_dev, rel_fro, to_dev
+
+pytestmark = pytest.mark.gpu
+GRID = synth.DEFAULT_GRID
+
+
+@pytest.fixture(scope="module")
+def lrq():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2508_03485_amd as m
+    m.lib()
+    return m
+
+
+def _acts(M, K, seed, n_salient=4, gain=40.0):
+    return synth.make_activations(M, K, (900, seed, 0), 0.05, n_salient, gain)
+
+
+# ------------------------------------------------------------------ rotate + quantize
+@pytest.mark.parametrize("M,K,h,a_bits", [
+    (256, 1152, 128, 8),      # config 1
+    (37, 1152, 128, 4),       # ragged token count, 4-bit
+    (5, 64, 1, 8), (5, 64, 2, 8), (9, 64, 4, 4), (3, 192, 8, 8), (33, 192, 64, 8),
+    (70, 1536, 512, 8), (65, 4608, 512, 8), (40, 3072, 1024, 4), (19, 12288, 4096, 8), (3, 16384, 16384, 8),
+    (1, 1152, 128, 8),
+])
+def test_hadamard_rotate_quant_bit_exact(lrq, M, K, h, a_bits):
+    print(f"case M={M} K={K} h={h} a={a_bits}", flush=True)
+    X = _acts(M, K, K + h + M)
+    q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "hadamard", h)
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), lrq.Rotation("hadamard", h), a_bits)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+
+
+def test_rotate_quant_edge_rows(lrq):
+    K, h = 1152, 128
+    X = oracle.bf16_bits_to_f64(_acts(6, K, 1)).astype(np.float32)
+    X[0] = 0.0                                   # all-zero token
+    X[1] = 0.0; X[1, 700] = -244.0               # one-hot salient outlier
+    X[2, :] = X[2, :] * 2.0 ** -60               # tiny magnitudes
+    X[3, ::7] *= 2.0 ** 20                       # wide dynamic range inside a block
+    X[4] = 1.0                                   # constant row: all energy in one coefficient per block
+    Xb = synth.f32_to_bf16_bits(X)
+    for a_bits in (8, 4):
+        q_ref, s_ref = oracle.ars_rotate_quant(Xb, a_bits, "hadamard", h)
+        q, s = lrq.ars_rotate_quant(bf16_to_dev(Xb), lrq.Rotation("hadamard", h), a_bits)
+        assert np.array_equal(q.cpu().numpy(), q_ref)
+        assert np.array_equal(s.cpu().numpy(), s_ref)
+        assert np.all(q_ref[0] == 0) and s_ref[0] == 0
+
+
+def test_no_rotation_quant(lrq):
+    X = _acts(11, 256, 2)
+    q_ref, s_ref = oracle.ars_rotate_quant(X, 8, "none")
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), lrq.Rotation("none"), 8)
+    assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
+
+
+@pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8)])
+def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
+    print(f"case dense M={M} K={K} a={a_bits}", flush=True)
+    X = _acts(M, K, 3 + K)
+    R = synth.make_rotation(K, (901, K, 0))
+    q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "dense", R_bits=R)
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), lrq.Rotation("dense", 0, bf16_to_dev(R)), a_bits)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+
+
+# ------------------------------------------------------------------ TLQ calibrate + pack
+def _check_weight(lrq, W, bits, I=7, alpha=GRID, beta=GRID):
+    p = oracle.tlq_calibrate(W, bits, alpha, beta)
+    codes = oracle.tlq_encode(W, p)
+    lut, wscale = oracle.tlq_lut(p, I)
+    w = lrq.tlq_quantize_pack(to_dev(W), bits, I, to_dev(alpha), to_dev(beta))
+    assert np.array_equal(w.codes.cpu().numpy(), oracle.pack_codes(codes, bits))          # bit-exact packed codes
+    assert np.array_equal(w.z_pos.cpu().numpy(), p.z_pos) and np.array_equal(w.z_neg.cpu().numpy(), p.z_neg)
+    assert np.array_equal(w.alpha.cpu().numpy(), p.alpha) and np.array_equal(w.beta.cpu().numpy(), p.beta)
+    # scales come out of log2 / division chains evaluated by two different math libraries
+    assert np.allclose(w.s_pos.cpu().numpy(), p.s_pos, rtol=1e-14, atol=0)
+    assert np.allclose(w.s_neg.cpu().numpy(), p.s_neg, rtol=1e-14, atol=0)
+    assert np.array_equal(w.lut.cpu().numpy()[:, :2 ** bits], lut)
+    assert np.all(w.lut.cpu().numpy()[:, 2 ** bits:] == 0)
+    assert np.allclose(w.wscale.cpu().numpy(), wscale, rtol=1e-6, atol=0)
+    return w, codes, lut, wscale
+
+
+@pytest.mark.parametrize("N,K,bits,I", [(96, 1152, 4, 7), (40, 1152, 3, 7), (33, 256, 4, 6), (64, 4608, 3, 8),
+                                        (17, 12288, 4, -1), (1152, 1152, 4, 7)])
+def test_tlq_quantize_pack_bit_exact(lrq, N, K, bits, I):
+    print(f"case tlq N={N} K={K} b={bits} I={I}", flush=True)
+    W = synth.make_weights(N, K, (902, N, K))
+    _check_weight(lrq, W, bits, I)
+
+
+def test_tlq_degenerate_channels(lrq):
+    W = synth.make_weights(8, 128, (903, 0, 0))
+    W[0] = 0.0
+    W[1] = 0.25
+    W[2, :64] = -0.5; W[2, 64:] = 0.0
+    W[3] = 0.0; W[3, 0], W[3, 1] = 0.5, -0.125
+    W[4] = np.abs(W[4])
+    W[5] = -np.abs(W[5])
+    for bits in (3, 4):
+        _check_weight(lrq, W, bits)
+    _check_weight(lrq, W, 4, 7, np.array([1.0], np.float32), np.array([1.0, 1.5], np.float32))
+
+
+# ------------------------------------------------------------------ GEMM + rescale
+@pytest.mark.parametrize("M,N,K,w_bits,a_bits", [
+    (256, 1152, 1152, 4, 8),      # config 1
+    (300, 352, 1152, 4, 8),       # ragged M, N not a multiple of the workgroup tile
+    (513, 200, 256, 3, 4),        # N not a multiple of 32, 3-bit weights
+    (70, 4608, 128, 4, 4),
+    (2, 6912, 1152, 3, 4),        # adaLN-shaped: two tokens
+])
+def test_qgemm_against_oracle(lrq, M, N, K, w_bits, a_bits):
+    import torch
+    print(f"case qgemm M={M} N={N} K={K} W{w_bits}A{a_bits}", flush=True)
+    W = synth.make_weights(N, K, (904, N, K))
+    w, codes, lut, wscale = _check_weight(lrq, W, w_bits)
+    X = _acts(M, K, 5 + M)
+    q, s = oracle.ars_rotate_quant(X, a_bits, "hadamard", synth.default_had_block(K))
+    bias = synth.make_bias(N, (904, N, K))
+    qd, sd = to_dev(q), to_dev(s)
+    y_ref = oracle.qlinear_from_parts(q, s, codes, lut, wscale, w_bits, bias)
+    y32 = lrq.qgemm(qd, sd, w, bias=to_dev(bias), out_dtype=torch.float32).cpu().numpy()
+    assert rel_fro(y32, y_ref) <= 1e-3
+    assert np.allclose(y32, y_ref, rtol=2e-6, atol=1e-6 * np.abs(y_ref).max())            # fp32 epilogue of an exact integer sum
+    y_ref_nb = oracle.qlinear_from_parts(q, s, codes, lut, wscale, w_bits)
+    y16 = bf16_bits_from_dev(lrq.qgemm(qd, sd, w, out_dtype=torch.bfloat16))
+    ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref_nb))
+    assert rel_fro(oracle.bf16_bits_to_f64(y16), ref16) <= 1e-3
+    # the integer accumulators themselves: scale = wscale = 1 gives the exact int32 sums in fp32 (|acc| < 2^24 here)
+    if K <= 256:
+        ones_m, ones_n = torch.ones(M, device=qd.device), w.wscale.clone()
+        w.wscale.fill_(1.0)
+        acc = lrq.qgemm(qd, ones_m, w, out_dtype=torch.float32).cpu().numpy()
+        w.wscale.copy_(ones_n)
+        ref_acc = oracle.qlinear_from_parts(q, np.ones(M, np.float32), codes, lut, np.ones(N, np.float32), w_bits)
+        assert np.array_equal(acc.astype(np.float64), ref_acc)
+
+
+# ------------------------------------------------------------------ fused path
+@pytest.mark.parametrize("cfg_case", ["config1", "dense", "w3a4"])
+def test_qlinear_end_to_end(lrq, cfg_case):
+    import torch
+    print(f"case qlinear {cfg_case}", flush=True)
+    if cfg_case == "config1":
+        spec = synth.config_layers(1)[0]
+    elif cfg_case == "dense":
+        spec = synth.LayerSpec("d", 905, 0, 0, 150, 256, 96, 4, 8, "dense", 256, 0.05, 4, 40.0)
+    else:
+        spec = synth.LayerSpec("w3", 906, 0, 0, 333, 1152, 416, 3, 4, "hadamard", 128, 0.05, 8, 40.0)
+    X, W, R, bias = synth.layer_tensors(spec, with_bias=True)
+    ref = oracle.qlinear(X, W, spec.w_bits, spec.a_bits, spec.rotation, spec.had_block, R, 7, GRID, GRID, bias)
+    w = lrq.tlq_quantize_pack(to_dev(W), spec.w_bits, 7, to_dev(GRID), to_dev(GRID))
+    rot = lrq.Rotation(spec.rotation, spec.had_block, None if R is None else bf16_to_dev(R))
+    assert np.array_equal(w.codes.cpu().numpy(), oracle.pack_codes(ref["codes"], spec.w_bits))
+    y = lrq.qlinear(bf16_to_dev(X), rot, spec.a_bits, w, bias=to_dev(bias), out_dtype=torch.float32).cpu().numpy()
+    assert rel_fro(y, ref["y"]) <= 1e-3
+    y16 = bf16_bits_from_dev(lrq.qlinear(bf16_to_dev(X), rot, spec.a_bits, w, bias=to_dev(bias), out_dtype=torch.bfloat16))
+    ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(ref["y"]))
+    assert rel_fro(oracle.bf16_bits_to_f64(y16), ref16) <= 1e-3
+    # the activation codes inside the fused call are the standalone call's
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, spec.a_bits)
+    assert np.array_equal(q.cpu().numpy(), ref["q"]) and np.array_equal(s.cpu().numpy(), ref["scale"])
+
+
+def test_smoke_entry(lrq):
+    import __graft_entry__
+    __graft_entry__.smoke()
