@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the LRQ-DiT quantized-linear hot path on one MI355X.
+
+A "step" is one pass of the whole runtime path (lrq_qlinear = rotate + per-token quantize + TLQ
+decode + int8 MFMA GEMM + rescale) over every linear of the chosen workload, inputs resident in HBM.
+Weight calibration/packing (lrq_tlq_quantize_pack) is the offline step; it is timed once and reported
+beside the step, not inside it.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c1|c2|c3|c4|c5] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
+FP64_VEC_PEAK_TFLOPS = 78.6
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--blocks", type=int, default=0, help="c5 only: number of transformer blocks (0 = all 28)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
+    ap.add_argument("--cpu-channels", type=int, default=2304, help="output channels per layer in the oracle sample")
+    ap.add_argument("--cache-bytes", type=int, default=768 << 20,
+                    help="cycle through enough buffer copies that a step's working set exceeds this")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2508_03485_amd as lrq
+    import synth
+
+    if not os.path.exists(lrq.LIB_PATH):
+        from paper_2508_03485_amd.build import build
+        build()
+    lrq.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = int(args.workload[1])
+    specs = synth.config_layers(cfg)
+    if cfg == 5 and args.blocks:
+        specs = [s for s in specs if s.block < args.blocks]
+    grid = torch.from_numpy(synth.DEFAULT_GRID).to(dev)
+
+    # ---------------------------------------------------------------- inputs (seeded, synthetic), resident in HBM
+    t_gen = time.time()
+    layers = []
+    shape_cache = {}
+    pack_ms = 0.0
+    for s in specs:
+        # config 5 re-uses one set of activations per distinct shape (seeded by the first block that has it): the
+        # kernels' work does not depend on the values, and 140 separate 8192-token inputs would not fit the run time
+        skey = (s.M, s.K, s.N, s.rotation) if cfg == 5 else s.key
+        if skey not in shape_cache:
+            Xb = synth.make_activations(s.M, s.K, s.key, s.p_mild, s.n_salient, s.gain)
+            X = torch.from_numpy(Xb.view(np.int16)).to(dev).view(torch.bfloat16)
+            W = torch.from_numpy(synth.make_weights(s.N, s.K, s.key)).to(dev)
+            R = None
+            if s.rotation == "dense":
+                R = torch.from_numpy(synth.make_rotation(s.K, s.key).view(np.int16)).to(dev).view(torch.bfloat16)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            w = lrq.tlq_quantize_pack(W, s.w_bits, 7, grid, grid)
+            e1.record()
+            torch.cuda.synchronize()
+            pack_ms += e0.elapsed_time(e1)
+            del W
+            shape_cache[skey] = (X, w, R)
+        X, w, R = shape_cache[skey]
+        rot = lrq.Rotation(s.rotation, s.had_block, R)
+        layers.append(dict(spec=s, X=[X], w=w, rot=rot))
+    gen_s = time.time() - t_gen
+
+    # buffer copies so that consecutive steps do not find their inputs in the 256 MB Infinity Cache
+    step_bytes = sum(l["spec"].M * l["spec"].K * 3 + l["spec"].M * l["spec"].N * 2 for l in layers)
+    copies = max(1, min(8, math.ceil(args.cache_bytes / max(step_bytes, 1))))
+    for l in layers:
+        s = l["spec"]
+        while len(l["X"]) < copies:
+            l["X"].append(l["X"][0].clone())
+        l["Y"] = [torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev) for _ in range(copies)]
+        nws = lrq.workspace_bytes(s.M, s.N, s.K, l["rot"], s.a_bits)
+        l["ws"] = [torch.empty(nws, dtype=torch.uint8, device=dev) for _ in range(copies)]
+        l["q"] = [torch.empty((s.M, s.K), dtype=torch.int8, device=dev) for _ in range(copies)]
+        l["sc"] = [torch.empty(s.M, dtype=torch.float32, device=dev) for _ in range(copies)]
+        na = lrq.ars_workspace_bytes(s.M, s.K, l["rot"], s.a_bits)
+        l["aws"] = torch.empty(na, dtype=torch.uint8, device=dev) if na else None
+
+    def step(i):
+        c = i % copies
+        for l in layers:
+            lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c])
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    total_ops = sum(l["spec"].ops for l in layers)
+    tops = total_ops / (ms_per_step * 1e-3) / 1e12
+
+    # ---------------------------------------------------------------- per-kernel durations (HIP events on the launch stream)
+    ksteps = max(3, min(args.steps, 10))
+    ev = []
+    for i in range(ksteps):
+        c = (args.warmup + args.steps + i) % copies
+        for li, l in enumerate(layers):
+            s = l["spec"]
+            a, b, d = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            a.record()
+            lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"])
+            b.record()
+            lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c])
+            d.record()
+            ev.append((li, a, b, d))
+    torch.cuda.synchronize()
+    rot_ms = [0.0] * len(layers)
+    gemm_ms = [0.0] * len(layers)
+    for li, a, b, d in ev:
+        rot_ms[li] += a.elapsed_time(b) / ksteps
+        gemm_ms[li] += b.elapsed_time(d) / ksteps
+
+    per_layer = []
+    agg = {}
+    for li, l in enumerate(layers):
+        s = l["spec"]
+        key = s.name.split(".")[-1] if cfg == 5 else s.name
+        if cfg == 5 and s.rotation == "dense":
+            key += "(dense)"
+        rq_bytes = 3 * s.M * s.K + 4 * s.M
+        e = agg.setdefault(key, dict(name=key, M=s.M, K=s.K, N=s.N, rotation=s.rotation, count=0, rot_ms=0.0,
+                                     gemm_ms=0.0, ops=0, rq_bytes=0))
+        e["count"] += 1
+        e["rot_ms"] += rot_ms[li]
+        e["gemm_ms"] += gemm_ms[li]
+        e["ops"] += s.ops
+        e["rq_bytes"] += rq_bytes
+    for e in agg.values():
+        e["gemm_tops"] = round(e["ops"] / (e["gemm_ms"] * 1e-3) / 1e12, 2) if e["gemm_ms"] > 0 else None
+        e["rotate_quant_gbs"] = round(e["rq_bytes"] / (e["rot_ms"] * 1e-3) / 1e9, 1) if e["rot_ms"] > 0 else None
+        e["rot_ms"] = round(e["rot_ms"], 4)
+        e["gemm_ms"] = round(e["gemm_ms"], 4)
+        del e["ops"], e["rq_bytes"]
+        per_layer.append(e)
+
+    # dominant kernel: the decode + MFMA GEMM.  Algorithmic ops per launch = 2*M*N*K.
+    gemm_total_ms = sum(gemm_ms)
+    gemm_tops = total_ops / (gemm_total_ms * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel="qgemm_kernel (decode + int8 MFMA + rescale)", achieved=round(gemm_tops, 2),
+                    peak=INT8_MFMA_PEAK_TOPS, unit="TFLOP/s", frac=round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
+                    traffic=None, note="int8 multiply-accumulates counted as 2 ops (TOP/s); averaged over the "
+                    "workload's layers, %d launches each" % ksteps,
+                    avg_launch_ms=round(gemm_total_ms / len(layers), 4))
+    # Hadamard rotate+quantize: algorithmic bytes = 2 (bf16 in) + 1 (code out) per element + 4 per token
+    had = [(li, l) for li, l in enumerate(layers) if l["spec"].rotation == "hadamard"]
+    roofline_rq = None
+    if had:
+        b = sum(3 * l["spec"].M * l["spec"].K + 4 * l["spec"].M for _, l in had)
+        t = sum(rot_ms[li] for li, _ in had)
+        gbs = b / (t * 1e-3) / 1e9
+        roofline_rq = dict(bound="hbm", kernel="hadamard rotate + quantize", achieved=round(gbs, 1), peak=HBM_PEAK_GBS,
+                           unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4), traffic=None,
+                           avg_launch_ms=round(t / len(had), 4))
+
+    out = dict(metric="fused W-TLQ/A-ARS qlinear TOPS + % int8 MFMA peak; rotate+quant HBM GB/s",
+               value=round(tops, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="int8", data="synthetic",
+               config=dict(workload={1: "config1: single 256x1152->1152 W4A8 Hadamard",
+                                     2: "config2: PixArt-style block linears, 8192 tokens, hidden 1152, W4A8, Hadamard",
+                                     3: "config3: FLUX-style block linears, 4608 tokens, hidden 3072, W4A4, Hadamard",
+                                     4: "config4: video-DiT block linears, 35100 tokens, hidden 3072, W4A8, per-layer ARS",
+                                     5: "config5: 28-block PixArt-style stack, W3A4, per-layer ARS"}[cfg],
+                           layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
+                           step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
+               roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
+               offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, args.cpu_rows, args.cpu_channels)
+    print(json.dumps(out))
+
+
+def cpu_baseline(specs, rows, channels):
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the same workload:
+    the first `rows` token rows of up to four distinct layers (rows are independent under per-token
+    quantization), runtime path only (rotate + quantize + integer GEMM + rescale); its own weight
+    calibration is done beforehand and not timed, like the GPU's."""
+    import oracle
+    import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    seen, sample = set(), []
+    for s in specs:
+        k = (s.K, s.N, s.rotation)
+        if k in seen or len(sample) >= 4:
+            continue
+        seen.add(k)
+        sample.append(s)
+    ops, t_run = 0, 0.0
+    for s in sample:
+        m = min(rows, s.M)
+        if s.rotation == "dense":
+            m = min(m, 128)                 # the oracle's dense rotation accumulates k by k
+        # the sample's weights are restricted to `channels` output channels to bound the calibration time
+        n = min(s.N, channels)
+        X = synth.make_activations(s.M, s.K, s.key, s.p_mild, s.n_salient, s.gain, rows=(0, m))
+        W = synth.make_weights(s.N, s.K, s.key)[:n]
+        R = synth.make_rotation(s.K, s.key) if s.rotation == "dense" else None
+        p = oracle.tlq_calibrate(W, s.w_bits, synth.DEFAULT_GRID, synth.DEFAULT_GRID)
+        codes = oracle.tlq_encode(W, p)
+        lut, wscale = oracle.tlq_lut(p, 7)
+        t0 = time.perf_counter()
+        q, sc = oracle.ars_rotate_quant(X, s.a_bits, s.rotation, s.had_block, R)
+        y = oracle.qlinear_from_parts(q, sc, codes, lut, wscale, s.w_bits)
+        oracle.f64_to_bf16_bits(y)
+        t_run += time.perf_counter() - t0
+        ops += 2 * m * n * s.K
+    return dict(value=round(ops / t_run / 1e12, 5), unit="TOPS", cores=int(cores), kind="oracle",
+                seconds=round(t_run, 2),
+                sample="first %d token rows x first %d output channels of %d distinct layers (%s); runtime path only "
+                       "(rotate + quantize + integer GEMM + rescale), calibration untimed"
+                       % (rows, channels, len(sample), ", ".join(s.name for s in sample)))
+
+
+if __name__ == "__main__":
+    main()
