@@ -29,15 +29,6 @@ __device__ __forceinline__ unsigned perm(unsigned hi, unsigned lo, unsigned sel)
     return __builtin_amdgcn_perm(hi, lo, sel);
 }
 
-// 4 codes (one per byte of sel, values 0..15) -> 4 int8 levels from a 16-entry table held in L[0..3].
-__device__ __forceinline__ unsigned lut16(const unsigned L[4], unsigned sel) {
-    const unsigned idx = sel & 0x07070707u;
-    const unsigned a = perm(L[1], L[0], idx);
-    const unsigned b = perm(L[3], L[2], idx);
-    const unsigned pick = ((sel >> 1) & 0x04040404u) | 0x03020100u;   // byte j: j (from a) or 4 + j (from b)
-    return perm(b, a, pick);
-}
-
 template <int BITS>
 struct BRaw {
     unsigned d[BITS == 4 ? 4 : 3];
@@ -56,32 +47,93 @@ __device__ __forceinline__ BRaw<BITS> load_braw(const uint8_t* __restrict__ p) {
     return r;
 }
 
-// Decode the 16 codes a lane feeds to MFMA step s (0 | 1) of the current K block.
+// Decode the 4 codes of operand dword g (0..3) of MFMA step s (0 | 1) of a K block.
+// 4-bit: raw dword 2s + g/2 holds 8 codes, byte j = code[j] | code[4+j] << 4; the level table has 16
+// entries (L[0..1] codes 0..7, L[2..3] codes 8..15 = negative twin): two 8-entry byte permutes and a
+// third that picks per byte by the code's sign bit.  C = 0x03020100 must live in a VGPR so that the
+// pick selector is a single v_and_or_b32.
+// 3-bit: d[s] holds the low two bits of the 16 codes of step s, d[2] the third bits; 8-entry table.
 template <int BITS>
-__device__ __forceinline__ v4i decode_step(const BRaw<BITS>& raw, const unsigned L[4], int s) {
-    v4i out;
+__device__ __forceinline__ unsigned decode_dword(const BRaw<BITS>& raw, const unsigned L[4], int s, int g, unsigned C) {
     if constexpr (BITS == 4) {
-#pragma unroll
-        for (int d = 0; d < 2; ++d) {
-            const unsigned w = raw.d[2 * s + d];
-            out[2 * d] = (int)lut16(L, w & 0x0F0F0F0Fu);
-            out[2 * d + 1] = (int)lut16(L, (w >> 4) & 0x0F0F0F0Fu);
+        const unsigned w = raw.d[2 * s + g / 2];
+        unsigned idx, pick;
+        if (g % 2 == 0) {
+            idx = w & 0x07070707u;
+            pick = ((w >> 1) & 0x04040404u) | C;
+        } else {
+            idx = (w >> 4) & 0x07070707u;
+            pick = ((w >> 5) & 0x04040404u) | C;
         }
+        const unsigned a = perm(L[1], L[0], idx);
+        const unsigned b = perm(L[3], L[2], idx);
+        return perm(b, a, pick);
     } else {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const unsigned lo2 = (raw.d[s] >> (2 * g)) & 0x03030303u;
-            const unsigned b2 = (raw.d[2] >> (4 * s + g)) & 0x01010101u;
-            out[g] = (int)perm(L[1], L[0], (b2 << 2) | lo2);
-        }
+        const unsigned lo2 = (raw.d[s] >> (2 * g)) & 0x03030303u;
+        const unsigned b2 = (raw.d[2] >> (4 * s + g)) & 0x01010101u;
+        return perm(L[1], L[0], (b2 << 2) | lo2);
     }
-    return out;
 }
 
 __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
     unsigned u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
+}
+
+// One K block of the main loop.  On entry: Acur holds A tile kb, aS holds tile kb+1 (staged into Anxt, then
+// reloaded with tile kb+3), bCur holds B block kb (its MFMA step 0 already decoded in bd0; reloaded with block
+// kb+2 once step 1 is decoded), bNxt holds block kb+1 whose step 0 is decoded into bd0 while step 1 multiplies.
+// Decode work is spread evenly between the MFMAs so that it issues in their shadow.
+template <int BITS, int MT, int ALOADS>
+__device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char* Anxt, v4i (&aS)[ALOADS],
+                                       BRaw<BITS> (&bCur)[NTW], const BRaw<BITS> (&bNxt)[NTW], int kb, int KB,
+                                       const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
+                                       const uint8_t* const (&bptr)[NTW], const unsigned (&L)[NTW][4], unsigned C,
+                                       v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off) {
+    constexpr int UNIT = 64 * (BITS == 4 ? 16 : 12);
+#pragma unroll
+    for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&Anxt[aoff[i]]) = aS[i];
+    const int ka = kb + 3 < KB ? kb + 3 : KB - 1;
+    const int kbn = kb + 2 < KB ? kb + 2 : KB - 1;
+#pragma unroll
+    for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * BK);
+    v4i af[2 * MT], bd1[NTW];
+    constexpr int DPB = (NTW * 4 + MT - 1) / MT;       // operand dwords decoded per MFMA row tile
+    af[0] = *reinterpret_cast<const v4i*>(&Acur[0 * PLANE + rd_off]);
+    af[1] = *reinterpret_cast<const v4i*>(&Acur[(MT > 1 ? 4 : 2) * PLANE + rd_off]);
+#pragma unroll
+    for (int p = 0; p < 2 * MT; ++p) {
+        const int s = p / MT, i = p % MT;
+        if (p + 2 < 2 * MT) {
+            const int s2 = (p + 2) / MT, i2 = (p + 2) % MT;
+            af[p + 2] = *reinterpret_cast<const v4i*>(&Acur[(i2 * 4 + s2 * 2) * PLANE + rd_off]);
+        }
+        if (s == 0) {
+#pragma unroll
+            for (int d = 0; d < DPB; ++d) {
+                const int dd = i * DPB + d;
+                if (dd < NTW * 4) bd1[dd / 4][dd % 4] = (int)decode_dword<BITS>(bCur[dd / 4], L[dd / 4], 1, dd % 4, C);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NTW; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[p], s == 0 ? bd0[j] : bd1[j], acc[i][j], 0, 0, 0);
+        if (s == 1) {
+            // step 0 of the next block: bd0 is free now (step 1 multiplies with bd1)
+#pragma unroll
+            for (int d = 0; d < DPB; ++d) {
+                const int dd = i * DPB + d;
+                if (dd < NTW * 4) bd0[dd / 4][dd % 4] = (int)decode_dword<BITS>(bNxt[dd / 4], L[dd / 4], 0, dd % 4, C);
+            }
+        }
+        if (p == MT - 1) {
+#pragma unroll
+            for (int j = 0; j < NTW; ++j) bCur[j] = load_braw<BITS>(bptr[j] + (size_t)kbn * UNIT);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
 }
 
 // BM rows x 256 columns per workgroup of 4 waves; MT = BM / 32 MFMA row tiles per wave.
@@ -152,73 +204,42 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // ---- prologue: A tile 0 -> LDS buffer 0; A tiles 1, 2 and B blocks 0, 1, 2 in flight in registers
-    uint4 a1[ALOADS], a2[ALOADS];
-    BRaw<BITS> b0[NTW], b1[NTW], b2[NTW];
+    // ---- prologue: A tile 0 -> LDS buffer 0; A tiles 1 (aO), 2 (aE) and B blocks 0 (bE), 1 (bO) in registers
+    unsigned C = 0x03020100u;
+    asm volatile("" : "+v"(C));
+    v4i aO[ALOADS], aE[ALOADS];
+    BRaw<BITS> bE[NTW], bO[NTW];
+    v4i bd0[NTW];
     {
-        uint4 a0[ALOADS];
+        v4i a0[ALOADS];
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) a0[i] = *reinterpret_cast<const uint4*>(aptr[i]);
+        for (int i = 0; i < ALOADS; ++i) a0[i] = *reinterpret_cast<const v4i*>(aptr[i]);
         const int k1 = KB > 1 ? 1 : 0, k2 = KB > 2 ? 2 : KB - 1;
 #pragma unroll
         for (int j = 0; j < NTW; ++j) {
-            b0[j] = load_braw<BITS>(bptr[j]);
-            b1[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
-            b2[j] = load_braw<BITS>(bptr[j] + (size_t)k2 * UNIT);
+            bE[j] = load_braw<BITS>(bptr[j]);
+            bO[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
         }
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
-            a1[i] = *reinterpret_cast<const uint4*>(aptr[i] + (size_t)k1 * BK);
-            a2[i] = *reinterpret_cast<const uint4*>(aptr[i] + (size_t)k2 * BK);
+            aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k1 * BK);
+            aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * BK);
         }
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<uint4*>(&smem[aoff[i]]) = a0[i];
+        for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&smem[aoff[i]]) = a0[i];
+#pragma unroll
+        for (int j = 0; j < NTW; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) bd0[j][g] = (int)decode_dword<BITS>(bE[j], L[j], 0, g, C);
     }
     __syncthreads();
 
     const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
-    for (int kb = 0; kb < KB; ++kb) {
-        const unsigned char* Acur = smem + (kb & 1) * ABUF;
-        unsigned char* Anxt = smem + ((kb & 1) ^ 1) * ABUF;
-        // stage A tile kb+1 (loaded two iterations ago) and start the loads of tile kb+3 / block kb+3
-#pragma unroll
-        for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<uint4*>(&Anxt[aoff[i]]) = a1[i];
-        const int k3 = kb + 3 < KB ? kb + 3 : KB - 1;
-        BRaw<BITS> b3[NTW];
-#pragma unroll
-        for (int i = 0; i < ALOADS; ++i) {
-            a1[i] = a2[i];
-            a2[i] = *reinterpret_cast<const uint4*>(aptr[i] + (size_t)k3 * BK);
-        }
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) b3[j] = load_braw<BITS>(bptr[j] + (size_t)k3 * UNIT);
 
-        v4i af0[MT], af1[MT], bd[NTW];
-#pragma unroll
-        for (int i = 0; i < MT; ++i) af0[i] = *reinterpret_cast<const v4i*>(&Acur[(i * 4 + 0) * PLANE + rd_off]);
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) bd[j] = decode_step<BITS>(b0[j], L[j], 0);
-#pragma unroll
-        for (int i = 0; i < MT; ++i) af1[i] = *reinterpret_cast<const v4i*>(&Acur[(i * 4 + 2) * PLANE + rd_off]);
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTW; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af0[i], bd[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) bd[j] = decode_step<BITS>(b0[j], L[j], 1);
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTW; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af1[i], bd[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) {
-            b0[j] = b1[j];
-            b1[j] = b2[j];
-            b2[j] = b3[j];
-        }
-        __syncthreads();
+    for (int kb = 0; kb < KB; kb += 2) {
+        kblock<BITS, MT, ALOADS>(smem, smem + ABUF, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
+        if (kb + 1 < KB)
+            kblock<BITS, MT, ALOADS>(smem + ABUF, smem, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
     }
 
     // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS, store 16 bytes per lane.
@@ -257,9 +278,10 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
                     if (vec && col + 8 <= N) {
                         *reinterpret_cast<uint4*>(&Yh[(size_t)row * N + col]) = v;
                     } else {
-                        const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
+                        const unsigned e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
                         for (int x = 0; x < 8; ++x)
-                            if (col + x < N) Yh[(size_t)row * N + col + x] = e[x];
+                            if (col + x < N) Yh[(size_t)row * N + col + x] = (uint16_t)(e[x / 2] >> (16 * (x % 2)));
                     }
                 }
             }
@@ -287,9 +309,10 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
                         if (vec && col + 4 <= N) {
                             *reinterpret_cast<uint4*>(&Yf[(size_t)row * N + col]) = v;
                         } else {
-                            const float* e = reinterpret_cast<const float*>(&v);
+                            const unsigned e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
                             for (int x = 0; x < 4; ++x)
-                                if (col + x < N) Yf[(size_t)row * N + col + x] = e[x];
+                                if (col + x < N) Yf[(size_t)row * N + col + x] = __uint_as_float(e[x]);
                         }
                     }
                 }
@@ -312,10 +335,18 @@ hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, int M, in
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y) {
     const int fp32 = out_dtype == LRQ_OUT_FP32;
-    static const int bm = [] { const char* e = getenv("LRQ_GEMM_BM"); return e ? atoi(e) : 128; }();
+    static const int bm_env = [] { const char* e = getenv("LRQ_GEMM_BM"); return e ? atoi(e) : 0; }();
+    // 256-row tiles halve the decode work per multiply-accumulate; 128-row tiles fill the chip on small problems
+    const long tiles256 = (long)((M + 255) / 256) * ((w.N + BN - 1) / BN);
+    const int bm = bm_env ? bm_env : 128;   // 192/256-row variants are kept for experiments (LRQ_GEMM_BM)
+    (void)tiles256;
     if (bm == 256) {
         if (w.bits == 4) return launch<4, 256>(st, q, scale, M, K, w, bias, fp32, Y);
         return launch<3, 256>(st, q, scale, M, K, w, bias, fp32, Y);
+    }
+    if (bm == 192) {
+        if (w.bits == 4) return launch<4, 192>(st, q, scale, M, K, w, bias, fp32, Y);
+        return launch<3, 192>(st, q, scale, M, K, w, bias, fp32, Y);
     }
     if (w.bits == 4) return launch<4, 128>(st, q, scale, M, K, w, bias, fp32, Y);
     return launch<3, 128>(st, q, scale, M, K, w, bias, fp32, Y);
