@@ -20,7 +20,8 @@ LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
 
 EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes",
            "lrq_tlq_workspace_bytes", "lrq_tlq_quantize_pack", "lrq_ars_workspace_bytes",
-           "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm")
+           "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm", "lrq_probe_mfma_i8",
+           "lrq_probe_copy")
 
 
 class LrqError(RuntimeError):
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
                               vp, vp, sz]
     L.lrq_qgemm.restype = ci
     L.lrq_qgemm.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
+    L.lrq_probe_mfma_i8.restype = ci
+    L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+    L.lrq_probe_copy.restype = ci
+    L.lrq_probe_copy.argtypes = [vp, vp, vp, sz]
     _lib = L
     return L
 
@@ -216,3 +221,35 @@ def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
                          _ptr(out))
     _check(st, "lrq_qgemm")
     return out
+
+
+def probe_mfma_i8(blocks: int = 2048, iters: int = 4096, reps: int = 5) -> float:
+    """Sustained int8 MFMA rate of the device in TOP/s (lrq_probe_mfma_i8 timed with events)."""
+    import torch
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ops = ctypes.c_double(0.0)
+    _check(lib().lrq_probe_mfma_i8(_stream(), blocks, iters, _ptr(out), ctypes.byref(ops)), "lrq_probe_mfma_i8")
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        lib().lrq_probe_mfma_i8(_stream(), blocks, iters, _ptr(out), None)
+    b.record()
+    torch.cuda.synchronize()
+    return ops.value * reps / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
+def probe_copy(nbytes: int = 1 << 30, reps: int = 10) -> float:
+    """Device copy bandwidth in GB/s counting read + written bytes (lrq_probe_copy timed with events)."""
+    import torch
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    _check(lib().lrq_probe_copy(_stream(), _ptr(src), _ptr(dst), nbytes), "lrq_probe_copy")
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        lib().lrq_probe_copy(_stream(), _ptr(src), _ptr(dst), nbytes)
+    b.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9

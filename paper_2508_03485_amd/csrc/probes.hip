@@ -1,0 +1,49 @@
+// Measurement probes: a pure int8 MFMA loop and a plain copy kernel.  They give the sustained matrix
+// rate and the copy bandwidth of the device the benchmark runs on, next to which the published peaks
+// (and the fractions of them that the real kernels reach) can be read.
+#include "lrq_internal.h"
+
+namespace lrq {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// Every wave issues iters x 8 independent 32x32x32 int8 MFMAs; nothing else competes for the pipe.
+__global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(int iters, int* __restrict__ out) {
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    v4i a = {(int)threadIdx.x, 1, 2, 3}, b = {4, 5, 6, (int)blockIdx.x};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
+    if (s == 0x7fffffff) out[0] = s;   // keeps the loop alive; practically never taken
+}
+
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+
+hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int* out) {
+    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_probe(hipStream_t st, const void* src, void* dst, size_t bytes) {
+    const size_t n16 = bytes / 16;
+    hipLaunchKernelGGL(copy_probe_kernel, dim3(256 * 16), dim3(256), 0, st, static_cast<const uint4*>(src),
+                       static_cast<uint4*>(dst), n16);
+    return hipGetLastError();
+}
+
+}  // namespace lrq

@@ -21,11 +21,12 @@ __device__ __forceinline__ void load8_bf16(const uint16_t* __restrict__ p, doubl
     }
 }
 
-// n-point butterfly network on v[0..n), ascending strides, (a, b) -> (a + b, a - b).
-template <int N>
+// n-point butterfly network on v[0..n), ascending strides first_stride, 2*first_stride, ... for `stages`
+// stages, (a, b) -> (a + b, a - b).
+template <int N, int FIRST = 1>
 __device__ __forceinline__ void butterflies(double* v, int stages) {
 #pragma unroll
-    for (int s = 0, st = 1; st < N; ++s, st <<= 1) {
+    for (int s = 0, st = FIRST; st < N; ++s, st <<= 1) {
         if (s < stages) {
 #pragma unroll
             for (int i = 0; i < N; ++i) {
@@ -120,6 +121,190 @@ __global__ void hadamard_quant_generic_kernel(const uint16_t* __restrict__ X, in
         store8_codes(q + base + (size_t)c * 8, v, inv, qmax);
     }
     if (t == 0) scale[blockIdx.x] = (float)(amax / norm);
+}
+
+// ---------------------------------------------------------------- register-resident Hadamard, h <= 128
+// Every lane owns 32 contiguous elements of a token row (64 bytes in, 32 bytes out): five butterfly
+// stages run in registers, and for h = 64 / 128 the last one or two run across the lanes of a quad with
+// DPP moves (a Hadamard block is 2 / 4 adjacent lanes).  A workgroup holds R whole rows, so the only
+// exchange through LDS is the per-row maximum (one 64-bit LDS atomic per quad).  All arithmetic is
+// fp64 and every stage is taken in ascending stride order, like the definition's recursion.
+constexpr int E32 = 32;
+
+template <int CTRL>
+__device__ __forceinline__ double quad_swap(double v) {
+    const int lo = __builtin_amdgcn_mov_dpp(__double2loint(v), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(v), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+// low bytes of four rounded values -> one dword of int8 codes.  The product and the sum must round
+// separately (this file is compiled with floating-point contraction off).
+__device__ __forceinline__ unsigned pack4(const double* v, double inv) {
+    constexpr double kMagic = 6755399441055744.0;   // 1.5 * 2^52: adding it rounds to an integer, ties to even
+    unsigned b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = (unsigned)__double2loint(v[i] * inv + kMagic);
+    const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+    return (hi << 16) | lo;
+}
+
+template <int LOG2H>
+__global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t* __restrict__ X, int M, int K,
+                                                                  int rows_per_wg, double qmax, double norm,
+                                                                  int8_t* __restrict__ q, float* __restrict__ scale) {
+    __shared__ unsigned long long amax_bits[32];
+    const int lpr = K / E32;                       // lanes per row
+    const int t = threadIdx.x;
+    const int rw = t / lpr, slot = t % lpr;
+    const int row = blockIdx.x * rows_per_wg + rw;
+    const bool live = rw < rows_per_wg && row < M;
+    if (t < 32) amax_bits[t] = 0ull;
+
+    double v[E32];
+    {
+        const int lrow = live ? row : M - 1;
+        const uint16_t* src = X + (size_t)lrow * K + (size_t)slot * E32;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) load8_bf16(src + c * 8, v + c * 8);
+    }
+    constexpr int IN_REG = LOG2H < 5 ? LOG2H : 5;
+    butterflies<E32>(v, IN_REG);
+    if constexpr (LOG2H >= 6) {
+        const double sg = (t & 1) ? -1.0 : 1.0;
+#pragma unroll
+        for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0xB1>(v[i]));
+    }
+    if constexpr (LOG2H >= 7) {
+        const double sg = (t & 2) ? -1.0 : 1.0;
+#pragma unroll
+        for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0x4E>(v[i]));
+    }
+    double m = 0.0;
+#pragma unroll
+    for (int i = 0; i < E32; ++i) m = fmax(m, fabs(v[i]));
+    m = fmax(m, quad_swap<0xB1>(m));
+    m = fmax(m, quad_swap<0x4E>(m));
+    __syncthreads();
+    if (live && (t & 3) == 0) atomicMax(&amax_bits[rw], (unsigned long long)__double_as_longlong(m));
+    __syncthreads();
+    if (!live) return;
+    const double amax = __longlong_as_double((long long)amax_bits[rw]);
+    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    unsigned out[8];
+#pragma unroll
+    for (int g = 0; g < 8; ++g) out[g] = pack4(v + 4 * g, inv);
+    uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
+    dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
+    dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
+    if (slot == 0) scale[row] = (float)(amax / norm);
+}
+
+// ---------------------------------------------------------------- two-pass Hadamard, 256 <= h <= 4096
+// Pass 1: every lane owns 32 contiguous elements (stages 0..4 in registers) and writes them to LDS as
+// doubles.  Pass 2: the G = h / 32 lanes of a block re-read the block transposed - a lane now owns, for
+// its 32 / G (at least one) element offsets e, the values of up to 32 pass-1 lanes g - and runs the
+// stages 5..9 in registers; for h = 2048 / 4096 the last one / two stages run across a lane pair / quad
+// with DPP moves.  Codes go back through LDS as bytes so that every lane stores 32 contiguous bytes.
+// Rows of doubles in LDS are padded by 2 per 32 so that the 16-byte writes of pass 1 spread over banks.
+template <int LOG2H>
+__global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
+                                                                    int rows_per_wg, double qmax, double norm,
+                                                                    int8_t* __restrict__ q, float* __restrict__ scale) {
+    constexpr int G = 1 << (LOG2H - 5);            // pass-1 lanes per block
+    constexpr int NG = G < 32 ? G : 32;            // values per element offset held by a pass-2 lane
+    constexpr int EPL = 32 / NG;                   // element offsets per pass-2 lane (4, 2, 1)
+    constexpr int Q = G / NG;                      // lanes that share an element offset (1, 2, 4)
+    extern __shared__ double lds[];
+    __shared__ unsigned long long amax_bits[32];
+    const int lpr = K / E32;
+    const int rs = K + 2 * lpr;                    // doubles per padded row
+    const int t = threadIdx.x;
+    const int rw = t / lpr, slot = t % lpr;
+    const int row = blockIdx.x * rows_per_wg + rw;
+    const bool live = rw < rows_per_wg && row < M;
+    const bool inwg = rw < rows_per_wg;
+    if (t < 32) amax_bits[t] = 0ull;
+    double* rowbuf = lds + (size_t)(inwg ? rw : 0) * rs;
+
+    double v[E32];
+    {
+        const int lrow = live ? row : M - 1;
+        const uint16_t* src = X + (size_t)lrow * K + (size_t)slot * E32;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) load8_bf16(src + c * 8, v + c * 8);
+    }
+    butterflies<E32>(v, 5);
+    if (inwg) {
+        double2* dst = reinterpret_cast<double2*>(rowbuf + (size_t)slot * 34);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dst[i] = make_double2(v[2 * i], v[2 * i + 1]);
+    }
+    __syncthreads();
+
+    // pass 2: this thread is lane j of block b
+    const int b = slot / G, j = slot % G;
+    const int e0 = (j / Q) * EPL, gq = j % Q;
+    const double* blk = rowbuf + (size_t)b * G * 34;
+#pragma unroll
+    for (int r = 0; r < NG; ++r) {
+        const double* p = blk + (size_t)(r + 32 * gq) * 34 + e0;
+        if constexpr (EPL == 4) {
+            const double2 a = *reinterpret_cast<const double2*>(p), c = *reinterpret_cast<const double2*>(p + 2);
+            v[r * 4 + 0] = a.x; v[r * 4 + 1] = a.y; v[r * 4 + 2] = c.x; v[r * 4 + 3] = c.y;
+        } else if constexpr (EPL == 2) {
+            const double2 a = *reinterpret_cast<const double2*>(p);
+            v[r * 2 + 0] = a.x; v[r * 2 + 1] = a.y;
+        } else {
+            v[r] = *p;
+        }
+    }
+    butterflies<E32, EPL>(v, LOG2H - 5 < 5 ? LOG2H - 5 : 5);
+    if constexpr (Q >= 2) {
+        const double sg = (t & 1) ? -1.0 : 1.0;
+#pragma unroll
+        for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0xB1>(v[i]));
+    }
+    if constexpr (Q >= 4) {
+        const double sg = (t & 2) ? -1.0 : 1.0;
+#pragma unroll
+        for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0x4E>(v[i]));
+    }
+    double m = 0.0;
+#pragma unroll
+    for (int i = 0; i < E32; ++i) m = fmax(m, fabs(v[i]));
+    m = fmax(m, quad_swap<0xB1>(m));
+    m = fmax(m, quad_swap<0x4E>(m));
+    if (live && (t & 3) == 0) atomicMax(&amax_bits[rw], (unsigned long long)__double_as_longlong(m));
+    __syncthreads();          // every pass-2 read is done: the buffer can be reused for the codes
+
+    const double amax = __longlong_as_double((long long)amax_bits[inwg ? rw : 0]);
+    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    unsigned char* cbuf = reinterpret_cast<unsigned char*>(rowbuf) + (size_t)b * (G * 32);
+    if (inwg) {
+        constexpr double kMagic = 6755399441055744.0;
+#pragma unroll
+        for (int r = 0; r < NG; ++r) {
+            unsigned char* p = cbuf + (r + 32 * gq) * 32 + e0;
+            if constexpr (EPL == 4) {
+                *reinterpret_cast<unsigned*>(p) = pack4(v + 4 * r, inv);
+            } else if constexpr (EPL == 2) {
+                const unsigned c0 = (unsigned)__double2loint(v[2 * r] * inv + kMagic);
+                const unsigned c1 = (unsigned)__double2loint(v[2 * r + 1] * inv + kMagic);
+                *reinterpret_cast<unsigned short*>(p) = (unsigned short)((c0 & 0xffu) | (c1 << 8));
+            } else {
+                *p = (unsigned char)__double2loint(v[r] * inv + kMagic);
+            }
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    const uint4* src = reinterpret_cast<const uint4*>(cbuf + j * 32);
+    uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
+    dst[0] = src[0];
+    dst[1] = src[1];
+    if (slot == 0) scale[row] = (float)(amax / norm);
 }
 
 // ---------------------------------------------------------------- dense rotation, fp64, k ascending
@@ -217,6 +402,43 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
                                  int8_t* q, float* scale) {
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
     const double norm = qmax * sqrt((double)h);
+    if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
+        // R rows per workgroup: as many as fit 1024 threads, at most 32, a multiple that keeps quads inside rows
+        const int lpr = K / E32;
+        int R = 576 / lpr;                       // about nine waves per workgroup
+        if (R < 1) R = 1;
+        if (R > 32) R = 32;
+        const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
+        const dim3 grid((M + R - 1) / R), block(nt);
+        switch (ilog2(h)) {
+#define LRQ_CASE(L) case L: hipLaunchKernelGGL(hadamard_quant_e32_kernel<L>, grid, block, 0, st, X, M, K, R, qmax, norm, q, scale); break;
+            LRQ_CASE(0) LRQ_CASE(1) LRQ_CASE(2) LRQ_CASE(3) LRQ_CASE(4) LRQ_CASE(5) LRQ_CASE(6) LRQ_CASE(7)
+#undef LRQ_CASE
+        }
+        return hipGetLastError();
+    }
+    if (h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512) {
+        const int lpr = K / E32;
+        int R = 256 / lpr;                       // about four waves per workgroup; whole rows only
+        if (R < 1) R = 1;
+        if (R > 32) R = 32;
+        const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
+        const size_t ldsb = (size_t)R * (K + 2 * lpr) * sizeof(double);
+        const dim3 grid((M + R - 1) / R), block(nt);
+        static bool attr2 = false;
+        if (!attr2) {
+#define LRQ_ATTR(L) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L>), hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024); if (e != hipSuccess) return e; }
+            LRQ_ATTR(8) LRQ_ATTR(9) LRQ_ATTR(10) LRQ_ATTR(11) LRQ_ATTR(12)
+#undef LRQ_ATTR
+            attr2 = true;
+        }
+        switch (ilog2(h)) {
+#define LRQ_CASE(L) case L: hipLaunchKernelGGL(hadamard_quant_2pass_kernel<L>, grid, block, ldsb, st, X, M, K, R, qmax, norm, q, scale); break;
+            LRQ_CASE(8) LRQ_CASE(9) LRQ_CASE(10) LRQ_CASE(11) LRQ_CASE(12)
+#undef LRQ_CASE
+        }
+        return hipGetLastError();
+    }
     const int nt = threads_for_row(K);
     const size_t lds = (size_t)(K + 16) * sizeof(double);
     static bool attr_done = false;
