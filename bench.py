@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--blocks", type=int, default=0, help="c5 only: number of transformer blocks (0 = all 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probes-only", action="store_true",
+                    help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
     ap.add_argument("--cpu-channels", type=int, default=2304, help="output channels per layer in the oracle sample")
     ap.add_argument("--cache-bytes", type=int, default=768 << 20,
@@ -56,6 +58,10 @@ def main():
     lrq.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.probes_only:
+        print(json.dumps(dict(copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1), copy_bytes_per_launch=1 << 30,
+                              mfma_i8_tops=round(lrq.probe_mfma_i8(), 1))))
+        return
     cfg = int(args.workload[1])
     specs = synth.config_layers(cfg)
     if cfg == 5 and args.blocks:
@@ -201,6 +207,16 @@ def main():
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
 
+    # what this device sustains on a pure int8 MFMA loop and on a plain copy kernel (context for the published peaks)
+    out["measured_ceilings"] = dict(mfma_i8_tops=round(lrq.probe_mfma_i8(), 1), copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1),
+                                    note="pure 32x32x32 int8 MFMA loop on constant operands; 1 GiB device copy, read + written bytes")
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        tr = json.load(open(traffic_file)).get(args.workload)
+        if tr:
+            out["roofline"]["traffic"] = tr.get("qgemm")
+            if out["roofline_rotate_quant"]:
+                out["roofline_rotate_quant"]["traffic"] = tr.get("rotate_quant")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.cpu_rows, args.cpu_channels)
     print(json.dumps(out))

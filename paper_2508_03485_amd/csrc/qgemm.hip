@@ -17,12 +17,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WAVES = 4;
-constexpr int WN = 64;              // columns of Y per wave (two 32-wide MFMA tiles)
-constexpr int BN = WAVES * WN;      // 256
 constexpr int BK = kGemmBlockK;     // 64
-constexpr int NTW = WN / 32;        // 2 MFMA column tiles per wave
 constexpr int PLANE = 32 * 16 + 64; // bytes of one (row tile, 16-byte k chunk) plane in LDS, padded
-constexpr int EPI_ROW = 64 * 2 + 16;   // bytes of one staged output row of a wave (64 bf16 / 32 fp32) + pad
+constexpr int EPI_ROW = 64 * 2 + 16;   // bytes of one staged output row of a wave (up to 64 bf16 / 32 fp32) + pad
 constexpr int EPI_WAVE = 32 * EPI_ROW; // one 32-row slab per wave
 
 __device__ __forceinline__ unsigned perm(unsigned hi, unsigned lo, unsigned sel) {
@@ -85,7 +82,7 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
 // reloaded with tile kb+3), bCur holds B block kb (its MFMA step 0 already decoded in bd0; reloaded with block
 // kb+2 once step 1 is decoded), bNxt holds block kb+1 whose step 0 is decoded into bd0 while step 1 multiplies.
 // Decode work is spread evenly between the MFMAs so that it issues in their shadow.
-template <int BITS, int MT, int ALOADS>
+template <int BITS, int MT, int NTW, int ALOADS>
 __device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char* Anxt, v4i (&aS)[ALOADS],
                                        BRaw<BITS> (&bCur)[NTW], const BRaw<BITS> (&bNxt)[NTW], int kb, int KB,
                                        const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
@@ -136,21 +133,26 @@ __device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char*
     __syncthreads();
 }
 
-// BM rows x 256 columns per workgroup of 4 waves; MT = BM / 32 MFMA row tiles per wave.
-template <int BITS, int BM>
-__global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
+// BM rows x (4 waves x NTW x 32) columns per workgroup; MT = BM / 32 MFMA row tiles per wave.  Two shapes
+// are used: 128 x 256 (NTW = 2) and 256 x 128 (NTW = 1); both keep 128 accumulator registers per lane, i.e.
+// two workgroups per CU.  The second halves the decode work per MFMA and doubles the LDS reads per MFMA.
+template <int BITS, int BM, int NTW>
+__global__ __launch_bounds__(256, BM * NTW <= 256 ? 2 : 1) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
     const uint8_t* __restrict__ gcodes, const int8_t* __restrict__ lut, const float* __restrict__ wscale,
     const float* __restrict__ bias, int out_fp32, void* __restrict__ Y, int tiles_m, int tiles_n) {
     constexpr int MT = BM / 32;
+    constexpr int WN = 32 * NTW, BN = WAVES * WN;
     constexpr int ABUF = MT * 4 * PLANE;
     constexpr int ALOADS = BM * 4 / 256;        // 16-byte chunks of the A tile per thread
     constexpr int LDS_BYTES = (2 * ABUF > WAVES * EPI_WAVE) ? 2 * ABUF : WAVES * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
     __shared__ float sc[BM];
 
-    // XCD-aware tile order: consecutive workgroup ids go round-robin over the 8 XCDs, so hand each XCD a
-    // contiguous range of tiles (neighbouring tiles share rows of q / channels of W in that XCD's L2).
+    // XCD-aware tile order.  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2), so
+    // XCD x is handed a contiguous range of a linear tile order; that order walks 8-row-tile groups n-fastest
+    // within 8 consecutive m (grouped ordering), so the ~64 tiles resident on an XCD at any time form an
+    // 8 x 8 patch that shares each row panel of q and each channel panel of W eight ways through that L2.
     const int ntiles = tiles_m * tiles_n;
     int tile;
     {
@@ -158,8 +160,16 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
         const int base = ntiles / 8, rem = ntiles % 8;           // XCD x owns base + (x < rem) tiles
         tile = x * base + (x < rem ? x : rem) + i;
     }
-    // column-major over tiles: consecutive tiles of an XCD walk down M and share the same weight columns
-    const int tn = tile / tiles_m, tm = tile % tiles_m;
+    int tm, tn;
+    {
+        constexpr int GM = 8;
+        const int per_group = GM * tiles_n;
+        const int group = tile / per_group, first_m = group * GM;
+        const int gsize = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+        const int r = tile % per_group;
+        tm = first_m + r % gsize;
+        tn = r / gsize;
+    }
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int t = threadIdx.x, lane = t % 64, wv = t / 64;
@@ -237,9 +247,9 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
     const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
 
     for (int kb = 0; kb < KB; kb += 2) {
-        kblock<BITS, MT, ALOADS>(smem, smem + ABUF, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
+        kblock<BITS, MT, NTW, ALOADS>(smem, smem + ABUF, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
         if (kb + 1 < KB)
-            kblock<BITS, MT, ALOADS>(smem + ABUF, smem, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
+            kblock<BITS, MT, NTW, ALOADS>(smem + ABUF, smem, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
     }
 
     // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS, store 16 bytes per lane.
@@ -268,10 +278,11 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
                     *reinterpret_cast<uint16_t*>(&slab[lr * EPI_ROW + (j * 32 + lane % 32) * 2]) = (uint16_t)f32_to_bf16_rne(y);
                 }
             __syncthreads();
-            // 32 rows x 128 bytes: 8 lanes per row, 8 rows per pass
+            // 32 rows x (WN * 2) bytes: WN / 8 lanes per row, 16 bytes per lane
+            constexpr int LPR = WN / 8, RPP = 64 / LPR;
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int lr = p * 8 + lane / 8, cb = (lane % 8) * 8;        // 8 bf16 per lane
+            for (int p = 0; p < 32 / RPP; ++p) {
+                const int lr = p * RPP + lane / LPR, cb = (lane % LPR) * 8;   // 8 bf16 per lane
                 const uint4 v = *reinterpret_cast<const uint4*>(&slab[lr * EPI_ROW + cb * 2]);
                 const int row = m0 + i * 32 + lr, col = ncol0 + cb;
                 if (row < M) {
@@ -321,11 +332,12 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qgemm_kernel(
     }
 }
 
-template <int BITS, int BM>
+template <int BITS, int BM, int NTW>
 hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight& w,
                   const float* bias, int fp32, void* Y) {
+    constexpr int BN = WAVES * 32 * NTW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + BN - 1) / BN;
-    hipLaunchKernelGGL((qgemm_kernel<BITS, BM>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
+    hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
                        w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -335,21 +347,15 @@ hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, int M, in
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y) {
     const int fp32 = out_dtype == LRQ_OUT_FP32;
-    static const int bm_env = [] { const char* e = getenv("LRQ_GEMM_BM"); return e ? atoi(e) : 0; }();
-    // 256-row tiles halve the decode work per multiply-accumulate; 128-row tiles fill the chip on small problems
-    const long tiles256 = (long)((M + 255) / 256) * ((w.N + BN - 1) / BN);
-    const int bm = bm_env ? bm_env : 128;   // 192/256-row variants are kept for experiments (LRQ_GEMM_BM)
-    (void)tiles256;
+    // LRQ_GEMM_SHAPE=128 | 256 forces the workgroup tile height (experiments); default: see below
+    static const int env = [] { const char* e = getenv("LRQ_GEMM_SHAPE"); return e ? atoi(e) : 0; }();
+    const int bm = env ? env : 128;
     if (bm == 256) {
-        if (w.bits == 4) return launch<4, 256>(st, q, scale, M, K, w, bias, fp32, Y);
-        return launch<3, 256>(st, q, scale, M, K, w, bias, fp32, Y);
+        if (w.bits == 4) return launch<4, 256, 1>(st, q, scale, M, K, w, bias, fp32, Y);
+        return launch<3, 256, 1>(st, q, scale, M, K, w, bias, fp32, Y);
     }
-    if (bm == 192) {
-        if (w.bits == 4) return launch<4, 192>(st, q, scale, M, K, w, bias, fp32, Y);
-        return launch<3, 192>(st, q, scale, M, K, w, bias, fp32, Y);
-    }
-    if (w.bits == 4) return launch<4, 128>(st, q, scale, M, K, w, bias, fp32, Y);
-    return launch<3, 128>(st, q, scale, M, K, w, bias, fp32, Y);
+    if (w.bits == 4) return launch<4, 128, 2>(st, q, scale, M, K, w, bias, fp32, Y);
+    return launch<3, 128, 2>(st, q, scale, M, K, w, bias, fp32, Y);
 }
 
 }  // namespace lrq
