@@ -60,7 +60,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.probes_only:
         print(json.dumps(dict(copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1), copy_bytes_per_launch=1 << 30,
-                              mfma_i8_tops=round(lrq.probe_mfma_i8(), 1))))
+                              mfma_i8_tops_constant_operands=round(lrq.probe_mfma_i8(0), 1),
+                              mfma_i8_tops_random_operands=round(lrq.probe_mfma_i8(1), 1))))
         return
     cfg = int(args.workload[1])
     specs = synth.config_layers(cfg)
@@ -208,8 +209,11 @@ def main():
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
 
     # what this device sustains on a pure int8 MFMA loop and on a plain copy kernel (context for the published peaks)
-    out["measured_ceilings"] = dict(mfma_i8_tops=round(lrq.probe_mfma_i8(), 1), copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1),
-                                    note="pure 32x32x32 int8 MFMA loop on constant operands; 1 GiB device copy, read + written bytes")
+    out["measured_ceilings"] = dict(mfma_i8_tops_constant_operands=round(lrq.probe_mfma_i8(0), 1),
+                                    mfma_i8_tops_random_operands=round(lrq.probe_mfma_i8(1), 1),
+                                    copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1),
+                                    note="pure 32x32x32 int8 MFMA loops (operand toggling lowers the sustained clock); "
+                                         "1 GiB device copy, read + written bytes")
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         tr = json.load(open(traffic_file)).get(args.workload)

@@ -171,11 +171,13 @@ int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K,
 /*
  * Measurement probes (no counterpart in the paper; they calibrate the roofline on the device at hand).
  * lrq_probe_mfma_i8: `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent
- *   v_mfma_i32_32x32x32_i8; *ops_per_launch (host, may be NULL) receives the int8 operations one launch
- *   performs (2 per multiply-accumulate).  out: int[1] device scratch.  Time it from the caller.
+ *   v_mfma_i32_32x32x32_i8; pattern 0 = all operand bytes 1, pattern 1 = pseudo-random operand bytes (the
+ *   sustained matrix clock depends on operand toggling).  *ops_per_launch (host, may be NULL) receives the
+ *   int8 operations one launch performs (2 per multiply-accumulate).  out: int[1] device scratch.  Time it
+ *   from the caller.
  * lrq_probe_copy: plain 16-byte-per-lane device copy of `bytes` (multiple of 16) from src to dst.
  */
-int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int* out, double* ops_per_launch);
+int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out, double* ops_per_launch);
 int lrq_probe_copy(void* stream, const void* src, void* dst, size_t bytes);
 
 #ifdef __cplusplus

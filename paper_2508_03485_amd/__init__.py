@@ -74,7 +74,7 @@ def lib() -> ctypes.CDLL:
     L.lrq_qgemm.restype = ci
     L.lrq_qgemm.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
     L.lrq_probe_mfma_i8.restype = ci
-    L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+    L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     L.lrq_probe_copy.restype = ci
     L.lrq_probe_copy.argtypes = [vp, vp, vp, sz]
     _lib = L
@@ -223,17 +223,18 @@ def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
     return out
 
 
-def probe_mfma_i8(blocks: int = 2048, iters: int = 4096, reps: int = 5) -> float:
-    """Sustained int8 MFMA rate of the device in TOP/s (lrq_probe_mfma_i8 timed with events)."""
+def probe_mfma_i8(pattern: int = 1, blocks: int = 2048, iters: int = 4096, reps: int = 5) -> float:
+    """Sustained int8 MFMA rate of the device in TOP/s (lrq_probe_mfma_i8 timed with events);
+    pattern 0 = constant operands, 1 = pseudo-random operands."""
     import torch
     out = torch.zeros(1, dtype=torch.int32, device="cuda")
     ops = ctypes.c_double(0.0)
-    _check(lib().lrq_probe_mfma_i8(_stream(), blocks, iters, _ptr(out), ctypes.byref(ops)), "lrq_probe_mfma_i8")
+    _check(lib().lrq_probe_mfma_i8(_stream(), blocks, iters, pattern, _ptr(out), ctypes.byref(ops)), "lrq_probe_mfma_i8")
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(reps):
-        lib().lrq_probe_mfma_i8(_stream(), blocks, iters, _ptr(out), None)
+        lib().lrq_probe_mfma_i8(_stream(), blocks, iters, pattern, _ptr(out), None)
     b.record()
     torch.cuda.synchronize()
     return ops.value * reps / (a.elapsed_time(b) * 1e-3) / 1e12

@@ -179,10 +179,10 @@ int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* r
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 
-int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int* out, double* ops_per_launch) {
-    if (blocks <= 0 || iters <= 0 || !out) return LRQ_EINVAL;
+int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out, double* ops_per_launch) {
+    if (blocks <= 0 || iters <= 0 || !out || (pattern != 0 && pattern != 1)) return LRQ_EINVAL;
     if (ops_per_launch) *ops_per_launch = 2.0 * 32 * 32 * 32 * 8.0 * iters * 4.0 * blocks;
-    return lrq::launch_mfma_probe(static_cast<hipStream_t>(stream), blocks, iters, out) == hipSuccess ? LRQ_OK : LRQ_EHIP;
+    return lrq::launch_mfma_probe(static_cast<hipStream_t>(stream), blocks, iters, pattern, out) == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 
 int lrq_probe_copy(void* stream, const void* src, void* dst, size_t bytes) {

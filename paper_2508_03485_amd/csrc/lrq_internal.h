@@ -27,7 +27,7 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y);
 
-hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int* out);
+hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int pattern, int* out);
 hipError_t launch_copy_probe(hipStream_t st, const void* src, void* dst, size_t bytes);
 
 // ---- private GEMM weight layout ----

@@ -9,17 +9,34 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+__device__ __forceinline__ unsigned mix(unsigned x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
 // Every wave issues iters x 8 independent 32x32x32 int8 MFMAs; nothing else competes for the pipe.
-__global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(int iters, int* __restrict__ out) {
+// pattern 0: every operand byte is 1 (no data toggling); pattern 1: pseudo-random operand bytes, four
+// different A and four different B register sets in rotation (the matrix pipe's power draw, and with it
+// the sustained clock, depends on how many operand bits toggle).
+__global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(int iters, int pattern, int* __restrict__ out) {
     v16i acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0;
-    v4i a = {(int)threadIdx.x, 1, 2, 3}, b = {4, 5, 6, (int)blockIdx.x};
+    v4i a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned seed = (threadIdx.x * 16u + i * 4u + c) * 2654435761u + blockIdx.x;
+            a[i][c] = pattern ? (int)mix(seed) : 0x01010101;
+            b[i][c] = pattern ? (int)mix(seed ^ 0x9e3779b9u) : 0x01010101;
+        }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i % 4], b[(i / 2) % 4], acc[i], 0, 0, 0);
     }
     int s = 0;
 #pragma unroll
@@ -34,8 +51,8 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict
 
 }  // namespace
 
-hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int* out) {
-    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, out);
+hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int pattern, int* out) {
+    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, pattern, out);
     return hipGetLastError();
 }
 

@@ -1,0 +1,100 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+
+The whole layer runs on the GPU (TLQ pack of the full weight matrix, rotate + quantize of every token,
+fused lrq_qlinear with bf16 output).  The oracle then recomputes, one by one, a seeded sample of token
+rows and output channels - rows are independent under per-token quantization and channels under
+per-channel weight quantization, so parity on the sample is exact for those rows / channels:
+  * activation codes and scales of the sampled rows: bit-exact;
+  * packed weight codes, level tables of the sampled channels: bit-exact;
+  * Y on the sampled rows x channels: relative Frobenius error <= 1e-3 against the oracle rounded to bf16.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import bf16_bits_from_dev, bf16_to_dev, rel_fro, to_dev
+
+pytestmark = pytest.mark.gpu
+GRID = synth.DEFAULT_GRID
+N_ROWS, N_CH = 40, 160
+
+
+@pytest.fixture(scope="module")
+def lrq():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2508_03485_amd as m
+    m.lib()
+    return m
+
+
+def _sample(n, k, key):
+    g = synth.rng_for(777, *key, n)
+    idx = set(g.choice(n, size=min(k, n), replace=False).tolist()) | {0, n - 1}
+    return np.array(sorted(idx))
+
+
+def _check_layer(lrq, spec):
+    import torch
+    print(f"layer {spec.name} cfg{spec.config} M={spec.M} K={spec.K} N={spec.N} W{spec.w_bits}A{spec.a_bits} "
+          f"{spec.rotation} h={spec.had_block}", flush=True)
+    X, W, R, _ = synth.layer_tensors(spec)
+    rows, chans = _sample(spec.M, N_ROWS, spec.key), _sample(spec.N, N_CH, spec.key)
+    Xd = bf16_to_dev(X)
+    rot = lrq.Rotation(spec.rotation, spec.had_block, None if R is None else bf16_to_dev(R))
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), spec.w_bits, 7, gd, gd)
+    q, sc = lrq.ars_rotate_quant(Xd, rot, spec.a_bits)
+    Y = lrq.qlinear(Xd, rot, spec.a_bits, w, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    ridx, cidx = torch.from_numpy(rows).to(Xd.device), torch.from_numpy(chans).to(Xd.device)
+    q_s, sc_s = q[ridx].cpu().numpy(), sc[ridx].cpu().numpy()
+    y_s = bf16_bits_from_dev(Y[ridx][:, cidx].contiguous())
+    codes_s, lut_s = w.codes[cidx].cpu().numpy(), w.lut[cidx].cpu().numpy()
+    wscale_s = w.wscale[cidx].cpu().numpy()
+    del Xd, q, Y
+
+    q_ref, s_ref = oracle.ars_rotate_quant(X[rows], spec.a_bits, spec.rotation, spec.had_block, R)
+    assert np.array_equal(q_s, q_ref), "activation codes differ"
+    assert np.array_equal(sc_s, s_ref), "activation scales differ"
+    p = oracle.tlq_calibrate(W[chans], spec.w_bits, GRID, GRID)
+    codes = oracle.tlq_encode(W[chans], p)
+    lut, wscale = oracle.tlq_lut(p, 7)
+    assert np.array_equal(codes_s, oracle.pack_codes(codes, spec.w_bits)), "packed weight codes differ"
+    assert np.array_equal(lut_s[:, :2 ** spec.w_bits], lut), "level tables differ"
+    assert np.allclose(wscale_s, wscale, rtol=1e-6, atol=0)
+    y_ref = oracle.qlinear_from_parts(q_ref, s_ref, codes, lut, wscale, spec.w_bits)
+    ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref))
+    err = rel_fro(oracle.bf16_bits_to_f64(y_s), ref16)
+    assert err <= 1e-3, f"relative output error {err}"
+
+
+@pytest.mark.parametrize("cfg,layer", [(2, 0), (2, 1), (2, 2), (2, 3), (3, 0), (3, 1), (3, 2), (3, 3)])
+def test_configs_2_and_3(lrq, cfg, layer):
+    _check_layer(lrq, synth.config_layers(cfg)[layer])
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
+def test_config_4(lrq, layer):
+    _check_layer(lrq, synth.config_layers(4)[layer])
+
+
+def test_config_5_block_and_a_dense_layer(lrq):
+    specs = synth.config_layers(5)
+    for s in specs[:5]:                       # block 0: qkv, proj, fc1, fc2, adaLN (two tokens)
+        _check_layer(lrq, s)
+    dense = [s for s in specs if s.rotation == "dense"]
+    assert dense, "config 5 has layers above the fluctuation threshold"
+    _check_layer(lrq, dense[0])
+
+
+def test_config_4_weight_codes_in_full(lrq):
+    # every channel of the largest weight matrix shape, packed codes compared in full
+    spec = synth.config_layers(4)[0]          # 3072 -> 9216
+    W = synth.make_weights(spec.N, spec.K, spec.key)
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), spec.w_bits, 7, gd, gd)
+    got = w.codes.cpu().numpy()
+    p = oracle.tlq_calibrate(W, spec.w_bits, GRID, GRID)
+    assert np.array_equal(got, oracle.pack_codes(oracle.tlq_encode(W, p), spec.w_bits))
