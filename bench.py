@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--probes-only", action="store_true",
                     help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
-    ap.add_argument("--cpu-channels", type=int, default=2304, help="output channels per layer in the oracle sample")
+    ap.add_argument("--cpu-channels", type=int, default=4608, help="output channels per layer in the oracle sample")
     ap.add_argument("--cache-bytes", type=int, default=768 << 20,
                     help="cycle through enough buffer copies that a step's working set exceeds this")
     return ap.parse_args()
