@@ -6,6 +6,8 @@
 // integer codes do not depend on the order in which a kernel schedules its work.
 #include "lrq_internal.h"
 
+#include <cstdlib>
+
 namespace lrq {
 namespace {
 
@@ -202,109 +204,145 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------- two-pass Hadamard, 256 <= h <= 4096
-// Pass 1: every lane owns 32 contiguous elements (stages 0..4 in registers) and writes them to LDS as
-// doubles.  Pass 2: the G = h / 32 lanes of a block re-read the block transposed - a lane now owns, for
-// its 32 / G (at least one) element offsets e, the values of up to 32 pass-1 lanes g - and runs the
-// stages 5..9 in registers; for h = 2048 / 4096 the last one / two stages run across a lane pair / quad
-// with DPP moves.  Codes go back through LDS as bytes so that every lane stores 32 contiguous bytes.
-// Rows of doubles in LDS are padded by 2 per 32 so that the 16-byte writes of pass 1 spread over banks.
-template <int LOG2H>
+// Pass 1: every lane owns 32 contiguous elements (stages 0..4 in registers).  Pass 2: the G = h / 32 lanes
+// of a block exchange the block transposed through LDS - a lane then owns, for its 32 / G (at least one)
+// element offsets e, the values of up to 32 pass-1 lanes g - and runs stages 5..9 in registers; for
+// h = 2048 / 4096 the last one / two stages run across a lane pair / quad with DPP moves.  The exchange is
+// done in two rounds of 16 element offsets each, which halves the LDS footprint (9 bytes per element in
+// flight) and so doubles the resident waves.  Codes return through LDS as bytes so that every lane stores
+// 32 contiguous bytes.  LDS rows: 16 doubles + 2 of padding per pass-1 lane and 4 more per 32 lanes (the byte
+// buffer: 16 bytes per 32 lanes), which keeps the 16-byte writes of pass 1 and the quad-strided accesses of
+// pass 2 on distinct banks.  A workgroup is persistent: it walks over row groups and loads the next group's
+// bf16 data while it transforms the current one.
+__device__ __forceinline__ int lds_row(int slot) { return 18 * slot + 4 * (slot >> 5); }
+
+template <int LOG2H, bool PERSIST>
 __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
-                                                                    int rows_per_wg, double qmax, double norm,
-                                                                    int8_t* __restrict__ q, float* __restrict__ scale) {
+                                                                   int rows_per_wg, double qmax, double norm,
+                                                                   int8_t* __restrict__ q, float* __restrict__ scale) {
     constexpr int G = 1 << (LOG2H - 5);            // pass-1 lanes per block
     constexpr int NG = G < 32 ? G : 32;            // values per element offset held by a pass-2 lane
     constexpr int EPL = 32 / NG;                   // element offsets per pass-2 lane (4, 2, 1)
     constexpr int Q = G / NG;                      // lanes that share an element offset (1, 2, 4)
-    extern __shared__ double lds[];
-    __shared__ unsigned long long amax_bits[32];
+    extern __shared__ __attribute__((aligned(16))) double lds[];
+    __shared__ unsigned long long amax_bits[2][32];
     const int lpr = K / E32;
-    const int rs = K + 2 * lpr;                    // doubles per padded row
+    const int rs = lds_row(lpr) + 8;               // doubles per row buffer
     const int t = threadIdx.x;
     const int rw = t / lpr, slot = t % lpr;
-    const int row = blockIdx.x * rows_per_wg + rw;
-    const bool live = rw < rows_per_wg && row < M;
     const bool inwg = rw < rows_per_wg;
-    if (t < 32) amax_bits[t] = 0ull;
     double* rowbuf = lds + (size_t)(inwg ? rw : 0) * rs;
-
-    double v[E32];
-    {
-        const int lrow = live ? row : M - 1;
-        const uint16_t* src = X + (size_t)lrow * K + (size_t)slot * E32;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) load8_bf16(src + c * 8, v + c * 8);
-    }
-    butterflies<E32>(v, 5);
-    if (inwg) {
-        double2* dst = reinterpret_cast<double2*>(rowbuf + (size_t)slot * 34);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dst[i] = make_double2(v[2 * i], v[2 * i + 1]);
-    }
-    __syncthreads();
-
-    // pass 2: this thread is lane j of block b
+    // pass 2 role of this thread: lane j of block b, element offsets e0 .. e0 + EPL - 1, quad position gq
     const int b = slot / G, j = slot % G;
     const int e0 = (j / Q) * EPL, gq = j % Q;
-    const double* blk = rowbuf + (size_t)b * G * 34;
-#pragma unroll
-    for (int r = 0; r < NG; ++r) {
-        const double* p = blk + (size_t)(r + 32 * gq) * 34 + e0;
-        if constexpr (EPL == 4) {
-            const double2 a = *reinterpret_cast<const double2*>(p), c = *reinterpret_cast<const double2*>(p + 2);
-            v[r * 4 + 0] = a.x; v[r * 4 + 1] = a.y; v[r * 4 + 2] = c.x; v[r * 4 + 3] = c.y;
-        } else if constexpr (EPL == 2) {
-            const double2 a = *reinterpret_cast<const double2*>(p);
-            v[r * 2 + 0] = a.x; v[r * 2 + 1] = a.y;
-        } else {
-            v[r] = *p;
-        }
-    }
-    butterflies<E32, EPL>(v, LOG2H - 5 < 5 ? LOG2H - 5 : 5);
-    if constexpr (Q >= 2) {
-        const double sg = (t & 1) ? -1.0 : 1.0;
-#pragma unroll
-        for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0xB1>(v[i]));
-    }
-    if constexpr (Q >= 4) {
-        const double sg = (t & 2) ? -1.0 : 1.0;
-#pragma unroll
-        for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0x4E>(v[i]));
-    }
-    double m = 0.0;
-#pragma unroll
-    for (int i = 0; i < E32; ++i) m = fmax(m, fabs(v[i]));
-    m = fmax(m, quad_swap<0xB1>(m));
-    m = fmax(m, quad_swap<0x4E>(m));
-    if (live && (t & 3) == 0) atomicMax(&amax_bits[rw], (unsigned long long)__double_as_longlong(m));
-    __syncthreads();          // every pass-2 read is done: the buffer can be reused for the codes
+    const int my_round = e0 >> 4;
+    const int ngroups = (M + rows_per_wg - 1) / rows_per_wg;
+    if (t < 64) amax_bits[t / 32][t % 32] = 0ull;
 
-    const double amax = __longlong_as_double((long long)amax_bits[inwg ? rw : 0]);
-    const double inv = amax > 0.0 ? qmax / amax : 0.0;
-    unsigned char* cbuf = reinterpret_cast<unsigned char*>(rowbuf) + (size_t)b * (G * 32);
-    if (inwg) {
-        constexpr double kMagic = 6755399441055744.0;
+    uint4 raw[4];
+    {
+        int r0 = blockIdx.x * rows_per_wg + rw;
+        if (!inwg || r0 >= M) r0 = M - 1;
+        const uint4* src = reinterpret_cast<const uint4*>(X + (size_t)r0 * K + (size_t)slot * E32);
 #pragma unroll
-        for (int r = 0; r < NG; ++r) {
-            unsigned char* p = cbuf + (r + 32 * gq) * 32 + e0;
-            if constexpr (EPL == 4) {
-                *reinterpret_cast<unsigned*>(p) = pack4(v + 4 * r, inv);
-            } else if constexpr (EPL == 2) {
-                const unsigned c0 = (unsigned)__double2loint(v[2 * r] * inv + kMagic);
-                const unsigned c1 = (unsigned)__double2loint(v[2 * r + 1] * inv + kMagic);
-                *reinterpret_cast<unsigned short*>(p) = (unsigned short)((c0 & 0xffu) | (c1 << 8));
-            } else {
-                *p = (unsigned char)__double2loint(v[r] * inv + kMagic);
+        for (int c = 0; c < 4; ++c) raw[c] = src[c];
+    }
+    int par = 0;
+    for (int grp = blockIdx.x; grp < ngroups; grp += gridDim.x, par ^= 1) {
+        const int row = grp * rows_per_wg + rw;
+        const bool live = inwg && row < M;
+        double v[E32], w[E32];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned wd[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[c * 8 + 2 * i] = (double)__uint_as_float(wd[i] << 16);
+                v[c * 8 + 2 * i + 1] = (double)__uint_as_float(wd[i] & 0xffff0000u);
             }
         }
+        butterflies<E32>(v, 5);
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+            if (PERSIST || round == 1) __syncthreads();   // earlier readers of the buffer (round 0 / previous group) are done
+            if (inwg) {
+                double2* dst = reinterpret_cast<double2*>(rowbuf + lds_row(slot));
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dst[i] = make_double2(v[16 * round + 2 * i], v[16 * round + 2 * i + 1]);
+            }
+            if (PERSIST && round == 0 && t < 32) amax_bits[par ^ 1][t] = 0ull;   // the other parity's slots, for the next group
+            __syncthreads();
+            if (my_round == round) {
+#pragma unroll
+                for (int r = 0; r < NG; ++r) {
+                    const double* p = rowbuf + lds_row(b * G + r + 32 * gq) + (e0 - 16 * round);
+                    if constexpr (EPL == 4) {
+                        const double2 a = *reinterpret_cast<const double2*>(p), c = *reinterpret_cast<const double2*>(p + 2);
+                        w[r * 4 + 0] = a.x; w[r * 4 + 1] = a.y; w[r * 4 + 2] = c.x; w[r * 4 + 3] = c.y;
+                    } else if constexpr (EPL == 2) {
+                        const double2 a = *reinterpret_cast<const double2*>(p);
+                        w[r * 2 + 0] = a.x; w[r * 2 + 1] = a.y;
+                    } else {
+                        w[r] = *p;
+                    }
+                }
+            }
+        }
+        if constexpr (PERSIST) {   // next group's data: in flight while pass 2 runs (pass-1 registers are dead by now)
+            int rn = (grp + gridDim.x) * rows_per_wg + rw;
+            if (!inwg || rn >= M) rn = M - 1;
+            const uint4* src = reinterpret_cast<const uint4*>(X + (size_t)rn * K + (size_t)slot * E32);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) raw[c] = src[c];
+        }
+        butterflies<E32, EPL>(w, LOG2H - 5 < 5 ? LOG2H - 5 : 5);
+        if constexpr (Q >= 2) {
+            const double sg = (t & 1) ? -1.0 : 1.0;
+#pragma unroll
+            for (int i = 0; i < E32; ++i) w[i] = fma(w[i], sg, quad_swap<0xB1>(w[i]));
+        }
+        if constexpr (Q >= 4) {
+            const double sg = (t & 2) ? -1.0 : 1.0;
+#pragma unroll
+            for (int i = 0; i < E32; ++i) w[i] = fma(w[i], sg, quad_swap<0x4E>(w[i]));
+        }
+        double m = 0.0;
+#pragma unroll
+        for (int i = 0; i < E32; ++i) m = fmax(m, fabs(w[i]));
+        m = fmax(m, quad_swap<0xB1>(m));
+        m = fmax(m, quad_swap<0x4E>(m));
+        if (live && (t & 3) == 0) atomicMax(&amax_bits[par][rw], (unsigned long long)__double_as_longlong(m));
+        __syncthreads();          // every pass-2 read is done: the buffer can be reused for the codes
+
+        const double amax = __longlong_as_double((long long)amax_bits[par][inwg ? rw : 0]);
+        const double inv = amax > 0.0 ? qmax / amax : 0.0;
+        // byte buffer: 32 bytes per pass-1 lane, 16 bytes of padding per 32 lanes
+        unsigned char* cbuf = reinterpret_cast<unsigned char*>(rowbuf) + (size_t)b * (G * 32 + (G >> 5) * 16);
+        if (inwg) {
+            constexpr double kMagic = 6755399441055744.0;
+#pragma unroll
+            for (int r = 0; r < NG; ++r) {
+                unsigned char* p = cbuf + (r + 32 * gq) * 32 + gq * 16 + e0;
+                if constexpr (EPL == 4) {
+                    *reinterpret_cast<unsigned*>(p) = pack4(w + 4 * r, inv);
+                } else if constexpr (EPL == 2) {
+                    const unsigned c0 = (unsigned)__double2loint(w[2 * r] * inv + kMagic);
+                    const unsigned c1 = (unsigned)__double2loint(w[2 * r + 1] * inv + kMagic);
+                    *reinterpret_cast<unsigned short*>(p) = (unsigned short)((c0 & 0xffu) | (c1 << 8));
+                } else {
+                    *p = (unsigned char)__double2loint(w[r] * inv + kMagic);
+                }
+            }
+        }
+        __syncthreads();
+        if (live) {
+            const uint4* src = reinterpret_cast<const uint4*>(cbuf + j * 32 + (j >> 5) * 16);
+            uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
+            dst[0] = src[0];
+            dst[1] = src[1];
+            if (slot == 0) scale[row] = (float)(amax / norm);
+        }
     }
-    __syncthreads();
-    if (!live) return;
-    const uint4* src = reinterpret_cast<const uint4*>(cbuf + j * 32);
-    uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
-    dst[0] = src[0];
-    dst[1] = src[1];
-    if (slot == 0) scale[row] = (float)(amax / norm);
 }
 
 // ---------------------------------------------------------------- dense rotation, fp64, k ascending
@@ -423,20 +461,33 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
-        const size_t ldsb = (size_t)R * (K + 2 * lpr) * sizeof(double);
-        const dim3 grid((M + R - 1) / R), block(nt);
+        const size_t ldsb = (size_t)R * (18 * lpr + 4 * (lpr >> 5) + 8) * sizeof(double);
+        // resident workgroups per CU: two waves per SIMD by registers, LDS permitting
+        const int groups = (M + R - 1) / R;
+        int per_cu = (int)((160 * 1024 - 1024) / (ldsb + 512));
+        const int by_waves = 8 / (nt / kWave) > 0 ? 8 / (nt / kWave) : 1;
+        if (per_cu > by_waves) per_cu = by_waves;
+        if (per_cu < 1) per_cu = 1;
+        // large blocks run as persistent workgroups that load the next row group while transforming the current one
+        const bool persist = h >= 2048 && groups > 256 * per_cu;
+        const dim3 grid(persist ? 256 * per_cu : groups), block(nt);
         static bool attr2 = false;
         if (!attr2) {
-#define LRQ_ATTR(L) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L>), hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024); if (e != hipSuccess) return e; }
-            LRQ_ATTR(8) LRQ_ATTR(9) LRQ_ATTR(10) LRQ_ATTR(11) LRQ_ATTR(12)
+#define LRQ_ATTR(L, P) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P>), hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024); if (e != hipSuccess) return e; }
+            LRQ_ATTR(8, false) LRQ_ATTR(9, false) LRQ_ATTR(10, false) LRQ_ATTR(11, false) LRQ_ATTR(12, false)
+            LRQ_ATTR(11, true) LRQ_ATTR(12, true)
 #undef LRQ_ATTR
             attr2 = true;
         }
+#define LRQ_CASE(L, P) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P>), grid, block, ldsb, st, X, M, K, R, qmax, norm, q, scale)
         switch (ilog2(h)) {
-#define LRQ_CASE(L) case L: hipLaunchKernelGGL(hadamard_quant_2pass_kernel<L>, grid, block, ldsb, st, X, M, K, R, qmax, norm, q, scale); break;
-            LRQ_CASE(8) LRQ_CASE(9) LRQ_CASE(10) LRQ_CASE(11) LRQ_CASE(12)
-#undef LRQ_CASE
+            case 8: LRQ_CASE(8, false); break;
+            case 9: LRQ_CASE(9, false); break;
+            case 10: LRQ_CASE(10, false); break;
+            case 11: if (persist) LRQ_CASE(11, true); else LRQ_CASE(11, false); break;
+            case 12: if (persist) LRQ_CASE(12, true); else LRQ_CASE(12, false); break;
         }
+#undef LRQ_CASE
         return hipGetLastError();
     }
     const int nt = threads_for_row(K);
