@@ -12,7 +12,7 @@ from dataclasses import dataclass
 from typing import Optional, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblrq.so")
+LIB_PATH = os.environ.get("LRQ_LIB", os.path.join(_HERE, "liblrq.so"))   # LRQ_LIB: developer override
 
 LRQ_OK, LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP = 0, -1, -2, -3, -4
 LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE = 0, 1, 2

@@ -18,7 +18,13 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WAVES = 4;
 constexpr int BK = kGemmBlockK;     // 64
-constexpr int PLANE = 32 * 16 + 64; // bytes of one (row tile, 16-byte k chunk) plane in LDS, padded
+#ifndef LRQ_PLANE_PAD
+#define LRQ_PLANE_PAD 32
+#endif
+#ifndef LRQ_AF_DIST
+#define LRQ_AF_DIST 2
+#endif
+constexpr int PLANE = 32 * 16 + LRQ_PLANE_PAD; // bytes of one (row tile, 16-byte k chunk) plane in LDS, padded
 constexpr int EPI_ROW = 64 * 2 + 16;   // bytes of one staged output row of a wave (up to 64 bf16 / 32 fp32) + pad
 constexpr int EPI_WAVE = 32 * EPI_ROW; // one 32-row slab per wave
 
@@ -97,14 +103,16 @@ __device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char*
     for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * BK);
     v4i af[2 * MT], bd1[NTW];
     constexpr int DPB = (NTW * 4 + MT - 1) / MT;       // operand dwords decoded per MFMA row tile
-    af[0] = *reinterpret_cast<const v4i*>(&Acur[0 * PLANE + rd_off]);
-    af[1] = *reinterpret_cast<const v4i*>(&Acur[(MT > 1 ? 4 : 2) * PLANE + rd_off]);
+    constexpr int DIST = LRQ_AF_DIST;                   // A fragments are read this many MFMA groups ahead
+#pragma unroll
+    for (int p = 0; p < DIST; ++p)
+        af[p] = *reinterpret_cast<const v4i*>(&Acur[((p % MT) * 4 + (p / MT) * 2) * PLANE + rd_off]);
 #pragma unroll
     for (int p = 0; p < 2 * MT; ++p) {
         const int s = p / MT, i = p % MT;
-        if (p + 2 < 2 * MT) {
-            const int s2 = (p + 2) / MT, i2 = (p + 2) % MT;
-            af[p + 2] = *reinterpret_cast<const v4i*>(&Acur[(i2 * 4 + s2 * 2) * PLANE + rd_off]);
+        if (p + DIST < 2 * MT) {
+            const int s2 = (p + DIST) / MT, i2 = (p + DIST) % MT;
+            af[p + DIST] = *reinterpret_cast<const v4i*>(&Acur[(i2 * 4 + s2 * 2) * PLANE + rd_off]);
         }
         if (s == 0) {
 #pragma unroll
@@ -128,7 +136,9 @@ __device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char*
 #pragma unroll
             for (int j = 0; j < NTW; ++j) bCur[j] = load_braw<BITS>(bptr[j] + (size_t)kbn * UNIT);
         }
+#ifndef LRQ_NO_SCHED_BARRIER
         __builtin_amdgcn_sched_barrier(0);
+#endif
     }
     __syncthreads();
 }
@@ -137,7 +147,7 @@ __device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char*
 // are used: 128 x 256 (NTW = 2) and 256 x 128 (NTW = 1); both keep 128 accumulator registers per lane, i.e.
 // two workgroups per CU.  The second halves the decode work per MFMA and doubles the LDS reads per MFMA.
 template <int BITS, int BM, int NTW>
-__global__ __launch_bounds__(256, BM * NTW <= 256 ? 2 : 1) void qgemm_kernel(
+__global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
     const uint8_t* __restrict__ gcodes, const int8_t* __restrict__ lut, const float* __restrict__ wscale,
     const float* __restrict__ bias, int out_fp32, void* __restrict__ Y, int tiles_m, int tiles_n) {
@@ -347,12 +357,19 @@ hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, int M, in
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y) {
     const int fp32 = out_dtype == LRQ_OUT_FP32;
-    // LRQ_GEMM_SHAPE=128 | 256 forces the workgroup tile height (experiments); default: see below
+    // Tile shape.  128 x 256 (two workgroups per CU) is the fastest on long K loops; 128 x 128 (three per CU)
+    // hides the prologue / epilogue of short K loops better and wastes less on N that is not a multiple of 256.
+    // LRQ_GEMM_SHAPE = 128 | 1281 | 256 forces 128x256 | 128x128 | 256x128 (experiments).
     static const int env = [] { const char* e = getenv("LRQ_GEMM_SHAPE"); return e ? atoi(e) : 0; }();
-    const int bm = env ? env : 128;
+    const bool narrow = K <= 2048 || (w.N % 256 != 0 && w.N <= 2048);
+    const int bm = env ? env : (narrow ? 1281 : 128);
     if (bm == 256) {
         if (w.bits == 4) return launch<4, 256, 1>(st, q, scale, M, K, w, bias, fp32, Y);
         return launch<3, 256, 1>(st, q, scale, M, K, w, bias, fp32, Y);
+    }
+    if (bm == 1281) {
+        if (w.bits == 4) return launch<4, 128, 1>(st, q, scale, M, K, w, bias, fp32, Y);
+        return launch<3, 128, 1>(st, q, scale, M, K, w, bias, fp32, Y);
     }
     if (w.bits == 4) return launch<4, 128, 2>(st, q, scale, M, K, w, bias, fp32, Y);
     return launch<3, 128, 2>(st, q, scale, M, K, w, bias, fp32, Y);
