@@ -443,7 +443,8 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
     if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
         // R rows per workgroup: as many as fit 1024 threads, at most 32, a multiple that keeps quads inside rows
         const int lpr = K / E32;
-        int R = 576 / lpr;                       // about nine waves per workgroup
+        static const int tgt = [] { const char* e = getenv("LRQ_ROT_THREADS"); return e ? atoi(e) : 288; }();
+        int R = tgt / lpr;                       // about five waves per workgroup (finer granularity measured faster)
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
@@ -457,7 +458,8 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
     }
     if (h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512) {
         const int lpr = K / E32;
-        int R = 256 / lpr;                       // about four waves per workgroup; whole rows only
+        static const int tgt2 = [] { const char* e = getenv("LRQ_ROT2_THREADS"); return e ? atoi(e) : 256; }();
+        int R = tgt2 / lpr;                      // about four waves per workgroup; whole rows only
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
