@@ -403,6 +403,84 @@ __global__ __launch_bounds__(256) void dense_rotate_f64_kernel(const uint16_t* _
     }
 }
 
+// Same product on the fp64 matrix cores: v_mfma_f64_16x16x4_f64 accumulates its four k in ascending order,
+// one fused multiply-add each, so chaining the instructions over ascending k gives the same bits as the
+// scalar chain above (a GPU test compares the two kernels' U bit for bit).
+// Workgroup = 4 waves (2 x 2), tile 128 x 128, wave tile 64 x 64 (16 accumulator tiles), K step 16.
+typedef double v4d __attribute__((ext_vector_type(4)));
+constexpr int MT_ = 128, MK_ = 16, XP_ = MK_ + 1, RP_ = MT_ + 4;
+
+__global__ __launch_bounds__(256, 2) void dense_rotate_mfma_f64_kernel(const uint16_t* __restrict__ X,
+                                                                        const uint16_t* __restrict__ R, int M, int K,
+                                                                        double* __restrict__ U) {
+    __shared__ __attribute__((aligned(16))) double Xs[2][MT_ * XP_];     // [row][k], k contiguous, padded rows
+    __shared__ __attribute__((aligned(16))) double Rs[2][MK_ * RP_];     // [k][col]
+    const int t = threadIdx.x, lane = t % 64, wv = t / 64;
+    const int wm = wv / 2, wn = wv % 2;
+    const int row0 = blockIdx.y * MT_, col0 = blockIdx.x * MT_;
+    v4d acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = v4d{0.0, 0.0, 0.0, 0.0};
+    // loaders: X tile 128 rows x 16 k (8 bf16 per thread), R tile 16 k x 128 cols (8 bf16 per thread)
+    const int xr = t / 2, xk = (t % 2) * 8;
+    const int rk = t / 16, rc = (t % 16) * 8;
+    int xrow = row0 + xr;
+    if (xrow >= M) xrow = M - 1;
+    const uint16_t* xp = X + (size_t)xrow * K + xk;
+    const uint16_t* rp = R + (size_t)rk * K + col0 + rc;
+    uint4 xa = *reinterpret_cast<const uint4*>(xp);
+    uint4 ra = *reinterpret_cast<const uint4*>(rp);
+    const int nk = K / MK_;
+    for (int kb = 0; kb < nk; ++kb) {
+        const int cur = kb & 1;
+        {
+            const unsigned xw[4] = {xa.x, xa.y, xa.z, xa.w}, rw[4] = {ra.x, ra.y, ra.z, ra.w};
+            double* xd = &Xs[cur][xr * XP_ + xk];
+            double* rd = &Rs[cur][rk * RP_ + rc];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                xd[2 * i] = (double)__uint_as_float(xw[i] << 16);
+                xd[2 * i + 1] = (double)__uint_as_float(xw[i] & 0xffff0000u);
+                rd[2 * i] = (double)__uint_as_float(rw[i] << 16);
+                rd[2 * i + 1] = (double)__uint_as_float(rw[i] & 0xffff0000u);
+            }
+        }
+        if (kb + 1 < nk) {
+            xa = *reinterpret_cast<const uint4*>(xp + (size_t)(kb + 1) * MK_);
+            ra = *reinterpret_cast<const uint4*>(rp + (size_t)(kb + 1) * MK_ * K);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            double a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = Xs[cur][(wm * 64 + i * 16 + lane % 16) * XP_ + ks * 4 + lane / 16];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Rs[cur][(ks * 4 + lane / 16) * RP_ + wn * 64 + j * 16 + lane % 16];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        // the other buffer is free for the next tile once every wave has passed this barrier's predecessor;
+        // with two buffers one barrier per iteration is enough
+    }
+    // lane holds D[4 * r + lane / 16][lane % 16] of each 16 x 16 tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = row0 + wm * 64 + i * 16 + 4 * r + lane / 16;
+            if (row < M) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) U[(size_t)row * K + col0 + wn * 64 + j * 16 + lane % 16] = acc[i][j][r];
+            }
+        }
+}
+
 // One workgroup per row: absmax and codes from fp64 U.
 __global__ void quant_from_f64_kernel(const double* __restrict__ U, int K, double qmax, double norm,
                                       int8_t* __restrict__ q, float* __restrict__ scale) {
@@ -513,8 +591,14 @@ hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, i
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
                                      int act_bits, double* U, int8_t* q, float* scale) {
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
-    dim3 grid(K / DT, (M + DT - 1) / DT);
-    hipLaunchKernelGGL(dense_rotate_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U);
+    static const int use_mfma = [] { const char* e = getenv("LRQ_DENSE_MFMA"); return e ? atoi(e) : 1; }();
+    if (use_mfma && K % MT_ == 0) {
+        dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
+        hipLaunchKernelGGL(dense_rotate_mfma_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U);
+    } else {
+        dim3 grid(K / DT, (M + DT - 1) / DT);
+        hipLaunchKernelGGL(dense_rotate_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qmax, qmax, q, scale);

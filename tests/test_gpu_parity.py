@@ -67,15 +67,23 @@ def test_no_rotation_quant(lrq):
     assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
 
 
-@pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8)])
+@pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8), (200, 192, 8)])
 def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
     print(f"case dense M={M} K={K} a={a_bits}", flush=True)
     X = _acts(M, K, 3 + K)
     R = synth.make_rotation(K, (901, K, 0))
+    import torch
     q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "dense", R_bits=R)
-    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), lrq.Rotation("dense", 0, bf16_to_dev(R)), a_bits)
+    rot = lrq.Rotation("dense", 0, bf16_to_dev(R))
+    ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, a_bits), dtype=torch.uint8, device="cuda")
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, workspace=ws)
     assert np.array_equal(q.cpu().numpy(), q_ref)
     assert np.array_equal(s.cpu().numpy(), s_ref)
+    # the rotated activations themselves (fp64 scratch at the head of the workspace): same bits as the
+    # definition's ascending-k accumulation, i.e. the kernel's summation order is the oracle's
+    u = ws[:M * K * 8].view(torch.float64).view(M, K).cpu().numpy()
+    u_ref = oracle.rotate_dense(oracle.bf16_bits_to_f64(X), oracle.bf16_bits_to_f64(R))
+    assert np.array_equal(u, u_ref)
 
 
 # ------------------------------------------------------------------ TLQ calibrate + pack
