@@ -78,6 +78,13 @@ __device__ __forceinline__ unsigned decode_dword(const BRaw<BITS>& raw, const un
     }
 }
 
+// Orders a wave's own LDS writes before its own later LDS reads (the LDS pipe serves one wave's requests in
+// order; this only stops the compiler from moving accesses across it).  Enough for wave-private LDS regions.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
     unsigned u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
@@ -262,7 +269,8 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
             kblock<BITS, MT, NTW, ALOADS>(smem + ABUF, smem, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
     }
 
-    // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS, store 16 bytes per lane.
+    // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS (wave-private, so only wave-level
+    // ordering is needed after the K loop's final barrier), store 16 bytes per lane.
     // Lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of every 32x32 accumulator tile.
     float wsc[NTW], bs[NTW];
 #pragma unroll
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
                     const float y = ((float)acc[i][j][r] * sc[i * 32 + lr]) * wsc[j] + bs[j];
                     *reinterpret_cast<uint16_t*>(&slab[lr * EPI_ROW + (j * 32 + lane % 32) * 2]) = (uint16_t)f32_to_bf16_rne(y);
                 }
-            __syncthreads();
+            wave_sync();
             // 32 rows x (WN * 2) bytes: WN / 8 lanes per row, 16 bytes per lane
             constexpr int LPR = WN / 8, RPP = 64 / LPR;
 #pragma unroll
@@ -306,7 +314,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
                     }
                 }
             }
-            __syncthreads();
+            wave_sync();
         }
     } else {
         float* Yf = reinterpret_cast<float*>(Y);
@@ -320,7 +328,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
                     const float y = ((float)acc[i][j][r] * sc[i * 32 + lr]) * wsc[j] + bs[j];
                     *reinterpret_cast<float*>(&slab[lr * EPI_ROW + (lane % 32) * 4]) = y;
                 }
-                __syncthreads();
+                wave_sync();
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     const int lr = p * 8 + lane / 8, cb = (lane % 8) * 4;    // 4 floats per lane
@@ -337,7 +345,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
                         }
                     }
                 }
-                __syncthreads();
+                wave_sync();
             }
     }
 }
