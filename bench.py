@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--blocks", type=int, default=0, help="c5 only: number of transformer blocks (0 = all 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--asym", action="store_true",
+                    help="use the zero-point form of the activation quantizer (the paper's Eq. 1 as printed)")
     ap.add_argument("--probes-only", action="store_true",
                     help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
@@ -107,17 +109,18 @@ def main():
         while len(l["X"]) < copies:
             l["X"].append(l["X"][0].clone())
         l["Y"] = [torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev) for _ in range(copies)]
-        nws = lrq.workspace_bytes(s.M, s.N, s.K, l["rot"], s.a_bits)
+        nws = lrq.workspace_bytes(s.M, s.N, s.K, l["rot"], s.a_bits, asym=args.asym)
         l["ws"] = [torch.empty(nws, dtype=torch.uint8, device=dev) for _ in range(copies)]
         l["q"] = [torch.empty((s.M, s.K), dtype=torch.int8, device=dev) for _ in range(copies)]
         l["sc"] = [torch.empty(s.M, dtype=torch.float32, device=dev) for _ in range(copies)]
+        l["zr"] = [torch.empty(s.M, dtype=torch.int32, device=dev) for _ in range(copies)]
         na = lrq.ars_workspace_bytes(s.M, s.K, l["rot"], s.a_bits)
         l["aws"] = torch.empty(na, dtype=torch.uint8, device=dev) if na else None
 
     def step(i):
         c = i % copies
         for l in layers:
-            lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c])
+            lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym)
 
     for i in range(args.warmup):
         step(i)
@@ -144,9 +147,10 @@ def main():
             s = l["spec"]
             a, b, d = (torch.cuda.Event(enable_timing=True) for _ in range(3))
             a.record()
-            lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"])
+            lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"],
+                                 asym=args.asym, zero=l["zr"][c] if args.asym else None)
             b.record()
-            lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c])
+            lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c], zero=l["zr"][c] if args.asym else None)
             d.record()
             ev.append((li, a, b, d))
     torch.cuda.synchronize()
@@ -208,6 +212,7 @@ def main():
                                      4: "config4: video-DiT block linears, 35100 tokens, hidden 3072, W4A8, per-layer ARS",
                                      5: "config5: 28-block PixArt-style stack, W3A4, per-layer ARS"}[cfg],
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
+                           activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))

@@ -73,6 +73,8 @@ typedef struct {
  *   wscale     float [N]: max_c |level| / 127.
  *   gemm_codes uint8 [lrq_tlq_gemm_codes_bytes()]: the same codes re-tiled for the GEMM's operand
  *              loader (private layout, subject to change; only lrq_qlinear reads it).
+ *   colsum     int32 [N]: the sum over k of the channel's decoded int8 levels; multiplied by a token's
+ *              zero-point in the *_asym calls (Eq. 1 of the paper keeps a zero-point per quantizer).
  */
 typedef struct {
     int N, K;
@@ -88,6 +90,7 @@ typedef struct {
     int8_t* lut;
     float* wscale;
     uint8_t* gemm_codes;
+    int32_t* colsum;     /* int32 [N]: sum_k lut[n][code[n,k]], the weight of an activation zero-point */
 } lrq_tlq_weight;
 
 /* Human-readable text of a status code (static storage). */
@@ -167,6 +170,25 @@ int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* r
  */
 int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K,
               const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y);
+
+/*
+ * Zero-point variants: the activation quantizer exactly as the paper's Eq. 1 (Preliminaries), per token:
+ *   s = (x_max - x_min) / (2^b - 1), z = round(x_min / s), x_q = clamp(round(x / s) - z, 0, 2^b - 1), x_f = s (x_q + z).
+ * The quotients x / s are taken as products with one reciprocal inv = (2^b - 1) / (x_max - x_min); rounding is
+ * half-to-even; a constant token takes x_q = 0 and (s, z) = (|c|, sign c).  Outputs are in the form the integer GEMM
+ * consumes: q = x_q - 2^(b-1) (int8 [M,K]), zero = z + 2^(b-1) (int32 [M]), scale = s (/ sqrt(h) for Hadamard)
+ * (float [M]), so that x_f = scale * (q + zero).  The linear layer then is
+ *   Y[t,n] = scale_t * wscale_n * (sum_k q[t,k] lut_n[code[n,k]] + zero_t * colsum_n)  (+ bias_n).
+ * Everything else (arguments, constraints, workspace rules, errors) is as for the symmetric calls;
+ * lrq_workspace_bytes_asym gives lrq_qlinear_asym's workspace.
+ */
+int lrq_ars_rotate_quant_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                              int8_t* q, float* scale, int32_t* zero, void* ws, size_t ws_bytes);
+int lrq_qgemm_asym(void* stream, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
+                   const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y);
+size_t lrq_workspace_bytes_asym(int M, int N, int K, const lrq_rotation* rot, int act_bits);
+int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                     const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes);
 
 /*
  * Measurement probes (no counterpart in the paper; they calibrate the roofline on the device at hand).

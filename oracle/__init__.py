@@ -29,7 +29,8 @@ special cases and brute force.
 """
 from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits  # noqa: F401
 from .rotation import hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense  # noqa: F401
-from .actquant import quantize_per_token  # noqa: F401
+from .actquant import quantize_per_token, quantize_per_token_asym  # noqa: F401
 from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
                   tlq_level_values, tlq_lut, pack_codes, unpack_codes)
-from .qlinear import ars_rotate_quant, qlinear, qlinear_from_parts, reference_linear  # noqa: F401
+from .qlinear import (ars_rotate_quant, ars_rotate_quant_asym, qlinear, qlinear_from_parts,  # noqa: F401
+                      qlinear_from_parts_asym, reference_linear)

@@ -28,3 +28,34 @@ def quantize_per_token(u: np.ndarray, a_bits: int, norm: float = 1.0):
     q = np.clip(np.rint(u * inv[:, None]), -qmax, qmax).astype(np.int8)
     scale = (amax / (qmax * np.float64(norm))).astype(np.float32)
     return q, scale
+
+
+def quantize_per_token_asym(u: np.ndarray, a_bits: int, norm: float = 1.0):
+    """The paper's uniform quantizer with zero-point (Preliminaries, Eq. 1), per token:
+        s = (x_max - x_min) / (2^b - 1),  z = round(x_min / s),  x_q = clamp(round(x / s) - z, 0, 2^b - 1),
+        x_f = s (x_q + z).
+    Arithmetic (fixed so that an fp64 implementation elsewhere reproduces it bit for bit): with
+    L = 2^b - 1 and range = x_max - x_min, the quotients x / s are taken as products with one
+    reciprocal, inv = L / range (one fp64 division): z = rint(x_min * inv), x_q = clamp(rint(x * inv) - z, 0, L);
+    s = range / L.  A constant token (range = 0, value c) takes inv = 0, x_q = 0 and (s, z) = (|c|, sign c)
+    (s = 1, z = 0 for c = 0), so that s (x_q + z) = c exactly.
+    Returned in the form the integer GEMM consumes: q = x_q - 2^(b-1) (int8), zero = z + 2^(b-1) (int32), so that
+    x_f = scale * (q + zero) with scale = fp32(s / norm).  u fp64 [M, K] -> (q int8 [M, K], scale fp32 [M],
+    zero int32 [M])."""
+    assert a_bits in (4, 8)
+    u = np.asarray(u, dtype=np.float64)
+    L = float(2 ** a_bits - 1)
+    half = 2 ** (a_bits - 1)
+    umax, umin = np.max(u, axis=1), np.min(u, axis=1)
+    rng = umax - umin
+    pos = rng > 0
+    inv = np.zeros_like(rng)
+    inv[pos] = L / rng[pos]
+    s = np.where(pos, rng / L, np.where(umin != 0, np.abs(umin), 1.0))
+    z = np.where(pos, np.rint(umin * inv), np.sign(umin))
+    xq = np.clip(np.rint(u * inv[:, None]) - z[:, None], 0.0, L)
+    xq = np.where(pos[:, None], xq, 0.0)
+    q = (xq - half).astype(np.int8)
+    zero = (z + half).astype(np.int32)
+    scale = (s / np.float64(norm)).astype(np.float32)
+    return q, scale, zero

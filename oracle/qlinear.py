@@ -9,7 +9,7 @@ in for the shift datapath, and per-token / per-channel granularity as in Experim
 """
 import numpy as np
 
-from .actquant import quantize_per_token
+from .actquant import quantize_per_token, quantize_per_token_asym
 from .bf16 import bf16_bits_to_f64
 from .rotation import rotate_dense, rotate_hadamard
 from .tlq import TLQParams, tlq_calibrate, tlq_encode, tlq_lut
@@ -28,6 +28,35 @@ def ars_rotate_quant(X_bits, a_bits, rotation, had_block=None, R_bits=None):
         assert rotation == "none"
         u, norm = x, 1.0
     return quantize_per_token(u, a_bits, norm)
+
+
+def _rotate(X_bits, rotation, had_block, R_bits):
+    x = bf16_bits_to_f64(X_bits)
+    if rotation == "hadamard":
+        return rotate_hadamard(x, had_block), np.sqrt(np.float64(had_block))
+    if rotation == "dense":
+        return rotate_dense(x, bf16_bits_to_f64(R_bits)), 1.0
+    assert rotation == "none"
+    return x, 1.0
+
+
+def ars_rotate_quant_asym(X_bits, a_bits, rotation, had_block=None, R_bits=None):
+    """Rotate and quantize per token with the zero-point form of Eq. 1.
+    Returns (q int8 [M, K], scale fp32 [M], zero int32 [M]) with x_f = scale * (q + zero)."""
+    u, norm = _rotate(X_bits, rotation, had_block, R_bits)
+    return quantize_per_token_asym(u, a_bits, norm)
+
+
+def qlinear_from_parts_asym(q, scale, zero, codes, lut, wscale, bits, bias=None):
+    """Y[t, n] = scale_t wscale_n (sum_k q[t,k] lut_n[code[n,k]] + zero_t sum_k lut_n[code[n,k]]) (+ bias_n):
+    the zero-point of Eq. 1 contributes a per-token multiple of each channel's level sum."""
+    idx = codes.astype(np.int64) & (2 ** bits - 1)
+    wv = np.take_along_axis(lut.astype(np.float64), idx, axis=1)
+    acc = q.astype(np.float64) @ wv.T + zero.astype(np.float64)[:, None] * wv.sum(axis=1)[None, :]
+    y = (acc * scale.astype(np.float64)[:, None]) * wscale.astype(np.float64)[None, :]
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y
 
 
 def qlinear_from_parts(q, scale, codes, lut, wscale, bits, bias=None):

@@ -21,7 +21,8 @@ LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
 EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes",
            "lrq_tlq_workspace_bytes", "lrq_tlq_quantize_pack", "lrq_ars_workspace_bytes",
            "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm", "lrq_probe_mfma_i8",
-           "lrq_probe_copy")
+           "lrq_probe_copy", "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
+           "lrq_qlinear_asym")
 
 
 class LrqError(RuntimeError):
@@ -39,7 +40,7 @@ class _TlqWeight(ctypes.Structure):
                 ("codes", ctypes.c_void_p), ("s_pos", ctypes.c_void_p), ("s_neg", ctypes.c_void_p),
                 ("z_pos", ctypes.c_void_p), ("z_neg", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("beta", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("wscale", ctypes.c_void_p),
-                ("gemm_codes", ctypes.c_void_p)]
+                ("gemm_codes", ctypes.c_void_p), ("colsum", ctypes.c_void_p)]
 
 
 _lib = None
@@ -73,6 +74,14 @@ def lib() -> ctypes.CDLL:
                               vp, vp, sz]
     L.lrq_qgemm.restype = ci
     L.lrq_qgemm.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
+    L.lrq_ars_rotate_quant_asym.restype = ci
+    L.lrq_ars_rotate_quant_asym.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, vp, vp, vp, vp, sz]
+    L.lrq_qgemm_asym.restype = ci
+    L.lrq_qgemm_asym.argtypes = [vp, vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
+    L.lrq_workspace_bytes_asym.restype = sz
+    L.lrq_workspace_bytes_asym.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
+    L.lrq_qlinear_asym.restype = ci
+    L.lrq_qlinear_asym.argtypes = L.lrq_qlinear.argtypes
     L.lrq_probe_mfma_i8.restype = ci
     L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     L.lrq_probe_copy.restype = ci
@@ -132,11 +141,12 @@ class TLQWeight:
         self.lut = torch.empty((N, 16), dtype=torch.int8, **kw)
         self.wscale = torch.empty(N, dtype=torch.float32, **kw)
         self.gemm_codes = torch.zeros(ng, dtype=torch.uint8, **kw)
+        self.colsum = torch.empty(N, dtype=torch.int32, **kw)
 
     def c_struct(self) -> _TlqWeight:
         return _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
                           _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
-                          _ptr(self.wscale), _ptr(self.gemm_codes))
+                          _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum))
 
 
 def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None, out: Optional[TLQWeight] = None):
@@ -161,13 +171,16 @@ def ars_workspace_bytes(M: int, K: int, rot: Rotation, act_bits: int) -> int:
     return lib().lrq_ars_workspace_bytes(M, K, ctypes.byref(r), act_bits)
 
 
-def workspace_bytes(M: int, N: int, K: int, rot: Rotation, act_bits: int) -> int:
+def workspace_bytes(M: int, N: int, K: int, rot: Rotation, act_bits: int, asym: bool = False) -> int:
     r = rot.c_struct()
-    return lib().lrq_workspace_bytes(M, N, K, ctypes.byref(r), act_bits)
+    fn = lib().lrq_workspace_bytes_asym if asym else lib().lrq_workspace_bytes
+    return fn(M, N, K, ctypes.byref(r), act_bits)
 
 
-def ars_rotate_quant(X, rot: Rotation, act_bits: int, q=None, scale=None, workspace=None) -> Tuple[object, object]:
-    """lrq_ars_rotate_quant: X bf16 [M, K] -> (q int8 [M, K], scale fp32 [M])."""
+def ars_rotate_quant(X, rot: Rotation, act_bits: int, q=None, scale=None, workspace=None, asym: bool = False,
+                     zero=None):
+    """lrq_ars_rotate_quant: X bf16 [M, K] -> (q int8 [M, K], scale fp32 [M]);
+    asym=True: lrq_ars_rotate_quant_asym -> (q, scale, zero int32 [M])."""
     import torch
     assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
     M, K = X.shape
@@ -179,8 +192,16 @@ def ars_rotate_quant(X, rot: Rotation, act_bits: int, q=None, scale=None, worksp
     need = lib().lrq_ars_workspace_bytes(M, K, ctypes.byref(r), act_bits)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    nws = 0 if workspace is None else workspace.numel()
+    if asym:
+        if zero is None:
+            zero = torch.empty(M, dtype=torch.int32, device=X.device)
+        st = lib().lrq_ars_rotate_quant_asym(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, _ptr(q), _ptr(scale),
+                                             _ptr(zero), _ptr(workspace), nws)
+        _check(st, "lrq_ars_rotate_quant_asym")
+        return q, scale, zero
     st = lib().lrq_ars_rotate_quant(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, _ptr(q), _ptr(scale),
-                                    _ptr(workspace), 0 if workspace is None else workspace.numel())
+                                    _ptr(workspace), nws)
     _check(st, "lrq_ars_rotate_quant")
     return q, scale
 
@@ -190,8 +211,9 @@ def _out_code(dtype) -> int:
     return {torch.bfloat16: LRQ_OUT_BF16, torch.float32: LRQ_OUT_FP32}[dtype]
 
 
-def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=None, out=None, workspace=None):
-    """lrq_qlinear: fused rotate, quantize, decode, GEMM and rescale.  Returns Y [M, N]."""
+def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=None, out=None, workspace=None,
+            asym: bool = False):
+    """lrq_qlinear (asym=True: lrq_qlinear_asym): fused rotate, quantize, decode, GEMM and rescale.  Returns Y [M, N]."""
     import torch
     assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
     M, K = X.shape
@@ -199,17 +221,18 @@ def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=
     if out is None:
         out = torch.empty((M, w.N), dtype=out_dtype, device=X.device)
     r, cs = rot.c_struct(), w.c_struct()
+    size_fn = lib().lrq_workspace_bytes_asym if asym else lib().lrq_workspace_bytes
     if workspace is None:
-        workspace = torch.empty(lib().lrq_workspace_bytes(M, w.N, K, ctypes.byref(r), act_bits), dtype=torch.uint8,
-                                device=X.device)
-    st = lib().lrq_qlinear(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
-                           _out_code(out_dtype), _ptr(out), _ptr(workspace), workspace.numel())
-    _check(st, "lrq_qlinear")
+        workspace = torch.empty(size_fn(M, w.N, K, ctypes.byref(r), act_bits), dtype=torch.uint8, device=X.device)
+    fn = lib().lrq_qlinear_asym if asym else lib().lrq_qlinear
+    st = fn(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
+            _out_code(out_dtype), _ptr(out), _ptr(workspace), workspace.numel())
+    _check(st, "lrq_qlinear_asym" if asym else "lrq_qlinear")
     return out
 
 
-def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
-    """lrq_qgemm: the decode + GEMM + rescale stage on existing activation codes."""
+def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None, zero=None):
+    """lrq_qgemm (zero given: lrq_qgemm_asym): the decode + GEMM + rescale stage on existing activation codes."""
     import torch
     assert q.is_cuda and q.dtype == torch.int8 and q.is_contiguous()
     M, K = q.shape
@@ -217,6 +240,11 @@ def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
     if out is None:
         out = torch.empty((M, w.N), dtype=out_dtype, device=q.device)
     cs = w.c_struct()
+    if zero is not None:
+        st = lib().lrq_qgemm_asym(_stream(), _ptr(q), _ptr(scale), _ptr(zero), M, K, ctypes.byref(cs), _ptr(bias),
+                                  _out_code(out_dtype), _ptr(out))
+        _check(st, "lrq_qgemm_asym")
+        return out
     st = lib().lrq_qgemm(_stream(), _ptr(q), _ptr(scale), M, K, ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
                          _ptr(out))
     _check(st, "lrq_qgemm")

@@ -38,7 +38,7 @@ int check_weight(const lrq_tlq_weight* w) {
     if (!w || w->N <= 0 || w->K <= 0) return LRQ_EINVAL;
     if (w->bits != 3 && w->bits != 4) return LRQ_EUNSUPPORTED;
     if (!w->codes || !w->s_pos || !w->s_neg || !w->z_pos || !w->z_neg || !w->alpha || !w->beta || !w->lut ||
-        !w->wscale || !w->gemm_codes)
+        !w->wscale || !w->gemm_codes || !w->colsum)
         return LRQ_EINVAL;
     if (!aligned16(w->codes) || !aligned16(w->lut) || !aligned16(w->gemm_codes)) return LRQ_EINVAL;
     return LRQ_OK;
@@ -54,19 +54,19 @@ ArsWs ars_layout(int M, int K, const lrq_rotation* rot) {
 }
 
 int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
-                     int8_t* q, float* scale, void* ws) {
+                     int8_t* q, float* scale, int32_t* zero, void* ws) {
     hipError_t e = hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(X);
     switch (rot->kind) {
         case LRQ_ROT_NONE:
-            e = lrq::launch_plain_quant(st, x, M, K, act_bits, q, scale);
+            e = lrq::launch_plain_quant(st, x, M, K, act_bits, q, scale, zero);
             break;
         case LRQ_ROT_HADAMARD:
-            e = lrq::launch_hadamard_quant(st, x, M, K, rot->had_block, act_bits, q, scale);
+            e = lrq::launch_hadamard_quant(st, x, M, K, rot->had_block, act_bits, q, scale, zero);
             break;
         default:
             e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
-                                               static_cast<double*>(ws), q, scale);
+                                               static_cast<double*>(ws), q, scale, zero);
             break;
     }
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
@@ -129,14 +129,24 @@ size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bi
     return ars_layout(M, K, rot).total;
 }
 
-int lrq_ars_rotate_quant(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
-                         int8_t* q, float* scale, void* ws, size_t ws_bytes) {
+static int ars_impl(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits, int8_t* q,
+                    float* scale, int32_t* zero, bool asym, void* ws, size_t ws_bytes) {
     int st = check_act(X, M, K, rot, act_bits);
     if (st != LRQ_OK) return st;
-    if (!q || !scale || !aligned16(q)) return LRQ_EINVAL;
+    if (!q || !scale || !aligned16(q) || (asym && !zero)) return LRQ_EINVAL;
     const size_t need = ars_layout(M, K, rot).total;
     if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) return LRQ_EWORKSPACE;
-    return run_rotate_quant(static_cast<hipStream_t>(stream), X, M, K, rot, act_bits, q, scale, ws);
+    return run_rotate_quant(static_cast<hipStream_t>(stream), X, M, K, rot, act_bits, q, scale, asym ? zero : nullptr, ws);
+}
+
+int lrq_ars_rotate_quant(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                         int8_t* q, float* scale, void* ws, size_t ws_bytes) {
+    return ars_impl(stream, X, M, K, rot, act_bits, q, scale, nullptr, false, ws, ws_bytes);
+}
+
+int lrq_ars_rotate_quant_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                              int8_t* q, float* scale, int32_t* zero, void* ws, size_t ws_bytes) {
+    return ars_impl(stream, X, M, K, rot, act_bits, q, scale, zero, true, ws, ws_bytes);
 }
 
 size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act_bits) {
@@ -145,20 +155,37 @@ size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act
     return round256((size_t)M * K) + round256((size_t)M * sizeof(float)) + ars_layout(M, K, rot).total;
 }
 
-int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight* w,
-              const float* bias, int out_dtype, void* Y) {
-    if (!q || !scale || !Y || M <= 0 || K <= 0 || !aligned16(q) || !aligned16(Y)) return LRQ_EINVAL;
+size_t lrq_workspace_bytes_asym(int M, int N, int K, const lrq_rotation* rot, int act_bits) {
+    if (M <= 0 || K <= 0) return 0;
+    return lrq_workspace_bytes(M, N, K, rot, act_bits) + round256((size_t)M * sizeof(int32_t));
+}
+
+static int qgemm_impl(void* stream, const int8_t* q, const float* scale, const int32_t* zero, bool asym, int M, int K,
+                      const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y) {
+    if (!q || !scale || !Y || M <= 0 || K <= 0 || !aligned16(q) || !aligned16(Y) || (asym && !zero)) return LRQ_EINVAL;
     int st = check_weight(w);
     if (st != LRQ_OK) return st;
     if (w->K != K) return LRQ_EINVAL;
     if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
     if (K % lrq::kGemmBlockK != 0) return LRQ_EUNSUPPORTED;
-    hipError_t e = lrq::launch_qgemm(static_cast<hipStream_t>(stream), q, scale, M, K, *w, bias, out_dtype, Y);
+    hipError_t e = lrq::launch_qgemm(static_cast<hipStream_t>(stream), q, scale, asym ? zero : nullptr, M, K, *w, bias,
+                                     out_dtype, Y);
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 
-int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
-                const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight* w,
+              const float* bias, int out_dtype, void* Y) {
+    return qgemm_impl(stream, q, scale, nullptr, false, M, K, w, bias, out_dtype, Y);
+}
+
+int lrq_qgemm_asym(void* stream, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
+                   const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y) {
+    return qgemm_impl(stream, q, scale, zero, true, M, K, w, bias, out_dtype, Y);
+}
+
+static int qlinear_impl(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                        const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes,
+                        bool asym) {
     int st = check_act(X, M, K, rot, act_bits);
     if (st != LRQ_OK) return st;
     st = check_weight(w);
@@ -166,17 +193,29 @@ int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* r
     if (!Y || !aligned16(Y) || w->K != K) return LRQ_EINVAL;
     if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
     if (K % lrq::kGemmBlockK != 0) return LRQ_EUNSUPPORTED;
-    const size_t need = lrq_workspace_bytes(M, w->N, K, rot, act_bits);
+    const size_t need = asym ? lrq_workspace_bytes_asym(M, w->N, K, rot, act_bits) : lrq_workspace_bytes(M, w->N, K, rot, act_bits);
     if (!ws || ws_bytes < need || !aligned16(ws)) return LRQ_EWORKSPACE;
+    // workspace: q | scale | rotation scratch | zero (zero-point form only)
     char* base = static_cast<char*>(ws);
     int8_t* q = reinterpret_cast<int8_t*>(base);
     float* scale = reinterpret_cast<float*>(base + round256((size_t)M * K));
     void* rot_ws = base + round256((size_t)M * K) + round256((size_t)M * sizeof(float));
+    int32_t* zero = asym ? reinterpret_cast<int32_t*>(static_cast<char*>(rot_ws) + ars_layout(M, K, rot).total) : nullptr;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = run_rotate_quant(s, X, M, K, rot, act_bits, q, scale, rot_ws);
+    st = run_rotate_quant(s, X, M, K, rot, act_bits, q, scale, zero, rot_ws);
     if (st != LRQ_OK) return st;
-    hipError_t e = lrq::launch_qgemm(s, q, scale, M, K, *w, bias, out_dtype, Y);
+    hipError_t e = lrq::launch_qgemm(s, q, scale, zero, M, K, *w, bias, out_dtype, Y);
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, false);
+}
+
+int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                     const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, true);
 }
 
 int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out, double* ops_per_launch) {

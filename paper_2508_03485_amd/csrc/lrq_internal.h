@@ -10,21 +10,31 @@ namespace lrq {
 
 // ---- launchers implemented in the .hip files; each returns hipGetLastError() after the launch ----
 
-// u = x.(I (x) H_h) in fp64, per-token absmax, round to codes.  K % 8 == 0, h | K, h power of two.
+// Per-token quantizer description handed to the kernels by value (host-filled).
+struct QuantSpec {
+    int asym;               // 0: symmetric absmax form, 1: zero-point form of Eq. 1
+    double qmax, norm;      // symmetric: 2^(a-1) - 1 and qmax * sqrt(h)
+    double L, half, sqrt_h; // zero-point form: 2^a - 1, 2^(a-1), sqrt(h)
+    int32_t* zero;          // zero-point form: output [M]
+};
+
+// u = x.(I (x) H_h) in fp64, per-token statistics, round to codes.  K % 8 == 0, h | K, h power of two.
+// zero == nullptr selects the symmetric quantizer, otherwise the zero-point form (zero receives z + 2^(a-1)).
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale);
+                                 int8_t* q, float* scale, int32_t* zero);
 // u = x (no rotation), same quantizer.
 hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, int act_bits,
-                              int8_t* q, float* scale);
+                              int8_t* q, float* scale, int32_t* zero);
 // u = x.R in fp64 (k ascending), written to U [M,K] doubles, then quantized from U.
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
-                                     int act_bits, double* U, int8_t* q, float* scale);
+                                     int act_bits, double* U, int8_t* q, float* scale, int32_t* zero);
 
 hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
                                     const lrq_tlq_weight& out);
 
-hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
+// zero == nullptr: symmetric codes; otherwise the epilogue adds zero_t * colsum_n to the integer sum.
+hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y);
 
 hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int pattern, int* out);

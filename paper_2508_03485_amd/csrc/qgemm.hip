@@ -157,7 +157,8 @@ template <int BITS, int BM, int NTW>
 __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
     const uint8_t* __restrict__ gcodes, const int8_t* __restrict__ lut, const float* __restrict__ wscale,
-    const float* __restrict__ bias, int out_fp32, void* __restrict__ Y, int tiles_m, int tiles_n) {
+    const float* __restrict__ bias, int out_fp32, void* __restrict__ Y, int tiles_m, int tiles_n,
+    const int32_t* __restrict__ zero, const int32_t* __restrict__ colsum) {
     constexpr int MT = BM / 32;
     constexpr int WN = 32 * NTW, BN = WAVES * WN;
     constexpr int ABUF = MT * 4 * PLANE;
@@ -165,6 +166,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     constexpr int LDS_BYTES = (2 * ABUF > WAVES * EPI_WAVE) ? 2 * ABUF : WAVES * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
     __shared__ float sc[BM];
+    __shared__ int zr[BM];          // per-token zero-points (zero-point form only)
 
     // XCD-aware tile order.  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2), so
     // XCD x is handed a contiguous range of a linear tile order; that order walks 8-row-tile groups n-fastest
@@ -221,6 +223,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     if (t < BM) {
         const int r = m0 + t;
         sc[t] = r < M ? scale[r] : 0.0f;
+        zr[t] = (zero && r < M) ? zero[r] : 0;
     }
 
     v16i acc[MT][NTW];
@@ -273,13 +276,19 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     // ordering is needed after the K loop's final barrier), store 16 bytes per lane.
     // Lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of every 32x32 accumulator tile.
     float wsc[NTW], bs[NTW];
+    int csum[NTW];
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
         int n = n0 + wv * WN + j * 32 + lane % 32;
         if (n >= N) n = N - 1;
         wsc[j] = wscale[n];
         bs[j] = bias ? bias[n] : 0.0f;
+        csum[j] = zero ? colsum[n] : 0;
     }
+    // integer sum of one output: accumulator plus zero_t * colsum_n (64-bit: the product can exceed 32 bits)
+    auto total = [&](int a, int lr, int j) -> float {
+        return zero ? (float)((long long)a + (long long)zr[lr] * (long long)csum[j]) : (float)a;
+    };
     unsigned char* slab = smem + wv * EPI_WAVE;
     const int ncol0 = n0 + wv * WN;                 // first column of this wave
     const bool vec = (N % (out_fp32 ? 4 : 8)) == 0; // rows of Y are 16-byte aligned
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int lr = 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-                    const float y = ((float)acc[i][j][r] * sc[i * 32 + lr]) * wsc[j] + bs[j];
+                    const float y = (total(acc[i][j][r], i * 32 + lr, j) * sc[i * 32 + lr]) * wsc[j] + bs[j];
                     *reinterpret_cast<uint16_t*>(&slab[lr * EPI_ROW + (j * 32 + lane % 32) * 2]) = (uint16_t)f32_to_bf16_rne(y);
                 }
             wave_sync();
@@ -325,7 +334,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int lr = 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-                    const float y = ((float)acc[i][j][r] * sc[i * 32 + lr]) * wsc[j] + bs[j];
+                    const float y = (total(acc[i][j][r], i * 32 + lr, j) * sc[i * 32 + lr]) * wsc[j] + bs[j];
                     *reinterpret_cast<float*>(&slab[lr * EPI_ROW + (lane % 32) * 4]) = y;
                 }
                 wave_sync();
@@ -351,18 +360,18 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 }
 
 template <int BITS, int BM, int NTW>
-hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight& w,
-                  const float* bias, int fp32, void* Y) {
+hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
+                  const lrq_tlq_weight& w, const float* bias, int fp32, void* Y) {
     constexpr int BN = WAVES * 32 * NTW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + BN - 1) / BN;
     hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
-                       w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n);
+                       w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int M, int K,
+hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y) {
     const int fp32 = out_dtype == LRQ_OUT_FP32;
     // Tile shape.  128 x 256 (two workgroups per CU) is the fastest on long K loops; 128 x 128 (three per CU)
@@ -372,15 +381,15 @@ hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, int
     const bool narrow = K <= 2048 || (w.N % 256 != 0 && w.N <= 2048);
     const int bm = env ? env : (narrow ? 1281 : 128);
     if (bm == 256) {
-        if (w.bits == 4) return launch<4, 256, 1>(st, q, scale, M, K, w, bias, fp32, Y);
-        return launch<3, 256, 1>(st, q, scale, M, K, w, bias, fp32, Y);
+        if (w.bits == 4) return launch<4, 256, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+        return launch<3, 256, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
     }
     if (bm == 1281) {
-        if (w.bits == 4) return launch<4, 128, 1>(st, q, scale, M, K, w, bias, fp32, Y);
-        return launch<3, 128, 1>(st, q, scale, M, K, w, bias, fp32, Y);
+        if (w.bits == 4) return launch<4, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+        return launch<3, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
     }
-    if (w.bits == 4) return launch<4, 128, 2>(st, q, scale, M, K, w, bias, fp32, Y);
-    return launch<3, 128, 2>(st, q, scale, M, K, w, bias, fp32, Y);
+    if (w.bits == 4) return launch<4, 128, 2>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+    return launch<3, 128, 2>(st, q, scale, zero, M, K, w, bias, fp32, Y);
 }
 
 }  // namespace lrq

@@ -61,26 +61,94 @@ __device__ __forceinline__ double block_max(double m, double* red) {
     return r;
 }
 
-__device__ __forceinline__ int quant1(double u, double inv, double qmax) {
-    double r = rint(u * inv);
-    r = fmin(fmax(r, -qmax), qmax);
-    return (int)r;
+// ---- per-token quantizer ---------------------------------------------------------------------------------
+// Symmetric form: amax = max |u|, inv = qmax / amax, code = rint(u * inv), scale = amax / (qmax sqrt(h)).
+// Zero-point form (Eq. 1 as printed): range = max u - min u, L = 2^b - 1, inv = L / range, z = rint(min u * inv),
+// x_q = clamp(rint(u * inv) - z, 0, L), s = range / L; stored as q = x_q - 2^(b-1) and zero = z + 2^(b-1), so
+// that x_f = scale (q + zero), scale = s / sqrt(h).  A constant token takes x_q = 0 and (s, z) = (|c|, sign c).
+struct RowQ {
+    double inv;     // multiplier of u
+    double zsub;    // zero-point form: what is subtracted from rint(u * inv) before the clamp to [-half, half-1]
+    float scale;
+    int izero;
+};
+
+__device__ __forceinline__ RowQ rowq_sym(double amax, const QuantSpec& qs) {
+    RowQ r;
+    r.inv = amax > 0.0 ? qs.qmax / amax : 0.0;
+    r.zsub = 0.0;
+    r.scale = (float)(amax / qs.norm);
+    r.izero = 0;
+    return r;
 }
 
-__device__ __forceinline__ void store8_codes(int8_t* __restrict__ dst, const double v[8], double inv, double qmax) {
-    unsigned lo = 0, hi = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        lo |= (unsigned)(quant1(v[i], inv, qmax) & 0xff) << (8 * i);
-        hi |= (unsigned)(quant1(v[4 + i], inv, qmax) & 0xff) << (8 * i);
+__device__ __forceinline__ RowQ rowq_asym(double vmax, double vmin, const QuantSpec& qs) {
+    RowQ r;
+    const double rng = vmax - vmin;
+    double sc, z;
+    if (rng > 0.0) {
+        r.inv = qs.L / rng;
+        sc = rng / qs.L;
+        z = rint(vmin * r.inv);
+        r.zsub = z + qs.half;
+    } else {
+        r.inv = 0.0;
+        sc = vmin != 0.0 ? fabs(vmin) : 1.0;
+        z = vmin > 0.0 ? 1.0 : (vmin < 0.0 ? -1.0 : 0.0);
+        r.zsub = qs.half;                       // every code is x_q = 0, i.e. q = -2^(b-1)
     }
-    *reinterpret_cast<uint2*>(dst) = make_uint2(lo, hi);
+    r.scale = (float)(sc / qs.sqrt_h);
+    r.izero = (int)(z + qs.half);
+    return r;
 }
+
+constexpr double kMagic = 6755399441055744.0;   // 1.5 * 2^52: adding it rounds to an integer, ties to even
+
+// One code (low byte of the result).  The product, the magic sum and the later steps round separately
+// (this file is compiled with floating-point contraction off).
+template <bool ASYM>
+__device__ __forceinline__ unsigned code1(double u, const RowQ& p, double half) {
+    if constexpr (!ASYM) {
+        return (unsigned)__double2loint(u * p.inv + kMagic);
+    } else {
+        const double r = (u * p.inv + kMagic) - kMagic;
+        const double t = fmin(fmax(r - p.zsub, -half), half - 1.0);
+        return (unsigned)__double2loint(t + kMagic);
+    }
+}
+
+// four codes -> one dword of int8
+template <bool ASYM>
+__device__ __forceinline__ unsigned pack4(const double* v, const RowQ& p, double half) {
+    unsigned b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = code1<ASYM>(v[i], p, half);
+    const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+    const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+    return (hi << 16) | lo;
+}
+
+template <bool ASYM>
+__device__ __forceinline__ void store8_codes(int8_t* __restrict__ dst, const double v[8], const RowQ& p, double half) {
+    *reinterpret_cast<uint2*>(dst) = make_uint2(pack4<ASYM>(v, p, half), pack4<ASYM>(v + 4, p, half));
+}
+
+// order-preserving map of a double onto unsigned 64-bit keys (for LDS atomic max on signed values)
+__device__ __forceinline__ unsigned long long okey(double x) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double okey_inv(unsigned long long k) {
+    const unsigned long long b = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
+    return __longlong_as_double((long long)b);
+}
+
+__device__ __forceinline__ double block_min(double m, double* red) { return -block_max(-m, red); }
 
 // One workgroup per token row.  The row lives in LDS as doubles; the first three butterfly stages
 // run in registers on each 8-element chunk, the remaining ones as radix-8 passes over LDS.
-__global__ void hadamard_quant_generic_kernel(const uint16_t* __restrict__ X, int K, int log2h, double qmax,
-                                              double norm, int8_t* __restrict__ q, float* __restrict__ scale) {
+__global__ void hadamard_quant_generic_kernel(const uint16_t* __restrict__ X, int K, int log2h, QuantSpec qs,
+                                              int8_t* __restrict__ q, float* __restrict__ scale) {
     extern __shared__ double lds[];
     double* row = lds;
     double* red = lds + K;
@@ -112,17 +180,29 @@ __global__ void hadamard_quant_generic_kernel(const uint16_t* __restrict__ X, in
         }
         __syncthreads();
     }
-    double m = 0.0;
-    for (int i = t; i < K; i += nt) m = fmax(m, fabs(row[i]));
-    const double amax = block_max(m, red);
-    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    RowQ p;
+    if (!qs.asym) {
+        double m = 0.0;
+        for (int i = t; i < K; i += nt) m = fmax(m, fabs(row[i]));
+        p = rowq_sym(block_max(m, red), qs);
+    } else {
+        double hi = -INFINITY, lo = INFINITY;
+        for (int i = t; i < K; i += nt) { hi = fmax(hi, row[i]); lo = fmin(lo, row[i]); }
+        hi = block_max(hi, red);
+        lo = block_min(lo, red);
+        p = rowq_asym(hi, lo, qs);
+    }
     for (int c = t; c < nchunks; c += nt) {
         double v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = row[c * 8 + i];
-        store8_codes(q + base + (size_t)c * 8, v, inv, qmax);
+        if (qs.asym) store8_codes<true>(q + base + (size_t)c * 8, v, p, qs.half);
+        else store8_codes<false>(q + base + (size_t)c * 8, v, p, qs.half);
     }
-    if (t == 0) scale[blockIdx.x] = (float)(amax / norm);
+    if (t == 0) {
+        scale[blockIdx.x] = p.scale;
+        if (qs.asym) qs.zero[blockIdx.x] = p.izero;
+    }
 }
 
 // ---------------------------------------------------------------- register-resident Hadamard, h <= 128
@@ -140,29 +220,17 @@ __device__ __forceinline__ double quad_swap(double v) {
     return __hiloint2double(hi, lo);
 }
 
-// low bytes of four rounded values -> one dword of int8 codes.  The product and the sum must round
-// separately (this file is compiled with floating-point contraction off).
-__device__ __forceinline__ unsigned pack4(const double* v, double inv) {
-    constexpr double kMagic = 6755399441055744.0;   // 1.5 * 2^52: adding it rounds to an integer, ties to even
-    unsigned b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) b[i] = (unsigned)__double2loint(v[i] * inv + kMagic);
-    const unsigned lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-    const unsigned hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
-    return (hi << 16) | lo;
-}
-
-template <int LOG2H>
+template <int LOG2H, bool ASYM>
 __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t* __restrict__ X, int M, int K,
-                                                                  int rows_per_wg, double qmax, double norm,
+                                                                  int rows_per_wg, QuantSpec qs,
                                                                   int8_t* __restrict__ q, float* __restrict__ scale) {
-    __shared__ unsigned long long amax_bits[32];
+    __shared__ unsigned long long amax_bits[2][32];          // [0]: max |u| (or key of max u), [1]: key of max -u
     const int lpr = K / E32;                       // lanes per row
     const int t = threadIdx.x;
     const int rw = t / lpr, slot = t % lpr;
     const int row = blockIdx.x * rows_per_wg + rw;
     const bool live = rw < rows_per_wg && row < M;
-    if (t < 32) amax_bits[t] = 0ull;
+    if (t < 64) amax_bits[t / 32][t % 32] = 0ull;
 
     double v[E32];
     {
@@ -183,24 +251,42 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 #pragma unroll
         for (int i = 0; i < E32; ++i) v[i] = fma(v[i], sg, quad_swap<0x4E>(v[i]));
     }
-    double m = 0.0;
+    double m = ASYM ? -INFINITY : 0.0, m2 = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < E32; ++i) m = fmax(m, fabs(v[i]));
+    for (int i = 0; i < E32; ++i) {
+        if constexpr (ASYM) { m = fmax(m, v[i]); m2 = fmax(m2, -v[i]); }
+        else m = fmax(m, fabs(v[i]));
+    }
     m = fmax(m, quad_swap<0xB1>(m));
     m = fmax(m, quad_swap<0x4E>(m));
+    if constexpr (ASYM) {
+        m2 = fmax(m2, quad_swap<0xB1>(m2));
+        m2 = fmax(m2, quad_swap<0x4E>(m2));
+    }
     __syncthreads();
-    if (live && (t & 3) == 0) atomicMax(&amax_bits[rw], (unsigned long long)__double_as_longlong(m));
+    if (live && (t & 3) == 0) {
+        if constexpr (ASYM) {
+            atomicMax(&amax_bits[0][rw], okey(m));
+            atomicMax(&amax_bits[1][rw], okey(m2));
+        } else {
+            atomicMax(&amax_bits[0][rw], (unsigned long long)__double_as_longlong(m));
+        }
+    }
     __syncthreads();
     if (!live) return;
-    const double amax = __longlong_as_double((long long)amax_bits[rw]);
-    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    RowQ p;
+    if constexpr (ASYM) p = rowq_asym(okey_inv(amax_bits[0][rw]), -okey_inv(amax_bits[1][rw]), qs);
+    else p = rowq_sym(__longlong_as_double((long long)amax_bits[0][rw]), qs);
     unsigned out[8];
 #pragma unroll
-    for (int g = 0; g < 8; ++g) out[g] = pack4(v + 4 * g, inv);
+    for (int g = 0; g < 8; ++g) out[g] = pack4<ASYM>(v + 4 * g, p, qs.half);
     uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
     dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
     dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
-    if (slot == 0) scale[row] = (float)(amax / norm);
+    if (slot == 0) {
+        scale[row] = p.scale;
+        if constexpr (ASYM) qs.zero[row] = p.izero;
+    }
 }
 
 // ---------------------------------------------------------------- two-pass Hadamard, 256 <= h <= 4096
@@ -216,16 +302,16 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 // bf16 data while it transforms the current one.
 __device__ __forceinline__ int lds_row(int slot) { return 18 * slot + 4 * (slot >> 5); }
 
-template <int LOG2H, bool PERSIST>
+template <int LOG2H, bool PERSIST, bool ASYM>
 __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
-                                                                   int rows_per_wg, double qmax, double norm,
+                                                                   int rows_per_wg, QuantSpec qs,
                                                                    int8_t* __restrict__ q, float* __restrict__ scale) {
     constexpr int G = 1 << (LOG2H - 5);            // pass-1 lanes per block
     constexpr int NG = G < 32 ? G : 32;            // values per element offset held by a pass-2 lane
     constexpr int EPL = 32 / NG;                   // element offsets per pass-2 lane (4, 2, 1)
     constexpr int Q = G / NG;                      // lanes that share an element offset (1, 2, 4)
     extern __shared__ __attribute__((aligned(16))) double lds[];
-    __shared__ unsigned long long amax_bits[2][32];
+    __shared__ unsigned long long amax_bits[2][2][32];       // [parity][max |u| or key of max u / key of max -u][row]
     const int lpr = K / E32;
     const int rs = lds_row(lpr) + 8;               // doubles per row buffer
     const int t = threadIdx.x;
@@ -237,7 +323,7 @@ __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_
     const int e0 = (j / Q) * EPL, gq = j % Q;
     const int my_round = e0 >> 4;
     const int ngroups = (M + rows_per_wg - 1) / rows_per_wg;
-    if (t < 64) amax_bits[t / 32][t % 32] = 0ull;
+    if (t < 128) amax_bits[t / 64][(t / 32) % 2][t % 32] = 0ull;
 
     uint4 raw[4];
     {
@@ -270,7 +356,7 @@ __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_
 #pragma unroll
                 for (int i = 0; i < 8; ++i) dst[i] = make_double2(v[16 * round + 2 * i], v[16 * round + 2 * i + 1]);
             }
-            if (PERSIST && round == 0 && t < 32) amax_bits[par ^ 1][t] = 0ull;   // the other parity's slots, for the next group
+            if (PERSIST && round == 0 && t < 64) amax_bits[par ^ 1][t / 32][t % 32] = 0ull;   // the other parity's slots, for the next group
             __syncthreads();
             if (my_round == round) {
 #pragma unroll
@@ -306,31 +392,52 @@ __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_
 #pragma unroll
             for (int i = 0; i < E32; ++i) w[i] = fma(w[i], sg, quad_swap<0x4E>(w[i]));
         }
-        double m = 0.0;
+        double m = ASYM ? -INFINITY : 0.0, m2 = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < E32; ++i) m = fmax(m, fabs(w[i]));
+        for (int i = 0; i < E32; ++i) {
+            if constexpr (ASYM) { m = fmax(m, w[i]); m2 = fmax(m2, -w[i]); }
+            else m = fmax(m, fabs(w[i]));
+        }
         m = fmax(m, quad_swap<0xB1>(m));
         m = fmax(m, quad_swap<0x4E>(m));
-        if (live && (t & 3) == 0) atomicMax(&amax_bits[par][rw], (unsigned long long)__double_as_longlong(m));
+        if constexpr (ASYM) {
+            m2 = fmax(m2, quad_swap<0xB1>(m2));
+            m2 = fmax(m2, quad_swap<0x4E>(m2));
+        }
+        if (live && (t & 3) == 0) {
+            if constexpr (ASYM) {
+                atomicMax(&amax_bits[par][0][rw], okey(m));
+                atomicMax(&amax_bits[par][1][rw], okey(m2));
+            } else {
+                atomicMax(&amax_bits[par][0][rw], (unsigned long long)__double_as_longlong(m));
+            }
+        }
         __syncthreads();          // every pass-2 read is done: the buffer can be reused for the codes
 
-        const double amax = __longlong_as_double((long long)amax_bits[par][inwg ? rw : 0]);
-        const double inv = amax > 0.0 ? qmax / amax : 0.0;
+        RowQ p;
+        {
+            const int rr = inwg ? rw : 0;
+            if constexpr (ASYM) {
+                // rows beyond M leave the keys at 0; feed finite values then (their codes are never stored)
+                const unsigned long long k0 = amax_bits[par][0][rr], k1 = amax_bits[par][1][rr];
+                p = rowq_asym(k0 ? okey_inv(k0) : 0.0, k1 ? -okey_inv(k1) : 0.0, qs);
+            } else {
+                p = rowq_sym(__longlong_as_double((long long)amax_bits[par][0][rr]), qs);
+            }
+        }
         // byte buffer: 32 bytes per pass-1 lane, 16 bytes of padding per 32 lanes
         unsigned char* cbuf = reinterpret_cast<unsigned char*>(rowbuf) + (size_t)b * (G * 32 + (G >> 5) * 16);
         if (inwg) {
-            constexpr double kMagic = 6755399441055744.0;
 #pragma unroll
             for (int r = 0; r < NG; ++r) {
-                unsigned char* p = cbuf + (r + 32 * gq) * 32 + gq * 16 + e0;
+                unsigned char* dstb = cbuf + (r + 32 * gq) * 32 + gq * 16 + e0;
                 if constexpr (EPL == 4) {
-                    *reinterpret_cast<unsigned*>(p) = pack4(w + 4 * r, inv);
+                    *reinterpret_cast<unsigned*>(dstb) = pack4<ASYM>(w + 4 * r, p, qs.half);
                 } else if constexpr (EPL == 2) {
-                    const unsigned c0 = (unsigned)__double2loint(w[2 * r] * inv + kMagic);
-                    const unsigned c1 = (unsigned)__double2loint(w[2 * r + 1] * inv + kMagic);
-                    *reinterpret_cast<unsigned short*>(p) = (unsigned short)((c0 & 0xffu) | (c1 << 8));
+                    const unsigned c0 = code1<ASYM>(w[2 * r], p, qs.half), c1 = code1<ASYM>(w[2 * r + 1], p, qs.half);
+                    *reinterpret_cast<unsigned short*>(dstb) = (unsigned short)((c0 & 0xffu) | (c1 << 8));
                 } else {
-                    *p = (unsigned char)__double2loint(w[r] * inv + kMagic);
+                    *dstb = (unsigned char)code1<ASYM>(w[r], p, qs.half);
                 }
             }
         }
@@ -340,7 +447,10 @@ __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_
             uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
             dst[0] = src[0];
             dst[1] = src[1];
-            if (slot == 0) scale[row] = (float)(amax / norm);
+            if (slot == 0) {
+                scale[row] = p.scale;
+                if constexpr (ASYM) qs.zero[row] = p.izero;
+            }
         }
     }
 }
@@ -482,22 +592,34 @@ __global__ __launch_bounds__(256, 2) void dense_rotate_mfma_f64_kernel(const uin
 }
 
 // One workgroup per row: absmax and codes from fp64 U.
-__global__ void quant_from_f64_kernel(const double* __restrict__ U, int K, double qmax, double norm,
+__global__ void quant_from_f64_kernel(const double* __restrict__ U, int K, QuantSpec qs,
                                       int8_t* __restrict__ q, float* __restrict__ scale) {
     __shared__ double red[16];
     const int t = threadIdx.x, nt = blockDim.x;
     const size_t base = (size_t)blockIdx.x * K;
-    double m = 0.0;
-    for (int i = t; i < K; i += nt) m = fmax(m, fabs(U[base + i]));
-    const double amax = block_max(m, red);
-    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    RowQ p;
+    if (!qs.asym) {
+        double m = 0.0;
+        for (int i = t; i < K; i += nt) m = fmax(m, fabs(U[base + i]));
+        p = rowq_sym(block_max(m, red), qs);
+    } else {
+        double hi = -INFINITY, lo = INFINITY;
+        for (int i = t; i < K; i += nt) { hi = fmax(hi, U[base + i]); lo = fmin(lo, U[base + i]); }
+        hi = block_max(hi, red);
+        lo = block_min(lo, red);
+        p = rowq_asym(hi, lo, qs);
+    }
     for (int c = t; c < (K >> 3); c += nt) {
         double v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = U[base + (size_t)c * 8 + i];
-        store8_codes(q + base + (size_t)c * 8, v, inv, qmax);
+        if (qs.asym) store8_codes<true>(q + base + (size_t)c * 8, v, p, qs.half);
+        else store8_codes<false>(q + base + (size_t)c * 8, v, p, qs.half);
     }
-    if (t == 0) scale[blockIdx.x] = (float)(amax / norm);
+    if (t == 0) {
+        scale[blockIdx.x] = p.scale;
+        if (qs.asym) qs.zero[blockIdx.x] = p.izero;
+    }
 }
 
 int ilog2(int v) {
@@ -514,24 +636,37 @@ int threads_for_row(int K) {
 
 }  // namespace
 
+static QuantSpec make_spec(int act_bits, int h, int32_t* zero) {
+    QuantSpec qs;
+    qs.asym = zero != nullptr;
+    qs.qmax = (double)((1 << (act_bits - 1)) - 1);
+    qs.sqrt_h = sqrt((double)h);
+    qs.norm = qs.qmax * qs.sqrt_h;
+    qs.L = (double)((1 << act_bits) - 1);
+    qs.half = (double)(1 << (act_bits - 1));
+    qs.zero = zero;
+    return qs;
+}
+
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale) {
-    const double qmax = (double)((1 << (act_bits - 1)) - 1);
-    const double norm = qmax * sqrt((double)h);
+                                 int8_t* q, float* scale, int32_t* zero) {
+    const QuantSpec qs = make_spec(act_bits, h, zero);
     if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
-        // R rows per workgroup: as many as fit 1024 threads, at most 32, a multiple that keeps quads inside rows
+        // R whole rows per workgroup, about five waves (finer granularity measured faster than nine)
         const int lpr = K / E32;
         static const int tgt = [] { const char* e = getenv("LRQ_ROT_THREADS"); return e ? atoi(e) : 288; }();
-        int R = tgt / lpr;                       // about five waves per workgroup (finer granularity measured faster)
+        int R = tgt / lpr;
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
         const dim3 grid((M + R - 1) / R), block(nt);
-        switch (ilog2(h)) {
-#define LRQ_CASE(L) case L: hipLaunchKernelGGL(hadamard_quant_e32_kernel<L>, grid, block, 0, st, X, M, K, R, qmax, norm, q, scale); break;
-            LRQ_CASE(0) LRQ_CASE(1) LRQ_CASE(2) LRQ_CASE(3) LRQ_CASE(4) LRQ_CASE(5) LRQ_CASE(6) LRQ_CASE(7)
+#define LRQ_CASE(L)                                                                                              \
+    case L:                                                                                                      \
+        if (qs.asym) hipLaunchKernelGGL((hadamard_quant_e32_kernel<L, true>), grid, block, 0, st, X, M, K, R, qs, q, scale); \
+        else hipLaunchKernelGGL((hadamard_quant_e32_kernel<L, false>), grid, block, 0, st, X, M, K, R, qs, q, scale);        \
+        break;
+        switch (ilog2(h)) { LRQ_CASE(0) LRQ_CASE(1) LRQ_CASE(2) LRQ_CASE(3) LRQ_CASE(4) LRQ_CASE(5) LRQ_CASE(6) LRQ_CASE(7) }
 #undef LRQ_CASE
-        }
         return hipGetLastError();
     }
     if (h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512) {
@@ -544,7 +679,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         const size_t ldsb = (size_t)R * (18 * lpr + 4 * (lpr >> 5) + 8) * sizeof(double);
         // resident workgroups per CU: two waves per SIMD by registers, LDS permitting
         const int groups = (M + R - 1) / R;
-        int per_cu = (int)((160 * 1024 - 1024) / (ldsb + 512));
+        int per_cu = (int)((160 * 1024 - 2048) / (ldsb + 512));
         const int by_waves = 8 / (nt / kWave) > 0 ? 8 / (nt / kWave) : 1;
         if (per_cu > by_waves) per_cu = by_waves;
         if (per_cu < 1) per_cu = 1;
@@ -553,21 +688,27 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         const dim3 grid(persist ? 256 * per_cu : groups), block(nt);
         static bool attr2 = false;
         if (!attr2) {
-#define LRQ_ATTR(L, P) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P>), hipFuncAttributeMaxDynamicSharedMemorySize, 159 * 1024); if (e != hipSuccess) return e; }
-            LRQ_ATTR(8, false) LRQ_ATTR(9, false) LRQ_ATTR(10, false) LRQ_ATTR(11, false) LRQ_ATTR(12, false)
-            LRQ_ATTR(11, true) LRQ_ATTR(12, true)
+#define LRQ_ATTR(L, P, A) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A>), hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024); if (e != hipSuccess) return e; }
+#define LRQ_ATTR2(L, P) LRQ_ATTR(L, P, false) LRQ_ATTR(L, P, true)
+            LRQ_ATTR2(8, false) LRQ_ATTR2(9, false) LRQ_ATTR2(10, false) LRQ_ATTR2(11, false) LRQ_ATTR2(12, false)
+            LRQ_ATTR2(11, true) LRQ_ATTR2(12, true)
+#undef LRQ_ATTR2
 #undef LRQ_ATTR
             attr2 = true;
         }
-#define LRQ_CASE(L, P) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P>), grid, block, ldsb, st, X, M, K, R, qmax, norm, q, scale)
+#define LRQ_GO(L, P)                                                                                                      \
+    {                                                                                                                     \
+        if (qs.asym) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);  \
+        else hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);         \
+    }
         switch (ilog2(h)) {
-            case 8: LRQ_CASE(8, false); break;
-            case 9: LRQ_CASE(9, false); break;
-            case 10: LRQ_CASE(10, false); break;
-            case 11: if (persist) LRQ_CASE(11, true); else LRQ_CASE(11, false); break;
-            case 12: if (persist) LRQ_CASE(12, true); else LRQ_CASE(12, false); break;
+            case 8: LRQ_GO(8, false) break;
+            case 9: LRQ_GO(9, false) break;
+            case 10: LRQ_GO(10, false) break;
+            case 11: if (persist) LRQ_GO(11, true) else LRQ_GO(11, false) break;
+            case 12: if (persist) LRQ_GO(12, true) else LRQ_GO(12, false) break;
         }
-#undef LRQ_CASE
+#undef LRQ_GO
         return hipGetLastError();
     }
     const int nt = threads_for_row(K);
@@ -579,18 +720,17 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(hadamard_quant_generic_kernel, dim3(M), dim3(nt), lds, st, X, K, ilog2(h), qmax, norm, q, scale);
+    hipLaunchKernelGGL(hadamard_quant_generic_kernel, dim3(M), dim3(nt), lds, st, X, K, ilog2(h), qs, q, scale);
     return hipGetLastError();
 }
 
 hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, int act_bits, int8_t* q,
-                              float* scale) {
-    return launch_hadamard_quant(st, X, M, K, 1, act_bits, q, scale);
+                              float* scale, int32_t* zero) {
+    return launch_hadamard_quant(st, X, M, K, 1, act_bits, q, scale, zero);
 }
 
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
-                                     int act_bits, double* U, int8_t* q, float* scale) {
-    const double qmax = (double)((1 << (act_bits - 1)) - 1);
+                                     int act_bits, double* U, int8_t* q, float* scale, int32_t* zero) {
     static const int use_mfma = [] { const char* e = getenv("LRQ_DENSE_MFMA"); return e ? atoi(e) : 1; }();
     if (use_mfma && K % MT_ == 0) {
         dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
@@ -601,7 +741,8 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qmax, qmax, q, scale);
+    const QuantSpec qs = make_spec(act_bits, 1, zero);
+    hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qs, q, scale);
     return hipGetLastError();
 }
 

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     const float* __restrict__ bgrid, int nb, uint8_t* __restrict__ codes_out, double* __restrict__ s_pos,
     double* __restrict__ s_neg, int32_t* __restrict__ z_pos, int32_t* __restrict__ z_neg,
     float* __restrict__ alpha, float* __restrict__ beta, int8_t* __restrict__ lut, float* __restrict__ wscale,
-    uint8_t* __restrict__ gemm_codes) {
+    uint8_t* __restrict__ gemm_codes, int32_t* __restrict__ colsum) {
     extern __shared__ double sm[];
     double* ell = sm;                                   // K doubles: log2|w|
     double* red = sm + K;                               // 64 doubles of reduction scratch
@@ -144,10 +144,12 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     double vmax = 0.0;
     for (int i = 0; i < nlev; ++i) vmax = fmax(vmax, red[i]);
     const float ws = (float)(vmax / 127.0);
+    __shared__ int lutv[16];
     if (t < 16) {
         int8_t entry = 0;
         if (t < nlev) entry = (int8_t)(int)clampd(rint(v / (double)ws), -127.0, 127.0);
         lut[(size_t)n * 16 + t] = entry;
+        lutv[t] = entry;
     }
     if (t == 0) wscale[n] = ws;
 
@@ -162,6 +164,12 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     __syncthreads();
 
     const unsigned mask = (unsigned)nlev - 1u;
+    {   // sum of the channel's decoded levels (exact in fp64: |sum| <= 127 K)
+        double part = 0.0;
+        for (int k = t; k < K; k += NT) part += (double)lutv[(unsigned)code[k] & mask];
+        const double tot = block_sum(part, red);
+        if (t == 0) colsum[n] = (int32_t)tot;
+    }
     if (bits == 4) {
         // canonical: byte j = code[2j] | code[2j+1] << 4, written 4 bytes at a time
         uint32_t* dst = reinterpret_cast<uint32_t*>(codes_out + (size_t)n * (K / 2));
@@ -220,13 +228,13 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tlq_quantize_pack_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
                        beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
-                       out.lut, out.wscale, out.gemm_codes);
+                       out.lut, out.wscale, out.gemm_codes, out.colsum);
     return hipGetLastError();
 }
 

@@ -65,7 +65,7 @@ def test_rotate_quant_rejects_bad_arguments_on_the_host(L):
 
 def _weight(N=64, K=128, bits=4, I=7, p=4096, **over):
     kw = dict(N=N, K=K, bits=bits, I=I, codes=p, s_pos=p, s_neg=p, z_pos=p, z_neg=p, alpha=p, beta=p, lut=p,
-              wscale=p, gemm_codes=p)
+              wscale=p, gemm_codes=p, colsum=p)
     kw.update(over)
     return lrq._TlqWeight(**kw)
 
@@ -110,3 +110,18 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(lrq, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError, match="no fallback"):
         lrq.lib()
+
+
+def test_zero_point_variants_reject_bad_arguments_on_the_host(L):
+    P = 4096
+    had = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_HADAMARD, 128, None))
+    w = ctypes.byref(_weight())
+    big = 1 << 30
+    assert L.lrq_ars_rotate_quant_asym(None, P, 4, 128, had, 8, P, P, None, None, 0) == lrq.LRQ_EINVAL      # zero null
+    assert L.lrq_ars_rotate_quant_asym(None, P, 4, 128, had, 5, P, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED
+    assert L.lrq_qgemm_asym(None, P, P, None, 16, 128, w, None, 0, P) == lrq.LRQ_EINVAL
+    assert L.lrq_qgemm_asym(None, P, P, P, 16, 128, ctypes.byref(_weight(colsum=None)), None, 0, P) == lrq.LRQ_EINVAL
+    need = L.lrq_workspace_bytes_asym(16, 64, 128, had, 8)
+    assert need >= L.lrq_workspace_bytes(16, 64, 128, had, 8) + 16 * 4
+    assert L.lrq_qlinear_asym(None, P, 16, 128, had, 8, w, None, 0, P, P, need - 1) == lrq.LRQ_EWORKSPACE
+    assert L.lrq_qlinear_asym(None, P, 16, 128, had, 8, w, None, 0, None, P, big) == lrq.LRQ_EINVAL

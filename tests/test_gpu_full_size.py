@@ -98,3 +98,32 @@ def test_config_4_weight_codes_in_full(lrq):
     got = w.codes.cpu().numpy()
     p = oracle.tlq_calibrate(W, spec.w_bits, GRID, GRID)
     assert np.array_equal(got, oracle.pack_codes(oracle.tlq_encode(W, p), spec.w_bits))
+
+
+@pytest.mark.parametrize("cfg,layer", [(2, 3), (4, 1), (3, 3)])
+def test_zero_point_form_at_full_size(lrq, cfg, layer):
+    """The paper's Eq. 1 quantizer (zero-point per token) through lrq_qlinear_asym at full size, sampled."""
+    import torch
+    spec = synth.config_layers(cfg)[layer]
+    print(f"asym layer {spec.name} cfg{cfg} M={spec.M} K={spec.K} N={spec.N} h={spec.had_block}", flush=True)
+    X, W, _, _ = synth.layer_tensors(spec)
+    rows, chans = _sample(spec.M, N_ROWS, spec.key), _sample(spec.N, N_CH, spec.key)
+    Xd = bf16_to_dev(X)
+    rot = lrq.Rotation("hadamard", spec.had_block)
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), spec.w_bits, 7, gd, gd)
+    q, sc, zr = lrq.ars_rotate_quant(Xd, rot, spec.a_bits, asym=True)
+    Y = lrq.qlinear(Xd, rot, spec.a_bits, w, out_dtype=torch.bfloat16, asym=True)
+    torch.cuda.synchronize()
+    ridx, cidx = torch.from_numpy(rows).to(Xd.device), torch.from_numpy(chans).to(Xd.device)
+    q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(X[rows], spec.a_bits, "hadamard", spec.had_block)
+    assert np.array_equal(q[ridx].cpu().numpy(), q_ref)
+    assert np.array_equal(zr[ridx].cpu().numpy(), z_ref)
+    assert np.array_equal(sc[ridx].cpu().numpy(), s_ref)
+    p = oracle.tlq_calibrate(W[chans], spec.w_bits, GRID, GRID)
+    codes = oracle.tlq_encode(W[chans], p)
+    lut, wscale = oracle.tlq_lut(p, 7)
+    y_ref = oracle.qlinear_from_parts_asym(q_ref, s_ref, z_ref, codes, lut, wscale, spec.w_bits)
+    ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref))
+    y_s = bf16_bits_from_dev(Y[ridx][:, cidx].contiguous())
+    assert rel_fro(oracle.bf16_bits_to_f64(y_s), ref16) <= 1e-3

@@ -186,6 +186,55 @@ def test_qlinear_end_to_end(lrq, cfg_case):
     assert np.array_equal(q.cpu().numpy(), ref["q"]) and np.array_equal(s.cpu().numpy(), ref["scale"])
 
 
+# ------------------------------------------------------------------ zero-point form of Eq. 1
+@pytest.mark.parametrize("M,K,rotation,h,a_bits", [
+    (256, 1152, "hadamard", 128, 8), (37, 1152, "hadamard", 128, 4), (9, 64, "hadamard", 4, 8),
+    (70, 1536, "hadamard", 512, 8), (40, 3072, "hadamard", 1024, 4), (19, 12288, "hadamard", 4096, 8),
+    (3, 16384, "hadamard", 16384, 8), (11, 256, "none", 0, 8), (70, 128, "dense", 0, 8), (64, 1152, "dense", 0, 4),
+])
+def test_zero_point_rotate_quant_bit_exact(lrq, M, K, rotation, h, a_bits):
+    print(f"case asym M={M} K={K} {rotation} h={h} a={a_bits}", flush=True)
+    X = oracle.bf16_bits_to_f64(_acts(M, K, 7 + K + M)).astype(np.float32)
+    X += np.float32(0.75)                           # non-zero mean: the zero-points matter
+    X[0] = 2.5                                      # constant token
+    if M > 2:
+        X[1] = 0.0                                  # all-zero token
+        X[2] = -np.abs(X[2])                        # one-sided token
+    Xb = synth.f32_to_bf16_bits(X)
+    R = synth.make_rotation(K, (907, K, 0)) if rotation == "dense" else None
+    q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(Xb, a_bits, rotation, h, R)
+    rot = lrq.Rotation(rotation, h, None if R is None else bf16_to_dev(R))
+    q, s, z = lrq.ars_rotate_quant(bf16_to_dev(Xb), rot, a_bits, asym=True)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(z.cpu().numpy(), z_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+
+
+@pytest.mark.parametrize("M,N,K,w_bits,a_bits", [(300, 352, 1152, 4, 8), (513, 200, 256, 3, 4), (256, 1152, 1152, 4, 8)])
+def test_zero_point_qlinear_against_oracle(lrq, M, N, K, w_bits, a_bits):
+    import torch
+    print(f"case asym qlinear M={M} N={N} K={K} W{w_bits}A{a_bits}", flush=True)
+    W = synth.make_weights(N, K, (908, N, K))
+    w, codes, lut, wscale = _check_weight(lrq, W, w_bits)
+    wv = np.take_along_axis(lut.astype(np.int64), codes.astype(np.int64) & (2 ** w_bits - 1), axis=1)
+    assert np.array_equal(w.colsum.cpu().numpy(), wv.sum(axis=1).astype(np.int32))          # level sums, exact
+    h = synth.default_had_block(K)
+    Xb = synth.f32_to_bf16_bits(oracle.bf16_bits_to_f64(_acts(M, K, 9 + M)).astype(np.float32) + np.float32(1.25))
+    bias = synth.make_bias(N, (908, N, K))
+    q, s, z = oracle.ars_rotate_quant_asym(Xb, a_bits, "hadamard", h)
+    y_ref = oracle.qlinear_from_parts_asym(q, s, z, codes, lut, wscale, w_bits, bias)
+    rot = lrq.Rotation("hadamard", h)
+    y32 = lrq.qlinear(bf16_to_dev(Xb), rot, a_bits, w, bias=to_dev(bias), out_dtype=torch.float32, asym=True).cpu().numpy()
+    assert rel_fro(y32, y_ref) <= 1e-3
+    assert np.allclose(y32, y_ref, rtol=3e-6, atol=2e-6 * np.abs(y_ref).max())
+    y16 = bf16_bits_from_dev(lrq.qlinear(bf16_to_dev(Xb), rot, a_bits, w, bias=to_dev(bias), out_dtype=torch.bfloat16, asym=True))
+    ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref))
+    assert rel_fro(oracle.bf16_bits_to_f64(y16), ref16) <= 1e-3
+    # the GEMM stage alone on oracle codes
+    yg = lrq.qgemm(to_dev(q), to_dev(s), w, bias=to_dev(bias), out_dtype=torch.float32, zero=to_dev(z)).cpu().numpy()
+    assert np.allclose(yg, y_ref, rtol=3e-6, atol=2e-6 * np.abs(y_ref).max())
+
+
 def test_smoke_entry(lrq):
     import __graft_entry__
     __graft_entry__.smoke()
