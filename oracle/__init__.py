@@ -10,7 +10,10 @@ What follows the paper and where:
 * rotation.py  - Sylvester Hadamard matrix and its butterfly form
                  (Preliminaries, "Rotation Transformation", Eq. hadamard), the
                  dense rotation X.R used for the outlier-aware branch of the
-                 Adaptive Rotation Scheme (Method, ARS case equation).
+                 Adaptive Rotation Scheme (Method, ARS case equation), that branch in
+                 its structured form X.R1.P.R2 (block-diagonal rotations, staggered
+                 permutation) and the greedy builder of R1, P, R2 from calibration
+                 activations (equation R^i = E R~ Q E).
 * actquant.py  - per-token dynamic uniform quantizer (Preliminaries, Eq. 1, in
                  its symmetric absmax form; Experiment, "Implementation Details":
                  per-token dynamic activations).
@@ -28,7 +31,8 @@ by their own stated definitions, everything else against closed forms, library
 special cases and brute force.
 """
 from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits  # noqa: F401
-from .rotation import hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense  # noqa: F401
+from .rotation import (hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense, rotate_blockdiag,  # noqa: F401
+                       rotate_blockperm, zigzag_permutation, greedy_block_rotation, build_outlier_rotation)
 from .actquant import quantize_per_token, quantize_per_token_asym  # noqa: F401
 from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
                   tlq_level_values, tlq_lut, pack_codes, unpack_codes)

@@ -11,39 +11,37 @@ import numpy as np
 
 from .actquant import quantize_per_token, quantize_per_token_asym
 from .bf16 import bf16_bits_to_f64
-from .rotation import rotate_dense, rotate_hadamard
+from .rotation import rotate_blockperm, rotate_dense, rotate_hadamard
 from .tlq import TLQParams, tlq_calibrate, tlq_encode, tlq_lut
 
 
-def ars_rotate_quant(X_bits, a_bits, rotation, had_block=None, R_bits=None):
-    """Rotate (per-layer choice) and quantize per token.
-    X_bits: bf16 bit patterns [M, K]; rotation: "none" | "hadamard" | "dense".
-    Returns (q int8 [M, K], scale fp32 [M])."""
-    x = bf16_bits_to_f64(X_bits)
-    if rotation == "hadamard":
-        u, norm = rotate_hadamard(x, had_block), np.sqrt(np.float64(had_block))
-    elif rotation == "dense":
-        u, norm = rotate_dense(x, bf16_bits_to_f64(R_bits)), 1.0
-    else:
-        assert rotation == "none"
-        u, norm = x, 1.0
-    return quantize_per_token(u, a_bits, norm)
-
-
-def _rotate(X_bits, rotation, had_block, R_bits):
+def _rotate(X_bits, rotation, had_block, R_bits, blockperm=None):
+    """(u fp64 [M, K], norm) for the layer's rotation choice (Method, ARS case equation).
+    rotation: "none" | "hadamard" | "dense" (R_bits: bf16 bit patterns [K, K]) | "blockperm" (blockperm =
+    (R1_bits [nb, B, B], perm [K], R2_bits [nb, B, B]): the structured form X . R1 . P . R2)."""
     x = bf16_bits_to_f64(X_bits)
     if rotation == "hadamard":
         return rotate_hadamard(x, had_block), np.sqrt(np.float64(had_block))
     if rotation == "dense":
         return rotate_dense(x, bf16_bits_to_f64(R_bits)), 1.0
+    if rotation == "blockperm":
+        R1_bits, perm, R2_bits = blockperm
+        return rotate_blockperm(x, bf16_bits_to_f64(R1_bits), perm, bf16_bits_to_f64(R2_bits)), 1.0
     assert rotation == "none"
     return x, 1.0
 
 
-def ars_rotate_quant_asym(X_bits, a_bits, rotation, had_block=None, R_bits=None):
+def ars_rotate_quant(X_bits, a_bits, rotation, had_block=None, R_bits=None, blockperm=None):
+    """Rotate (per-layer choice) and quantize per token.
+    X_bits: bf16 bit patterns [M, K].  Returns (q int8 [M, K], scale fp32 [M])."""
+    u, norm = _rotate(X_bits, rotation, had_block, R_bits, blockperm)
+    return quantize_per_token(u, a_bits, norm)
+
+
+def ars_rotate_quant_asym(X_bits, a_bits, rotation, had_block=None, R_bits=None, blockperm=None):
     """Rotate and quantize per token with the zero-point form of Eq. 1.
     Returns (q int8 [M, K], scale fp32 [M], zero int32 [M]) with x_f = scale * (q + zero)."""
-    u, norm = _rotate(X_bits, rotation, had_block, R_bits)
+    u, norm = _rotate(X_bits, rotation, had_block, R_bits, blockperm)
     return quantize_per_token_asym(u, a_bits, norm)
 
 

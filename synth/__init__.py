@@ -132,6 +132,43 @@ def make_rotation(K: int, key: Sequence[int]) -> np.ndarray:
     return f32_to_bf16_bits(q.astype(np.float32))
 
 
+def make_block_rotations(K: int, B: int, key: Sequence[int], which: int = 0) -> np.ndarray:
+    """bf16 bit patterns [K/B, B, B] of a block-diagonal rotation: one seeded QR factor per block (sign
+    convention diag(R_qr) > 0); `which` separates the two rotations of a layer."""
+    out = np.empty((K // B, B, B), dtype=np.uint16)
+    for g in range(K // B):
+        a = rng_for(*key, _STREAM_R, 1 + which, g).standard_normal((B, B))
+        q, r = np.linalg.qr(a)
+        out[g] = f32_to_bf16_bits((q * np.sign(np.diag(r))[None, :]).astype(np.float32))
+    return out
+
+
+def make_channel_permutation(K: int, key: Sequence[int]) -> np.ndarray:
+    """A seeded permutation of the K channels (int32, gather form)."""
+    return rng_for(*key, _STREAM_R, 7).permutation(K).astype(np.int32)
+
+
+def make_spreading_matrix(B: int) -> np.ndarray:
+    """fp64 [B, B] orthogonal, symmetric matrix whose first row is 1/sqrt(B) everywhere (the Householder
+    reflection that maps e_0 to the uniform unit vector): an initial matrix for the greedy rotation builder."""
+    v = -np.full(B, 1.0 / np.sqrt(B))
+    v[0] += 1.0
+    return np.eye(B) - 2.0 * np.outer(v, v) / float(v @ v)
+
+
+def make_step_rotations(nb: int, n: int, B: int, key: Sequence[int], which: int = 0) -> np.ndarray:
+    """fp64 [nb, n, B, B]: per block and greedy step an orthogonal matrix diag(1, Q') with Q' the QR factor of
+    a seeded (B-1) x (B-1) Gaussian - the random rotations the greedy builder takes as an input."""
+    out = np.zeros((nb, n, B, B))
+    for g in range(nb):
+        for i in range(n):
+            a = rng_for(*key, _STREAM_R, 11 + which, g, i).standard_normal((B - 1, B - 1))
+            q, r = np.linalg.qr(a)
+            out[g, i, 0, 0] = 1.0
+            out[g, i, 1:, 1:] = q * np.sign(np.diag(r))[None, :]
+    return out
+
+
 def layer_tensors(spec: LayerSpec, rows: Optional[Tuple[int, int]] = None, with_bias: bool = False):
     """(X bf16 bits [rows,K], W fp32 [N,K], R bf16 bits [K,K] or None, bias or None)."""
     X = make_activations(spec.M, spec.K, spec.key, spec.p_mild, spec.n_salient, spec.gain, rows)
