@@ -168,27 +168,14 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     __shared__ float sc[BM];
     __shared__ int zr[BM];          // per-token zero-points (zero-point form only)
 
-    // Persistent workgroups: the grid is one resident set (CUs x workgroups per CU) and every workgroup walks
-    // tiles b = blockIdx.x, blockIdx.x + gridDim.x, ...; the stores of one tile's epilogue drain while the next
-    // tile's K loop runs instead of holding the CU slot until they are acknowledged.
-    // XCD-aware tile order.  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2) and
-    // gridDim.x is a multiple of 8 whenever a workgroup takes more than one tile, so XCD x is handed a contiguous
-    // range of a linear tile order; that order walks 8-row-tile groups n-fastest within 8 consecutive m (grouped
-    // ordering), so the ~64 tiles resident on an XCD at any time form an 8 x 8 patch that shares each row panel
-    // of q and each channel panel of W eight ways through that L2.
+    // XCD-aware tile order.  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2), so
+    // XCD x is handed a contiguous range of a linear tile order; that order walks 8-row-tile groups n-fastest
+    // within 8 consecutive m (grouped ordering), so the ~64 tiles resident on an XCD at any time form an
+    // 8 x 8 patch that shares each row panel of q and each channel panel of W eight ways through that L2.
     const int ntiles = tiles_m * tiles_n;
-    const int t = threadIdx.x, lane = t % 64, wv = t / 64;
-    const int KB = K / BK;
-    const int ntile32 = (N + 31) / 32;
-    constexpr int UNIT = 64 * (BITS == 4 ? 16 : 12);
-    unsigned C = 0x03020100u;
-    asm volatile("" : "+v"(C));
-    const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
-
-  for (int b = blockIdx.x; b < ntiles; b += gridDim.x) {
     int tile;
     {
-        const int x = b % 8, i = b / 8;
+        const int x = blockIdx.x % 8, i = blockIdx.x / 8;
         const int base = ntiles / 8, rem = ntiles % 8;           // XCD x owns base + (x < rem) tiles
         tile = x * base + (x < rem ? x : rem) + i;
     }
@@ -203,6 +190,11 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         tn = r / gsize;
     }
     const int m0 = tm * BM, n0 = tn * BN;
+
+    const int t = threadIdx.x, lane = t % 64, wv = t / 64;
+    const int KB = K / BK;
+    const int ntile32 = (N + 31) / 32;
+    constexpr int UNIT = 64 * (BITS == 4 ? 16 : 12);
 
     unsigned L[NTW][4];
     const uint8_t* bptr[NTW];
@@ -243,6 +235,8 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     // ---- prologue: A tile 0 -> LDS buffer 0; A tiles 1 (aO), 2 (aE) and B blocks 0 (bE), 1 (bO) in registers
+    unsigned C = 0x03020100u;
+    asm volatile("" : "+v"(C));
     v4i aO[ALOADS], aE[ALOADS];
     BRaw<BITS> bE[NTW], bO[NTW];
     v4i bd0[NTW];
@@ -270,26 +264,14 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     }
     __syncthreads();
 
+    const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
+
     for (int kb = 0; kb < KB; kb += 2) {
         kblock<BITS, MT, NTW, ALOADS>(smem, smem + ABUF, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
         if (kb + 1 < KB)
             kblock<BITS, MT, NTW, ALOADS>(smem + ABUF, smem, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
     }
 
-#ifdef LRQ_EXP_NOEPI
-    {
-        int sum = 0;
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTW; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
-        reinterpret_cast<int*>(Y)[(size_t)tile * 256 + t] = sum;
-        __syncthreads();
-        continue;
-    }
-#endif
     // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS (wave-private, so only wave-level
     // ordering is needed after the K loop's final barrier), store 16 bytes per lane.
     // Lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of every 32x32 accumulator tile.
@@ -375,27 +357,14 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
                 wave_sync();
             }
     }
-    __syncthreads();        // the next tile's prologue overwrites the staging slabs, sc and zr
-  }
 }
 
 template <int BITS, int BM, int NTW>
 hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
                   const lrq_tlq_weight& w, const float* bias, int fp32, void* Y) {
     constexpr int BN = WAVES * 32 * NTW;
-    constexpr int WG_PER_CU = BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1);     // as in __launch_bounds__
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + BN - 1) / BN;
-    static const int n_cu = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        return n;
-    }();
-    static const int persist = [] { const char* e = getenv("LRQ_GEMM_PERSIST"); return e ? atoi(e) : 1; }();
-    const long long ntiles = (long long)tiles_m * tiles_n;
-    long long resident = (long long)n_cu * WG_PER_CU;
-    resident -= resident % 8;
-    const int grid = (int)((persist && ntiles > resident) ? resident : ntiles);
-    hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW>), dim3(grid), dim3(256), 0, st, q, scale, M, K, w.N,
+    hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
                        w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
     return hipGetLastError();
 }
