@@ -38,7 +38,7 @@ typedef enum {
     LRQ_EHIP = -4          /* the HIP runtime reported an error while launching                           */
 } lrq_status;
 
-typedef enum { LRQ_ROT_NONE = 0, LRQ_ROT_HADAMARD = 1, LRQ_ROT_DENSE = 2 } lrq_rotation_kind;
+typedef enum { LRQ_ROT_NONE = 0, LRQ_ROT_HADAMARD = 1, LRQ_ROT_DENSE = 2, LRQ_ROT_BLOCKPERM = 3 } lrq_rotation_kind;
 typedef enum { LRQ_OUT_BF16 = 0, LRQ_OUT_FP32 = 1 } lrq_out_dtype;
 
 /*
@@ -49,12 +49,23 @@ typedef enum { LRQ_OUT_BF16 = 0, LRQ_OUT_FP32 = 1 } lrq_out_dtype;
  *                     transform is taken unnormalised (+-1 entries) and 1/sqrt(h) goes into the scale.
  *   LRQ_ROT_DENSE     u = x . R with R a K x K bf16 matrix (row-major, device): any orthogonal matrix,
  *                     e.g. the paper's greedy outlier-aware product R1.P.R2 materialised.
+ *   LRQ_ROT_BLOCKPERM u = ((x . R1) . P) . R2: the outlier-aware branch in the structured form the paper
+ *                     prints.  R1, R2 are block-diagonal with blocks of `block` channels, stored as bf16
+ *                     [K/block, block, block] (block g acts on channels g*block ...); P is the staggered
+ *                     channel permutation in gather form, (z . P)[:, j] = z[:, perm[j]], perm int32 [K]
+ *                     (a permutation of 0..K-1: the library does not verify that, it only clamps every
+ *                     index into range).  The intermediate x . R1 is rounded once to fp32.  block must be a
+ *                     multiple of 128 that divides K.  Costs O(K * block) per token instead of O(K^2).
  *   LRQ_ROT_NONE      u = x.
  */
 typedef struct {
     int kind;        /* lrq_rotation_kind                                   */
     int had_block;   /* h for LRQ_ROT_HADAMARD, ignored otherwise           */
     const void* R;   /* bf16 [K,K] device pointer for LRQ_ROT_DENSE or NULL */
+    int block;             /* LRQ_ROT_BLOCKPERM: block size of R1, R2, else ignored     */
+    const void* R1;        /* LRQ_ROT_BLOCKPERM: bf16 [K/block, block, block] (device)  */
+    const int32_t* perm;   /* LRQ_ROT_BLOCKPERM: int32 [K] (device)                     */
+    const void* R2;        /* LRQ_ROT_BLOCKPERM: bf16 [K/block, block, block] (device)  */
 } lrq_rotation;
 
 /*

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LRQ_LIB", os.path.join(_HERE, "liblrq.so"))   # LRQ_LIB: developer override
 
 LRQ_OK, LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP = 0, -1, -2, -3, -4
-LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE = 0, 1, 2
+LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE, LRQ_ROT_BLOCKPERM = 0, 1, 2, 3
 LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
 
 EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes",
@@ -32,7 +32,8 @@ class LrqError(RuntimeError):
 
 
 class _Rotation(ctypes.Structure):
-    _fields_ = [("kind", ctypes.c_int), ("had_block", ctypes.c_int), ("R", ctypes.c_void_p)]
+    _fields_ = [("kind", ctypes.c_int), ("had_block", ctypes.c_int), ("R", ctypes.c_void_p),
+                ("block", ctypes.c_int), ("R1", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("R2", ctypes.c_void_p)]
 
 
 class _TlqWeight(ctypes.Structure):
@@ -110,14 +111,20 @@ def _ptr(t) -> Optional[int]:
 
 @dataclass
 class Rotation:
-    """Per-layer rotation choice: kind in {"none", "hadamard", "dense"}."""
+    """Per-layer rotation choice: kind in {"none", "hadamard", "dense", "blockperm"}."""
     kind: str = "hadamard"
     had_block: int = 0
     R: object = None        # torch bf16 [K, K] on the device for kind == "dense"
+    block: int = 0          # kind == "blockperm": block size of R1, R2
+    R1: object = None       # torch bf16 [K/block, block, block] on the device
+    perm: object = None     # torch int32 [K] on the device (gather form)
+    R2: object = None       # torch bf16 [K/block, block, block] on the device
 
     def c_struct(self) -> _Rotation:
-        kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE}
-        return _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R))
+        kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE,
+                 "blockperm": LRQ_ROT_BLOCKPERM}
+        return _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R), int(self.block), _ptr(self.R1),
+                         _ptr(self.perm), _ptr(self.R2))
 
 
 class TLQWeight:

@@ -22,6 +22,11 @@ int check_rotation(const lrq_rotation* rot, int K) {
         case LRQ_ROT_DENSE:
             if (!rot->R || !aligned16(rot->R)) return LRQ_EINVAL;
             return K % 64 == 0 ? LRQ_OK : LRQ_EUNSUPPORTED;
+        case LRQ_ROT_BLOCKPERM:
+            if (!rot->R1 || !rot->R2 || !rot->perm || rot->block <= 0) return LRQ_EINVAL;
+            if (!aligned16(rot->R1) || !aligned16(rot->R2) || !aligned16(rot->perm)) return LRQ_EINVAL;
+            if (rot->block % 128 != 0 || K % rot->block != 0) return LRQ_EUNSUPPORTED;
+            return K <= kMaxRowLds ? LRQ_OK : LRQ_EUNSUPPORTED;
         default:
             return LRQ_EINVAL;
     }
@@ -45,11 +50,15 @@ int check_weight(const lrq_tlq_weight* w) {
 }
 
 struct ArsWs {
-    size_t u_off, total;
+    size_t u_off, zp_off, total;
 };
 ArsWs ars_layout(int M, int K, const lrq_rotation* rot) {
-    ArsWs l{0, 0};
+    ArsWs l{0, 0, 0};
     if (rot && rot->kind == LRQ_ROT_DENSE) l.total = round256((size_t)M * K * sizeof(double));
+    if (rot && rot->kind == LRQ_ROT_BLOCKPERM) {       // U doubles (its first half doubles as Z), then Zp floats
+        l.zp_off = round256((size_t)M * K * sizeof(double));
+        l.total = l.zp_off + round256((size_t)M * K * sizeof(float));
+    }
     return l;
 }
 
@@ -63,6 +72,12 @@ int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rota
             break;
         case LRQ_ROT_HADAMARD:
             e = lrq::launch_hadamard_quant(st, x, M, K, rot->had_block, act_bits, q, scale, zero);
+            break;
+        case LRQ_ROT_BLOCKPERM:
+            e = lrq::launch_blockperm_rotate_quant(
+                st, x, M, K, rot->block, static_cast<const uint16_t*>(rot->R1), rot->perm,
+                static_cast<const uint16_t*>(rot->R2), act_bits, static_cast<double*>(ws),
+                reinterpret_cast<float*>(static_cast<char*>(ws) + ars_layout(M, K, rot).zp_off), q, scale, zero);
             break;
         default:
             e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,

@@ -29,6 +29,12 @@ hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, i
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
                                      int act_bits, double* U, int8_t* q, float* scale, int32_t* zero);
 
+// u = ((x.R1).P).R2 with block-diagonal R1, R2 (bf16 [K/B,B,B]), fp32 intermediate, perm in gather form; U [M,K]
+// doubles and Zp [M,K] floats are scratch.  B % 128 == 0, B | K.
+hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
+                                         const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
+                                         int8_t* q, float* scale, int32_t* zero);
+
 hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
                                     const lrq_tlq_weight& out);

@@ -513,53 +513,81 @@ __global__ __launch_bounds__(256) void dense_rotate_f64_kernel(const uint16_t* _
     }
 }
 
-// Same product on the fp64 matrix cores: v_mfma_f64_16x16x4_f64 accumulates its four k in ascending order,
-// one fused multiply-add each, so chaining the instructions over ascending k gives the same bits as the
-// scalar chain above (a GPU test compares the two kernels' U bit for bit).
-// Workgroup = 4 waves (2 x 2), tile 128 x 128, wave tile 64 x 64 (16 accumulator tiles), K step 16.
+// Block-diagonal product on the fp64 matrix cores: dst[:, block g] = src[:, block g] . R_g with R [K/B, B, B]
+// bf16 (B = K is the dense rotation, one block).  v_mfma_f64_16x16x4_f64 accumulates its four k in ascending
+// order, one fused multiply-add each, so chaining the instructions over ascending k gives the same bits as the
+// scalar chain above whenever every product is exact in fp64 - bf16 x bf16 and fp32 x bf16 both are (a GPU test
+// compares the two kernels' U bit for bit).
+// SRC_F32: the left operand is fp32 [M, K] instead of bf16.  OUT_F32: the result is rounded once to fp32.
+// Workgroup = 4 waves (2 x 2), tile 128 x 128, wave tile 64 x 64 (16 accumulator tiles), K step 16; B must be a
+// multiple of 128 so that a column tile lies inside one block.
 typedef double v4d __attribute__((ext_vector_type(4)));
 constexpr int MT_ = 128, MK_ = 16, XP_ = MK_ + 1, RP_ = MT_ + 4;
 
-__global__ __launch_bounds__(256, 2) void dense_rotate_mfma_f64_kernel(const uint16_t* __restrict__ X,
-                                                                        const uint16_t* __restrict__ R, int M, int K,
-                                                                        double* __restrict__ U) {
+template <bool SRC_F32, bool OUT_F32>
+__global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const void* __restrict__ src,
+                                                                            const uint16_t* __restrict__ R, int M, int K,
+                                                                            int B, void* __restrict__ dst) {
     __shared__ __attribute__((aligned(16))) double Xs[2][MT_ * XP_];     // [row][k], k contiguous, padded rows
     __shared__ __attribute__((aligned(16))) double Rs[2][MK_ * RP_];     // [k][col]
     const int t = threadIdx.x, lane = t % 64, wv = t / 64;
     const int wm = wv / 2, wn = wv % 2;
     const int row0 = blockIdx.y * MT_, col0 = blockIdx.x * MT_;
+    const int g = col0 / B, kbase = g * B, cb = col0 - kbase;            // block, its first k, tile's column inside it
     v4d acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4d{0.0, 0.0, 0.0, 0.0};
-    // loaders: X tile 128 rows x 16 k (8 bf16 per thread), R tile 16 k x 128 cols (8 bf16 per thread)
+    // loaders: left tile 128 rows x 16 k (8 values per thread), R tile 16 k x 128 cols (8 bf16 per thread)
     const int xr = t / 2, xk = (t % 2) * 8;
     const int rk = t / 16, rc = (t % 16) * 8;
     int xrow = row0 + xr;
     if (xrow >= M) xrow = M - 1;
-    const uint16_t* xp = X + (size_t)xrow * K + xk;
-    const uint16_t* rp = R + (size_t)rk * K + col0 + rc;
-    uint4 xa = *reinterpret_cast<const uint4*>(xp);
+    const size_t xoff = (size_t)xrow * K + kbase + xk;
+    const uint16_t* rp = R + (size_t)g * B * B + (size_t)rk * B + cb + rc;
+    uint4 xa, xb;                                                        // xb: second half of 8 fp32 values
+    auto load_x = [&](int kb) {
+        if constexpr (SRC_F32) {
+            const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(src) + xoff + (size_t)kb * MK_);
+            xa = p[0];
+            xb = p[1];
+        } else {
+            xa = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + xoff + (size_t)kb * MK_);
+        }
+    };
+    load_x(0);
     uint4 ra = *reinterpret_cast<const uint4*>(rp);
-    const int nk = K / MK_;
+    const int nk = B / MK_;
     for (int kb = 0; kb < nk; ++kb) {
         const int cur = kb & 1;
         {
             const unsigned xw[4] = {xa.x, xa.y, xa.z, xa.w}, rw[4] = {ra.x, ra.y, ra.z, ra.w};
             double* xd = &Xs[cur][xr * XP_ + xk];
             double* rd = &Rs[cur][rk * RP_ + rc];
+            if constexpr (SRC_F32) {
+                const unsigned xv[4] = {xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xd[i] = (double)__uint_as_float(xw[i]);
+                    xd[4 + i] = (double)__uint_as_float(xv[i]);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xd[2 * i] = (double)__uint_as_float(xw[i] << 16);
+                    xd[2 * i + 1] = (double)__uint_as_float(xw[i] & 0xffff0000u);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                xd[2 * i] = (double)__uint_as_float(xw[i] << 16);
-                xd[2 * i + 1] = (double)__uint_as_float(xw[i] & 0xffff0000u);
                 rd[2 * i] = (double)__uint_as_float(rw[i] << 16);
                 rd[2 * i + 1] = (double)__uint_as_float(rw[i] & 0xffff0000u);
             }
         }
         if (kb + 1 < nk) {
-            xa = *reinterpret_cast<const uint4*>(xp + (size_t)(kb + 1) * MK_);
-            ra = *reinterpret_cast<const uint4*>(rp + (size_t)(kb + 1) * MK_ * K);
+            load_x(kb + 1);
+            ra = *reinterpret_cast<const uint4*>(rp + (size_t)(kb + 1) * MK_ * B);
         }
         __syncthreads();
 #pragma unroll
@@ -575,8 +603,8 @@ __global__ __launch_bounds__(256, 2) void dense_rotate_mfma_f64_kernel(const uin
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
         }
-        // the other buffer is free for the next tile once every wave has passed this barrier's predecessor;
-        // with two buffers one barrier per iteration is enough
+        // with two buffers one barrier per iteration is enough: a wave can only reach the writes of iteration
+        // kb + 2 (same buffer) after the barrier of iteration kb + 1, which every wave passes after its reads here
     }
     // lane holds D[4 * r + lane / 16][lane % 16] of each 16 x 16 tile
 #pragma unroll
@@ -586,9 +614,34 @@ __global__ __launch_bounds__(256, 2) void dense_rotate_mfma_f64_kernel(const uin
             const int row = row0 + wm * 64 + i * 16 + 4 * r + lane / 16;
             if (row < M) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) U[(size_t)row * K + col0 + wn * 64 + j * 16 + lane % 16] = acc[i][j][r];
+                for (int j = 0; j < 4; ++j) {
+                    const size_t o = (size_t)row * K + col0 + wn * 64 + j * 16 + lane % 16;
+                    if constexpr (OUT_F32) static_cast<float*>(dst)[o] = (float)acc[i][j][r];
+                    else static_cast<double*>(dst)[o] = acc[i][j][r];
+                }
             }
         }
+}
+
+// out[row, j] = in[row, perm[j]] for fp32 rows: the row is staged in LDS so that global reads and writes are both
+// contiguous.  Indices are clamped into [0, K) (a malformed perm gives wrong values, never an out-of-range access).
+__global__ __launch_bounds__(256) void permute_rows_f32_kernel(const float* __restrict__ in, const int32_t* __restrict__ perm,
+                                                                int M, int K, float* __restrict__ out) {
+    extern __shared__ __attribute__((aligned(16))) float prow[];
+    const int t = threadIdx.x;
+    for (int row = blockIdx.x; row < M; row += gridDim.x) {
+        const float4* src = reinterpret_cast<const float4*>(in + (size_t)row * K);
+        for (int c = t; c < K / 4; c += 256) reinterpret_cast<float4*>(prow)[c] = src[c];
+        __syncthreads();
+        float4* dst = reinterpret_cast<float4*>(out + (size_t)row * K);
+        for (int c = t; c < K / 4; c += 256) {
+            const int4 pi = reinterpret_cast<const int4*>(perm)[c];
+            const int i0 = min(max(pi.x, 0), K - 1), i1 = min(max(pi.y, 0), K - 1);
+            const int i2 = min(max(pi.z, 0), K - 1), i3 = min(max(pi.w, 0), K - 1);
+            dst[c] = make_float4(prow[i0], prow[i1], prow[i2], prow[i3]);
+        }
+        __syncthreads();
+    }
 }
 
 // One workgroup per row: absmax and codes from fp64 U.
@@ -734,12 +787,41 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
     static const int use_mfma = [] { const char* e = getenv("LRQ_DENSE_MFMA"); return e ? atoi(e) : 1; }();
     if (use_mfma && K % MT_ == 0) {
         dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
-        hipLaunchKernelGGL(dense_rotate_mfma_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U);
+        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), grid, dim3(256), 0, st, X, R, M, K, K, U);
     } else {
         dim3 grid(K / DT, (M + DT - 1) / DT);
         hipLaunchKernelGGL(dense_rotate_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U);
     }
     hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const QuantSpec qs = make_spec(act_bits, 1, zero);
+    hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qs, q, scale);
+    return hipGetLastError();
+}
+
+// Structured outlier-aware rotation u = ((x . R1) . P) . R2: block-diagonal product to fp32 (Z, in the first half of
+// U's storage), row permutation into Zp, block-diagonal product to fp64 U, then the per-token quantizer.
+hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
+                                         const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
+                                         int8_t* q, float* scale, int32_t* zero) {
+    float* Z = reinterpret_cast<float*>(U);
+    const dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
+    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    static bool attr_done = false;
+    if (!attr_done) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(permute_rows_f32_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const int pgrid = M < 4096 ? M : 4096;
+    hipLaunchKernelGGL(permute_rows_f32_kernel, dim3(pgrid), dim3(256), (size_t)K * sizeof(float), st, Z, perm, M, K, Zp);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<true, false>), grid, dim3(256), 0, st, Zp, R2, M, K, B, U);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     const QuantSpec qs = make_spec(act_bits, 1, zero);
     hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qs, q, scale);

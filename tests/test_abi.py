@@ -125,3 +125,18 @@ def test_zero_point_variants_reject_bad_arguments_on_the_host(L):
     assert need >= L.lrq_workspace_bytes(16, 64, 128, had, 8) + 16 * 4
     assert L.lrq_qlinear_asym(None, P, 16, 128, had, 8, w, None, 0, P, P, need - 1) == lrq.LRQ_EWORKSPACE
     assert L.lrq_qlinear_asym(None, P, 16, 128, had, 8, w, None, 0, None, P, big) == lrq.LRQ_EINVAL
+
+
+def test_structured_rotation_is_validated_on_the_host(L):
+    P = 4096
+    def rot(block=128, R1=P, perm=P, R2=P):
+        return ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_BLOCKPERM, 0, None, block, R1, perm, R2))
+    need = L.lrq_ars_workspace_bytes(16, 256, rot(), 8)
+    assert need >= 16 * 256 * (8 + 4)                    # fp64 U plus the permuted fp32 intermediate
+    assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(), 8, P, P, P, need - 1) == lrq.LRQ_EWORKSPACE
+    assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(R1=None), 8, P, P, P, need) == lrq.LRQ_EINVAL
+    assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(perm=None), 8, P, P, P, need) == lrq.LRQ_EINVAL
+    assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(R2=P + 2), 8, P, P, P, need) == lrq.LRQ_EINVAL   # misaligned
+    assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(block=0), 8, P, P, P, need) == lrq.LRQ_EINVAL
+    assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(block=64), 8, P, P, P, need) == lrq.LRQ_EUNSUPPORTED
+    assert L.lrq_ars_rotate_quant(None, P, 16, 384, rot(block=256), 8, P, P, P, 1 << 30) == lrq.LRQ_EUNSUPPORTED

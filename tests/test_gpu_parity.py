@@ -86,6 +86,56 @@ def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
     assert np.array_equal(u, u_ref)
 
 
+def _blockperm_inputs(lrq, K, B, seed):
+    R1 = synth.make_block_rotations(K, B, (903, K, seed), 0)
+    R2 = synth.make_block_rotations(K, B, (903, K, seed), 1)
+    perm = synth.make_channel_permutation(K, (903, K, seed))
+    rot = lrq.Rotation("blockperm", block=B, R1=bf16_to_dev(R1), perm=to_dev(perm), R2=bf16_to_dev(R2))
+    return (R1, perm, R2), rot
+
+
+@pytest.mark.parametrize("M,K,B,a_bits,asym", [(70, 128, 128, 8, False), (130, 256, 128, 4, False),
+                                               (200, 1152, 128, 8, False), (129, 768, 256, 8, True),
+                                               (1, 384, 128, 4, True), (300, 3072, 128, 8, False)])
+def test_blockperm_rotate_quant_bit_exact(lrq, M, K, B, a_bits, asym):
+    """Structured outlier-aware rotation X.R1.P.R2 (Method, ARS case equation, second branch)."""
+    import torch
+    print(f"case blockperm M={M} K={K} B={B} a={a_bits} asym={asym}", flush=True)
+    X = _acts(M, K, 5 + K)
+    bp, rot = _blockperm_inputs(lrq, K, B, M)
+    ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, a_bits), dtype=torch.uint8, device="cuda")
+    if asym:
+        q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(X, a_bits, "blockperm", blockperm=bp)
+        q, s, z = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, workspace=ws, asym=True)
+        assert np.array_equal(z.cpu().numpy(), z_ref)
+    else:
+        q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "blockperm", blockperm=bp)
+        q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, workspace=ws)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    # the rotated activations themselves (fp64 scratch at the head of the workspace), bit for bit
+    u = ws[:M * K * 8].view(torch.float64).view(M, K).cpu().numpy()
+    u_ref = oracle.rotate_blockperm(oracle.bf16_bits_to_f64(X), oracle.bf16_bits_to_f64(bp[0]), bp[1],
+                                    oracle.bf16_bits_to_f64(bp[2]))
+    assert np.array_equal(u, u_ref)
+
+
+def test_blockperm_qlinear_against_oracle(lrq):
+    import torch
+    M, K, N, B = 150, 1152, 320, 128
+    X = _acts(M, K, 77)
+    W = synth.make_weights(N, K, (904, N, K))
+    bp, rot = _blockperm_inputs(lrq, K, B, 1)
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), 4, 7, gd, gd)
+    Y = lrq.qlinear(bf16_to_dev(X), rot, 8, w, out_dtype=torch.float32)
+    p = oracle.tlq_calibrate(W, 4, GRID, GRID)
+    lut, wscale = oracle.tlq_lut(p, 7)
+    q_ref, s_ref = oracle.ars_rotate_quant(X, 8, "blockperm", blockperm=bp)
+    y_ref = oracle.qlinear_from_parts(q_ref, s_ref, oracle.tlq_encode(W, p), lut, wscale, 4)
+    assert rel_fro(Y.cpu().numpy(), y_ref) <= 1e-3
+
+
 # ------------------------------------------------------------------ TLQ calibrate + pack
 def _check_weight(lrq, W, bits, I=7, alpha=GRID, beta=GRID):
     p = oracle.tlq_calibrate(W, bits, alpha, beta)
