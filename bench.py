@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--blocks", type=int, default=0, help="c5 only: number of transformer blocks (0 = all 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--structured", type=int, default=0, metavar="B",
+                    help="run the layers that take the dense outlier-aware rotation with its structured form "
+                         "X.R1.P.R2 instead (block size B, seeded block rotations and permutation)")
     ap.add_argument("--asym", action="store_true",
                     help="use the zero-point form of the activation quantizer (the paper's Eq. 1 as printed)")
     ap.add_argument("--probes-only", action="store_true",
@@ -85,7 +88,13 @@ def main():
             X = torch.from_numpy(Xb.view(np.int16)).to(dev).view(torch.bfloat16)
             W = torch.from_numpy(synth.make_weights(s.N, s.K, s.key)).to(dev)
             R = None
-            if s.rotation == "dense":
+            if s.rotation == "dense" and args.structured:
+                B = args.structured
+                bf = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+                R = lrq.Rotation("blockperm", block=B, R1=bf(synth.make_block_rotations(s.K, B, s.key, 0)),
+                                 perm=torch.from_numpy(synth.make_channel_permutation(s.K, s.key)).to(dev),
+                                 R2=bf(synth.make_block_rotations(s.K, B, s.key, 1)))
+            elif s.rotation == "dense":
                 R = torch.from_numpy(synth.make_rotation(s.K, s.key).view(np.int16)).to(dev).view(torch.bfloat16)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -97,7 +106,7 @@ def main():
             del W
             shape_cache[skey] = (X, w, R)
         X, w, R = shape_cache[skey]
-        rot = lrq.Rotation(s.rotation, s.had_block, R)
+        rot = R if isinstance(R, lrq.Rotation) else lrq.Rotation(s.rotation, s.had_block, R)
         layers.append(dict(spec=s, X=[X], w=w, rot=rot))
     gen_s = time.time() - t_gen
 
@@ -212,6 +221,7 @@ def main():
                                      4: "config4: video-DiT block linears, 35100 tokens, hidden 3072, W4A8, per-layer ARS",
                                      5: "config5: 28-block PixArt-style stack, W3A4, per-layer ARS"}[cfg],
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
+                           outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,

@@ -202,6 +202,44 @@ int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotati
                      const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes);
 
 /*
+ * Calibration of the outlier-aware branch (paper: Method, "Adaptive Rotation Scheme": greedy rotations
+ * R^i = E_c* R~ Q E_c*, R^ = prod_i R^i, built block-wise; staggered permutation P; second rotation).
+ * Runs once per layer, off the inference path.
+ *   Xcal     bf16 [T, K] device: calibration activations of the layer.
+ *   block    block size B of both rotations (multiple of 128, at most 1024, dividing K).
+ *   n_steps  greedy updates per block (>= 1).
+ *   Rtilde   double [B, B] device: the initial orthogonal matrix R~ (its first row should be constant 1/sqrt(B),
+ *            which spreads channel 0 evenly over the block).
+ *   Q1, Q2   double [K/B, n_steps, B, B] device: the orthogonal matrix Q of every block and step, for the
+ *            first and the second rotation (the paper draws them at random: the caller does, and passes them in).
+ *   R1, R2   bf16 [K/B, B, B] device, written; perm int32 [K] device, written (gather form): exactly the
+ *            arrays a LRQ_ROT_BLOCKPERM rotation takes.
+ *   ws       device workspace of lrq_ars_build_workspace_bytes(T, K, block) bytes.
+ * Step i of a block: c* = its channel with the largest |value| over the T tokens (first one on ties); E exchanges
+ * channels 0 and c*; activations and running product are multiplied, left to right, by E, R~, Q[i], E.  P: channels
+ * sorted by range max - min of Xcal.R1 (descending, ties by index) and dealt across the blocks left to right on
+ * even rounds, right to left on odd rounds.  All sums run term by term in ascending index with separately rounded
+ * fp64 multiply and add; the working state stays fp64 and only R1, R2 are rounded (once) to bf16.
+ * Errors: LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP.
+ */
+size_t lrq_ars_build_workspace_bytes(int T, int K, int block);
+int lrq_ars_build_rotation(void* stream, const void* Xcal, int T, int K, int block, int n_steps,
+                           const double* Rtilde, const double* Q1, const double* Q2, void* R1, int32_t* perm,
+                           void* R2, void* ws, size_t ws_bytes);
+
+/*
+ * Fluctuation metric of a layer's activations (paper: Method, Eq. J): J = ||X||_F / sqrt(M K) for X bf16 [M, K]
+ * (M = batch x tokens).  J_out: double[1] device, written.  ws: device workspace of
+ * lrq_fluctuation_workspace_bytes() bytes.  Requires (M K) % 8 == 0.  The sum of squares is taken in fp64 in a
+ * fixed order (the same input gives the same bits on every run).
+ * lrq_ars_select (host only, launches nothing): the case equation that follows Eq. J - LRQ_ROT_HADAMARD when
+ * J < threshold, LRQ_ROT_BLOCKPERM otherwise (the paper uses threshold 1); LRQ_EINVAL if either argument is NaN.
+ */
+size_t lrq_fluctuation_workspace_bytes(void);
+int lrq_fluctuation_metric(void* stream, const void* X, int M, int K, double* J_out, void* ws, size_t ws_bytes);
+int lrq_ars_select(double J, double threshold);
+
+/*
  * Measurement probes (no counterpart in the paper; they calibrate the roofline on the device at hand).
  * lrq_probe_mfma_i8: `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent
  *   v_mfma_i32_32x32x32_i8; pattern 0 = all operand bytes 1, pattern 1 = pseudo-random operand bytes (the

@@ -22,7 +22,8 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_tlq_workspace_bytes", "lrq_tlq_quantize_pack", "lrq_ars_workspace_bytes",
            "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm", "lrq_probe_mfma_i8",
            "lrq_probe_copy", "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
-           "lrq_qlinear_asym")
+           "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
+           "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select")
 
 
 class LrqError(RuntimeError):
@@ -83,6 +84,13 @@ def lib() -> ctypes.CDLL:
     L.lrq_workspace_bytes_asym.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_qlinear_asym.restype = ci
     L.lrq_qlinear_asym.argtypes = L.lrq_qlinear.argtypes
+    L.lrq_ars_build_workspace_bytes.restype, L.lrq_ars_build_workspace_bytes.argtypes = sz, [ci, ci, ci]
+    L.lrq_ars_build_rotation.restype = ci
+    L.lrq_ars_build_rotation.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, sz]
+    L.lrq_fluctuation_workspace_bytes.restype, L.lrq_fluctuation_workspace_bytes.argtypes = sz, []
+    L.lrq_fluctuation_metric.restype = ci
+    L.lrq_fluctuation_metric.argtypes = [vp, vp, ci, ci, vp, vp, sz]
+    L.lrq_ars_select.restype, L.lrq_ars_select.argtypes = ci, [ctypes.c_double, ctypes.c_double]
     L.lrq_probe_mfma_i8.restype = ci
     L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     L.lrq_probe_copy.restype = ci
@@ -256,6 +264,45 @@ def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None, zero=None
                          _ptr(out))
     _check(st, "lrq_qgemm")
     return out
+
+
+def ars_build_rotation(Xcal, block: int, Rtilde, Q1, Q2) -> Rotation:
+    """lrq_ars_build_rotation: calibration activations bf16 [T, K], Rtilde fp64 [B, B], Q1/Q2 fp64
+    [K/B, n_steps, B, B] (all on the device) -> the "blockperm" Rotation (R1, perm, R2 device tensors)."""
+    import torch
+    assert Xcal.is_cuda and Xcal.dtype == torch.bfloat16 and Xcal.is_contiguous()
+    T, K = Xcal.shape
+    for a in (Rtilde, Q1, Q2):
+        assert a.is_cuda and a.dtype == torch.float64 and a.is_contiguous()
+    assert Q1.shape == Q2.shape and Q1.dim() == 4
+    n_steps = Q1.shape[1]
+    nb = K // block if block > 0 else 0
+    R1 = torch.empty((max(nb, 1), block, block), dtype=torch.bfloat16, device=Xcal.device)
+    R2 = torch.empty_like(R1)
+    perm = torch.empty(K, dtype=torch.int32, device=Xcal.device)
+    need = lib().lrq_ars_build_workspace_bytes(T, K, block)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=Xcal.device)
+    _check(lib().lrq_ars_build_rotation(_stream(), _ptr(Xcal), T, K, block, n_steps, _ptr(Rtilde), _ptr(Q1), _ptr(Q2),
+                                        _ptr(R1), _ptr(perm), _ptr(R2), _ptr(ws), ws.numel()), "lrq_ars_build_rotation")
+    return Rotation("blockperm", block=block, R1=R1, perm=perm, R2=R2)
+
+
+def fluctuation_metric(X):
+    """lrq_fluctuation_metric: X bf16 [M, K] on the device -> J as a device tensor double[1]."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    J = torch.empty(1, dtype=torch.float64, device=X.device)
+    ws = torch.empty(lib().lrq_fluctuation_workspace_bytes(), dtype=torch.uint8, device=X.device)
+    _check(lib().lrq_fluctuation_metric(_stream(), _ptr(X), M, K, _ptr(J), _ptr(ws), ws.numel()), "lrq_fluctuation_metric")
+    return J
+
+
+def ars_select(J: float, threshold: float = 1.0) -> str:
+    """lrq_ars_select: "hadamard" if J < threshold else "blockperm"."""
+    k = lib().lrq_ars_select(float(J), float(threshold))
+    _check(min(k, 0), "lrq_ars_select")
+    return {LRQ_ROT_HADAMARD: "hadamard", LRQ_ROT_BLOCKPERM: "blockperm"}[k]
 
 
 def probe_mfma_i8(pattern: int = 1, blocks: int = 2048, iters: int = 4096, reps: int = 5) -> float:

@@ -6,7 +6,7 @@ namespace {
 
 inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+using lrq::round256;
 
 constexpr int kMaxRowLds = 16384;   // a token row / weight row is staged in LDS as doubles
 
@@ -231,6 +231,43 @@ int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* r
 int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
                      const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
     return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, true);
+}
+
+size_t lrq_ars_build_workspace_bytes(int T, int K, int block) {
+    if (T <= 0 || K <= 0 || block <= 0 || K % block != 0) return 0;
+    return lrq::ars_build_workspace_bytes(T, K, block);
+}
+
+int lrq_ars_build_rotation(void* stream, const void* Xcal, int T, int K, int block, int n_steps, const double* Rtilde,
+                           const double* Q1, const double* Q2, void* R1, int32_t* perm, void* R2, void* ws,
+                           size_t ws_bytes) {
+    if (!Xcal || !Rtilde || !Q1 || !Q2 || !R1 || !perm || !R2 || T <= 0 || K <= 0 || block <= 0 || n_steps <= 0)
+        return LRQ_EINVAL;
+    if (!aligned16(Xcal) || !aligned16(Rtilde) || !aligned16(Q1) || !aligned16(Q2) || !aligned16(R1) ||
+        !aligned16(perm) || !aligned16(R2))
+        return LRQ_EINVAL;
+    if (block % 128 != 0 || block > 1024 || K % block != 0 || K > kMaxRowLds) return LRQ_EUNSUPPORTED;
+    if (!ws || !aligned16(ws) || ws_bytes < lrq::ars_build_workspace_bytes(T, K, block)) return LRQ_EWORKSPACE;
+    const hipError_t e = lrq::launch_ars_build_rotation(
+        static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(Xcal), T, K, block, n_steps, Rtilde, Q1, Q2,
+        static_cast<uint16_t*>(R1), perm, static_cast<uint16_t*>(R2), ws);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+size_t lrq_fluctuation_workspace_bytes(void) { return lrq::fluctuation_workspace_bytes(); }
+
+int lrq_fluctuation_metric(void* stream, const void* X, int M, int K, double* J_out, void* ws, size_t ws_bytes) {
+    if (!X || !J_out || M <= 0 || K <= 0 || !aligned16(X)) return LRQ_EINVAL;
+    if (((size_t)M * K) % 8 != 0) return LRQ_EUNSUPPORTED;
+    if (!ws || !aligned16(ws) || ws_bytes < lrq::fluctuation_workspace_bytes()) return LRQ_EWORKSPACE;
+    const hipError_t e = lrq::launch_fluctuation_metric(static_cast<hipStream_t>(stream),
+                                                        static_cast<const uint16_t*>(X), (size_t)M * K, J_out, ws);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_ars_select(double J, double threshold) {
+    if (J != J || threshold != threshold) return LRQ_EINVAL;
+    return J < threshold ? LRQ_ROT_HADAMARD : LRQ_ROT_BLOCKPERM;
 }
 
 int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out, double* ops_per_launch) {

@@ -8,6 +8,9 @@
 
 namespace lrq {
 
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+
 // ---- launchers implemented in the .hip files; each returns hipGetLastError() after the launch ----
 
 // Per-token quantizer description handed to the kernels by value (host-filled).
@@ -34,6 +37,14 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
 hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
                                          const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
                                          int8_t* q, float* scale, int32_t* zero);
+
+// Calibration: greedy block rotations R1, R2 and staggered permutation from calibration activations; metric J.
+size_t ars_build_workspace_bytes(int T, int K, int B);
+hipError_t launch_ars_build_rotation(hipStream_t st, const uint16_t* Xcal, int T, int K, int B, int n_steps,
+                                     const double* Rtilde, const double* Q1, const double* Q2, uint16_t* R1,
+                                     int32_t* perm, uint16_t* R2, void* ws);
+size_t fluctuation_workspace_bytes();
+hipError_t launch_fluctuation_metric(hipStream_t st, const uint16_t* X, size_t n, double* J, void* ws);
 
 hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,

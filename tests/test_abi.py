@@ -140,3 +140,37 @@ def test_structured_rotation_is_validated_on_the_host(L):
     assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(block=0), 8, P, P, P, need) == lrq.LRQ_EINVAL
     assert L.lrq_ars_rotate_quant(None, P, 16, 256, rot(block=64), 8, P, P, P, need) == lrq.LRQ_EUNSUPPORTED
     assert L.lrq_ars_rotate_quant(None, P, 16, 384, rot(block=256), 8, P, P, P, 1 << 30) == lrq.LRQ_EUNSUPPORTED
+
+
+def test_calibration_entry_points_validate_on_the_host(L):
+    P = 4096
+    need = L.lrq_ars_build_workspace_bytes(64, 256, 128)
+    assert need >= 2 * 64 * 256 * 8 + 256 * 128 * 8
+    assert L.lrq_ars_build_workspace_bytes(64, 250, 128) == 0
+    ok_args = (None, P, 64, 256, 128, 2, P, P, P, P, P, P, P, need)
+    def call(**kw):
+        a = list(ok_args)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return L.lrq_ars_build_rotation(*a)
+    assert call(_1=None) == lrq.LRQ_EINVAL               # Xcal
+    assert call(_6=None) == lrq.LRQ_EINVAL               # Rtilde
+    assert call(_10=None) == lrq.LRQ_EINVAL              # perm
+    assert call(_5=0) == lrq.LRQ_EINVAL                  # n_steps
+    assert call(_4=64) == lrq.LRQ_EUNSUPPORTED           # block not a multiple of 128
+    assert call(_3=384, _4=256) == lrq.LRQ_EUNSUPPORTED  # block does not divide K
+    assert call(_13=need - 1) == lrq.LRQ_EWORKSPACE
+    nj = L.lrq_fluctuation_workspace_bytes()
+    assert nj > 0
+    assert L.lrq_fluctuation_metric(None, None, 4, 64, P, P, nj) == lrq.LRQ_EINVAL
+    assert L.lrq_fluctuation_metric(None, P, 3, 3, P, P, nj) == lrq.LRQ_EUNSUPPORTED
+    assert L.lrq_fluctuation_metric(None, P, 4, 64, P, P, nj - 1) == lrq.LRQ_EWORKSPACE
+
+
+def test_threshold_rule_runs_on_the_host(L):
+    # Method, ARS case equation: Hadamard below the threshold, the dual transformation at or above it
+    assert L.lrq_ars_select(0.5, 1.0) == lrq.LRQ_ROT_HADAMARD
+    assert L.lrq_ars_select(1.0, 1.0) == lrq.LRQ_ROT_BLOCKPERM
+    assert L.lrq_ars_select(7.0, 1.0) == lrq.LRQ_ROT_BLOCKPERM
+    assert L.lrq_ars_select(float("nan"), 1.0) == lrq.LRQ_EINVAL
+    assert lrq.ars_select(0.2) == "hadamard" and lrq.ars_select(1.5) == "blockperm"

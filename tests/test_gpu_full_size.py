@@ -127,3 +127,23 @@ def test_zero_point_form_at_full_size(lrq, cfg, layer):
     ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref))
     y_s = bf16_bits_from_dev(Y[ridx][:, cidx].contiguous())
     assert rel_fro(oracle.bf16_bits_to_f64(y_s), ref16) <= 1e-3
+
+
+def test_structured_rotation_at_config_4_size(lrq):
+    """X.R1.P.R2 with 128-channel blocks on a config-4 layer that takes the outlier-aware branch, sampled rows."""
+    import torch
+    spec = [s for s in synth.config_layers(4) if s.rotation == "dense"][0]
+    B = 128
+    print(f"structured layer {spec.name} M={spec.M} K={spec.K} N={spec.N} B={B}", flush=True)
+    X = synth.make_activations(spec.M, spec.K, spec.key, spec.p_mild, spec.n_salient, spec.gain)
+    R1 = synth.make_block_rotations(spec.K, B, spec.key, 0)
+    R2 = synth.make_block_rotations(spec.K, B, spec.key, 1)
+    perm = synth.make_channel_permutation(spec.K, spec.key)
+    rot = lrq.Rotation("blockperm", block=B, R1=bf16_to_dev(R1), perm=to_dev(perm), R2=bf16_to_dev(R2))
+    q, sc = lrq.ars_rotate_quant(bf16_to_dev(X), rot, spec.a_bits)
+    torch.cuda.synchronize()
+    rows = _sample(spec.M, N_ROWS, spec.key)
+    ridx = torch.from_numpy(rows).to(q.device)
+    q_ref, s_ref = oracle.ars_rotate_quant(X[rows], spec.a_bits, "blockperm", blockperm=(R1, perm, R2))
+    assert np.array_equal(q[ridx].cpu().numpy(), q_ref)
+    assert np.array_equal(sc[ridx].cpu().numpy(), s_ref)

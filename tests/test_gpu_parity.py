@@ -136,6 +136,40 @@ def test_blockperm_qlinear_against_oracle(lrq):
     assert rel_fro(Y.cpu().numpy(), y_ref) <= 1e-3
 
 
+@pytest.mark.parametrize("T,K,B,n", [(96, 256, 128, 2), (333, 384, 128, 4), (64, 512, 256, 3)])
+def test_greedy_rotation_builder_bit_exact(lrq, T, K, B, n):
+    """Greedy block rotations, staggered permutation, second rotation (Method, equation R^i = E R~ Q E):
+    every output bit for bit, because both sides sum term by term in the same order."""
+    print(f"case builder T={T} K={K} B={B} n={n}", flush=True)
+    nb = K // B
+    key = (905, T, K)
+    X = synth.make_activations(T, K, key, 0.05, 6, 50.0)
+    Rt = synth.make_spreading_matrix(B)
+    Q1, Q2 = synth.make_step_rotations(nb, n, B, key, 0), synth.make_step_rotations(nb, n, B, key, 1)
+    R1_ref, perm_ref, R2_ref = oracle.build_outlier_rotation(oracle.bf16_bits_to_f64(X), B, Rt, Q1, Q2)
+    rot = lrq.ars_build_rotation(bf16_to_dev(X), B, to_dev(Rt), to_dev(Q1), to_dev(Q2))
+    assert np.array_equal(rot.perm.cpu().numpy(), perm_ref)
+    assert np.array_equal(bf16_bits_from_dev(rot.R1), oracle.f64_to_bf16_bits(R1_ref))
+    assert np.array_equal(bf16_bits_from_dev(rot.R2), oracle.f64_to_bf16_bits(R2_ref))
+    # and the built rotation drives the runtime path
+    q_ref, s_ref = oracle.ars_rotate_quant(X, 8, "blockperm", blockperm=(oracle.f64_to_bf16_bits(R1_ref), perm_ref,
+                                                                        oracle.f64_to_bf16_bits(R2_ref)))
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, 8)
+    assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
+
+
+@pytest.mark.parametrize("M,K", [(8, 64), (300, 1152), (4608, 3072)])
+def test_fluctuation_metric(lrq, M, K):
+    """J = ||X||_F / sqrt(M K) (Method, Eq. J); the sum order differs from numpy's, so 1e-13 relative."""
+    X = synth.make_activations(M, K, (906, M, K), 0.05, 4, 40.0)
+    J = float(lrq.fluctuation_metric(bf16_to_dev(X)).cpu()[0])
+    J_ref = oracle.fluctuation_J(X)
+    assert abs(J - J_ref) <= 1e-13 * J_ref
+    assert lrq.ars_select(J, 1.0) == {"hadamard": "hadamard", "outlier-aware": "blockperm"}[oracle.select_rotation(J_ref, 1.0)]
+    J2 = float(lrq.fluctuation_metric(bf16_to_dev(X)).cpu()[0])
+    assert J2 == J                                       # fixed summation order: same bits on every run
+
+
 # ------------------------------------------------------------------ TLQ calibrate + pack
 def _check_weight(lrq, W, bits, I=7, alpha=GRID, beta=GRID):
     p = oracle.tlq_calibrate(W, bits, alpha, beta)
