@@ -15,7 +15,8 @@ What follows the paper and where:
                  permutation) and the greedy builder of R1, P, R2 from calibration
                  activations (equation R^i = E R~ Q E).
 * calib.py     - fluctuation metric J and the threshold rule that picks a layer's
-                 rotation (Method, Eq. J and the ARS case equation).
+                 rotation (Method, Eq. J and the ARS case equation); per-channel
+                 smoothing factor (Experiment, "Implementation Details").
 * actquant.py  - per-token dynamic uniform quantizer (Preliminaries, Eq. 1, in
                  its symmetric absmax form; Experiment, "Implementation Details":
                  per-token dynamic activations).
@@ -35,7 +36,7 @@ special cases and brute force.
 from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits  # noqa: F401
 from .rotation import (hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense, rotate_blockdiag,  # noqa: F401
                        rotate_blockperm, zigzag_permutation, greedy_block_rotation, build_outlier_rotation)
-from .calib import fluctuation_J, select_rotation  # noqa: F401
+from .calib import fluctuation_J, select_rotation, smoothing_factor, smooth_weights  # noqa: F401
 from .actquant import quantize_per_token, quantize_per_token_asym  # noqa: F401
 from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
                   tlq_level_values, tlq_lut, pack_codes, unpack_codes)

@@ -15,11 +15,15 @@ from .rotation import rotate_blockperm, rotate_dense, rotate_hadamard
 from .tlq import TLQParams, tlq_calibrate, tlq_encode, tlq_lut
 
 
-def _rotate(X_bits, rotation, had_block, R_bits, blockperm=None):
+def _rotate(X_bits, rotation, had_block, R_bits, blockperm=None, prescale=None):
     """(u fp64 [M, K], norm) for the layer's rotation choice (Method, ARS case equation).
     rotation: "none" | "hadamard" | "dense" (R_bits: bf16 bit patterns [K, K]) | "blockperm" (blockperm =
-    (R1_bits [nb, B, B], perm [K], R2_bits [nb, B, B]): the structured form X . R1 . P . R2)."""
+    (R1_bits [nb, B, B], perm [K], R2_bits [nb, B, B]): the structured form X . R1 . P . R2).
+    prescale: optional fp32 [K], the reciprocal smoothing factor; x is multiplied by it channel-wise first (each
+    product of a bf16 and an fp32 value is exact in fp64)."""
     x = bf16_bits_to_f64(X_bits)
+    if prescale is not None:
+        x = x * np.asarray(prescale, dtype=np.float32).astype(np.float64)[None, :]
     if rotation == "hadamard":
         return rotate_hadamard(x, had_block), np.sqrt(np.float64(had_block))
     if rotation == "dense":
@@ -31,17 +35,17 @@ def _rotate(X_bits, rotation, had_block, R_bits, blockperm=None):
     return x, 1.0
 
 
-def ars_rotate_quant(X_bits, a_bits, rotation, had_block=None, R_bits=None, blockperm=None):
-    """Rotate (per-layer choice) and quantize per token.
+def ars_rotate_quant(X_bits, a_bits, rotation, had_block=None, R_bits=None, blockperm=None, prescale=None):
+    """(Smooth,) rotate (per-layer choice) and quantize per token.
     X_bits: bf16 bit patterns [M, K].  Returns (q int8 [M, K], scale fp32 [M])."""
-    u, norm = _rotate(X_bits, rotation, had_block, R_bits, blockperm)
+    u, norm = _rotate(X_bits, rotation, had_block, R_bits, blockperm, prescale)
     return quantize_per_token(u, a_bits, norm)
 
 
-def ars_rotate_quant_asym(X_bits, a_bits, rotation, had_block=None, R_bits=None, blockperm=None):
-    """Rotate and quantize per token with the zero-point form of Eq. 1.
+def ars_rotate_quant_asym(X_bits, a_bits, rotation, had_block=None, R_bits=None, blockperm=None, prescale=None):
+    """(Smooth,) rotate and quantize per token with the zero-point form of Eq. 1.
     Returns (q int8 [M, K], scale fp32 [M], zero int32 [M]) with x_f = scale * (q + zero)."""
-    u, norm = _rotate(X_bits, rotation, had_block, R_bits, blockperm)
+    u, norm = _rotate(X_bits, rotation, had_block, R_bits, blockperm, prescale)
     return quantize_per_token_asym(u, a_bits, norm)
 
 
