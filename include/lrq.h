@@ -66,6 +66,9 @@ typedef struct {
     const void* R1;        /* LRQ_ROT_BLOCKPERM: bf16 [K/block, block, block] (device)  */
     const int32_t* perm;   /* LRQ_ROT_BLOCKPERM: int32 [K] (device)                     */
     const void* R2;        /* LRQ_ROT_BLOCKPERM: bf16 [K/block, block, block] (device)  */
+    const float* prescale; /* any kind: NULL, or fp32 [K] (device) multiplied into x channel by channel before the
+                              rotation - the reciprocal smoothing factor of lrq_smooth_factor (Experiment,
+                              "Implementation Details": difficulty migration from activations to weights)     */
 } lrq_rotation;
 
 /*
@@ -226,6 +229,23 @@ size_t lrq_ars_build_workspace_bytes(int T, int K, int block);
 int lrq_ars_build_rotation(void* stream, const void* Xcal, int T, int K, int block, int n_steps,
                            const double* Rtilde, const double* Q1, const double* Q2, void* R1, int32_t* perm,
                            void* R2, void* ws, size_t ws_bytes);
+
+/*
+ * Smoothing factor with migration strength alpha (paper: Experiment, "Implementation Details", strength 0.5; the
+ * factor is the cited SmoothQuant one): per input channel c
+ *     s_c = max_t |Xcal[t,c]|^alpha / max_n |W[n,c]|^(1-alpha)          (s_c = 1 if either maximum is 0)
+ * evaluated in fp64 (alpha == 0.5 as sqrt(a / w), otherwise with pow).  Runs once per layer, off the inference path.
+ *   Xcal bf16 [T, K], W fp32 [N, K] device inputs.
+ *   s     fp32 [K] device, written: fp32(s_c).
+ *   inv_s fp32 [K] device, written: fp32(1 / s_c) - the `prescale` of lrq_rotation.
+ *   W_out fp32 [N, K] device or NULL: if given, receives W[n,c] * s[c] (one fp32 multiplication; may alias W) -
+ *         the smoothed weights that then go through the rotation and lrq_tlq_quantize_pack.
+ *   ws    device workspace of lrq_smooth_workspace_bytes(K) bytes.
+ * Requires K % 8 == 0.  Errors: LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP.
+ */
+size_t lrq_smooth_workspace_bytes(int K);
+int lrq_smooth_factor(void* stream, const void* Xcal, int T, const float* W, int N, int K, double alpha, float* s,
+                      float* inv_s, float* W_out, void* ws, size_t ws_bytes);
 
 /*
  * Fluctuation metric of a layer's activations (paper: Method, Eq. J): J = ||X||_F / sqrt(M K) for X bf16 [M, K]

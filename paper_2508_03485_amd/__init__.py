@@ -23,7 +23,8 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm", "lrq_probe_mfma_i8",
            "lrq_probe_copy", "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
-           "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select")
+           "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
+           "lrq_smooth_workspace_bytes", "lrq_smooth_factor")
 
 
 class LrqError(RuntimeError):
@@ -34,7 +35,8 @@ class LrqError(RuntimeError):
 
 class _Rotation(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("had_block", ctypes.c_int), ("R", ctypes.c_void_p),
-                ("block", ctypes.c_int), ("R1", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("R2", ctypes.c_void_p)]
+                ("block", ctypes.c_int), ("R1", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("R2", ctypes.c_void_p),
+                ("prescale", ctypes.c_void_p)]
 
 
 class _TlqWeight(ctypes.Structure):
@@ -91,6 +93,9 @@ def lib() -> ctypes.CDLL:
     L.lrq_fluctuation_metric.restype = ci
     L.lrq_fluctuation_metric.argtypes = [vp, vp, ci, ci, vp, vp, sz]
     L.lrq_ars_select.restype, L.lrq_ars_select.argtypes = ci, [ctypes.c_double, ctypes.c_double]
+    L.lrq_smooth_workspace_bytes.restype, L.lrq_smooth_workspace_bytes.argtypes = sz, [ci]
+    L.lrq_smooth_factor.restype = ci
+    L.lrq_smooth_factor.argtypes = [vp, vp, ci, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz]
     L.lrq_probe_mfma_i8.restype = ci
     L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     L.lrq_probe_copy.restype = ci
@@ -127,12 +132,13 @@ class Rotation:
     R1: object = None       # torch bf16 [K/block, block, block] on the device
     perm: object = None     # torch int32 [K] on the device (gather form)
     R2: object = None       # torch bf16 [K/block, block, block] on the device
+    prescale: object = None # any kind: torch fp32 [K] on the device multiplied into x before the rotation
 
     def c_struct(self) -> _Rotation:
         kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE,
                  "blockperm": LRQ_ROT_BLOCKPERM}
         return _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R), int(self.block), _ptr(self.R1),
-                         _ptr(self.perm), _ptr(self.R2))
+                         _ptr(self.perm), _ptr(self.R2), _ptr(self.prescale))
 
 
 class TLQWeight:
@@ -285,6 +291,22 @@ def ars_build_rotation(Xcal, block: int, Rtilde, Q1, Q2) -> Rotation:
     _check(lib().lrq_ars_build_rotation(_stream(), _ptr(Xcal), T, K, block, n_steps, _ptr(Rtilde), _ptr(Q1), _ptr(Q2),
                                         _ptr(R1), _ptr(perm), _ptr(R2), _ptr(ws), ws.numel()), "lrq_ars_build_rotation")
     return Rotation("blockperm", block=block, R1=R1, perm=perm, R2=R2)
+
+
+def smooth_factor(Xcal, W, alpha: float = 0.5, smooth_weights: bool = True):
+    """lrq_smooth_factor: Xcal bf16 [T, K], W fp32 [N, K] on the device -> (s fp32 [K], inv_s fp32 [K],
+    W * s fp32 [N, K] or None)."""
+    import torch
+    assert Xcal.is_cuda and Xcal.dtype == torch.bfloat16 and Xcal.is_contiguous()
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and W.shape[1] == Xcal.shape[1]
+    T, K = Xcal.shape
+    s = torch.empty(K, dtype=torch.float32, device=W.device)
+    inv = torch.empty_like(s)
+    Wout = torch.empty_like(W) if smooth_weights else None
+    ws = torch.empty(max(lib().lrq_smooth_workspace_bytes(K), 16), dtype=torch.uint8, device=W.device)
+    _check(lib().lrq_smooth_factor(_stream(), _ptr(Xcal), T, _ptr(W), W.shape[0], K, float(alpha), _ptr(s), _ptr(inv),
+                                   _ptr(Wout), _ptr(ws), ws.numel()), "lrq_smooth_factor")
+    return s, inv, Wout
 
 
 def fluctuation_metric(X):

@@ -195,6 +195,46 @@ __global__ void j_finish_kernel(const double* __restrict__ part, int nparts, dou
     }
 }
 
+// Column maxima of |a| for a [rows, K] matrix of bf16 or fp32: keys are the bit patterns of |a| as fp32 (monotone
+// for non-negative floats), merged with atomicMax; keys must be zeroed first.  One thread per channel.
+template <typename T>
+__global__ void col_absmax_kernel(const T* __restrict__ A, int rows, int K, unsigned* __restrict__ keys) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= K) return;
+    const int per = (rows + gridDim.y - 1) / gridDim.y;
+    const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
+    unsigned m = 0u;
+    for (int r = r0; r < r1; ++r) {
+        unsigned b;
+        if constexpr (sizeof(T) == 2) b = ((unsigned)A[(size_t)r * K + c] << 16) & 0x7fffffffu;
+        else b = __float_as_uint(A[(size_t)r * K + c]) & 0x7fffffffu;
+        m = max(m, b);
+    }
+    if (r0 < r1) atomicMax(&keys[c], m);
+}
+
+__global__ void zero_u32_kernel(unsigned* __restrict__ p, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+__global__ void smooth_factor_kernel(const unsigned* __restrict__ akey, const unsigned* __restrict__ wkey, int K,
+                                     double alpha, float* __restrict__ s_out, float* __restrict__ inv_out) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= K) return;
+    const double a = (double)__uint_as_float(akey[c]), w = (double)__uint_as_float(wkey[c]);
+    double s = 1.0;
+    if (a > 0.0 && w > 0.0) s = (alpha == 0.5) ? sqrt(a / w) : pow(a, alpha) / pow(w, 1.0 - alpha);
+    s_out[c] = (float)s;
+    inv_out[c] = (float)(1.0 / s);
+}
+
+__global__ void scale_columns_kernel(const float* __restrict__ W, const float* __restrict__ s, size_t n, int K,
+                                     float* __restrict__ out) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) out[i] = W[i] * s[i % K];
+}
+
 inline int blocks_for(size_t n, int per = 256, int cap = 4096) {
     const size_t b = (n + per - 1) / per;
     return (int)(b < 1 ? 1 : (b > (size_t)cap ? (size_t)cap : b));
@@ -251,6 +291,24 @@ hipError_t launch_ars_build_rotation(hipStream_t st, const uint16_t* Xcal, int T
     hipLaunchKernelGGL(zigzag_perm_kernel, dim3((K + 255) / 256), dim3(256), 0, st, stats, K, B, perm);
     hipLaunchKernelGGL(permute_cols_f64_kernel, dim3(blocks_for(nY)), dim3(256), 0, st, Y, perm, T, K, Yp);
     greedy(Yp, Q2, R2);
+    return hipGetLastError();
+}
+
+size_t smooth_workspace_bytes(int K) { return round256(2 * (size_t)K * sizeof(unsigned)); }
+
+hipError_t launch_smooth_factor(hipStream_t st, const uint16_t* Xcal, int T, const float* W, int N, int K, double alpha,
+                                float* s, float* inv_s, float* W_out, void* ws) {
+    unsigned* akey = static_cast<unsigned*>(ws);
+    unsigned* wkey = akey + K;
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(blocks_for(2 * (size_t)K)), dim3(256), 0, st, akey, 2 * (size_t)K);
+    auto slices = [](int rows) { const int v = rows / 64; return v < 1 ? 1 : (v > 64 ? 64 : v); };
+    hipLaunchKernelGGL((col_absmax_kernel<uint16_t>), dim3((K + 255) / 256, slices(T)), dim3(256), 0, st, Xcal, T, K, akey);
+    hipLaunchKernelGGL((col_absmax_kernel<float>), dim3((K + 255) / 256, slices(N)), dim3(256), 0, st, W, N, K, wkey);
+    hipLaunchKernelGGL(smooth_factor_kernel, dim3((K + 255) / 256), dim3(256), 0, st, akey, wkey, K, alpha, s, inv_s);
+    if (W_out) {
+        const size_t n = (size_t)N * K;
+        hipLaunchKernelGGL(scale_columns_kernel, dim3(blocks_for(n)), dim3(256), 0, st, W, s, n, K, W_out);
+    }
     return hipGetLastError();
 }
 

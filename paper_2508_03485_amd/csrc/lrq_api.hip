@@ -12,6 +12,7 @@ constexpr int kMaxRowLds = 16384;   // a token row / weight row is staged in LDS
 
 int check_rotation(const lrq_rotation* rot, int K) {
     if (!rot) return LRQ_EINVAL;
+    if (rot->prescale && !aligned16(rot->prescale)) return LRQ_EINVAL;
     switch (rot->kind) {
         case LRQ_ROT_NONE:
             return K <= kMaxRowLds ? LRQ_OK : LRQ_EUNSUPPORTED;
@@ -68,20 +69,21 @@ int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rota
     const uint16_t* x = static_cast<const uint16_t*>(X);
     switch (rot->kind) {
         case LRQ_ROT_NONE:
-            e = lrq::launch_plain_quant(st, x, M, K, act_bits, q, scale, zero);
+            e = lrq::launch_plain_quant(st, x, M, K, act_bits, q, scale, zero, rot->prescale);
             break;
         case LRQ_ROT_HADAMARD:
-            e = lrq::launch_hadamard_quant(st, x, M, K, rot->had_block, act_bits, q, scale, zero);
+            e = lrq::launch_hadamard_quant(st, x, M, K, rot->had_block, act_bits, q, scale, zero, rot->prescale);
             break;
         case LRQ_ROT_BLOCKPERM:
             e = lrq::launch_blockperm_rotate_quant(
                 st, x, M, K, rot->block, static_cast<const uint16_t*>(rot->R1), rot->perm,
                 static_cast<const uint16_t*>(rot->R2), act_bits, static_cast<double*>(ws),
-                reinterpret_cast<float*>(static_cast<char*>(ws) + ars_layout(M, K, rot).zp_off), q, scale, zero);
+                reinterpret_cast<float*>(static_cast<char*>(ws) + ars_layout(M, K, rot).zp_off), q, scale, zero,
+                rot->prescale);
             break;
         default:
             e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
-                                               static_cast<double*>(ws), q, scale, zero);
+                                               static_cast<double*>(ws), q, scale, zero, rot->prescale);
             break;
     }
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
@@ -251,6 +253,19 @@ int lrq_ars_build_rotation(void* stream, const void* Xcal, int T, int K, int blo
     const hipError_t e = lrq::launch_ars_build_rotation(
         static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(Xcal), T, K, block, n_steps, Rtilde, Q1, Q2,
         static_cast<uint16_t*>(R1), perm, static_cast<uint16_t*>(R2), ws);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+size_t lrq_smooth_workspace_bytes(int K) { return K > 0 ? lrq::smooth_workspace_bytes(K) : 0; }
+
+int lrq_smooth_factor(void* stream, const void* Xcal, int T, const float* W, int N, int K, double alpha, float* s,
+                      float* inv_s, float* W_out, void* ws, size_t ws_bytes) {
+    if (!Xcal || !W || !s || !inv_s || T <= 0 || N <= 0 || K <= 0 || alpha != alpha) return LRQ_EINVAL;
+    if (!aligned16(Xcal) || !aligned16(W) || !aligned16(s) || !aligned16(inv_s) || !aligned16(W_out)) return LRQ_EINVAL;
+    if (K % 8 != 0 || alpha < 0.0 || alpha > 1.0) return LRQ_EUNSUPPORTED;
+    if (!ws || !aligned16(ws) || ws_bytes < lrq::smooth_workspace_bytes(K)) return LRQ_EWORKSPACE;
+    const hipError_t e = lrq::launch_smooth_factor(static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(Xcal),
+                                                   T, W, N, K, alpha, s, inv_s, W_out, ws);
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 

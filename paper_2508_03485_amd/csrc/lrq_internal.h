@@ -19,30 +19,36 @@ struct QuantSpec {
     double qmax, norm;      // symmetric: 2^(a-1) - 1 and qmax * sqrt(h)
     double L, half, sqrt_h; // zero-point form: 2^a - 1, 2^(a-1), sqrt(h)
     int32_t* zero;          // zero-point form: output [M]
+    const float* prescale;  // per-channel factor applied to x before the rotation ([K], nullptr = none)
 };
 
 // u = x.(I (x) H_h) in fp64, per-token statistics, round to codes.  K % 8 == 0, h | K, h power of two.
 // zero == nullptr selects the symmetric quantizer, otherwise the zero-point form (zero receives z + 2^(a-1)).
+// prescale (every launcher): nullptr, or fp32 [K] multiplied into x channel-wise before the rotation.
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale, int32_t* zero);
+                                 int8_t* q, float* scale, int32_t* zero, const float* prescale);
 // u = x (no rotation), same quantizer.
 hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, int act_bits,
-                              int8_t* q, float* scale, int32_t* zero);
+                              int8_t* q, float* scale, int32_t* zero, const float* prescale);
 // u = x.R in fp64 (k ascending), written to U [M,K] doubles, then quantized from U.
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
-                                     int act_bits, double* U, int8_t* q, float* scale, int32_t* zero);
+                                     int act_bits, double* U, int8_t* q, float* scale, int32_t* zero,
+                                     const float* prescale);
 
 // u = ((x.R1).P).R2 with block-diagonal R1, R2 (bf16 [K/B,B,B]), fp32 intermediate, perm in gather form; U [M,K]
 // doubles and Zp [M,K] floats are scratch.  B % 128 == 0, B | K.
 hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
                                          const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
-                                         int8_t* q, float* scale, int32_t* zero);
+                                         int8_t* q, float* scale, int32_t* zero, const float* prescale);
 
 // Calibration: greedy block rotations R1, R2 and staggered permutation from calibration activations; metric J.
 size_t ars_build_workspace_bytes(int T, int K, int B);
 hipError_t launch_ars_build_rotation(hipStream_t st, const uint16_t* Xcal, int T, int K, int B, int n_steps,
                                      const double* Rtilde, const double* Q1, const double* Q2, uint16_t* R1,
                                      int32_t* perm, uint16_t* R2, void* ws);
+size_t smooth_workspace_bytes(int K);
+hipError_t launch_smooth_factor(hipStream_t st, const uint16_t* Xcal, int T, const float* W, int N, int K, double alpha,
+                                float* s, float* inv_s, float* W_out, void* ws);
 size_t fluctuation_workspace_bytes();
 hipError_t launch_fluctuation_metric(hipStream_t st, const uint16_t* X, size_t n, double* J, void* ws);
 

@@ -23,6 +23,13 @@ __device__ __forceinline__ void load8_bf16(const uint16_t* __restrict__ p, doubl
     }
 }
 
+// v[i] *= ps[i] for 8 consecutive channels: a bf16 value times an fp32 value is exact in fp64.
+__device__ __forceinline__ void prescale8(const float* __restrict__ ps, double v[8]) {
+    const float4 a = reinterpret_cast<const float4*>(ps)[0], b = reinterpret_cast<const float4*>(ps)[1];
+    v[0] *= (double)a.x; v[1] *= (double)a.y; v[2] *= (double)a.z; v[3] *= (double)a.w;
+    v[4] *= (double)b.x; v[5] *= (double)b.y; v[6] *= (double)b.z; v[7] *= (double)b.w;
+}
+
 // n-point butterfly network on v[0..n), ascending strides first_stride, 2*first_stride, ... for `stages`
 // stages, (a, b) -> (a + b, a - b).
 template <int N, int FIRST = 1>
@@ -159,6 +166,7 @@ __global__ void hadamard_quant_generic_kernel(const uint16_t* __restrict__ X, in
     for (int c = t; c < nchunks; c += nt) {
         double v[8];
         load8_bf16(X + base + (size_t)c * 8, v);
+        if (qs.prescale) prescale8(qs.prescale + c * 8, v);
         butterflies<8>(v, s0);
 #pragma unroll
         for (int i = 0; i < 8; ++i) row[c * 8 + i] = v[i];
@@ -238,6 +246,10 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
         const uint16_t* src = X + (size_t)lrow * K + (size_t)slot * E32;
 #pragma unroll
         for (int c = 0; c < 4; ++c) load8_bf16(src + c * 8, v + c * 8);
+        if (qs.prescale) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) prescale8(qs.prescale + slot * E32 + c * 8, v + c * 8);
+        }
     }
     constexpr int IN_REG = LOG2H < 5 ? LOG2H : 5;
     butterflies<E32>(v, IN_REG);
@@ -302,7 +314,7 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 // bf16 data while it transforms the current one.
 __device__ __forceinline__ int lds_row(int slot) { return 18 * slot + 4 * (slot >> 5); }
 
-template <int LOG2H, bool PERSIST, bool ASYM>
+template <int LOG2H, bool PERSIST, bool ASYM, bool PRE>
 __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
                                                                    int rows_per_wg, QuantSpec qs,
                                                                    int8_t* __restrict__ q, float* __restrict__ scale) {
@@ -346,6 +358,10 @@ __global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_
                 v[c * 8 + 2 * i] = (double)__uint_as_float(wd[i] << 16);
                 v[c * 8 + 2 * i + 1] = (double)__uint_as_float(wd[i] & 0xffff0000u);
             }
+        }
+        if constexpr (PRE) {     // a template flag: as a run-time branch it costs the other variants 80 registers
+#pragma unroll
+            for (int c = 0; c < 4; ++c) prescale8(qs.prescale + slot * E32 + c * 8, v + c * 8);
         }
         butterflies<E32>(v, 5);
 #pragma unroll
@@ -461,7 +477,7 @@ constexpr int DK = 16;   // K step
 
 __global__ __launch_bounds__(256) void dense_rotate_f64_kernel(const uint16_t* __restrict__ X,
                                                                 const uint16_t* __restrict__ R, int M, int K,
-                                                                double* __restrict__ U) {
+                                                                double* __restrict__ U, const float* __restrict__ ps) {
     __shared__ double Xs[DK][DT + 1];
     __shared__ double Rs[DK][DT];
     const int t = threadIdx.x;
@@ -483,6 +499,10 @@ __global__ __launch_bounds__(256) void dense_rotate_f64_kernel(const uint16_t* _
         Xs[xk + 1][xr] = (double)__uint_as_float(xa.x & 0xffff0000u);
         Xs[xk + 2][xr] = (double)__uint_as_float(xa.y << 16);
         Xs[xk + 3][xr] = (double)__uint_as_float(xa.y & 0xffff0000u);
+        if (ps) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) Xs[xk + i][xr] *= (double)ps[k0 + xk + i];
+        }
         Rs[rk][rc + 0] = (double)__uint_as_float(ra.x << 16);
         Rs[rk][rc + 1] = (double)__uint_as_float(ra.x & 0xffff0000u);
         Rs[rk][rc + 2] = (double)__uint_as_float(ra.y << 16);
@@ -527,7 +547,8 @@ constexpr int MT_ = 128, MK_ = 16, XP_ = MK_ + 1, RP_ = MT_ + 4;
 template <bool SRC_F32, bool OUT_F32>
 __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const void* __restrict__ src,
                                                                             const uint16_t* __restrict__ R, int M, int K,
-                                                                            int B, void* __restrict__ dst) {
+                                                                            int B, void* __restrict__ dst,
+                                                                            const float* __restrict__ ps) {
     __shared__ __attribute__((aligned(16))) double Xs[2][MT_ * XP_];     // [row][k], k contiguous, padded rows
     __shared__ __attribute__((aligned(16))) double Rs[2][MK_ * RP_];     // [k][col]
     const int t = threadIdx.x, lane = t % 64, wv = t / 64;
@@ -547,6 +568,7 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
     const size_t xoff = (size_t)xrow * K + kbase + xk;
     const uint16_t* rp = R + (size_t)g * B * B + (size_t)rk * B + cb + rc;
     uint4 xa, xb;                                                        // xb: second half of 8 fp32 values
+    float4 pa = make_float4(1.f, 1.f, 1.f, 1.f), pb = pa;                // per-channel pre-scale of the 8 values (bf16 source)
     auto load_x = [&](int kb) {
         if constexpr (SRC_F32) {
             const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(src) + xoff + (size_t)kb * MK_);
@@ -554,6 +576,11 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
             xb = p[1];
         } else {
             xa = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + xoff + (size_t)kb * MK_);
+            if (ps) {
+                const float4* p = reinterpret_cast<const float4*>(ps + kbase + xk + kb * MK_);
+                pa = p[0];
+                pb = p[1];
+            }
         }
     };
     load_x(0);
@@ -577,6 +604,11 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
                 for (int i = 0; i < 4; ++i) {
                     xd[2 * i] = (double)__uint_as_float(xw[i] << 16);
                     xd[2 * i + 1] = (double)__uint_as_float(xw[i] & 0xffff0000u);
+                }
+                if (ps) {
+                    const float pv[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) xd[i] *= (double)pv[i];
                 }
             }
 #pragma unroll
@@ -689,7 +721,7 @@ int threads_for_row(int K) {
 
 }  // namespace
 
-static QuantSpec make_spec(int act_bits, int h, int32_t* zero) {
+static QuantSpec make_spec(int act_bits, int h, int32_t* zero, const float* prescale = nullptr) {
     QuantSpec qs;
     qs.asym = zero != nullptr;
     qs.qmax = (double)((1 << (act_bits - 1)) - 1);
@@ -698,12 +730,13 @@ static QuantSpec make_spec(int act_bits, int h, int32_t* zero) {
     qs.L = (double)((1 << act_bits) - 1);
     qs.half = (double)(1 << (act_bits - 1));
     qs.zero = zero;
+    qs.prescale = prescale;
     return qs;
 }
 
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale, int32_t* zero) {
-    const QuantSpec qs = make_spec(act_bits, h, zero);
+                                 int8_t* q, float* scale, int32_t* zero, const float* prescale) {
+    const QuantSpec qs = make_spec(act_bits, h, zero, prescale);
     if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
         // R whole rows per workgroup, about five waves (finer granularity measured faster than nine)
         const int lpr = K / E32;
@@ -741,8 +774,8 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         const dim3 grid(persist ? 256 * per_cu : groups), block(nt);
         static bool attr2 = false;
         if (!attr2) {
-#define LRQ_ATTR(L, P, A) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A>), hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024); if (e != hipSuccess) return e; }
-#define LRQ_ATTR2(L, P) LRQ_ATTR(L, P, false) LRQ_ATTR(L, P, true)
+#define LRQ_ATTR(L, P, A, S) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A, S>), hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024); if (e != hipSuccess) return e; }
+#define LRQ_ATTR2(L, P) LRQ_ATTR(L, P, false, false) LRQ_ATTR(L, P, true, false) LRQ_ATTR(L, P, false, true) LRQ_ATTR(L, P, true, true)
             LRQ_ATTR2(8, false) LRQ_ATTR2(9, false) LRQ_ATTR2(10, false) LRQ_ATTR2(11, false) LRQ_ATTR2(12, false)
             LRQ_ATTR2(11, true) LRQ_ATTR2(12, true)
 #undef LRQ_ATTR2
@@ -751,8 +784,10 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         }
 #define LRQ_GO(L, P)                                                                                                      \
     {                                                                                                                     \
-        if (qs.asym) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);  \
-        else hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);         \
+        if (qs.asym && qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
+        else if (qs.asym) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, false>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);       \
+        else if (qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
+        else hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false, false>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);                   \
     }
         switch (ilog2(h)) {
             case 8: LRQ_GO(8, false) break;
@@ -778,19 +813,20 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
 }
 
 hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, int act_bits, int8_t* q,
-                              float* scale, int32_t* zero) {
-    return launch_hadamard_quant(st, X, M, K, 1, act_bits, q, scale, zero);
+                              float* scale, int32_t* zero, const float* prescale) {
+    return launch_hadamard_quant(st, X, M, K, 1, act_bits, q, scale, zero, prescale);
 }
 
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
-                                     int act_bits, double* U, int8_t* q, float* scale, int32_t* zero) {
+                                     int act_bits, double* U, int8_t* q, float* scale, int32_t* zero,
+                                     const float* prescale) {
     static const int use_mfma = [] { const char* e = getenv("LRQ_DENSE_MFMA"); return e ? atoi(e) : 1; }();
     if (use_mfma && K % MT_ == 0) {
         dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
-        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), grid, dim3(256), 0, st, X, R, M, K, K, U);
+        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), grid, dim3(256), 0, st, X, R, M, K, K, U, prescale);
     } else {
         dim3 grid(K / DT, (M + DT - 1) / DT);
-        hipLaunchKernelGGL(dense_rotate_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U);
+        hipLaunchKernelGGL(dense_rotate_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U, prescale);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -803,10 +839,10 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
 // U's storage), row permutation into Zp, block-diagonal product to fp64 U, then the per-token quantizer.
 hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
                                          const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
-                                         int8_t* q, float* scale, int32_t* zero) {
+                                         int8_t* q, float* scale, int32_t* zero, const float* prescale) {
     float* Z = reinterpret_cast<float*>(U);
     const dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
-    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z);
+    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z, prescale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     static bool attr_done = false;
@@ -820,7 +856,8 @@ hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int 
     hipLaunchKernelGGL(permute_rows_f32_kernel, dim3(pgrid), dim3(256), (size_t)K * sizeof(float), st, Z, perm, M, K, Zp);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<true, false>), grid, dim3(256), 0, st, Zp, R2, M, K, B, U);
+    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<true, false>), grid, dim3(256), 0, st, Zp, R2, M, K, B, U,
+                       static_cast<const float*>(nullptr));
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const QuantSpec qs = make_spec(act_bits, 1, zero);

@@ -174,3 +174,24 @@ def test_threshold_rule_runs_on_the_host(L):
     assert L.lrq_ars_select(7.0, 1.0) == lrq.LRQ_ROT_BLOCKPERM
     assert L.lrq_ars_select(float("nan"), 1.0) == lrq.LRQ_EINVAL
     assert lrq.ars_select(0.2) == "hadamard" and lrq.ars_select(1.5) == "blockperm"
+
+
+def test_smoothing_entry_point_validates_on_the_host(L):
+    P = 4096
+    need = L.lrq_smooth_workspace_bytes(256)
+    assert need >= 2 * 256 * 4
+    ok = [None, P, 32, P, 16, 256, 0.5, P, P, None, P, need]
+    def call(i=None, v=None):
+        a = list(ok)
+        if i is not None:
+            a[i] = v
+        return L.lrq_smooth_factor(*a)
+    assert call(1, None) == lrq.LRQ_EINVAL
+    assert call(7, None) == lrq.LRQ_EINVAL
+    assert call(6, float("nan")) == lrq.LRQ_EINVAL
+    assert call(6, 1.5) == lrq.LRQ_EUNSUPPORTED
+    assert call(5, 250) == lrq.LRQ_EUNSUPPORTED
+    assert call(11, need - 1) == lrq.LRQ_EWORKSPACE
+    # a misaligned pre-scale vector in the rotation struct
+    rot = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_HADAMARD, 128, None, 0, None, None, None, P + 4))
+    assert L.lrq_ars_rotate_quant(None, P, 4, 128, rot, 8, P, P, None, 0) == lrq.LRQ_EINVAL

@@ -170,6 +170,50 @@ def test_fluctuation_metric(lrq, M, K):
     assert J2 == J                                       # fixed summation order: same bits on every run
 
 
+@pytest.mark.parametrize("alpha", [0.5, 0.3])
+def test_smoothing_factor(lrq, alpha):
+    """Per-channel smoothing factor with migration strength alpha (Experiment, "Implementation Details")."""
+    T, N, K = 300, 200, 1152
+    X = synth.make_activations(T, K, (907, 0, 0), 0.05, 5, 40.0)
+    X[:, 17] = 0                                                     # a dead activation channel: factor 1
+    W = synth.make_weights(N, K, (907, 0, 1))
+    s_ref, inv_ref = oracle.smoothing_factor(X, W, alpha)
+    s, inv, Ws = lrq.smooth_factor(bf16_to_dev(X), to_dev(W), alpha)
+    s, inv, Ws = s.cpu().numpy(), inv.cpu().numpy(), Ws.cpu().numpy()
+    if alpha == 0.5:                                                 # division and square root: correctly rounded on both sides
+        assert np.array_equal(s, s_ref) and np.array_equal(inv, inv_ref)
+    else:                                                            # pow comes from two different math libraries
+        assert np.allclose(s, s_ref, rtol=2e-7, atol=0) and np.allclose(inv, inv_ref, rtol=2e-7, atol=0)
+    assert s[17] == 1.0 and inv[17] == 1.0
+    assert np.array_equal(Ws, oracle.smooth_weights(W, s))           # one fp32 multiplication per weight
+
+
+@pytest.mark.parametrize("M,K,kind,h", [(70, 1152, "hadamard", 128), (130, 4608, "hadamard", 512), (33, 192, "hadamard", 64),
+                                        (50, 4096, "hadamard", 4096), (64, 256, "none", 0), (90, 256, "dense", 0),
+                                        (75, 192, "dense", 0), (140, 384, "blockperm", 128)])
+def test_prescaled_rotate_quant_bit_exact(lrq, M, K, kind, h):
+    """The reciprocal smoothing factor multiplied into x ahead of every rotation kind."""
+    print(f"case prescale M={M} K={K} {kind} h={h}", flush=True)
+    X = _acts(M, K, 11 + K)
+    ps = (0.25 + synth.rng_for(908, M, K).random(K) * 3.0).astype(np.float32)
+    kw, okw = {}, {}
+    if kind == "dense":
+        R = synth.make_rotation(K, (908, K, 0))
+        kw, okw = dict(R=bf16_to_dev(R)), dict(R_bits=R)
+    if kind == "blockperm":
+        bp, rot0 = _blockperm_inputs(lrq, K, h, M)
+        kw, okw = dict(block=h, R1=rot0.R1, perm=rot0.perm, R2=rot0.R2), dict(blockperm=bp)
+    rot = lrq.Rotation(kind, had_block=h if kind == "hadamard" else 0, prescale=to_dev(ps), **kw)
+    for a_bits, asym in ((8, False), (4, True)):
+        if asym:
+            ref = oracle.ars_rotate_quant_asym(X, a_bits, kind, h, prescale=ps, **okw)
+        else:
+            ref = oracle.ars_rotate_quant(X, a_bits, kind, h, prescale=ps, **okw)
+        got = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, asym=asym)
+        for g, r in zip(got, ref):
+            assert np.array_equal(g.cpu().numpy(), r)
+
+
 # ------------------------------------------------------------------ TLQ calibrate + pack
 def _check_weight(lrq, W, bits, I=7, alpha=GRID, beta=GRID):
     p = oracle.tlq_calibrate(W, bits, alpha, beta)
