@@ -37,6 +37,12 @@ def parse():
     ap.add_argument("--structured", type=int, default=0, metavar="B",
                     help="run the layers that take the dense outlier-aware rotation with its structured form "
                          "X.R1.P.R2 instead (block size B, seeded block rotations and permutation)")
+    ap.add_argument("--smooth", action="store_true",
+                    help="give every layer a smoothing pre-scale (from lrq_smooth_factor on its own inputs), multiplied "
+                         "into the activations inside the rotate+quantize kernels")
+    ap.add_argument("--calibration", action="store_true",
+                    help="also time the calibration-time entry points (J metric, smoothing factor, greedy rotation "
+                         "builder) on the workload's first layer and report them under 'calibration'")
     ap.add_argument("--asym", action="store_true",
                     help="use the zero-point form of the activation quantizer (the paper's Eq. 1 as printed)")
     ap.add_argument("--probes-only", action="store_true",
@@ -107,6 +113,12 @@ def main():
             shape_cache[skey] = (X, w, R)
         X, w, R = shape_cache[skey]
         rot = R if isinstance(R, lrq.Rotation) else lrq.Rotation(s.rotation, s.had_block, R)
+        if args.smooth:
+            if "inv" not in shape_cache.setdefault(("smooth", skey), {}):
+                Wd = torch.from_numpy(synth.make_weights(s.N, s.K, s.key)).to(dev)
+                shape_cache[("smooth", skey)]["inv"] = lrq.smooth_factor(X[:1024], Wd, 0.5, smooth_weights=False)[1]
+                del Wd
+            rot.prescale = shape_cache[("smooth", skey)]["inv"]
         layers.append(dict(spec=s, X=[X], w=w, rot=rot))
     gen_s = time.time() - t_gen
 
@@ -222,10 +234,14 @@ def main():
                                      5: "config5: 28-block PixArt-style stack, W3A4, per-layer ARS"}[cfg],
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
                            outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
+                           smoothing_prescale=bool(args.smooth),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
+
+    if args.calibration:
+        out["calibration"] = calibration_timings(lrq, layers[0], dev)
 
     # what this device sustains on a pure int8 MFMA loop and on a plain copy kernel (context for the published peaks)
     out["measured_ceilings"] = dict(mfma_i8_tops_constant_operands=round(lrq.probe_mfma_i8(0), 1),
@@ -243,6 +259,45 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.cpu_rows, args.cpu_channels)
     print(json.dumps(out))
+
+
+def calibration_timings(lrq, layer, dev):
+    """Calibration-time entry points on the first layer's shapes: fluctuation metric J over the whole activation
+    matrix (HBM-bound: 2 bytes per element), smoothing factor, and the greedy rotation builder on 1024 tokens."""
+    import torch
+    import synth
+    s = layer["spec"]
+    X = layer["X"][0]
+
+    def timed(fn, n=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    j_ms = timed(lambda: lrq.fluctuation_metric(X), 20)
+    J = float(lrq.fluctuation_metric(X).cpu()[0])
+    W = torch.from_numpy(synth.make_weights(s.N, s.K, s.key)).to(dev)
+    T = min(1024, s.M)
+    sm_ms = timed(lambda: lrq.smooth_factor(X[:T], W, 0.5))
+    B, n = 128, 8
+    out = dict(layer=s.name, J=round(J, 4), selected=lrq.ars_select(J, 1.0), fluctuation_metric_ms=round(j_ms, 4),
+               fluctuation_metric_gbs=round(2.0 * s.M * s.K / (j_ms * 1e-3) / 1e9, 1),
+               smooth_factor_ms=round(sm_ms, 4), smooth_factor_tokens=T)
+    if s.K % B == 0:
+        nb = s.K // B
+        Rt = torch.from_numpy(synth.make_spreading_matrix(B)).to(dev)
+        Q1 = torch.from_numpy(synth.make_step_rotations(nb, n, B, s.key, 0)).to(dev)
+        Q2 = torch.from_numpy(synth.make_step_rotations(nb, n, B, s.key, 1)).to(dev)
+        Xc = X[:T].contiguous()
+        out.update(build_rotation_ms=round(timed(lambda: lrq.ars_build_rotation(Xc, B, Rt, Q1, Q2), 2), 2),
+                   build_rotation=dict(tokens=T, block=B, greedy_steps=n))
+    return out
 
 
 def cpu_baseline(specs, rows, channels):
