@@ -1,7 +1,7 @@
 // Decode + int8 MFMA GEMM + rescale (gfx950):
 //   Y[t,n] = scale_t * wscale_n * sum_k q[t,k] * lut_n[code[n,k]]  (+ bias_n)
-// Activation codes q (int8, [M,K]) are staged through LDS and shared by the four waves of a
-// workgroup; every wave owns its own 64 output channels, streams the packed 3/4-bit TLQ codes of
+// Activation codes q (int8, [M,K]) are staged through LDS (three rotating buffers) and shared by the four
+// waves of a workgroup; every wave owns its own 64 output channels, streams the packed 3/4-bit TLQ codes of
 // those channels straight from global memory into registers and decodes them there with a per-lane
 // level table (byte permutes), so decoded weights never touch LDS.  v_mfma_i32_32x32x32_i8 does the
 // contraction with int32 accumulation ("SpeedUp and Latency": INT8 x INT8, higher-precision accumulate).
@@ -91,20 +91,24 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
     return u >> 16;
 }
 
-// One K block of the main loop.  On entry: Acur holds A tile kb, aS holds tile kb+1 (staged into Anxt, then
-// reloaded with tile kb+3), bCur holds B block kb (its MFMA step 0 already decoded in bd0; reloaded with block
-// kb+2 once step 1 is decoded), bNxt holds block kb+1 whose step 0 is decoded into bd0 while step 1 multiplies.
+// One K block of the main loop.  The A tiles rotate through three LDS buffers: block kb multiplies from `cur`
+// (tile kb), stages tile kb+2 (held in aS, which is then reloaded with tile kb+4) into `st`, and - because tile kb+1
+// in `nx` has been complete since the previous barrier - reads the first A fragments of block kb+1 before its own
+// closing barrier, so that the next block starts on the matrix cores without waiting for LDS.
+// bCur holds B block kb (its MFMA step 0 already decoded in bd0; reloaded with block kb+2 once step 1 is decoded),
+// bNxt holds block kb+1 whose step 0 is decoded into bd0 while step 1 multiplies.
 // Decode work is spread evenly between the MFMAs so that it issues in their shadow.
 template <int BITS, int MT, int NTW, int ALOADS>
-__device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char* Anxt, v4i (&aS)[ALOADS],
+__device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int nx, v4i (&aS)[ALOADS],
                                        BRaw<BITS> (&bCur)[NTW], const BRaw<BITS> (&bNxt)[NTW], int kb, int KB,
                                        const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
                                        const uint8_t* const (&bptr)[NTW], const unsigned (&L)[NTW][4], unsigned C,
-                                       v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off) {
+                                       v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off, v4i (&afp)[LRQ_AF_DIST]) {
     constexpr int UNIT = 64 * (BITS == 4 ? 16 : 12);
+    const unsigned char* Acur = smem + cur;
 #pragma unroll
-    for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&Anxt[aoff[i]]) = aS[i];
-    const int ka = kb + 3 < KB ? kb + 3 : KB - 1;
+    for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&smem[st + aoff[i]]) = aS[i];
+    const int ka = kb + 4 < KB ? kb + 4 : KB - 1;
     const int kbn = kb + 2 < KB ? kb + 2 : KB - 1;
 #pragma unroll
     for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * BK);
@@ -112,11 +116,15 @@ __device__ __forceinline__ void kblock(const unsigned char* Acur, unsigned char*
     constexpr int DPB = (NTW * 4 + MT - 1) / MT;       // operand dwords decoded per MFMA row tile
     constexpr int DIST = LRQ_AF_DIST;                   // A fragments are read this many MFMA groups ahead
 #pragma unroll
-    for (int p = 0; p < DIST; ++p)
-        af[p] = *reinterpret_cast<const v4i*>(&Acur[((p % MT) * 4 + (p / MT) * 2) * PLANE + rd_off]);
+    for (int p = 0; p < DIST; ++p) af[p] = afp[p];
 #pragma unroll
     for (int p = 0; p < 2 * MT; ++p) {
         const int s = p / MT, i = p % MT;
+        if (p == 2 * MT - 2) {      // next block's first fragments, early enough to land before the closing barrier
+#pragma unroll
+            for (int pp = 0; pp < DIST; ++pp)
+                afp[pp] = *reinterpret_cast<const v4i*>(&smem[nx + ((pp % MT) * 4 + (pp / MT) * 2) * PLANE + rd_off]);
+        }
         if (p + DIST < 2 * MT) {
             const int s2 = (p + DIST) / MT, i2 = (p + DIST) % MT;
             af[p + DIST] = *reinterpret_cast<const v4i*>(&Acur[(i2 * 4 + s2 * 2) * PLANE + rd_off]);
@@ -163,7 +171,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     constexpr int WN = 32 * NTW, BN = WAVES * WN;
     constexpr int ABUF = MT * 4 * PLANE;
     constexpr int ALOADS = BM * 4 / 256;        // 16-byte chunks of the A tile per thread
-    constexpr int LDS_BYTES = (2 * ABUF > WAVES * EPI_WAVE) ? 2 * ABUF : WAVES * EPI_WAVE;
+    constexpr int LDS_BYTES = (3 * ABUF > WAVES * EPI_WAVE) ? 3 * ABUF : WAVES * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
     __shared__ float sc[BM];
     __shared__ int zr[BM];          // per-token zero-points (zero-point form only)
@@ -234,17 +242,20 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // ---- prologue: A tile 0 -> LDS buffer 0; A tiles 1 (aO), 2 (aE) and B blocks 0 (bE), 1 (bO) in registers
+    // ---- prologue: A tiles 0, 1 -> LDS buffers 0, 1; A tiles 2 (aO), 3 (aE) and B blocks 0 (bE), 1 (bO) in registers
     unsigned C = 0x03020100u;
     asm volatile("" : "+v"(C));
     v4i aO[ALOADS], aE[ALOADS];
     BRaw<BITS> bE[NTW], bO[NTW];
     v4i bd0[NTW];
     {
-        v4i a0[ALOADS];
+        v4i a0[ALOADS], a1[ALOADS];
+        const int k1 = KB > 1 ? 1 : 0, k2 = KB > 2 ? 2 : KB - 1, k3 = KB > 3 ? 3 : KB - 1;
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) a0[i] = *reinterpret_cast<const v4i*>(aptr[i]);
-        const int k1 = KB > 1 ? 1 : 0, k2 = KB > 2 ? 2 : KB - 1;
+        for (int i = 0; i < ALOADS; ++i) {
+            a0[i] = *reinterpret_cast<const v4i*>(aptr[i]);
+            a1[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k1 * BK);
+        }
 #pragma unroll
         for (int j = 0; j < NTW; ++j) {
             bE[j] = load_braw<BITS>(bptr[j]);
@@ -252,11 +263,14 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         }
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
-            aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k1 * BK);
-            aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * BK);
+            aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * BK);
+            aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k3 * BK);
         }
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&smem[aoff[i]]) = a0[i];
+        for (int i = 0; i < ALOADS; ++i) {
+            *reinterpret_cast<v4i*>(&smem[aoff[i]]) = a0[i];
+            *reinterpret_cast<v4i*>(&smem[ABUF + aoff[i]]) = a1[i];
+        }
 #pragma unroll
         for (int j = 0; j < NTW; ++j)
 #pragma unroll
@@ -265,11 +279,20 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     __syncthreads();
 
     const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
+    v4i afp[LRQ_AF_DIST];
+#pragma unroll
+    for (int p = 0; p < LRQ_AF_DIST; ++p)
+        afp[p] = *reinterpret_cast<const v4i*>(&smem[((p % MT) * 4 + (p / MT) * 2) * PLANE + rd_off]);
 
+    int o0 = 0, o1 = ABUF, o2 = 2 * ABUF;       // LDS buffers of tiles kb, kb+1, kb+2
     for (int kb = 0; kb < KB; kb += 2) {
-        kblock<BITS, MT, NTW, ALOADS>(smem, smem + ABUF, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
+        kblock<BITS, MT, NTW, ALOADS>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
         if (kb + 1 < KB)
-            kblock<BITS, MT, NTW, ALOADS>(smem + ABUF, smem, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off);
+            kblock<BITS, MT, NTW, ALOADS>(smem, o1, o0, o2, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        const int t0 = o0;      // two blocks done: tiles kb+2, kb+3, kb+4 live in o2, o0, o1
+        o0 = o2;
+        o2 = o1;
+        o1 = t0;
     }
 
     // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS (wave-private, so only wave-level
