@@ -2,8 +2,9 @@
  * lrq.h - C ABI of the MI355X (gfx950) quantized-linear hot path of LRQ-DiT.
  *
  * The library implements one W-A-quantized linear layer of a Diffusion Transformer:
- *   activations  -> Adaptive Rotation Scheme (Hadamard, or a dense outlier-aware rotation, chosen per
- *                   layer) -> per-token uniform quantization to 4/8-bit codes
+ *   activations  -> (optional smoothing pre-scale) -> Adaptive Rotation Scheme (Hadamard, or the
+ *                   outlier-aware rotation in dense or structured R1.P.R2 form, chosen per layer)
+ *                   -> per-token uniform quantization to 4/8-bit codes
  *   weights      -> packed 3/4-bit Twin-Log Quantization (TLQ) codes, decoded through a per-channel
  *                   level table into int8 MFMA operands inside the GEMM
  *   output       -> int32 accumulators rescaled per token x per channel.

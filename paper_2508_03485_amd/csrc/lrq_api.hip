@@ -105,7 +105,7 @@ const char* lrq_status_string(int status) {
     }
 }
 
-int lrq_version(void) { return 100; }
+int lrq_version(void) { return 200; }   // 0.2.0: lrq_rotation grew the structured-rotation and pre-scale fields
 
 size_t lrq_tlq_codes_bytes(int N, int K, int bits) {
     if (N <= 0 || K <= 0 || (bits != 3 && bits != 4) || K % 8 != 0) return 0;
