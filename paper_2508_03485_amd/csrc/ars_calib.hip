@@ -259,12 +259,9 @@ hipError_t launch_ars_build_rotation(hipStream_t st, const uint16_t* Xcal, int T
     const size_t nY = (size_t)T * K, nR = (size_t)K * B;
     const size_t lds = 2 * RB * B * sizeof(double);
     const size_t q_blk = (size_t)n_steps * B * B;
-    static bool attr_done = false;
-    if (!attr_done) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(greedy_step_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024);
+    {
+        const hipError_t e = allow_large_lds(reinterpret_cast<const void*>(greedy_step_kernel), 158 * 1024);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     auto stats_pass = [&](const double* A) {
         hipLaunchKernelGGL(zero_u64_kernel, dim3(blocks_for(3 * (size_t)K)), dim3(256), 0, st, stats, 3 * (size_t)K);

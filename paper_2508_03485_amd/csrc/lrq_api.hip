@@ -2,6 +2,27 @@
 // carving and dispatch to the kernels.
 #include "lrq_internal.h"
 
+#include <mutex>
+#include <set>
+#include <utility>
+
+namespace lrq {
+
+hipError_t allow_large_lds(const void* kernel, int bytes) {
+    static std::mutex mu;
+    static std::set<std::pair<const void*, int>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count({kernel, dev})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.insert({kernel, dev});
+    return e;
+}
+
+}  // namespace lrq
+
 namespace {
 
 inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }

@@ -310,12 +310,13 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 // flight) and so doubles the resident waves.  Codes return through LDS as bytes so that every lane stores
 // 32 contiguous bytes.  LDS rows: 16 doubles + 2 of padding per pass-1 lane and 4 more per 32 lanes (the byte
 // buffer: 16 bytes per 32 lanes), which keeps the 16-byte writes of pass 1 and the quad-strided accesses of
-// pass 2 on distinct banks.  A workgroup is persistent: it walks over row groups and loads the next group's
-// bf16 data while it transforms the current one.
+// pass 2 on distinct banks.  With PERSIST (used for h = 4096) a workgroup walks over row groups and loads the next
+// group's bf16 data while it transforms the current one.
 __device__ __forceinline__ int lds_row(int slot) { return 18 * slot + 4 * (slot >> 5); }
 
 template <int LOG2H, bool PERSIST, bool ASYM, bool PRE>
-__global__ __launch_bounds__(512) void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(PERSIST || PRE ? 2 : 3, PERSIST || PRE ? 2 : 3)))
+void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
                                                                    int rows_per_wg, QuantSpec qs,
                                                                    int8_t* __restrict__ q, float* __restrict__ scale) {
     constexpr int G = 1 << (LOG2H - 5);            // pass-1 lanes per block
@@ -766,22 +767,26 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         // resident workgroups per CU: two waves per SIMD by registers, LDS permitting
         const int groups = (M + R - 1) / R;
         int per_cu = (int)((160 * 1024 - 2048) / (ldsb + 512));
-        const int by_waves = 8 / (nt / kWave) > 0 ? 8 / (nt / kWave) : 1;
+        static const int wpc = [] { const char* e = getenv("LRQ_ROT2_WAVES"); return e ? atoi(e) : 8; }();
+        const int by_waves = wpc / (nt / kWave) > 0 ? wpc / (nt / kWave) : 1;
         if (per_cu > by_waves) per_cu = by_waves;
         if (per_cu < 1) per_cu = 1;
-        // large blocks run as persistent workgroups that load the next row group while transforming the current one
-        const bool persist = h >= 2048 && groups > 256 * per_cu;
+        // the largest block runs as persistent workgroups that load the next row group while transforming the current
+        // one (measured: 566 vs 690 us at 35100 x 12288; at h = 2048 the plain form is the faster one, 208 vs 288 us)
+        static const int allow_persist = [] { const char* e = getenv("LRQ_ROT2_PERSIST"); return e ? atoi(e) : 1; }();
+        const bool persist = allow_persist && h >= 4096 && groups > 256 * per_cu;
         const dim3 grid(persist ? 256 * per_cu : groups), block(nt);
-        static bool attr2 = false;
-        if (!attr2) {
-#define LRQ_ATTR(L, P, A, S) { hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A, S>), hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024); if (e != hipSuccess) return e; }
-#define LRQ_ATTR2(L, P) LRQ_ATTR(L, P, false, false) LRQ_ATTR(L, P, true, false) LRQ_ATTR(L, P, false, true) LRQ_ATTR(L, P, true, true)
-            LRQ_ATTR2(8, false) LRQ_ATTR2(9, false) LRQ_ATTR2(10, false) LRQ_ATTR2(11, false) LRQ_ATTR2(12, false)
-            LRQ_ATTR2(11, true) LRQ_ATTR2(12, true)
+#define LRQ_ATTR(L, P, A, S) { hipError_t e = allow_large_lds(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A, S>), 158 * 1024); if (e != hipSuccess) return e; }
+#define LRQ_ATTR2(L, P) { if (qs.asym && qs.prescale) LRQ_ATTR(L, P, true, true) else if (qs.asym) LRQ_ATTR(L, P, true, false) else if (qs.prescale) LRQ_ATTR(L, P, false, true) else LRQ_ATTR(L, P, false, false) }
+        switch (ilog2(h)) {
+            case 8: LRQ_ATTR2(8, false) break;
+            case 9: LRQ_ATTR2(9, false) break;
+            case 10: LRQ_ATTR2(10, false) break;
+            case 11: LRQ_ATTR2(11, false) break;
+            case 12: if (persist) LRQ_ATTR2(12, true) else LRQ_ATTR2(12, false) break;
+        }
 #undef LRQ_ATTR2
 #undef LRQ_ATTR
-            attr2 = true;
-        }
 #define LRQ_GO(L, P)                                                                                                      \
     {                                                                                                                     \
         if (qs.asym && qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
@@ -793,7 +798,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
             case 8: LRQ_GO(8, false) break;
             case 9: LRQ_GO(9, false) break;
             case 10: LRQ_GO(10, false) break;
-            case 11: if (persist) LRQ_GO(11, true) else LRQ_GO(11, false) break;
+            case 11: LRQ_GO(11, false) break;
             case 12: if (persist) LRQ_GO(12, true) else LRQ_GO(12, false) break;
         }
 #undef LRQ_GO
@@ -801,12 +806,9 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
     }
     const int nt = threads_for_row(K);
     const size_t lds = (size_t)(K + 16) * sizeof(double);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(hadamard_quant_generic_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    {
+        const hipError_t e = allow_large_lds(reinterpret_cast<const void*>(hadamard_quant_generic_kernel), 160 * 1024);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     hipLaunchKernelGGL(hadamard_quant_generic_kernel, dim3(M), dim3(nt), lds, st, X, K, ilog2(h), qs, q, scale);
     return hipGetLastError();
@@ -845,13 +847,8 @@ hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int 
     hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z, prescale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    static bool attr_done = false;
-    if (!attr_done) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(permute_rows_f32_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    e = allow_large_lds(reinterpret_cast<const void*>(permute_rows_f32_kernel), 158 * 1024);
+    if (e != hipSuccess) return e;
     const int pgrid = M < 4096 ? M : 4096;
     hipLaunchKernelGGL(permute_rows_f32_kernel, dim3(pgrid), dim3(256), (size_t)K * sizeof(float), st, Z, perm, M, K, Zp);
     e = hipGetLastError();

@@ -225,12 +225,9 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
                                     const lrq_tlq_weight& out) {
     const size_t lds = (size_t)K * sizeof(double) + 64 * sizeof(double) + (size_t)K;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(tlq_quantize_pack_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 158 * 1024);
+    {
+        const hipError_t e = allow_large_lds(reinterpret_cast<const void*>(tlq_quantize_pack_kernel), 158 * 1024);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
                        beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
