@@ -78,7 +78,8 @@ constexpr int kGemmBlockK = 64;
 inline size_t gemm_codes_bytes(int N, int K, int bits) {
     size_t tiles = (size_t)(N + kGemmTileN - 1) / kGemmTileN;
     size_t kblocks = (size_t)K / kGemmBlockK;
-    return tiles * kblocks * 64 * (bits == 4 ? 16 : 12);
+    (void)bits;                       // one nibble per code for 3- and 4-bit codes alike
+    return tiles * kblocks * 64 * 16;
 }
 
 }  // namespace lrq

@@ -32,34 +32,30 @@ __device__ __forceinline__ unsigned perm(unsigned hi, unsigned lo, unsigned sel)
     return __builtin_amdgcn_perm(hi, lo, sel);
 }
 
+// Raw operand codes of one lane for one K block: 32 codes, one nibble each (16 bytes), either bit-width.
 template <int BITS>
 struct BRaw {
-    unsigned d[BITS == 4 ? 4 : 3];
+    unsigned d[4];
 };
 
 template <int BITS>
 __device__ __forceinline__ BRaw<BITS> load_braw(const uint8_t* __restrict__ p) {
     BRaw<BITS> r;
-    if constexpr (BITS == 4) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p);
-        r.d[0] = v.x; r.d[1] = v.y; r.d[2] = v.z; r.d[3] = v.w;
-    } else {
-        const unsigned* q = reinterpret_cast<const unsigned*>(p);
-        r.d[0] = q[0]; r.d[1] = q[1]; r.d[2] = q[2];
-    }
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    r.d[0] = v.x; r.d[1] = v.y; r.d[2] = v.z; r.d[3] = v.w;
     return r;
 }
 
-// Decode the 4 codes of operand dword g (0..3) of MFMA step s (0 | 1) of a K block.
-// 4-bit: raw dword 2s + g/2 holds 8 codes, byte j = code[j] | code[4+j] << 4; the level table has 16
-// entries (L[0..1] codes 0..7, L[2..3] codes 8..15 = negative twin): two 8-entry byte permutes and a
-// third that picks per byte by the code's sign bit.  C = 0x03020100 must live in a VGPR so that the
+// Decode the 4 codes of operand dword g (0..3) of MFMA step s (0 | 1) of a K block.  Raw dword 2s + g/2 holds 8
+// codes, byte j = code[j] | code[4+j] << 4.
+// 4-bit: the level table has 16 entries (L[0..1] codes 0..7, L[2..3] codes 8..15 = negative twin): two 8-entry byte
+// permutes and a third that picks per byte by the code's sign bit.  C = 0x03020100 must live in a VGPR so that the
 // pick selector is a single v_and_or_b32.
-// 3-bit: d[s] holds the low two bits of the 16 codes of step s, d[2] the third bits; 8-entry table.
+// 3-bit: 8-entry table, the masked nibbles are the selectors of one byte permute.
 template <int BITS>
 __device__ __forceinline__ unsigned decode_dword(const BRaw<BITS>& raw, const unsigned L[4], int s, int g, unsigned C) {
+    const unsigned w = raw.d[2 * s + g / 2];
     if constexpr (BITS == 4) {
-        const unsigned w = raw.d[2 * s + g / 2];
         unsigned idx, pick;
         if (g % 2 == 0) {
             idx = w & 0x07070707u;
@@ -72,9 +68,8 @@ __device__ __forceinline__ unsigned decode_dword(const BRaw<BITS>& raw, const un
         const unsigned b = perm(L[3], L[2], idx);
         return perm(b, a, pick);
     } else {
-        const unsigned lo2 = (raw.d[s] >> (2 * g)) & 0x03030303u;
-        const unsigned b2 = (raw.d[2] >> (4 * s + g)) & 0x01010101u;
-        return perm(L[1], L[0], (b2 << 2) | lo2);
+        const unsigned idx = (g % 2 == 0 ? w : (w >> 4)) & 0x07070707u;
+        return perm(L[1], L[0], idx);
     }
 }
 
@@ -104,7 +99,7 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
                                        const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
                                        const uint8_t* const (&bptr)[NTW], const unsigned (&L)[NTW][4], unsigned C,
                                        v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off, v4i (&afp)[LRQ_AF_DIST]) {
-    constexpr int UNIT = 64 * (BITS == 4 ? 16 : 12);
+    constexpr int UNIT = 64 * 16;
     const unsigned char* Acur = smem + cur;
 #pragma unroll
     for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&smem[st + aoff[i]]) = aS[i];
@@ -202,7 +197,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     const int t = threadIdx.x, lane = t % 64, wv = t / 64;
     const int KB = K / BK;
     const int ntile32 = (N + 31) / 32;
-    constexpr int UNIT = 64 * (BITS == 4 ? 16 : 12);
+    constexpr int UNIT = 64 * 16;
 
     unsigned L[NTW][4];
     const uint8_t* bptr[NTW];

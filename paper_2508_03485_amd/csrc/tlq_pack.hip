@@ -174,18 +174,10 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
         // canonical: byte j = code[2j] | code[2j+1] << 4, written 4 bytes at a time
         uint32_t* dst = reinterpret_cast<uint32_t*>(codes_out + (size_t)n * (K / 2));
         for (int g = t; g < K / 8; g += NT) {
-            unsigned canon = 0, tiled = 0;
+            unsigned canon = 0;
 #pragma unroll
             for (int i = 0; i < 8; ++i) canon |= ((unsigned)code[g * 8 + i] & mask) << (4 * i);
             dst[g] = canon;
-            // GEMM layout: byte j of the dword = code[k+j] | code[k+4+j] << 4
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                tiled |= (((unsigned)code[g * 8 + j] & mask) | (((unsigned)code[g * 8 + 4 + j] & mask) << 4)) << (8 * j);
-            const int kb = g / 8, r = g % 8, s = r / 4, hl = (r / 2) % 2, d = r % 2;
-            const size_t unit = (size_t)(n / kGemmTileN) * (K / kGemmBlockK) + kb;
-            const size_t off = (unit * 64 + (n % kGemmTileN) + 32 * hl) * 16 + (s * 2 + d) * 4;
-            *reinterpret_cast<uint32_t*>(gemm_codes + off) = tiled;
         }
     } else {
         // canonical: 8 codes -> 24-bit little-endian group
@@ -198,24 +190,18 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
             dst[g * 3 + 1] = (uint8_t)((v24 >> 8) & 255u);
             dst[g * 3 + 2] = (uint8_t)(v24 >> 16);
         }
-        // GEMM layout: per lane and K block three dwords: d0/d1 = low two bits of the 16 codes of
-        // step 0/1 (code 4g+j at bits [8j+2g, 8j+2g+2)), d2 = third bits (step s, code 4g+j at bit 8j+4s+g)
-        for (int u = t; u < K / 32; u += NT) {
-            const int kb = u / 2, hl = u % 2;
-            unsigned d[3] = {0u, 0u, 0u};
+    }
+    // GEMM layout, either bit-width: one nibble per code (a 3-bit code leaves its top bit clear, so that a single
+    // AND turns a dword into four byte-permute selectors); byte j of a dword = code[k+j] | code[k+4+j] << 4
+    for (int g = t; g < K / 8; g += NT) {
+        unsigned tiled = 0;
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const unsigned c = (unsigned)code[kb * 64 + 32 * s + 16 * hl + i] & mask;
-                    const int g = i / 4, j = i % 4;
-                    d[s] |= (c & 3u) << (8 * j + 2 * g);
-                    d[2] |= (c >> 2) << (8 * j + 4 * s + g);
-                }
-            const size_t unit = (size_t)(n / kGemmTileN) * (K / kGemmBlockK) + kb;
-            uint32_t* o = reinterpret_cast<uint32_t*>(gemm_codes + (unit * 64 + (n % kGemmTileN) + 32 * hl) * 12);
-            o[0] = d[0]; o[1] = d[1]; o[2] = d[2];
-        }
+        for (int j = 0; j < 4; ++j)
+            tiled |= (((unsigned)code[g * 8 + j] & mask) | (((unsigned)code[g * 8 + 4 + j] & mask) << 4)) << (8 * j);
+        const int kb = g / 8, r = g % 8, s2 = r / 4, hl = (r / 2) % 2, d = r % 2;
+        const size_t unit = (size_t)(n / kGemmTileN) * (K / kGemmBlockK) + kb;
+        const size_t off = (unit * 64 + (n % kGemmTileN) + 32 * hl) * 16 + (s2 * 2 + d) * 4;
+        *reinterpret_cast<uint32_t*>(gemm_codes + off) = tiled;
     }
 }
 

@@ -34,7 +34,7 @@ def test_sizes(L):
     assert L.lrq_tlq_codes_bytes(1152, 1152, 3) == 1152 * 1152 * 3 // 8
     assert L.lrq_tlq_codes_bytes(8, 12, 4) == 0 and L.lrq_tlq_codes_bytes(8, 16, 5) == 0
     assert L.lrq_tlq_gemm_codes_bytes(1152, 1152, 4) == 1152 * 1152 // 2
-    assert L.lrq_tlq_gemm_codes_bytes(33, 64, 3) == 64 * 64 * 3 // 8          # channels padded to 32
+    assert L.lrq_tlq_gemm_codes_bytes(33, 64, 3) == 64 * 64 // 2              # channels padded to 32; a nibble per code
     had = lrq.Rotation("hadamard", 128).c_struct()
     assert L.lrq_ars_workspace_bytes(256, 1152, ctypes.byref(had), 8) == 0
     dense = lrq._Rotation(lrq.LRQ_ROT_DENSE, 0, 4096)
