@@ -393,11 +393,16 @@ hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, con
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y) {
     const int fp32 = out_dtype == LRQ_OUT_FP32;
     // Tile shape.  128 x 256 (two workgroups per CU) is the fastest on long K loops; 128 x 128 (three per CU)
-    // hides the prologue / epilogue of short K loops better and wastes less on N that is not a multiple of 256.
-    // LRQ_GEMM_SHAPE = 128 | 1281 | 256 forces 128x256 | 128x128 | 256x128 (experiments).
+    // hides the prologue / epilogue of short K loops better and wastes less on N that is not a multiple of 256;
+    // 64 x 128 serves inputs of a few tokens (conditioning vectors), where taller tiles multiply padding.
+    // LRQ_GEMM_SHAPE = 128 | 1281 | 256 | 64 forces 128x256 | 128x128 | 256x128 | 64x128 (experiments).
     static const int env = [] { const char* e = getenv("LRQ_GEMM_SHAPE"); return e ? atoi(e) : 0; }();
     const bool narrow = K <= 2048 || (w.N % 256 != 0 && w.N <= 2048);
-    const int bm = env ? env : (narrow ? 1281 : 128);
+    const int bm = env ? env : (M <= 64 ? 64 : (narrow ? 1281 : 128));
+    if (bm == 64) {
+        if (w.bits == 4) return launch<4, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+        return launch<3, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+    }
     if (bm == 256) {
         if (w.bits == 4) return launch<4, 256, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
         return launch<3, 256, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);

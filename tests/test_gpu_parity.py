@@ -259,7 +259,9 @@ def test_tlq_degenerate_channels(lrq):
     (300, 352, 1152, 4, 8),       # ragged M, N not a multiple of the workgroup tile
     (513, 200, 256, 3, 4),        # N not a multiple of 32, 3-bit weights
     (70, 4608, 128, 4, 4),
-    (2, 6912, 1152, 3, 4),        # adaLN-shaped: two tokens
+    (2, 6912, 1152, 3, 4),        # adaLN-shaped: two tokens (64-row tiles)
+    (64, 200, 256, 4, 8),         # the largest M that takes the 64-row tiles, ragged N, exact-accumulator check
+    (33, 1152, 4608, 4, 8),       # 64-row tiles, long K loop, half-empty second row tile
 ])
 def test_qgemm_against_oracle(lrq, M, N, K, w_bits, a_bits):
     import torch
