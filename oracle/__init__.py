@@ -31,7 +31,12 @@ Pins (tests/test_oracle_*.py) and what is parity-unpinned by the paper: the int8
 normalisation of the level table and the [1, 2^(b-1)] clamp of the negative twin
 are this build's readings of points the paper leaves open; they are pinned only
 by their own stated definitions, everything else against closed forms, library
-special cases and brute force.
+special cases and brute force.  The greedy rotation builder fills in what the paper
+leaves unnamed (which matrix initialises R~, which Q, how c* is chosen, the dealing
+order of the staggered permutation); it is pinned by the printed matrix product, by
+orthogonality and by the Lemma's ||x'||_inf = ||x||_inf / sqrt(C) on a single outlier,
+and is otherwise parity-unpinned by the paper.  The smoothing factor's formula is the
+cited SmoothQuant one (the paper only names the migration strength).
 """
 from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits  # noqa: F401
 from .rotation import (hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense, rotate_blockdiag,  # noqa: F401
