@@ -290,6 +290,35 @@ def test_qgemm_against_oracle(lrq, M, N, K, w_bits, a_bits):
         assert np.array_equal(acc.astype(np.float64), ref_acc)
 
 
+def test_extreme_shapes(lrq):
+    """Smallest and largest shapes the entry points accept."""
+    import torch
+    gd = to_dev(GRID)
+    # one token, eight output channels, one K block
+    M, N, K = 1, 8, 64
+    X = _acts(M, K, 41)
+    W = synth.make_weights(N, K, (909, N, K))
+    w = lrq.tlq_quantize_pack(to_dev(W), 4, 7, gd, gd)
+    Y = lrq.qlinear(bf16_to_dev(X), lrq.Rotation("hadamard", 64), 8, w, out_dtype=torch.float32)
+    ref = oracle.qlinear(X, W, 4, 8, "hadamard", 64, alpha_grid=GRID, beta_grid=GRID)
+    assert rel_fro(Y.cpu().numpy(), ref["y"]) <= 1e-3
+    # the widest row the rotate kernels take (K = 16384), every block size of the two-pass kernel
+    K = 16384
+    X = _acts(5, K, 42)
+    for h in (16384, 16384 // 4, 2048, 256):
+        q_ref, s_ref = oracle.ars_rotate_quant(X, 8, "hadamard", h)
+        q, s = lrq.ars_rotate_quant(bf16_to_dev(X), lrq.Rotation("hadamard", h), 8)
+        assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
+    # an all-zero activation matrix: codes and scales are zero, the output is the bias
+    M, N, K = 40, 96, 256
+    W = synth.make_weights(N, K, (909, N, K))
+    w = lrq.tlq_quantize_pack(to_dev(W), 3, 7, gd, gd)
+    bias = synth.make_bias(N, (909, N, K))
+    Xz = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda")
+    Y = lrq.qlinear(Xz, lrq.Rotation("hadamard", 256), 4, w, bias=to_dev(bias), out_dtype=torch.float32)
+    assert np.array_equal(Y.cpu().numpy(), np.broadcast_to(bias, (M, N)))
+
+
 # ------------------------------------------------------------------ fused path
 @pytest.mark.parametrize("cfg_case", ["config1", "dense", "w3a4"])
 def test_qlinear_end_to_end(lrq, cfg_case):
