@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--structured", type=int, default=0, metavar="B",
                     help="run the layers that take the dense outlier-aware rotation with its structured form "
                          "X.R1.P.R2 instead (block size B, seeded block rotations and permutation)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each step (all layers) in a HIP graph once and time the replays")
     ap.add_argument("--smooth", action="store_true",
                     help="give every layer a smoothing pre-scale (from lrq_smooth_factor on its own inputs), multiplied "
                          "into the activations inside the rotate+quantize kernels")
@@ -143,6 +145,20 @@ def main():
         for l in layers:
             lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym)
 
+    if args.graph:
+        eager_step = step
+        eager_step(0)                       # one-time set-up (kernel attributes) outside the capture
+        torch.cuda.synchronize()
+        graphs = []
+        for c in range(copies):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                eager_step(c)
+            graphs.append(g)
+
+        def step(i):                        # noqa: F811
+            graphs[i % copies].replay()
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -234,7 +250,7 @@ def main():
                                      5: "config5: 28-block PixArt-style stack, W3A4, per-layer ARS"}[cfg],
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
                            outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
-                           smoothing_prescale=bool(args.smooth),
+                           smoothing_prescale=bool(args.smooth), hip_graph=bool(args.graph),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,

@@ -397,3 +397,33 @@ def test_zero_point_qlinear_against_oracle(lrq, M, N, K, w_bits, a_bits):
 def test_smoke_entry(lrq):
     import __graft_entry__
     __graft_entry__.smoke()
+
+
+def test_qlinear_replays_from_a_hip_graph(lrq):
+    """lrq_qlinear allocates nothing and synchronises nothing, so a captured call replays; every replay is checked
+    against the eager result on fresh input contents, with eager work and synchronisation between replays."""
+    import torch
+    M, K, N = 300, 1152, 352
+    gd = to_dev(GRID)
+    W = synth.make_weights(N, K, (910, N, K))
+    w = lrq.tlq_quantize_pack(to_dev(W), 4, 7, gd, gd)
+    rot = lrq.Rotation("hadamard", 128)
+    X_static = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda")
+    Y_static = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    ws = torch.zeros(lrq.workspace_bytes(M, N, K, rot, 8), dtype=torch.uint8, device="cuda")
+    X0 = bf16_to_dev(_acts(M, K, 50))
+    X_static.copy_(X0)
+    lrq.qlinear(X_static, rot, 8, w, out=Y_static, workspace=ws)          # warm-up outside the capture (one-time set-up)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        lrq.qlinear(X_static, rot, 8, w, out=Y_static, workspace=ws)
+    for rep in range(3):
+        Xr = bf16_to_dev(_acts(M, K, 51 + rep))
+        eager = lrq.qlinear(Xr, rot, 8, w)                                 # eager work between the replays
+        torch.cuda.synchronize()
+        X_static.copy_(Xr)
+        Y_static.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y_static, eager), f"replay {rep} differs from the eager result"
