@@ -23,6 +23,11 @@ Readings of what the paper leaves open (all per output channel, weights per-chan
     per-sign squared error sum (W_f - W)^2 with the exact Eq. dequant levels; the first
     minimum wins; a side with no element or no valid candidate takes s = 1,
     z = round(W_min) (0 if empty);
+  * optional extension, not in the paper: a lower clip factor gamma on W_min, searched jointly with alpha (beta):
+        s = (alpha * W_max - gamma * W_min) / intervals,  z = round(gamma * W_min / s)
+    (log2 values are negative for |w| < 1, so gamma < 1 raises the lower end; smaller magnitudes clamp to the lowest
+    level of their twin).  The grid {1} is the paper's formula; the search scans alpha in the outer loop and gamma
+    in the inner loop, first minimum wins;
   * the MFMA operand of a code is an int8: v(c) = +-round(2^r 2^I) 2^(f-I) (I < 0: exactly
     2^e), divided by wscale_n = fp32(max_c |v(c)| / 127) and rounded.  This int8
     normalisation is not in the paper (its datapath shifts inside the reduction).
@@ -41,6 +46,8 @@ class TLQParams:
     z_neg: np.ndarray   # int32 [N]
     alpha: np.ndarray   # fp32 [N]  chosen clip factor of the positive side
     beta: np.ndarray    # fp32 [N]  chosen clip factor of the negative side
+    gamma_pos: np.ndarray = None   # fp32 [N]  chosen lower clip factors (all ones without the extension)
+    gamma_neg: np.ndarray = None
 
 
 def _log2_abs(W):
@@ -55,8 +62,9 @@ def _encode_side(ell, s, z, lo, hi):
     return np.clip(np.rint(ell / s[:, None]) - z[:, None], lo, hi)
 
 
-def _search_side(ell, absw, mask, grid, n_intervals, q_lo, q_hi):
-    """Grid search of one clip factor for one sign.  Returns (s, z, chosen_factor)."""
+def _search_side(ell, absw, mask, grid, n_intervals, q_lo, q_hi, gamma_grid=(1.0,)):
+    """Grid search of one clip factor (and the optional lower clip) for one sign.
+    Returns (s, z, chosen_factor, chosen_gamma)."""
     N = ell.shape[0]
     has = mask.any(axis=1)
     wmax = np.max(np.where(mask, ell, -np.inf), axis=1)
@@ -67,40 +75,45 @@ def _search_side(ell, absw, mask, grid, n_intervals, q_lo, q_hi):
     best_s = np.ones(N)
     best_z = np.rint(wmin)
     best_c = np.ones(N, dtype=np.float32)
+    best_g = np.ones(N, dtype=np.float32)
     for c32 in np.asarray(grid, dtype=np.float32):
-        c = np.float64(c32)
-        T = c * wmax
-        valid = has & (T > wmin)
-        s = np.where(valid, (T - wmin) / n_intervals, 1.0)
-        z = np.rint(wmin / s)
-        q = _encode_side(ell, s, z, q_lo, q_hi)
-        lev = np.exp2(s[:, None] * (q + z[:, None]))
-        d = np.where(mask, lev - absw, 0.0)
-        err = np.sum(d * d, axis=1)
-        better = valid & (err < best_err)
-        best_err = np.where(better, err, best_err)
-        best_s = np.where(better, s, best_s)
-        best_z = np.where(better, z, best_z)
-        best_c = np.where(better, c32, best_c)
-    return best_s, best_z.astype(np.int32), best_c
+        T = np.float64(c32) * wmax
+        for g32 in np.asarray(gamma_grid, dtype=np.float32):
+            B = np.float64(g32) * wmin
+            valid = has & (T > B)
+            s = np.where(valid, (T - B) / n_intervals, 1.0)
+            z = np.rint(B / s)
+            q = _encode_side(ell, s, z, q_lo, q_hi)
+            lev = np.exp2(s[:, None] * (q + z[:, None]))
+            d = np.where(mask, lev - absw, 0.0)
+            err = np.sum(d * d, axis=1)
+            better = valid & (err < best_err)
+            best_err = np.where(better, err, best_err)
+            best_s = np.where(better, s, best_s)
+            best_z = np.where(better, z, best_z)
+            best_c = np.where(better, c32, best_c)
+            best_g = np.where(better, g32, best_g)
+    return best_s, best_z.astype(np.int32), best_c, best_g
 
 
-def tlq_calibrate(W, bits, alpha_grid, beta_grid, neg_lo=1, chunk=256):
-    """Search-based clipping per output channel.  W fp32/fp64 [N, K] -> TLQParams."""
+def tlq_calibrate(W, bits, alpha_grid, beta_grid, neg_lo=1, chunk=256, gamma_grid=None):
+    """Search-based clipping per output channel.  W fp32/fp64 [N, K] -> TLQParams.
+    gamma_grid: None (the paper's formula) or the grid of the lower clip factor (extension)."""
     assert bits in (3, 4)
     W = np.asarray(W, dtype=np.float64)
     N = W.shape[0]
     half = 2 ** (bits - 1)
+    gg = (1.0,) if gamma_grid is None else gamma_grid
     out = [np.empty(N), np.empty(N, np.int32), np.empty(N), np.empty(N, np.int32),
-           np.empty(N, np.float32), np.empty(N, np.float32)]
+           np.empty(N, np.float32), np.empty(N, np.float32), np.empty(N, np.float32), np.empty(N, np.float32)]
     for a in range(0, N, chunk):
         w = W[a:a + chunk]
         absw, ell = _log2_abs(w)
-        sp, zp, al = _search_side(ell, absw, w > 0, alpha_grid, float(half - 1), 0.0, float(half - 1))
-        sn, zn, be = _search_side(ell, absw, w < 0, beta_grid, float(half), float(neg_lo), float(half))
-        for dst, src in zip(out, (sp, zp, sn, zn, al, be)):
+        sp, zp, al, gp = _search_side(ell, absw, w > 0, alpha_grid, float(half - 1), 0.0, float(half - 1), gg)
+        sn, zn, be, gn = _search_side(ell, absw, w < 0, beta_grid, float(half), float(neg_lo), float(half), gg)
+        for dst, src in zip(out, (sp, zp, sn, zn, al, be, gp, gn)):
             dst[a:a + chunk] = src
-    return TLQParams(bits, out[0], out[1], out[2], out[3], out[4], out[5])
+    return TLQParams(bits, *out)
 
 
 def tlq_encode(W, p: TLQParams, neg_lo=1, chunk=256):

@@ -129,6 +129,71 @@ def test_search_picks_the_first_minimum_of_the_grid(bits):
             assert float(chosen) == firsts[0]
 
 
+# ------------------------------------------------------------------ lower clip factor gamma (extension)
+GAMMAS = np.array([1.0, 0.9, 0.8, 0.7, 0.6, 0.5, 0.4], dtype=np.float32)
+
+
+def _scalar_side_error_clip(ws, alpha, gamma, n_int, lo, hi):
+    ls = [math.log2(w) for w in ws]
+    T, B = alpha * max(ls), gamma * min(ls)
+    if not T > B:
+        return None
+    s = (T - B) / n_int
+    z = round(B / s)
+    err = 0.0
+    for w, ell in zip(ws, ls):
+        q = min(max(round(ell / s) - z, lo), hi)
+        err += (2.0 ** (s * (q + z)) - w) ** 2
+    return err
+
+
+def test_gamma_grid_of_one_is_the_paper_formula():
+    W = _weights(6, 300, 71)
+    for bits in (3, 4):
+        p0 = oracle.tlq_calibrate(W, bits, GRID, GRID)
+        p1 = oracle.tlq_calibrate(W, bits, GRID, GRID, gamma_grid=np.array([1.0], np.float32))
+        for a, b in ((p0.s_pos, p1.s_pos), (p0.s_neg, p1.s_neg), (p0.z_pos, p1.z_pos), (p0.z_neg, p1.z_neg),
+                     (p0.alpha, p1.alpha), (p0.beta, p1.beta)):
+            assert np.array_equal(a, b)
+        assert np.all(p1.gamma_pos == 1) and np.all(p1.gamma_neg == 1)
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_joint_search_picks_the_first_minimum_alpha_outer_gamma_inner(bits):
+    W = _weights(4, 160, 72 + bits)
+    grid = GRID[::4]
+    p = oracle.tlq_calibrate(W, bits, grid, grid, gamma_grid=GAMMAS)
+    half = 2 ** (bits - 1)
+    for n in range(W.shape[0]):
+        for ws, ca, cg, s_got, z_got, n_int, lo, hi in (
+                ([float(w) for w in W[n] if w > 0], p.alpha[n], p.gamma_pos[n], p.s_pos[n], p.z_pos[n], half - 1, 0, half - 1),
+                ([-float(w) for w in W[n] if w < 0], p.beta[n], p.gamma_neg[n], p.s_neg[n], p.z_neg[n], half, 1, half)):
+            cands = [(_scalar_side_error_clip(ws, float(a), float(g), n_int, lo, hi), float(a), float(g))
+                     for a in grid for g in GAMMAS]
+            cands = [c for c in cands if c[0] is not None]
+            emin = min(c[0] for c in cands)
+            first = [c for c in cands if c[0] <= emin * (1 + 1e-9)][0]
+            assert (float(ca), float(cg)) == first[1:]
+            ls = [math.log2(w) for w in ws]                    # scale and zero-point recomputed from the printed-style formulas
+            s_ref = (float(ca) * max(ls) - float(cg) * min(ls)) / n_int
+            assert math.isclose(s_got, s_ref, rel_tol=1e-13) and z_got == round(float(cg) * min(ls) / s_ref)
+
+
+def test_lower_clip_reduces_the_weight_error_and_clamps_small_magnitudes():
+    W = synth.make_weights(32, 1152, (7, 7, 7))
+    for bits in (3, 4):
+        p0 = oracle.tlq_calibrate(W, bits, GRID, GRID)
+        p1 = oracle.tlq_calibrate(W, bits, GRID, GRID, gamma_grid=np.arange(1.0, 0.29, -0.05).astype(np.float32))
+        e0 = np.linalg.norm(oracle.tlq_dequant(oracle.tlq_encode(W, p0), p0) - W) / np.linalg.norm(W)
+        e1 = np.linalg.norm(oracle.tlq_dequant(oracle.tlq_encode(W, p1), p1) - W) / np.linalg.norm(W)
+        assert e1 < 0.6 * e0
+        codes = oracle.tlq_encode(W, p1)
+        n = 0                                                  # weights below the raised lower end take the lowest level
+        lim = 2.0 ** (p1.s_pos[n] * p1.z_pos[n])
+        small = (W[n] > 0) & (W[n] < lim * 0.5)
+        assert small.any() and np.all(codes[n][small] == 0)
+
+
 def test_alpha_one_is_plain_min_max_log_quantization():
     W = _weights(5, 400, 50)
     p = oracle.tlq_calibrate(W, 4, ONE, ONE)
