@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--structured", type=int, default=0, metavar="B",
                     help="run the layers that take the dense outlier-aware rotation with its structured form "
                          "X.R1.P.R2 instead (block size B, seeded block rotations and permutation)")
+    ap.add_argument("--lower-clip", action="store_true",
+                    help="calibrate the weights with the lower clip factor gamma (grid 1.00 .. 0.30 step 0.05) searched "
+                         "jointly with alpha / beta (lrq_tlq_quantize_pack_clip)")
     ap.add_argument("--graph", action="store_true",
                     help="capture each step (all layers) in a HIP graph once and time the replays")
     ap.add_argument("--smooth", action="store_true",
@@ -81,6 +84,9 @@ def main():
     if cfg == 5 and args.blocks:
         specs = [s for s in specs if s.block < args.blocks]
     grid = torch.from_numpy(synth.DEFAULT_GRID).to(dev)
+    gamma_grid = None
+    if args.lower_clip:
+        gamma_grid = torch.tensor([1.0 - 0.05 * i for i in range(15)], dtype=torch.float32, device=dev)
 
     # ---------------------------------------------------------------- inputs (seeded, synthetic), resident in HBM
     t_gen = time.time()
@@ -107,7 +113,7 @@ def main():
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            w = lrq.tlq_quantize_pack(W, s.w_bits, 7, grid, grid)
+            w = lrq.tlq_quantize_pack(W, s.w_bits, 7, grid, grid, gamma_grid=gamma_grid)
             e1.record()
             torch.cuda.synchronize()
             pack_ms += e0.elapsed_time(e1)
@@ -251,6 +257,7 @@ def main():
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
                            outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
                            smoothing_prescale=bool(args.smooth), hip_graph=bool(args.graph),
+                           tlq_lower_clip=bool(args.lower_clip),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,

@@ -140,6 +140,21 @@ int lrq_tlq_quantize_pack(void* stream, const float* W, int N, int K, int bits, 
                           const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
                           lrq_tlq_weight* out, void* ws, size_t ws_bytes);
 
+/*
+ * lrq_tlq_quantize_pack with a lower clip (an extension, not in the paper: its Eq. hyperparameters clip only clips
+ * the large-magnitude end, so W_min stays the log of the channel's tiniest weight and most levels are spent far below
+ * the weights that matter).  A second factor gamma, searched jointly with alpha (beta), raises the lower end:
+ *     s = (alpha W_max - gamma W_min) / intervals,   z = round(gamma W_min / s)
+ * (log2 values are negative for |w| < 1, so gamma < 1 clips; smaller magnitudes clamp to the lowest level of their
+ * twin).  gamma_grid float [n_gamma] device, 1 <= n_gamma <= 64, scanned inside the loop over alpha (beta); the grid
+ * {1} reproduces lrq_tlq_quantize_pack bit for bit.  gamma_pos / gamma_neg: float [N] device or NULL, receive the
+ * chosen factors.  Everything else as lrq_tlq_quantize_pack.
+ */
+int lrq_tlq_quantize_pack_clip(void* stream, const float* W, int N, int K, int bits, int I,
+                               const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
+                               const float* gamma_grid, int n_gamma, lrq_tlq_weight* out, float* gamma_pos,
+                               float* gamma_neg, void* ws, size_t ws_bytes);
+
 /* Workspace of lrq_ars_rotate_quant (bytes). */
 size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bits);
 

@@ -24,7 +24,7 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_probe_copy", "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
-           "lrq_smooth_workspace_bytes", "lrq_smooth_factor")
+           "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip")
 
 
 class LrqError(RuntimeError):
@@ -67,6 +67,9 @@ def lib() -> ctypes.CDLL:
         f.restype, f.argtypes = sz, [ci, ci, ci]
     L.lrq_tlq_quantize_pack.restype = ci
     L.lrq_tlq_quantize_pack.argtypes = [vp, vp, ci, ci, ci, ci, vp, ci, vp, ci, ctypes.POINTER(_TlqWeight), vp, sz]
+    L.lrq_tlq_quantize_pack_clip.restype = ci
+    L.lrq_tlq_quantize_pack_clip.argtypes = [vp, vp, ci, ci, ci, ci, vp, ci, vp, ci, vp, ci, ctypes.POINTER(_TlqWeight),
+                                             vp, vp, vp, sz]
     L.lrq_ars_workspace_bytes.restype = sz
     L.lrq_ars_workspace_bytes.argtypes = [ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_ars_rotate_quant.restype = ci
@@ -170,8 +173,11 @@ class TLQWeight:
                           _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum))
 
 
-def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None, out: Optional[TLQWeight] = None):
-    """lrq_tlq_quantize_pack: W fp32 [N, K] on the device -> TLQWeight."""
+def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None, out: Optional[TLQWeight] = None,
+                      gamma_grid=None):
+    """lrq_tlq_quantize_pack: W fp32 [N, K] on the device -> TLQWeight.
+    gamma_grid (fp32 device tensor): lrq_tlq_quantize_pack_clip, the search with a lower clip factor; the chosen
+    factors land in w.gamma_pos / w.gamma_neg."""
     import torch
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous()
     N, K = W.shape
@@ -181,9 +187,18 @@ def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None,
         beta_grid = alpha_grid
     w = out if out is not None else TLQWeight(N, K, bits, I, W.device)
     cs = w.c_struct()
-    st = lib().lrq_tlq_quantize_pack(_stream(), _ptr(W), N, K, bits, I, _ptr(alpha_grid), alpha_grid.numel(),
-                                     _ptr(beta_grid), beta_grid.numel(), ctypes.byref(cs), None, 0)
-    _check(st, "lrq_tlq_quantize_pack")
+    if gamma_grid is None:
+        st = lib().lrq_tlq_quantize_pack(_stream(), _ptr(W), N, K, bits, I, _ptr(alpha_grid), alpha_grid.numel(),
+                                         _ptr(beta_grid), beta_grid.numel(), ctypes.byref(cs), None, 0)
+        _check(st, "lrq_tlq_quantize_pack")
+    else:
+        assert gamma_grid.is_cuda and gamma_grid.dtype == torch.float32
+        w.gamma_pos = torch.empty(N, dtype=torch.float32, device=W.device)
+        w.gamma_neg = torch.empty(N, dtype=torch.float32, device=W.device)
+        st = lib().lrq_tlq_quantize_pack_clip(_stream(), _ptr(W), N, K, bits, I, _ptr(alpha_grid), alpha_grid.numel(),
+                                              _ptr(beta_grid), beta_grid.numel(), _ptr(gamma_grid), gamma_grid.numel(),
+                                              ctypes.byref(cs), _ptr(w.gamma_pos), _ptr(w.gamma_neg), None, 0)
+        _check(st, "lrq_tlq_quantize_pack_clip")
     return w
 
 

@@ -145,10 +145,9 @@ size_t lrq_tlq_workspace_bytes(int N, int K, int bits) {
     return 0;
 }
 
-int lrq_tlq_quantize_pack(void* stream, const float* W, int N, int K, int bits, int I, const float* alpha_grid,
-                          int n_alpha, const float* beta_grid, int n_beta, lrq_tlq_weight* out, void* ws,
-                          size_t ws_bytes) {
-    (void)ws; (void)ws_bytes;
+static int tlq_impl(void* stream, const float* W, int N, int K, int bits, int I, const float* alpha_grid, int n_alpha,
+                    const float* beta_grid, int n_beta, const float* gamma_grid, int n_gamma, lrq_tlq_weight* out,
+                    float* gamma_pos, float* gamma_neg) {
     if (!W || !alpha_grid || !beta_grid || !out || N <= 0 || K <= 0 || !aligned16(W)) return LRQ_EINVAL;
     if (n_alpha < 1 || n_alpha > 64 || n_beta < 1 || n_beta > 64) return LRQ_EINVAL;
     if (bits != 3 && bits != 4) return LRQ_EUNSUPPORTED;
@@ -157,8 +156,25 @@ int lrq_tlq_quantize_pack(void* stream, const float* W, int N, int K, int bits, 
     if (st != LRQ_OK) return st;
     if (K % 64 != 0 || K > kMaxRowLds || I > 20) return LRQ_EUNSUPPORTED;
     hipError_t e = lrq::launch_tlq_quantize_pack(static_cast<hipStream_t>(stream), W, N, K, bits, I, alpha_grid,
-                                                 n_alpha, beta_grid, n_beta, *out);
+                                                 n_alpha, beta_grid, n_beta, *out, gamma_grid, n_gamma, gamma_pos,
+                                                 gamma_neg);
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_tlq_quantize_pack(void* stream, const float* W, int N, int K, int bits, int I, const float* alpha_grid,
+                          int n_alpha, const float* beta_grid, int n_beta, lrq_tlq_weight* out, void* ws,
+                          size_t ws_bytes) {
+    (void)ws; (void)ws_bytes;
+    return tlq_impl(stream, W, N, K, bits, I, alpha_grid, n_alpha, beta_grid, n_beta, nullptr, 0, out, nullptr, nullptr);
+}
+
+int lrq_tlq_quantize_pack_clip(void* stream, const float* W, int N, int K, int bits, int I, const float* alpha_grid,
+                               int n_alpha, const float* beta_grid, int n_beta, const float* gamma_grid, int n_gamma,
+                               lrq_tlq_weight* out, float* gamma_pos, float* gamma_neg, void* ws, size_t ws_bytes) {
+    (void)ws; (void)ws_bytes;
+    if (!gamma_grid || n_gamma < 1 || n_gamma > 64) return LRQ_EINVAL;
+    return tlq_impl(stream, W, N, K, bits, I, alpha_grid, n_alpha, beta_grid, n_beta, gamma_grid, n_gamma, out, gamma_pos,
+                    gamma_neg);
 }
 
 size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bits) {

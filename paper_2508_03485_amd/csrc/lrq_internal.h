@@ -54,7 +54,8 @@ hipError_t launch_fluctuation_metric(hipStream_t st, const uint16_t* X, size_t n
 
 hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
-                                    const lrq_tlq_weight& out);
+                                    const lrq_tlq_weight& out, const float* gamma_grid, int n_gamma, float* gamma_pos,
+                                    float* gamma_neg);
 
 // zero == nullptr: symmetric codes; otherwise the epilogue adds zero_t * colsum_n to the integer sum.
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,

@@ -44,18 +44,25 @@ __device__ __forceinline__ double clampd(double v, double lo, double hi) { retur
 
 // Grid search of one clip factor for one sign (Eq. hyperparameters clip); all threads return the
 // same (s, z, factor).  sgn = +1 scans the positive weights, -1 the negative ones.
+// ggrid / ngamma: optional grid of the lower clip factor (extension: s = (c W_max - g W_min) / intervals,
+// z = round(g W_min / s)), scanned inside the loop over c; ngamma = 0 is the paper's formula (g = 1).
 __device__ void search_side(const float* __restrict__ w, const double* __restrict__ ell, int K, double sgn,
                             bool has, double wmax, double wmin, const float* __restrict__ grid, int ngrid,
+                            const float* __restrict__ ggrid, int ngamma,
                             double nint, double qlo, double qhi, double* red, double& s_out, double& z_out,
-                            float& c_out) {
+                            float& c_out, float& g_out) {
     double best_err = INFINITY, best_s = 1.0, best_z = has ? rint(wmin) : 0.0;
-    float best_c = 1.0f;
-    for (int ci = 0; ci < ngrid; ++ci) {
+    float best_c = 1.0f, best_g = 1.0f;
+    const int ng = ngamma > 0 ? ngamma : 1;
+    for (int ci = 0; ci < ngrid; ++ci)
+    for (int gi = 0; gi < ng; ++gi) {
         const float c32 = grid[ci];
+        const float g32 = ngamma > 0 ? ggrid[gi] : 1.0f;
         const double T = (double)c32 * wmax;
-        if (!(has && T > wmin)) continue;                    // uniform over the workgroup
-        const double s = (T - wmin) / nint;
-        const double z = rint(wmin / s);
+        const double B = (double)g32 * wmin;
+        if (!(has && T > B)) continue;                       // uniform over the workgroup
+        const double s = (T - B) / nint;
+        const double z = rint(B / s);
         double err = 0.0;
         for (int k = threadIdx.x; k < K; k += NT) {
             const double wk = (double)w[k];
@@ -71,11 +78,13 @@ __device__ void search_side(const float* __restrict__ w, const double* __restric
             best_s = s;
             best_z = z;
             best_c = c32;
+            best_g = g32;
         }
     }
     s_out = best_s;
     z_out = best_z;
     c_out = best_c;
+    g_out = best_g;
 }
 
 __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
@@ -83,7 +92,8 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     const float* __restrict__ bgrid, int nb, uint8_t* __restrict__ codes_out, double* __restrict__ s_pos,
     double* __restrict__ s_neg, int32_t* __restrict__ z_pos, int32_t* __restrict__ z_neg,
     float* __restrict__ alpha, float* __restrict__ beta, int8_t* __restrict__ lut, float* __restrict__ wscale,
-    uint8_t* __restrict__ gemm_codes, int32_t* __restrict__ colsum) {
+    uint8_t* __restrict__ gemm_codes, int32_t* __restrict__ colsum, const float* __restrict__ ggrid, int ngamma,
+    float* __restrict__ gamma_pos, float* __restrict__ gamma_neg) {
     extern __shared__ double sm[];
     double* ell = sm;                                   // K doubles: log2|w|
     double* red = sm + K;                               // 64 doubles of reduction scratch
@@ -115,13 +125,17 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     if (!has_n) nmax = nmin = 0.0;
 
     double sp, zp, sn, zn;
-    float al, be;
-    search_side(w, ell, K, 1.0, has_p, pmax, pmin, agrid, na, (double)(half - 1), 0.0, (double)(half - 1), red, sp, zp, al);
-    search_side(w, ell, K, -1.0, has_n, nmax, nmin, bgrid, nb, (double)half, 1.0, (double)half, red, sn, zn, be);
+    float al, be, gp, gn;
+    search_side(w, ell, K, 1.0, has_p, pmax, pmin, agrid, na, ggrid, ngamma, (double)(half - 1), 0.0, (double)(half - 1),
+                red, sp, zp, al, gp);
+    search_side(w, ell, K, -1.0, has_n, nmax, nmin, bgrid, nb, ggrid, ngamma, (double)half, 1.0, (double)half, red, sn, zn,
+                be, gn);
 
     if (t == 0) {
         s_pos[n] = sp; s_neg[n] = sn; z_pos[n] = (int32_t)zp; z_neg[n] = (int32_t)zn;
         alpha[n] = al; beta[n] = be;
+        if (gamma_pos) gamma_pos[n] = gp;
+        if (gamma_neg) gamma_neg[n] = gn;
     }
 
     // level table: e(c) = s+(c + z+) for c >= 0, s-(-c + z-) for c < 0; exponent split and integerisation
@@ -209,7 +223,8 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
 
 hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K, int bits, int I,
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
-                                    const lrq_tlq_weight& out) {
+                                    const lrq_tlq_weight& out, const float* gamma_grid, int n_gamma, float* gamma_pos,
+                                    float* gamma_neg) {
     const size_t lds = (size_t)K * sizeof(double) + 64 * sizeof(double) + (size_t)K;
     {
         const hipError_t e = allow_large_lds(reinterpret_cast<const void*>(tlq_quantize_pack_kernel), 158 * 1024);
@@ -217,7 +232,7 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
     }
     hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
                        beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
-                       out.lut, out.wscale, out.gemm_codes, out.colsum);
+                       out.lut, out.wscale, out.gemm_codes, out.colsum, gamma_grid, n_gamma, gamma_pos, gamma_neg);
     return hipGetLastError();
 }
 

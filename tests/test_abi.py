@@ -195,3 +195,19 @@ def test_smoothing_entry_point_validates_on_the_host(L):
     # a misaligned pre-scale vector in the rotation struct
     rot = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_HADAMARD, 128, None, 0, None, None, None, P + 4))
     assert L.lrq_ars_rotate_quant(None, P, 4, 128, rot, 8, P, P, None, 0) == lrq.LRQ_EINVAL
+
+
+def test_lower_clip_entry_point_validates_on_the_host(L):
+    P = 4096
+    w = ctypes.byref(_weight())
+    ok = [None, P, 64, 128, 4, 7, P, 3, P, 3, P, 5, w, None, None, None, 0]
+    def call(i=None, v=None):
+        a = list(ok)
+        if i is not None:
+            a[i] = v
+        return L.lrq_tlq_quantize_pack_clip(*a)
+    assert call(10, None) == lrq.LRQ_EINVAL          # gamma grid missing
+    assert call(11, 0) == lrq.LRQ_EINVAL
+    assert call(11, 65) == lrq.LRQ_EINVAL
+    assert call(1, None) == lrq.LRQ_EINVAL
+    assert call(4, 5) == lrq.LRQ_EUNSUPPORTED

@@ -240,6 +240,34 @@ def test_tlq_quantize_pack_bit_exact(lrq, N, K, bits, I):
     _check_weight(lrq, W, bits, I)
 
 
+@pytest.mark.parametrize("N,K,bits", [(64, 1152, 4), (48, 1152, 3), (20, 4608, 4)])
+def test_tlq_lower_clip_bit_exact(lrq, N, K, bits):
+    """The search with a lower clip factor gamma (extension): codes, zero-points and all three chosen factors."""
+    print(f"case tlq clip N={N} K={K} b={bits}", flush=True)
+    W = synth.make_weights(N, K, (911, N, K))
+    gam = np.arange(1.0, 0.29, -0.05).astype(np.float32)
+    p = oracle.tlq_calibrate(W, bits, GRID, GRID, gamma_grid=gam)
+    codes = oracle.tlq_encode(W, p)
+    lut, wscale = oracle.tlq_lut(p, 7)
+    w = lrq.tlq_quantize_pack(to_dev(W), bits, 7, to_dev(GRID), to_dev(GRID), gamma_grid=to_dev(gam))
+    assert np.array_equal(w.alpha.cpu().numpy(), p.alpha) and np.array_equal(w.beta.cpu().numpy(), p.beta)
+    assert np.array_equal(w.gamma_pos.cpu().numpy(), p.gamma_pos) and np.array_equal(w.gamma_neg.cpu().numpy(), p.gamma_neg)
+    assert np.array_equal(w.z_pos.cpu().numpy(), p.z_pos) and np.array_equal(w.z_neg.cpu().numpy(), p.z_neg)
+    assert np.allclose(w.s_pos.cpu().numpy(), p.s_pos, rtol=1e-14, atol=0)
+    assert np.array_equal(w.codes.cpu().numpy(), oracle.pack_codes(codes, bits))
+    assert np.array_equal(w.lut.cpu().numpy()[:, :2 ** bits], lut)
+    assert (p.gamma_pos < 1).any()                                   # the clip is actually in use on these weights
+    # the grid {1} reproduces the plain entry point bit for bit
+    w0 = lrq.tlq_quantize_pack(to_dev(W), bits, 7, to_dev(GRID), to_dev(GRID))
+    w1 = lrq.tlq_quantize_pack(to_dev(W), bits, 7, to_dev(GRID), to_dev(GRID), gamma_grid=to_dev(np.array([1.0], np.float32)))
+    assert torch_equal(w0.codes, w1.codes) and torch_equal(w0.lut, w1.lut) and torch_equal(w0.s_pos, w1.s_pos)
+
+
+def torch_equal(a, b):
+    import torch
+    return torch.equal(a, b)
+
+
 def test_tlq_degenerate_channels(lrq):
     W = synth.make_weights(8, 128, (903, 0, 0))
     W[0] = 0.0
