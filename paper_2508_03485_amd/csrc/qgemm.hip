@@ -251,16 +251,16 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
             a0[i] = *reinterpret_cast<const v4i*>(aptr[i]);
             a1[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k1 * BK);
         }
+        // same issue order as the steady state of the K loop (A set, B block, A set, B block), so that the wait
+        // counters the compiler derives at the loop head are the loop's own and not a conservative merge
 #pragma unroll
-        for (int j = 0; j < NTW; ++j) {
-            bE[j] = load_braw<BITS>(bptr[j]);
-            bO[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
-        }
+        for (int i = 0; i < ALOADS; ++i) aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * BK);
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) {
-            aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * BK);
-            aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k3 * BK);
-        }
+        for (int j = 0; j < NTW; ++j) bE[j] = load_braw<BITS>(bptr[j]);
+#pragma unroll
+        for (int i = 0; i < ALOADS; ++i) aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k3 * BK);
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) bO[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
             *reinterpret_cast<v4i*>(&smem[aoff[i]]) = a0[i];
@@ -280,15 +280,19 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         afp[p] = *reinterpret_cast<const v4i*>(&smem[((p % MT) * 4 + (p / MT) * 2) * PLANE + rd_off]);
 
     int o0 = 0, o1 = ABUF, o2 = 2 * ABUF;       // LDS buffers of tiles kb, kb+1, kb+2
-    for (int kb = 0; kb < KB; kb += 2) {
+    int kb = 0;
+    // two K blocks per trip with no branch in between: with a conditional second block the compiler has to assume the
+    // shorter path at the loop head and drains the whole load queue there (s_waitcnt vmcnt(0)) on every trip
+    for (; kb + 1 < KB; kb += 2) {
         kblock<BITS, MT, NTW, ALOADS>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
-        if (kb + 1 < KB)
-            kblock<BITS, MT, NTW, ALOADS>(smem, o1, o0, o2, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        kblock<BITS, MT, NTW, ALOADS>(smem, o1, o0, o2, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
         const int t0 = o0;      // two blocks done: tiles kb+2, kb+3, kb+4 live in o2, o0, o1
         o0 = o2;
         o2 = o1;
         o1 = t0;
     }
+    if (kb < KB)                // odd number of K blocks
+        kblock<BITS, MT, NTW, ALOADS>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
 
     // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS (wave-private, so only wave-level
     // ordering is needed after the K loop's final barrier), store 16 bytes per lane.
