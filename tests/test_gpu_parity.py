@@ -455,3 +455,59 @@ def test_qlinear_replays_from_a_hip_graph(lrq):
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(Y_static, eager), f"replay {rep} differs from the eager result"
+
+
+def _random_case(seed):
+    g = synth.rng_for(912, seed)
+    K = int(g.choice([64, 128, 192, 256, 320, 384, 576, 1152, 2048, 2304]))
+    M = int(g.integers(1, 400))
+    N = int(g.integers(1, 700))
+    w_bits, a_bits = int(g.choice([3, 4])), int(g.choice([4, 8]))
+    kinds = ["hadamard", "hadamard", "none", "dense"] + (["blockperm"] if K % 128 == 0 else [])
+    kind = str(g.choice(kinds))
+    divs = [h for h in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048) if K % h == 0]
+    h = int(g.choice(divs))
+    return M, N, K, w_bits, a_bits, kind, h, bool(g.integers(0, 2)), bool(g.integers(0, 2)), bool(g.integers(0, 2))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_end_to_end(lrq, seed):
+    """Seeded random shapes, bit-widths, rotation kinds, quantizer forms, pre-scale and output types through
+    lrq_qlinear: activation codes bit-exact, outputs within 1e-3 of the oracle."""
+    import torch
+    M, N, K, w_bits, a_bits, kind, h, asym, pre, fp32 = _random_case(seed)
+    print(f"case random seed={seed} M={M} N={N} K={K} W{w_bits}A{a_bits} {kind} h={h} asym={asym} pre={pre} fp32={fp32}", flush=True)
+    X = _acts(M, K, 600 + seed)
+    W = synth.make_weights(N, K, (912, seed, 1))
+    bias = synth.make_bias(N, (912, seed, 2))
+    ps = (0.5 + synth.rng_for(912, seed, 3).random(K) * 2.0).astype(np.float32) if pre else None
+    kw, okw = {}, {}
+    if kind == "dense":
+        R = synth.make_rotation(K, (912, seed, 4))
+        kw, okw = dict(R=bf16_to_dev(R)), dict(R_bits=R)
+    if kind == "blockperm":
+        bp, rot0 = _blockperm_inputs(lrq, K, 128, seed)
+        kw, okw = dict(block=128, R1=rot0.R1, perm=rot0.perm, R2=rot0.R2), dict(blockperm=bp)
+    rot = lrq.Rotation(kind, had_block=h if kind == "hadamard" else 0, prescale=None if ps is None else to_dev(ps), **kw)
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), w_bits, 7, gd, gd)
+    p = oracle.tlq_calibrate(W, w_bits, GRID, GRID)
+    codes = oracle.tlq_encode(W, p)
+    lut, wscale = oracle.tlq_lut(p, 7)
+    Xd = bf16_to_dev(X)
+    out_dtype = torch.float32 if fp32 else torch.bfloat16
+    Y = lrq.qlinear(Xd, rot, a_bits, w, bias=to_dev(bias), out_dtype=out_dtype, asym=asym)
+    got = lrq.ars_rotate_quant(Xd, rot, a_bits, asym=asym)
+    if asym:
+        q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(X, a_bits, kind, h, prescale=ps, **okw)
+        assert np.array_equal(got[2].cpu().numpy(), z_ref)
+        y_ref = oracle.qlinear_from_parts_asym(q_ref, s_ref, z_ref, codes, lut, wscale, w_bits, bias)
+    else:
+        q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, kind, h, prescale=ps, **okw)
+        y_ref = oracle.qlinear_from_parts(q_ref, s_ref, codes, lut, wscale, w_bits, bias)
+    assert np.array_equal(got[0].cpu().numpy(), q_ref) and np.array_equal(got[1].cpu().numpy(), s_ref)
+    if fp32:
+        assert rel_fro(Y.cpu().numpy(), y_ref) <= 1e-3
+    else:
+        ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref))
+        assert rel_fro(oracle.bf16_bits_to_f64(bf16_bits_from_dev(Y)), ref16) <= 1e-3
