@@ -211,3 +211,26 @@ def test_lower_clip_entry_point_validates_on_the_host(L):
     assert call(11, 65) == lrq.LRQ_EINVAL
     assert call(1, None) == lrq.LRQ_EINVAL
     assert call(4, 5) == lrq.LRQ_EUNSUPPORTED
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/lrq.h is a C header: it compiles as C99 with no torch, HIP or C++ types in its signatures."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler on this host")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "lrq.h"\nint main(void) { lrq_rotation r = {0}; lrq_tlq_weight w = {0}; (void)r; (void)w; return 0; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I" + inc, "-fsyntax-only", str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    # the ctypes mirrors used by the binding have the C structs' sizes
+    probe = tmp_path / "sizes.c"
+    probe.write_text('#include <stdio.h>\n#include "lrq.h"\nint main(void) { printf("%zu %zu\\n", sizeof(lrq_rotation), sizeof(lrq_tlq_weight)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    r = subprocess.run([gcc, "-std=c99", "-I" + inc, str(probe), "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    a, b = (int(v) for v in subprocess.run([str(exe)], capture_output=True, text=True).stdout.split())
+    assert a == ctypes.sizeof(lrq._Rotation) and b == ctypes.sizeof(lrq._TlqWeight)
