@@ -367,7 +367,7 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
         butterflies<E32>(v, 5);
 #pragma unroll
         for (int round = 0; round < 2; ++round) {
-            if (PERSIST || round == 1) __syncthreads();   // earlier readers of the buffer (round 0 / previous group) are done
+            if (PERSIST || round == 1) __syncthreads();   // earlier readers of the buffer (first half / previous group) are done
             if (inwg) {
                 double2* dst = reinterpret_cast<double2*>(rowbuf + lds_row(slot));
 #pragma unroll

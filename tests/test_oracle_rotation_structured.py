@@ -84,8 +84,8 @@ def test_rejects_a_non_permutation():
 
 def test_zigzag_hand_example():
     # K = 6, two blocks of three.  Ranks (descending range): ch4, ch0, ch2, ch5, ch3, ch1.
-    # round 0 left to right: ch4 -> block 0, ch0 -> block 1; round 1 right to left: ch2 -> block 1, ch5 -> block 0;
-    # round 2 left to right: ch3 -> block 0, ch1 -> block 1.
+    # first deal, left to right: ch4 -> block 0, ch0 -> block 1; second deal, right to left: ch2 -> block 1, ch5 -> block 0;
+    # third deal, left to right: ch3 -> block 0, ch1 -> block 1.
     perm = rot.zigzag_permutation(np.array([5.0, 1.0, 4.0, 2.0, 6.0, 3.0]), 3)
     assert perm.tolist() == [4, 5, 3, 0, 2, 1]
 
