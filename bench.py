@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--structured", type=int, default=0, metavar="B",
                     help="run the layers that take the dense outlier-aware rotation with its structured form "
                          "X.R1.P.R2 instead (block size B, seeded block rotations and permutation)")
+    ap.add_argument("--clocks", action="store_true",
+                    help="also sample the shader clock (rocm-smi) while single kernels run back to back for ~2 s each and "
+                         "report it under 'sustained_clocks' (the int8 matrix peak scales with that clock)")
     ap.add_argument("--lower-clip", action="store_true",
                     help="calibrate the weights with the lower clip factor gamma (grid 1.00 .. 0.30 step 0.05) searched "
                          "jointly with alpha / beta (lrq_tlq_quantize_pack_clip)")
@@ -265,6 +268,8 @@ def main():
 
     if args.calibration:
         out["calibration"] = calibration_timings(lrq, layers[0], dev)
+    if args.clocks:
+        out["sustained_clocks"] = sustained_clocks(lrq, max(layers, key=lambda l: l["spec"].ops), dev)
 
     # what this device sustains on a pure int8 MFMA loop and on a plain copy kernel (context for the published peaks)
     out["measured_ceilings"] = dict(mfma_i8_tops_constant_operands=round(lrq.probe_mfma_i8(0), 1),
@@ -282,6 +287,51 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.cpu_rows, args.cpu_channels)
     print(json.dumps(out))
+
+
+def sustained_clocks(lrq, layer, dev):
+    """Shader clock reported by `rocm-smi --showclocks` while one kernel runs back to back (about 2 s of queued
+    launches, sampled after 1 s): the workload's largest GEMM on its real codes and on all-zero activation codes, the
+    pure MFMA probe with pseudo-random and with constant operands, and the layer's rotate+quantize."""
+    import re
+    import subprocess
+    import torch
+    s = layer["spec"]
+    X, w, rot = layer["X"][0], layer["w"], layer["rot"]
+    q, sc = lrq.ars_rotate_quant(X, rot, s.a_bits)
+    qz = torch.zeros_like(q)
+    Y = torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev)
+    scratch = torch.zeros(64, dtype=torch.int32, device=dev)
+    st = torch.cuda.current_stream().cuda_stream
+    L = lrq.lib()
+    cases = [("qgemm, the layer's own codes", lambda: lrq.qgemm(q, sc, w, out=Y)),
+             ("qgemm, all-zero activation codes", lambda: lrq.qgemm(qz, sc, w, out=Y)),
+             ("int8 MFMA loop, pseudo-random operands", lambda: L.lrq_probe_mfma_i8(st, 4096, 2048, 1, scratch.data_ptr(), None)),
+             ("int8 MFMA loop, constant operands", lambda: L.lrq_probe_mfma_i8(st, 4096, 2048, 0, scratch.data_ptr(), None)),
+             ("rotate + quantize", lambda: lrq.ars_rotate_quant(X, rot, s.a_bits, q=q, scale=sc))]
+
+    def sclk():
+        r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True)
+        m = re.search(r"sclk clock level:[^(]*\((\d+)Mhz\)", r.stdout)
+        return int(m.group(1)) if m else None
+
+    out = dict(layer=s.name, shape=[s.M, s.K, s.N], idle_mhz=sclk(), samples=[])
+    for name, fn in cases:
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        torch.cuda.synchronize()
+        one = max(a.elapsed_time(b), 0.02)
+        for _ in range(int(2000 / one)):
+            fn()
+        time.sleep(1.0)
+        mhz = sclk()
+        torch.cuda.synchronize()
+        out["samples"].append(dict(kernel=name, ms_per_launch=round(one, 4), sclk_mhz=mhz))
+    return out
 
 
 def calibration_timings(lrq, layer, dev):
