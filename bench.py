@@ -29,8 +29,10 @@ FP64_VEC_PEAK_TFLOPS = 78.6
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=0,
+                    help="timed steps; 0 (default) = as many as fill about 0.6 s, found with a short pilot run "
+                         "(the chip needs a few milliseconds of load to reach its steady clocks)")
+    ap.add_argument("--warmup", type=int, default=-1, help="untimed warm-up steps; -1 (default) = a tenth of the timed steps")
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--blocks", type=int, default=0, help="c5 only: number of transformer blocks (0 = all 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -168,6 +170,18 @@ def main():
         def step(i):                        # noqa: F811
             graphs[i % copies].replay()
 
+    if args.steps <= 0:                     # pilot: size the timed region to about 0.6 s
+        for i in range(3):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(10):
+            step(3 + i)
+        torch.cuda.synchronize()
+        pilot = (time.perf_counter() - t0) / 10
+        args.steps = int(min(4000, max(20, round(0.6 / pilot))))
+    if args.warmup < 0:
+        args.warmup = max(5, args.steps // 10)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -181,13 +195,13 @@ def main():
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
 
     # ---------------------------------------------------------------- per-kernel durations (HIP events on the launch stream)
-    ksteps = max(3, min(args.steps, 10))
+    ksteps = int(min(300, max(3, min(args.steps, round(0.25 / (ms_per_step * 1e-3))))))
     ev = []
     lead = torch.zeros(1, dtype=torch.int32, device=dev)
     for i in range(ksteps):
-        # a ~2 ms lead-in kernel keeps the host ahead of the device, so that an interval between two events holds
+        # a ~0.5 ms lead-in kernel keeps the host ahead of the device, so that an interval between two events holds
         # one kernel and no host-side launch gap (short kernels would otherwise be timed at the host's launch rate)
-        lrq.lib().lrq_probe_mfma_i8(torch.cuda.current_stream().cuda_stream, 2048, 2048, 0, lead.data_ptr(), None)
+        lrq.lib().lrq_probe_mfma_i8(torch.cuda.current_stream().cuda_stream, 2048, 512, 1, lead.data_ptr(), None)
         c = (args.warmup + args.steps + i) % copies
         for li, l in enumerate(layers):
             s = l["spec"]
