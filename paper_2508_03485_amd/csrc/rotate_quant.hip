@@ -767,8 +767,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         // resident workgroups per CU: two waves per SIMD by registers, LDS permitting
         const int groups = (M + R - 1) / R;
         int per_cu = (int)((160 * 1024 - 2048) / (ldsb + 512));
-        static const int wpc = [] { const char* e = getenv("LRQ_ROT2_WAVES"); return e ? atoi(e) : 8; }();
-        const int by_waves = wpc / (nt / kWave) > 0 ? wpc / (nt / kWave) : 1;
+        const int by_waves = 8 / (nt / kWave) > 0 ? 8 / (nt / kWave) : 1;
         if (per_cu > by_waves) per_cu = by_waves;
         if (per_cu < 1) per_cu = 1;
         // the largest block runs as persistent workgroups that load the next row group while transforming the current
