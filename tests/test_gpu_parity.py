@@ -279,6 +279,13 @@ def test_tlq_degenerate_channels(lrq):
     for bits in (3, 4):
         _check_weight(lrq, W, bits)
     _check_weight(lrq, W, 4, 7, np.array([1.0], np.float32), np.array([1.0, 1.5], np.float32))
+    # equal minima: all positive weights 4.0 are reproduced exactly by several factors; the first grid entry wins
+    W[6, :64] = 4.0
+    W[6, 64:] = -np.abs(W[6, 64:])
+    for grid in ([1.5, 1.25, 2.0], [2.0, 1.5, 1.25]):
+        for bits in (3, 4):
+            w, *_ = _check_weight(lrq, W, bits, 7, np.array(grid, np.float32), GRID)
+            assert float(w.alpha[6]) == grid[0]
 
 
 # ------------------------------------------------------------------ GEMM + rescale

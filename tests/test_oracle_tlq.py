@@ -129,6 +129,20 @@ def test_search_picks_the_first_minimum_of_the_grid(bits):
             assert float(chosen) == firsts[0]
 
 
+def test_equal_minima_keep_the_first_grid_entry():
+    # a side whose weights are all 4.0 is reproduced exactly by several clip factors (zero error each):
+    # the factor that comes first in the caller's grid order wins
+    W = np.full((2, 64), 4.0, dtype=np.float32)
+    W[:, 32:] = -np.abs(_weights(2, 32, 99))
+    for bits in (3, 4):
+        for grid, want in (([1.5, 1.25, 2.0], 1.5), ([2.0, 1.5, 1.25], 2.0), ([1.25, 2.0], 1.25)):
+            g = np.array(grid, dtype=np.float32)
+            p = oracle.tlq_calibrate(W, bits, g, GRID)
+            assert np.all(p.alpha == np.float32(want))
+            codes = oracle.tlq_encode(W, p)
+            assert np.array_equal(oracle.tlq_dequant(codes, p)[:, :32], W[:, :32].astype(np.float64))
+
+
 # ------------------------------------------------------------------ lower clip factor gamma (extension)
 GAMMAS = np.array([1.0, 0.9, 0.8, 0.7, 0.6, 0.5, 0.4], dtype=np.float32)
 
