@@ -9,6 +9,7 @@ import pytest
 
 import oracle
 import oracle.actquant
+import oracle.bf16
 import oracle.calib
 import oracle.rotation
 import oracle.tlq
@@ -218,8 +219,50 @@ def _greedy_without_swapping_back(xb, Rtilde, Q):
 def _asym_linear_wrong_sign(q, scale, zero, codes, lut, wscale, bits, bias=None):
     return _QLPA(q, scale, -np.asarray(zero), codes, lut, wscale, bits, bias)
 
+def _bf16_truncating(x):
+    x = np.asarray(x, dtype=np.float64)
+    f = x.astype(np.float32)
+    return (f.view(np.uint32) >> np.uint32(16)).astype(np.uint16)             # chops instead of rounding to nearest even
+
+
+def _asym_constant_row_scale_zero(u, a_bits, norm=1.0):
+    q, scale, zero = _ASYM(u, a_bits, norm)
+    u = np.asarray(u, dtype=np.float64)
+    const = u.max(axis=1) == u.min(axis=1)
+    return q, np.where(const, np.float32(0.0), scale).astype(np.float32), zero   # a constant token loses its value
+
+
+def _exponents_negative_twin_sign(p):
+    e, sign = _EXPO(p)
+    nlev = 2 ** p.bits
+    half = nlev // 2
+    for c in range(-half, 0):
+        e[:, c & (nlev - 1)] = p.s_neg * (c + p.z_neg.astype(np.float64))    # +c instead of -c for the negative twin
+    return e, sign
+
+
+def _build_with_absmax_ranks(xcal, B, Rtilde, Q1, Q2):
+    x = np.asarray(xcal, dtype=np.float64)
+    nb = x.shape[1] // B
+    R1 = np.empty((nb, B, B))
+    y = np.empty_like(x)
+    for g in range(nb):
+        R1[g], y[:, g * B:(g + 1) * B] = oracle.rotation.greedy_block_rotation(x[:, g * B:(g + 1) * B], Rtilde, Q1[g])
+    perm = oracle.rotation.zigzag_permutation(np.max(np.abs(y), axis=0), B)   # magnitude instead of max - min
+    yp = y[:, perm]
+    R2 = np.empty((nb, B, B))
+    for g in range(nb):
+        R2[g], _ = oracle.rotation.greedy_block_rotation(yp[:, g * B:(g + 1) * B], Rtilde, Q2[g])
+    rnd = lambda R: oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(R))
+    return rnd(R1), perm, rnd(R2)
+
+
+def _select_with_inclusive_threshold(J, threshold=1.0):
+    return "hadamard" if J <= threshold else "outlier-aware"
+
 
 _ASYM = oracle.actquant.quantize_per_token_asym
+_EXPO = oracle.tlq.tlq_exponents
 _SEARCH = oracle.tlq._search_side
 _CALIB = oracle.tlq.tlq_calibrate
 _QLPA = _qlinear_mod.qlinear_from_parts_asym
@@ -269,6 +312,15 @@ CASES = {
                                           [(t_str.test_one_greedy_step_is_the_printed_matrix_product, ())]),
     "zero-point term with the wrong sign": (_qlinear_mod.qlinear_from_parts_asym, _asym_linear_wrong_sign,
                                             [(t_asym.test_linear_layer_with_zero_point_equals_fake_quant_product, ())]),
+    "bf16 conversion truncates": (oracle.bf16.f64_to_bf16_bits, _bf16_truncating, [(t_rot.test_bf16_round_trip_against_torch, ())]),
+    "constant token loses its value": (oracle.actquant.quantize_per_token_asym, _asym_constant_row_scale_zero,
+                                       [(t_asym.test_constant_rows, ())]),
+    "negative twin's exponent with the wrong sign": (oracle.tlq.tlq_exponents, _exponents_negative_twin_sign,
+                                                    [(t_tlq.test_powers_of_two_are_reproduced_exactly, (4,)),
+                                                     (t_tlq.test_idempotent, (4,))]),
+    "permutation ranked by magnitude": (oracle.rotation.build_outlier_rotation, _build_with_absmax_ranks,
+                                        [(t_str.test_permutation_ranks_channels_by_max_minus_min_of_the_rotated_calibration_data, ())]),
+    "threshold rule inclusive": (oracle.calib.select_rotation, _select_with_inclusive_threshold, [(t_cal.test_threshold_rule, ())]),
     "smoothing factor as a product": (oracle.calib.smoothing_factor, _smoothing_product,
                                       [(t_cal.test_half_migration_equalises_activation_and_weight_ranges, ()),
                                        (t_cal.test_migration_extremes, ())]),

@@ -170,3 +170,23 @@ def test_built_rotation_suppresses_salient_channels_and_keeps_the_norm():
     # bf16-valued outputs
     for R in (R1, R2):
         assert np.array_equal(R, oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(R)))
+
+
+def test_permutation_ranks_channels_by_max_minus_min_of_the_rotated_calibration_data():
+    # identity rotations (R~ = Q = I) leave the data alone, so P must be the staggered dealing of the channels' ranges
+    # max - min; a one-sided channel (large values, small spread) must rank by its spread, not by its magnitude
+    rng = np.random.default_rng(11)
+    B, nb, T = 4, 3, 40
+    K = B * nb
+    x = rng.standard_normal((T, K))
+    x[:, 5] = 50.0 + 0.01 * rng.standard_normal(T)            # |x| large, range tiny
+    x[:, 2] *= 9.0                                             # widest range
+    eye = np.eye(B)
+    Q = np.broadcast_to(eye, (nb, 1, B, B)).copy()
+    R1, perm, R2 = rot.build_outlier_rotation(x, B, eye, Q, Q)
+    assert np.array_equal(R1, np.broadcast_to(eye, (nb, B, B))) and np.array_equal(R2, R1)
+    ranges = x.max(axis=0) - x.min(axis=0)
+    assert perm.tolist() == rot.zigzag_permutation(ranges, B).tolist()
+    assert perm[0] == 2                                        # the widest channel is dealt first
+    assert perm.tolist() != rot.zigzag_permutation(np.abs(x).max(axis=0), B).tolist()
+    assert list(perm).index(5) % B == B - 1                    # the one-sided channel lands in the last deal
