@@ -540,106 +540,128 @@ __global__ __launch_bounds__(256) void dense_rotate_f64_kernel(const uint16_t* _
 // scalar chain above whenever every product is exact in fp64 - bf16 x bf16 and fp32 x bf16 both are (a GPU test
 // compares the two kernels' U bit for bit).
 // SRC_F32: the left operand is fp32 [M, K] instead of bf16.  OUT_F32: the result is rounded once to fp32.
-// Workgroup = 4 waves (2 x 2), tile 128 x 128, wave tile 64 x 64 (16 accumulator tiles), K step 16; B must be a
-// multiple of 128 so that a column tile lies inside one block.
+// Workgroup = 4 waves (2 x 2), tile 128 x 128, wave tile 64 x 64 (16 accumulator tiles); B must be a multiple of
+// 128 so that a column tile lies inside one block.
+// The operand tiles stay in LDS in their storage format (bf16 / fp32, 2 / 4 bytes per element) and are widened to
+// fp64 when a fragment is read: a K step holds 64 (bf16 source) or 32 (fp32 source) k per barrier, the global ->
+// LDS path is a plain 16-byte copy, and LDS traffic is a quarter of what fp64 tiles would cost.
+// Row strides: 144 bytes for the left tile (36 dwords: the 16 rows a fragment read touches land on 16 distinct banks,
+// the four k of a read on consecutive ones) and 288 bytes for the R tile (its four k rows 8 banks apart).
 typedef double v4d __attribute__((ext_vector_type(4)));
-constexpr int MT_ = 128, MK_ = 16, XP_ = MK_ + 1, RP_ = MT_ + 4;
+constexpr int MT_ = 128;
 
 template <bool SRC_F32, bool OUT_F32>
 __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const void* __restrict__ src,
-                                                                            const uint16_t* __restrict__ R, int M, int K,
-                                                                            int B, void* __restrict__ dst,
-                                                                            const float* __restrict__ ps) {
-    __shared__ __attribute__((aligned(16))) double Xs[2][MT_ * XP_];     // [row][k], k contiguous, padded rows
-    __shared__ __attribute__((aligned(16))) double Rs[2][MK_ * RP_];     // [k][col]
+                                                                                 const uint16_t* __restrict__ R, int M, int K,
+                                                                                 int B, void* __restrict__ dst,
+                                                                                 const float* __restrict__ ps) {
+    constexpr int KS = SRC_F32 ? 32 : 64;           // k per step
+    constexpr int XS = 144, RS = 288;               // row strides in bytes
+    constexpr int XT = MT_ * XS, RT = KS * RS;      // tile bytes
+    static_assert(MT_ == 128, "tile loads are written out for 128 rows");
+    constexpr int XL = 4;                           // 16-byte chunks of the left tile per thread (128 rows x 128 bytes)
+    constexpr int RL = KS * 16 / 256;               // 16-byte chunks of the R tile per thread (KS rows x 256 bytes)
+    __shared__ __attribute__((aligned(16))) unsigned char Xs[2][XT];
+    __shared__ __attribute__((aligned(16))) unsigned char Rs[2][RT];
+    __shared__ float Ps[2][KS];
     const int t = threadIdx.x, lane = t % 64, wv = t / 64;
     const int wm = wv / 2, wn = wv % 2;
     const int row0 = blockIdx.y * MT_, col0 = blockIdx.x * MT_;
-    const int g = col0 / B, kbase = g * B, cb = col0 - kbase;            // block, its first k, tile's column inside it
+    const int g = col0 / B, kbase = g * B, cb = col0 - kbase;
     v4d acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4d{0.0, 0.0, 0.0, 0.0};
-    // loaders: left tile 128 rows x 16 k (8 values per thread), R tile 16 k x 128 cols (8 bf16 per thread)
-    const int xr = t / 2, xk = (t % 2) * 8;
-    const int rk = t / 16, rc = (t % 16) * 8;
-    int xrow = row0 + xr;
-    if (xrow >= M) xrow = M - 1;
-    const size_t xoff = (size_t)xrow * K + kbase + xk;
-    const uint16_t* rp = R + (size_t)g * B * B + (size_t)rk * B + cb + rc;
-    uint4 xa, xb;                                                        // xb: second half of 8 fp32 values
-    float4 pa = make_float4(1.f, 1.f, 1.f, 1.f), pb = pa;                // per-channel pre-scale of the 8 values (bf16 source)
-    auto load_x = [&](int kb) {
-        if constexpr (SRC_F32) {
-            const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(src) + xoff + (size_t)kb * MK_);
-            xa = p[0];
-            xb = p[1];
-        } else {
-            xa = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(src) + xoff + (size_t)kb * MK_);
-            if (ps) {
-                const float4* p = reinterpret_cast<const float4*>(ps + kbase + xk + kb * MK_);
-                pa = p[0];
-                pb = p[1];
-            }
-        }
-    };
-    load_x(0);
-    uint4 ra = *reinterpret_cast<const uint4*>(rp);
-    const int nk = B / MK_;
+    constexpr int XE = SRC_F32 ? 4 : 2;             // bytes per left element
+    constexpr int XCH = 128 / 16;                   // chunks per left-tile row (128 bytes of data)
+    const unsigned char* xsrc[XL];
+    int xdst[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        const int c = t + 256 * i, row = c / XCH, cc = c % XCH;
+        int grow = row0 + row;
+        if (grow >= M) grow = M - 1;
+        xsrc[i] = static_cast<const unsigned char*>(src) + ((size_t)grow * K + kbase) * XE + cc * 16;
+        xdst[i] = row * XS + cc * 16;
+    }
+    const unsigned char* rsrc[RL];
+    int rdst[RL];
+#pragma unroll
+    for (int i = 0; i < RL; ++i) {
+        const int c = t + 256 * i, row = c / 16, cc = c % 16;
+        rsrc[i] = reinterpret_cast<const unsigned char*>(R + (size_t)g * B * B + (size_t)row * B + cb) + cc * 16;
+        rdst[i] = row * RS + cc * 16;
+    }
+    const int nk = B / KS;
+    {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) *reinterpret_cast<uint4*>(&Xs[0][xdst[i]]) = *reinterpret_cast<const uint4*>(xsrc[i]);
+#pragma unroll
+        for (int i = 0; i < RL; ++i) *reinterpret_cast<uint4*>(&Rs[0][rdst[i]]) = *reinterpret_cast<const uint4*>(rsrc[i]);
+        if (t < KS) Ps[0][t] = ps ? ps[kbase + t] : 1.0f;
+    }
+    __syncthreads();
     for (int kb = 0; kb < nk; ++kb) {
         const int cur = kb & 1;
-        {
-            const unsigned xw[4] = {xa.x, xa.y, xa.z, xa.w}, rw[4] = {ra.x, ra.y, ra.z, ra.w};
-            double* xd = &Xs[cur][xr * XP_ + xk];
-            double* rd = &Rs[cur][rk * RP_ + rc];
-            if constexpr (SRC_F32) {
-                const unsigned xv[4] = {xb.x, xb.y, xb.z, xb.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    xd[i] = (double)__uint_as_float(xw[i]);
-                    xd[4 + i] = (double)__uint_as_float(xv[i]);
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    xd[2 * i] = (double)__uint_as_float(xw[i] << 16);
-                    xd[2 * i + 1] = (double)__uint_as_float(xw[i] & 0xffff0000u);
-                }
-                if (ps) {
-                    const float pv[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) xd[i] *= (double)pv[i];
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                rd[2 * i] = (double)__uint_as_float(rw[i] << 16);
-                rd[2 * i + 1] = (double)__uint_as_float(rw[i] & 0xffff0000u);
-            }
+        // next tile in flight during this step's MFMAs (the last step re-reads its own tile into the idle buffer:
+        // branch-free, and nothing reads that buffer afterwards)
+        const int kn = kb + 1 < nk ? kb + 1 : kb;
+        uint4 xn0 = *reinterpret_cast<const uint4*>(xsrc[0] + (size_t)kn * KS * XE);
+        uint4 xn1 = *reinterpret_cast<const uint4*>(xsrc[1] + (size_t)kn * KS * XE);
+        uint4 xn2 = *reinterpret_cast<const uint4*>(xsrc[2] + (size_t)kn * KS * XE);
+        uint4 xn3 = *reinterpret_cast<const uint4*>(xsrc[3] + (size_t)kn * KS * XE);
+        uint4 rn0 = *reinterpret_cast<const uint4*>(rsrc[0] + (size_t)kn * KS * B * 2);
+        uint4 rn1 = *reinterpret_cast<const uint4*>(rsrc[1] + (size_t)kn * KS * B * 2);
+        uint4 rn2 = rn0, rn3 = rn0;
+        if constexpr (RL == 4) {
+            rn2 = *reinterpret_cast<const uint4*>(rsrc[2] + (size_t)kn * KS * B * 2);
+            rn3 = *reinterpret_cast<const uint4*>(rsrc[3] + (size_t)kn * KS * B * 2);
         }
-        if (kb + 1 < nk) {
-            load_x(kb + 1);
-            ra = *reinterpret_cast<const uint4*>(rp + (size_t)(kb + 1) * MK_ * B);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        float pn = 1.0f;
+        if (ps && t < KS) pn = ps[kbase + kn * KS + t];
+        const unsigned char* xa = &Xs[cur][(wm * 64 + lane % 16) * XS + (lane / 16) * XE];
+        const unsigned char* rb = &Rs[cur][(lane / 16) * RS + (wn * 64 + lane % 16) * 2];
+#pragma unroll 2
+        for (int ks = 0; ks < KS / 4; ++ks) {
             double a[4], b[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = Xs[cur][(wm * 64 + i * 16 + lane % 16) * XP_ + ks * 4 + lane / 16];
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (SRC_F32) a[i] = (double)*reinterpret_cast<const float*>(xa + i * 16 * XS + ks * 4 * XE);
+                else a[i] = (double)__uint_as_float((unsigned)*reinterpret_cast<const uint16_t*>(xa + i * 16 * XS + ks * 4 * XE) << 16);
+            }
+            if (ps) {
+                const double pv = (double)Ps[cur][ks * 4 + lane / 16];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Rs[cur][(ks * 4 + lane / 16) * RP_ + wn * 64 + j * 16 + lane % 16];
+                for (int i = 0; i < 4; ++i) a[i] *= pv;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[j] = (double)__uint_as_float((unsigned)*reinterpret_cast<const uint16_t*>(rb + ks * 4 * RS + j * 32) << 16);
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
         }
-        // with two buffers one barrier per iteration is enough: a wave can only reach the writes of iteration
-        // kb + 2 (same buffer) after the barrier of iteration kb + 1, which every wave passes after its reads here
+        // the other buffer's last readers passed the barrier that closed the previous step
+        {
+            unsigned char* xw = Xs[cur ^ 1];
+            unsigned char* rw = Rs[cur ^ 1];
+            *reinterpret_cast<uint4*>(xw + xdst[0]) = xn0;
+            *reinterpret_cast<uint4*>(xw + xdst[1]) = xn1;
+            *reinterpret_cast<uint4*>(xw + xdst[2]) = xn2;
+            *reinterpret_cast<uint4*>(xw + xdst[3]) = xn3;
+            *reinterpret_cast<uint4*>(rw + rdst[0]) = rn0;
+            *reinterpret_cast<uint4*>(rw + rdst[1]) = rn1;
+            if constexpr (RL == 4) {
+                *reinterpret_cast<uint4*>(rw + rdst[2]) = rn2;
+                *reinterpret_cast<uint4*>(rw + rdst[3]) = rn3;
+            }
+            if (t < KS) Ps[cur ^ 1][t] = pn;
+        }
+        __syncthreads();
     }
-    // lane holds D[4 * r + lane / 16][lane % 16] of each 16 x 16 tile
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
