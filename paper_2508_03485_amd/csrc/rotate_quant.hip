@@ -312,7 +312,11 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 // buffer: 16 bytes per 32 lanes), which keeps the 16-byte writes of pass 1 and the quad-strided accesses of
 // pass 2 on distinct banks.  With PERSIST (used for h = 4096) a workgroup walks over row groups and loads the next
 // group's bf16 data while it transforms the current one.
-__device__ __forceinline__ int lds_row(int slot) { return 18 * slot + 4 * (slot >> 5); }
+// PAD doubles after every 32 pass-1 lanes: the Q lanes of a pass-2 pair / quad read rows 32 apart in one instruction,
+// next to 32 / Q element offsets of other lanes, so 32 / Q doubles of padding put all of them on distinct banks.
+template <int PAD>
+__device__ __forceinline__ int lds_row(int slot) { return 18 * slot + PAD * (slot >> 5); }
+constexpr int lds_pad(int log2h) { return log2h == 12 ? 8 : (log2h == 11 ? 16 : 4); }
 
 template <int LOG2H, bool PERSIST, bool ASYM, bool PRE>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(PERSIST || PRE ? 2 : 3, PERSIST || PRE ? 2 : 3)))
@@ -326,7 +330,8 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
     extern __shared__ __attribute__((aligned(16))) double lds[];
     __shared__ unsigned long long amax_bits[2][2][32];       // [parity][max |u| or key of max u / key of max -u][row]
     const int lpr = K / E32;
-    const int rs = lds_row(lpr) + 8;               // doubles per row buffer
+    constexpr int PAD = lds_pad(LOG2H);
+    const int rs = lds_row<PAD>(lpr) + 8;          // doubles per row buffer
     const int t = threadIdx.x;
     const int rw = t / lpr, slot = t % lpr;
     const bool inwg = rw < rows_per_wg;
@@ -369,7 +374,7 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
         for (int round = 0; round < 2; ++round) {
             if (PERSIST || round == 1) __syncthreads();   // earlier readers of the buffer (first half / previous group) are done
             if (inwg) {
-                double2* dst = reinterpret_cast<double2*>(rowbuf + lds_row(slot));
+                double2* dst = reinterpret_cast<double2*>(rowbuf + lds_row<PAD>(slot));
 #pragma unroll
                 for (int i = 0; i < 8; ++i) dst[i] = make_double2(v[16 * round + 2 * i], v[16 * round + 2 * i + 1]);
             }
@@ -378,7 +383,7 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
             if (my_round == round) {
 #pragma unroll
                 for (int r = 0; r < NG; ++r) {
-                    const double* p = rowbuf + lds_row(b * G + r + 32 * gq) + (e0 - 16 * round);
+                    const double* p = rowbuf + lds_row<PAD>(b * G + r + 32 * gq) + (e0 - 16 * round);
                     if constexpr (EPL == 4) {
                         const double2 a = *reinterpret_cast<const double2*>(p), c = *reinterpret_cast<const double2*>(p + 2);
                         w[r * 4 + 0] = a.x; w[r * 4 + 1] = a.y; w[r * 4 + 2] = c.x; w[r * 4 + 3] = c.y;
@@ -785,7 +790,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
-        const size_t ldsb = (size_t)R * (18 * lpr + 4 * (lpr >> 5) + 8) * sizeof(double);
+        const size_t ldsb = (size_t)R * (18 * lpr + lds_pad(ilog2(h)) * (lpr >> 5) + 8) * sizeof(double);
         // resident workgroups per CU: two waves per SIMD by registers, LDS permitting
         const int groups = (M + R - 1) / R;
         int per_cu = (int)((160 * 1024 - 2048) / (ldsb + 512));
