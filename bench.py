@@ -22,6 +22,7 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (the --levels path)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
 FP64_VEC_PEAK_TFLOPS = 78.6
 
@@ -55,6 +56,9 @@ def parse():
                          "builder) on the workload's first layer and report them under 'calibration'")
     ap.add_argument("--asym", action="store_true",
                     help="use the zero-point form of the activation quantizer (the paper's Eq. 1 as printed)")
+    ap.add_argument("--levels", action="store_true",
+                    help="run the GEMM on the TLQ levels themselves (lrq_qlinear_levels: bf16 matrix cores, the paper's value "
+                         "map without the int8 level table) - the fidelity-reference path, priced against the bf16 peak")
     ap.add_argument("--probes-only", action="store_true",
                     help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
@@ -154,7 +158,8 @@ def main():
     def step(i):
         c = i % copies
         for l in layers:
-            lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym)
+            lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym,
+                        levels=args.levels)
 
     if args.graph:
         eager_step = step
@@ -210,7 +215,8 @@ def main():
             lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"],
                                  asym=args.asym, zero=l["zr"][c] if args.asym else None)
             b.record()
-            lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c], zero=l["zr"][c] if args.asym else None)
+            lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c], zero=l["zr"][c] if args.asym else None,
+                      levels=args.levels)
             d.record()
             ev.append((li, a, b, d))
     torch.cuda.synchronize()
@@ -246,9 +252,11 @@ def main():
     # dominant kernel: the decode + MFMA GEMM.  Algorithmic ops per launch = 2*M*N*K.
     gemm_total_ms = sum(gemm_ms)
     gemm_tops = total_ops / (gemm_total_ms * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel="qgemm_kernel (decode + int8 MFMA + rescale)", achieved=round(gemm_tops, 2),
-                    peak=INT8_MFMA_PEAK_TOPS, unit="TFLOP/s", frac=round(gemm_tops / INT8_MFMA_PEAK_TOPS, 4),
-                    traffic=None, note="int8 multiply-accumulates counted as 2 ops (TOP/s); averaged over the "
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if args.levels else INT8_MFMA_PEAK_TOPS
+    roofline = dict(bound="mfma", kernel=("qgemm_levels_kernel (decode + bf16 MFMA + rescale)" if args.levels else
+                                          "qgemm_kernel (decode + int8 MFMA + rescale)"), achieved=round(gemm_tops, 2),
+                    peak=mfma_peak, unit="TFLOP/s", frac=round(gemm_tops / mfma_peak, 4),
+                    traffic=None, note="multiply-accumulates counted as 2 ops; averaged over the "
                     "workload's layers, %d launches each" % ksteps,
                     avg_launch_ms=round(gemm_total_ms / len(layers), 4))
     # Hadamard rotate+quantize: algorithmic bytes = 2 (bf16 in) + 1 (code out) per element + 4 per token
@@ -265,7 +273,7 @@ def main():
     out = dict(metric="fused W-TLQ/A-ARS qlinear TOPS + % int8 MFMA peak; rotate+quant HBM GB/s",
                value=round(tops, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype="int8", data="synthetic",
+               dtype="bf16" if args.levels else "int8", data="synthetic",
                config=dict(workload={1: "config1: single 256x1152->1152 W4A8 Hadamard",
                                      2: "config2: PixArt-style block linears, 8192 tokens, hidden 1152, W4A8, Hadamard",
                                      3: "config3: FLUX-style block linears, 4608 tokens, hidden 3072, W4A4, Hadamard",
@@ -276,7 +284,9 @@ def main():
                            smoothing_prescale=bool(args.smooth), hip_graph=bool(args.graph),
                            tlq_lower_clip=bool(args.lower_clip),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
-                           step="lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out"),
+                           value_map="levels round(2^r 2^I) 2^(f-I) as bf16 operands" if args.levels else "per-channel int8 level table",
+                           step=("lrq_qlinear_levels per layer: rotate + quantize + TLQ decode + bf16 MFMA GEMM + rescale, bf16 out" if args.levels else
+                                 "lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out")),
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
 
@@ -295,7 +305,8 @@ def main():
     if os.path.exists(traffic_file):
         tr = json.load(open(traffic_file)).get(args.workload)
         if tr:
-            out["roofline"]["traffic"] = tr.get("qgemm")
+            if not args.levels:
+                out["roofline"]["traffic"] = tr.get("qgemm")
             if out["roofline_rotate_quant"]:
                 out["roofline_rotate_quant"]["traffic"] = tr.get("rotate_quant")
     if not args.no_cpu_baseline:

@@ -90,6 +90,9 @@ typedef struct {
  *              loader (private layout, subject to change; only lrq_qlinear reads it).
  *   colsum     int32 [N]: the sum over k of the channel's decoded int8 levels; multiplied by a token's
  *              zero-point in the *_asym calls (Eq. 1 of the paper keeps a zero-point per quantizer).
+ *   levels     bf16 [N, 16] or NULL (then not written, and the *_levels calls refuse the struct):
+ *              levels[n][c & (2^bits-1)] is the level +-round(2^r 2^I) 2^(f-I) itself, rounded to nearest-even
+ *              bf16 - exact for 0 <= I <= 7, where a level has at most 8 significant bits.
  */
 typedef struct {
     int N, K;
@@ -106,6 +109,7 @@ typedef struct {
     float* wscale;
     uint8_t* gemm_codes;
     int32_t* colsum;     /* int32 [N]: sum_k lut[n][code[n,k]], the weight of an activation zero-point */
+    uint16_t* levels;    /* bf16 [N,16] or NULL: the levels themselves, operands of the *_levels calls  */
 } lrq_tlq_weight;
 
 /* Human-readable text of a status code (static storage). */
@@ -200,6 +204,21 @@ int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* r
  */
 int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K,
               const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y);
+
+/*
+ * The same layer on the levels themselves (paper: "Hardware Implementation", exponent split f / r and the
+ * integerisation of 2^r with I bits), without the per-channel int8 renormalisation that lrq_qlinear applies to them:
+ *   Y[t,n] = scale_t * sum_k q[t,k] * v_n(code[n,k])  (+ bias_n),   v_n(c) = +-round(2^r 2^I) 2^(f-I) = w->levels[n][c].
+ * Levels (for 0 <= I <= 7) and activation codes are bf16 values, so the contraction runs on the bf16 matrix cores
+ * with every product exact and fp32 accumulation: the fidelity reference of the int8 path at half its matrix rate.
+ * Requires w->levels != NULL and 0 <= w->I <= 7 (LRQ_EUNSUPPORTED otherwise); everything else (arguments, workspace
+ * = lrq_workspace_bytes, constraints, errors) as for lrq_qgemm / lrq_qlinear.
+ */
+int lrq_qgemm_levels(void* stream, const int8_t* q, const float* scale, int M, int K,
+                     const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y);
+int lrq_qlinear_levels(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                       const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y,
+                       void* ws, size_t ws_bytes);
 
 /*
  * Zero-point variants: the activation quantizer exactly as the paper's Eq. 1 (Preliminaries), per token:

@@ -46,4 +46,4 @@ from .actquant import quantize_per_token, quantize_per_token_asym  # noqa: F401
 from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
                   tlq_level_values, tlq_lut, pack_codes, unpack_codes)
 from .qlinear import (ars_rotate_quant, ars_rotate_quant_asym, qlinear, qlinear_from_parts,  # noqa: F401
-                      qlinear_from_parts_asym, reference_linear)
+                      qlinear_from_parts_asym, qlinear_levels_from_parts, reference_linear)

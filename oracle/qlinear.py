@@ -74,6 +74,18 @@ def qlinear_from_parts(q, scale, codes, lut, wscale, bits, bias=None):
     return y
 
 
+def qlinear_levels_from_parts(q, scale, codes, levels, bits, bias=None):
+    """The layer on the levels themselves ("Hardware Implementation": value of a code = +-round(2^r 2^I) 2^(f-I)),
+    without the per-channel int8 table: Y[t, n] = scale_t sum_k q[t, k] levels[n, code[n, k]] (+ bias_n), fp64.
+    levels: fp64 [N, 2^bits] indexed by the code's low bits (tlq_level_values)."""
+    idx = codes.astype(np.int64) & (2 ** bits - 1)
+    wv = np.take_along_axis(np.asarray(levels, dtype=np.float64), idx, axis=1)          # [N, K]
+    y = (q.astype(np.float64) @ wv.T) * scale.astype(np.float64)[:, None]
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y
+
+
 def qlinear(X_bits, W, w_bits, a_bits, rotation, had_block=None, R_bits=None, I=7,
             alpha_grid=None, beta_grid=None, bias=None):
     """Whole path: TLQ calibrate + encode the (already rotated) weights, rotate + quantize the

@@ -24,7 +24,8 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_probe_copy", "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
-           "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip")
+           "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
+           "lrq_qlinear_levels")
 
 
 class LrqError(RuntimeError):
@@ -44,7 +45,7 @@ class _TlqWeight(ctypes.Structure):
                 ("codes", ctypes.c_void_p), ("s_pos", ctypes.c_void_p), ("s_neg", ctypes.c_void_p),
                 ("z_pos", ctypes.c_void_p), ("z_neg", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("beta", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("wscale", ctypes.c_void_p),
-                ("gemm_codes", ctypes.c_void_p), ("colsum", ctypes.c_void_p)]
+                ("gemm_codes", ctypes.c_void_p), ("colsum", ctypes.c_void_p), ("levels", ctypes.c_void_p)]
 
 
 _lib = None
@@ -89,6 +90,8 @@ def lib() -> ctypes.CDLL:
     L.lrq_workspace_bytes_asym.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_qlinear_asym.restype = ci
     L.lrq_qlinear_asym.argtypes = L.lrq_qlinear.argtypes
+    L.lrq_qgemm_levels.restype, L.lrq_qgemm_levels.argtypes = ci, L.lrq_qgemm.argtypes
+    L.lrq_qlinear_levels.restype, L.lrq_qlinear_levels.argtypes = ci, L.lrq_qlinear.argtypes
     L.lrq_ars_build_workspace_bytes.restype, L.lrq_ars_build_workspace_bytes.argtypes = sz, [ci, ci, ci]
     L.lrq_ars_build_rotation.restype = ci
     L.lrq_ars_build_rotation.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, sz]
@@ -166,11 +169,12 @@ class TLQWeight:
         self.wscale = torch.empty(N, dtype=torch.float32, **kw)
         self.gemm_codes = torch.zeros(ng, dtype=torch.uint8, **kw)
         self.colsum = torch.empty(N, dtype=torch.int32, **kw)
+        self.levels = torch.empty((N, 16), dtype=torch.bfloat16, **kw)
 
     def c_struct(self) -> _TlqWeight:
         return _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
                           _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
-                          _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum))
+                          _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum), _ptr(self.levels))
 
 
 def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None, out: Optional[TLQWeight] = None,
@@ -248,8 +252,10 @@ def _out_code(dtype) -> int:
 
 
 def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=None, out=None, workspace=None,
-            asym: bool = False):
-    """lrq_qlinear (asym=True: lrq_qlinear_asym): fused rotate, quantize, decode, GEMM and rescale.  Returns Y [M, N]."""
+            asym: bool = False, levels: bool = False):
+    """lrq_qlinear (asym=True: lrq_qlinear_asym; levels=True: lrq_qlinear_levels): fused rotate, quantize, decode,
+    GEMM and rescale.  Returns Y [M, N]."""
+    assert not (asym and levels)
     import torch
     assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
     M, K = X.shape
@@ -260,15 +266,17 @@ def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=
     size_fn = lib().lrq_workspace_bytes_asym if asym else lib().lrq_workspace_bytes
     if workspace is None:
         workspace = torch.empty(size_fn(M, w.N, K, ctypes.byref(r), act_bits), dtype=torch.uint8, device=X.device)
-    fn = lib().lrq_qlinear_asym if asym else lib().lrq_qlinear
-    st = fn(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
-            _out_code(out_dtype), _ptr(out), _ptr(workspace), workspace.numel())
-    _check(st, "lrq_qlinear_asym" if asym else "lrq_qlinear")
+    name = "lrq_qlinear_asym" if asym else ("lrq_qlinear_levels" if levels else "lrq_qlinear")
+    st = getattr(lib(), name)(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
+                              _out_code(out_dtype), _ptr(out), _ptr(workspace), workspace.numel())
+    _check(st, name)
     return out
 
 
-def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None, zero=None):
-    """lrq_qgemm (zero given: lrq_qgemm_asym): the decode + GEMM + rescale stage on existing activation codes."""
+def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None, zero=None, levels: bool = False):
+    """lrq_qgemm (zero given: lrq_qgemm_asym; levels=True: lrq_qgemm_levels): the decode + GEMM + rescale stage on
+    existing activation codes."""
+    assert not (levels and zero is not None)
     import torch
     assert q.is_cuda and q.dtype == torch.int8 and q.is_contiguous()
     M, K = q.shape
@@ -281,9 +289,10 @@ def qgemm(q, scale, w: TLQWeight, bias=None, out_dtype=None, out=None, zero=None
                                   _out_code(out_dtype), _ptr(out))
         _check(st, "lrq_qgemm_asym")
         return out
-    st = lib().lrq_qgemm(_stream(), _ptr(q), _ptr(scale), M, K, ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
-                         _ptr(out))
-    _check(st, "lrq_qgemm")
+    name = "lrq_qgemm_levels" if levels else "lrq_qgemm"
+    st = getattr(lib(), name)(_stream(), _ptr(q), _ptr(scale), M, K, ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
+                              _ptr(out))
+    _check(st, name)
     return out
 
 

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblrq.so")
-SOURCES = ["lrq_api.hip", "rotate_quant.hip", "tlq_pack.hip", "qgemm.hip", "ars_calib.hip", "probes.hip"]
+SOURCES = ["lrq_api.hip", "rotate_quant.hip", "tlq_pack.hip", "qgemm.hip", "qgemm_levels.hip", "ars_calib.hip", "probes.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

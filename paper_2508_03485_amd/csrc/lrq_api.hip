@@ -68,6 +68,7 @@ int check_weight(const lrq_tlq_weight* w) {
         !w->wscale || !w->gemm_codes || !w->colsum)
         return LRQ_EINVAL;
     if (!aligned16(w->codes) || !aligned16(w->lut) || !aligned16(w->gemm_codes)) return LRQ_EINVAL;
+    if (w->levels && !aligned16(w->levels)) return LRQ_EINVAL;
     return LRQ_OK;
 }
 
@@ -126,7 +127,7 @@ const char* lrq_status_string(int status) {
     }
 }
 
-int lrq_version(void) { return 200; }   // 0.2.0: lrq_rotation grew the structured-rotation and pre-scale fields
+int lrq_version(void) { return 300; }   // 0.3.0: lrq_tlq_weight grew the bf16 level table (0.2.0: lrq_rotation grew its structured-rotation and pre-scale fields)
 
 size_t lrq_tlq_codes_bytes(int N, int K, int bits) {
     if (N <= 0 || K <= 0 || (bits != 3 && bits != 4) || K % 8 != 0) return 0;
@@ -214,36 +215,61 @@ size_t lrq_workspace_bytes_asym(int M, int N, int K, const lrq_rotation* rot, in
     return lrq_workspace_bytes(M, N, K, rot, act_bits) + round256((size_t)M * sizeof(int32_t));
 }
 
-static int qgemm_impl(void* stream, const int8_t* q, const float* scale, const int32_t* zero, bool asym, int M, int K,
+enum class Gemm { kInt8, kInt8Zero, kLevels };
+
+// the *_levels calls need the bf16 level table, and levels that are bf16 values
+static int check_levels(const lrq_tlq_weight* w) {
+    if (!w->levels) return LRQ_EINVAL;
+    return (w->I < 0 || w->I > 7) ? LRQ_EUNSUPPORTED : LRQ_OK;
+}
+
+static int qgemm_impl(void* stream, const int8_t* q, const float* scale, const int32_t* zero, Gemm kind, int M, int K,
                       const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y) {
+    const bool asym = kind == Gemm::kInt8Zero;
     if (!q || !scale || !Y || M <= 0 || K <= 0 || !aligned16(q) || !aligned16(Y) || (asym && !zero)) return LRQ_EINVAL;
     int st = check_weight(w);
     if (st != LRQ_OK) return st;
     if (w->K != K) return LRQ_EINVAL;
     if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
     if (K % lrq::kGemmBlockK != 0) return LRQ_EUNSUPPORTED;
-    hipError_t e = lrq::launch_qgemm(static_cast<hipStream_t>(stream), q, scale, asym ? zero : nullptr, M, K, *w, bias,
-                                     out_dtype, Y);
+    hipError_t e;
+    if (kind == Gemm::kLevels) {
+        st = check_levels(w);
+        if (st != LRQ_OK) return st;
+        e = lrq::launch_qgemm_levels(static_cast<hipStream_t>(stream), q, scale, M, K, *w, bias, out_dtype, Y);
+    } else {
+        e = lrq::launch_qgemm(static_cast<hipStream_t>(stream), q, scale, asym ? zero : nullptr, M, K, *w, bias, out_dtype, Y);
+    }
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_qgemm_levels(void* stream, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight* w,
+                     const float* bias, int out_dtype, void* Y) {
+    return qgemm_impl(stream, q, scale, nullptr, Gemm::kLevels, M, K, w, bias, out_dtype, Y);
 }
 
 int lrq_qgemm(void* stream, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight* w,
               const float* bias, int out_dtype, void* Y) {
-    return qgemm_impl(stream, q, scale, nullptr, false, M, K, w, bias, out_dtype, Y);
+    return qgemm_impl(stream, q, scale, nullptr, Gemm::kInt8, M, K, w, bias, out_dtype, Y);
 }
 
 int lrq_qgemm_asym(void* stream, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
                    const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y) {
-    return qgemm_impl(stream, q, scale, zero, true, M, K, w, bias, out_dtype, Y);
+    return qgemm_impl(stream, q, scale, zero, Gemm::kInt8Zero, M, K, w, bias, out_dtype, Y);
 }
 
 static int qlinear_impl(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
                         const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes,
-                        bool asym) {
+                        Gemm kind) {
+    const bool asym = kind == Gemm::kInt8Zero;
     int st = check_act(X, M, K, rot, act_bits);
     if (st != LRQ_OK) return st;
     st = check_weight(w);
     if (st != LRQ_OK) return st;
+    if (kind == Gemm::kLevels) {
+        st = check_levels(w);
+        if (st != LRQ_OK) return st;
+    }
     if (!Y || !aligned16(Y) || w->K != K) return LRQ_EINVAL;
     if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
     if (K % lrq::kGemmBlockK != 0) return LRQ_EUNSUPPORTED;
@@ -258,18 +284,24 @@ static int qlinear_impl(void* stream, const void* X, int M, int K, const lrq_rot
     hipStream_t s = static_cast<hipStream_t>(stream);
     st = run_rotate_quant(s, X, M, K, rot, act_bits, q, scale, zero, rot_ws);
     if (st != LRQ_OK) return st;
-    hipError_t e = lrq::launch_qgemm(s, q, scale, zero, M, K, *w, bias, out_dtype, Y);
+    hipError_t e = kind == Gemm::kLevels ? lrq::launch_qgemm_levels(s, q, scale, M, K, *w, bias, out_dtype, Y)
+                                         : lrq::launch_qgemm(s, q, scale, zero, M, K, *w, bias, out_dtype, Y);
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_qlinear_levels(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                       const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, Gemm::kLevels);
 }
 
 int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
                 const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
-    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, false);
+    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, Gemm::kInt8);
 }
 
 int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
                      const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
-    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, true);
+    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, Gemm::kInt8Zero);
 }
 
 size_t lrq_ars_build_workspace_bytes(int T, int K, int block) {

@@ -61,6 +61,10 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
                         const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y);
 
+// Y = scale_t * sum_k q * levels (+ bias) on the bf16 matrix cores; w.levels must be set.
+hipError_t launch_qgemm_levels(hipStream_t st, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight& w,
+                               const float* bias, int out_dtype, void* Y);
+
 // Raises a kernel's dynamic-LDS limit (hipFuncAttributeMaxDynamicSharedMemorySize) the first time it is asked for on
 // the current device; later calls for the same (kernel, device) return at once.  Safe from several host threads.
 hipError_t allow_large_lds(const void* kernel, int bytes);

@@ -44,9 +44,13 @@ __global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(int iters, int pa
     if (s == 0x7fffffff) out[0] = s;   // keeps the loop alive; practically never taken
 }
 
-__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+// One 16-byte element per thread, one workgroup per 4 KiB, streaming (non-temporal) accesses: workgroups are
+// dispatched in order, so the chip sweeps both buffers as one compact moving window.  Measured faster than a
+// persistent grid-stride loop (whose workgroups touch pages far apart) by 20 - 40 %.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void copy_probe_kernel(const v4u* __restrict__ src, v4u* __restrict__ dst, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
 }  // namespace
@@ -58,8 +62,8 @@ hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int pattern,
 
 hipError_t launch_copy_probe(hipStream_t st, const void* src, void* dst, size_t bytes) {
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(copy_probe_kernel, dim3(256 * 16), dim3(256), 0, st, static_cast<const uint4*>(src),
-                       static_cast<uint4*>(dst), n16);
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const v4u*>(src), static_cast<v4u*>(dst), n16);
     return hipGetLastError();
 }
 

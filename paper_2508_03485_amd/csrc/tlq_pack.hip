@@ -87,13 +87,25 @@ __device__ void search_side(const float* __restrict__ w, const double* __restric
     g_out = best_g;
 }
 
+// Round-to-nearest-even bf16 of a double.  The detour over fp32 could round twice only when the fp32 value lands
+// exactly on a bf16 midpoint; the sign of what the first rounding dropped then decides the tie.
+__device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
+    const float f = (float)x;
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)(u >> 16);     // inf / nan
+    const double d = fabs(x) - fabs((double)f);
+    if ((u & 0xffffu) == 0x8000u && d != 0.0) return (uint16_t)((u >> 16) + (d > 0.0 ? 1u : 0u));
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
 __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     const float* __restrict__ W, int N, int K, int bits, int I, const float* __restrict__ agrid, int na,
     const float* __restrict__ bgrid, int nb, uint8_t* __restrict__ codes_out, double* __restrict__ s_pos,
     double* __restrict__ s_neg, int32_t* __restrict__ z_pos, int32_t* __restrict__ z_neg,
     float* __restrict__ alpha, float* __restrict__ beta, int8_t* __restrict__ lut, float* __restrict__ wscale,
     uint8_t* __restrict__ gemm_codes, int32_t* __restrict__ colsum, const float* __restrict__ ggrid, int ngamma,
-    float* __restrict__ gamma_pos, float* __restrict__ gamma_neg) {
+    float* __restrict__ gamma_pos, float* __restrict__ gamma_neg, uint16_t* __restrict__ levels) {
     extern __shared__ double sm[];
     double* ell = sm;                                   // K doubles: log2|w|
     double* red = sm + K;                               // 64 doubles of reduction scratch
@@ -164,6 +176,7 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
         if (t < nlev) entry = (int8_t)(int)clampd(rint(v / (double)ws), -127.0, 127.0);
         lut[(size_t)n * 16 + t] = entry;
         lutv[t] = entry;
+        if (levels) levels[(size_t)n * 16 + t] = t < nlev ? f64_to_bf16_rne(v) : (uint16_t)0;
     }
     if (t == 0) wscale[n] = ws;
 
@@ -232,7 +245,7 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
     }
     hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
                        beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
-                       out.lut, out.wscale, out.gemm_codes, out.colsum, gamma_grid, n_gamma, gamma_pos, gamma_neg);
+                       out.lut, out.wscale, out.gemm_codes, out.colsum, gamma_grid, n_gamma, gamma_pos, gamma_neg, out.levels);
     return hipGetLastError();
 }
 

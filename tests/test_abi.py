@@ -105,6 +105,26 @@ def test_qlinear_rejects_bad_arguments_on_the_host(L):
     assert g(None, P, P, 16, 96, w96, None, 0, P) == lrq.LRQ_EUNSUPPORTED                    # K % 64
 
 
+def test_levels_entry_points_validate_on_the_host(L):
+    P = 4096
+    had = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_HADAMARD, 128, None))
+    big = 1 << 30
+    g, f = L.lrq_qgemm_levels, L.lrq_qlinear_levels
+    no_table = ctypes.byref(_weight())                                # levels == NULL
+    assert g(None, P, P, 16, 128, no_table, None, 0, P) == lrq.LRQ_EINVAL
+    assert f(None, P, 16, 128, had, 8, no_table, None, 0, P, P, big) == lrq.LRQ_EINVAL
+    for I in (8, -1):                                                 # levels that are not bf16 values
+        w = ctypes.byref(_weight(I=I, levels=P))
+        assert g(None, P, P, 16, 128, w, None, 0, P) == lrq.LRQ_EUNSUPPORTED
+        assert f(None, P, 16, 128, had, 8, w, None, 0, P, P, big) == lrq.LRQ_EUNSUPPORTED
+    w = ctypes.byref(_weight(levels=P))
+    assert g(None, None, P, 16, 128, w, None, 0, P) == lrq.LRQ_EINVAL                       # q null
+    assert g(None, P, P, 16, 128, w, None, 7, P) == lrq.LRQ_EUNSUPPORTED                    # out dtype
+    assert g(None, P, P, 16, 128, ctypes.byref(_weight(levels=P + 2)), None, 0, P) == lrq.LRQ_EINVAL   # misaligned table
+    assert f(None, P, 16, 128, had, 8, w, None, 0, P, None, 0) == lrq.LRQ_EWORKSPACE
+    assert f(None, P, 16, 256, had, 8, w, None, 0, P, P, big) == lrq.LRQ_EINVAL             # K mismatch
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(lrq, "_lib", None)
     monkeypatch.setattr(lrq, "LIB_PATH", str(tmp_path / "nope.so"))

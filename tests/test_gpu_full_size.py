@@ -147,3 +147,28 @@ def test_structured_rotation_at_config_4_size(lrq):
     q_ref, s_ref = oracle.ars_rotate_quant(X[rows], spec.a_bits, "blockperm", blockperm=(R1, perm, R2))
     assert np.array_equal(q[ridx].cpu().numpy(), q_ref)
     assert np.array_equal(sc[ridx].cpu().numpy(), s_ref)
+
+
+@pytest.mark.parametrize("cfg,layer", [(2, 2), (4, 3), (5, 1)])
+def test_levels_path_at_full_size(lrq, cfg, layer):
+    """lrq_qlinear_levels (the GEMM on the levels themselves, bf16 matrix cores) at full size, sampled rows x channels."""
+    import torch
+    spec = synth.config_layers(cfg)[layer]
+    print(f"levels layer {spec.name} cfg{cfg} M={spec.M} K={spec.K} N={spec.N} W{spec.w_bits}", flush=True)
+    X, W, _, _ = synth.layer_tensors(spec)
+    rows, chans = _sample(spec.M, N_ROWS, spec.key), _sample(spec.N, N_CH, spec.key)
+    rot = lrq.Rotation("hadamard", spec.had_block)
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), spec.w_bits, 7, gd, gd)
+    Y = lrq.qlinear(bf16_to_dev(X), rot, spec.a_bits, w, out_dtype=torch.float32, levels=True)
+    torch.cuda.synchronize()
+    ridx, cidx = torch.from_numpy(rows).to(Y.device), torch.from_numpy(chans).to(Y.device)
+    y_s = Y[ridx][:, cidx].cpu().numpy()
+    q_ref, s_ref = oracle.ars_rotate_quant(X[rows], spec.a_bits, "hadamard", spec.had_block)
+    p = oracle.tlq_calibrate(W[chans], spec.w_bits, GRID, GRID)
+    codes = oracle.tlq_encode(W[chans], p)
+    v = oracle.tlq_level_values(p, 7)
+    lv = w.levels[cidx].view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(lv[:, :2 ** spec.w_bits], oracle.f64_to_bf16_bits(v))
+    y_ref = oracle.qlinear_levels_from_parts(q_ref, s_ref, codes, v, spec.w_bits)
+    assert rel_fro(y_s, y_ref) <= 1e-5

@@ -325,6 +325,47 @@ def test_qgemm_against_oracle(lrq, M, N, K, w_bits, a_bits):
         assert np.array_equal(acc.astype(np.float64), ref_acc)
 
 
+@pytest.mark.parametrize("M,N,K,w_bits,a_bits,I", [
+    (256, 1152, 1152, 4, 8, 7),   # config 1
+    (300, 352, 1152, 4, 8, 7),    # ragged M, N not a multiple of the workgroup tile
+    (513, 200, 256, 3, 4, 7),     # N not a multiple of 32, 3-bit weights
+    (2, 6912, 1152, 3, 4, 5),     # two tokens, fewer mantissa bits
+    (130, 260, 64, 4, 4, 0),      # a single K block, N not a multiple of 8 (scalar stores), levels are powers of two
+])
+def test_levels_path_against_oracle(lrq, M, N, K, w_bits, a_bits, I):
+    """The layer on the levels themselves (bf16 matrix cores): the level table bit for bit, outputs to the fp32
+    accumulation of K exact products (relative Frobenius error <= 1e-3 is the stated bar; 1e-5 is what it gives)."""
+    import torch
+    print(f"case levels M={M} N={N} K={K} W{w_bits}A{a_bits} I={I}", flush=True)
+    W = synth.make_weights(N, K, (906, N, K))
+    w, codes, _, _ = _check_weight(lrq, W, w_bits, I)
+    p = oracle.tlq_calibrate(W, w_bits, GRID, GRID)
+    v = oracle.tlq_level_values(p, I)
+    lv = w.levels.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(lv[:, :2 ** w_bits], oracle.f64_to_bf16_bits(v))
+    assert np.all(lv[:, 2 ** w_bits:] == 0)
+    X = _acts(M, K, 7 + M)
+    q, s = oracle.ars_rotate_quant(X, a_bits, "hadamard", synth.default_had_block(K))
+    bias = synth.make_bias(N, (906, N, K))
+    qd, sd = to_dev(q), to_dev(s)
+    y_ref = oracle.qlinear_levels_from_parts(q, s, codes, v, w_bits, bias)
+    y32 = lrq.qgemm(qd, sd, w, bias=to_dev(bias), out_dtype=torch.float32, levels=True).cpu().numpy()
+    assert rel_fro(y32, y_ref) <= 1e-5
+    y_ref_nb = oracle.qlinear_levels_from_parts(q, s, codes, v, w_bits)
+    y16 = bf16_bits_from_dev(lrq.qgemm(qd, sd, w, out_dtype=torch.bfloat16, levels=True))
+    ref16 = oracle.bf16_bits_to_f64(oracle.f64_to_bf16_bits(y_ref_nb))
+    assert rel_fro(oracle.bf16_bits_to_f64(y16), ref16) <= 1e-3
+    # the fused call: same rotation + quantizer in front
+    Y = lrq.qlinear(bf16_to_dev(X), lrq.Rotation("hadamard", synth.default_had_block(K)), a_bits, w, bias=to_dev(bias),
+                    out_dtype=torch.float32, levels=True).cpu().numpy()
+    assert rel_fro(Y, y_ref) <= 1e-5
+    # and the int8-table path stays within its table rounding of it
+    y_i8 = lrq.qgemm(qd, sd, w, bias=to_dev(bias), out_dtype=torch.float32).cpu().numpy()
+    bound = (s.astype(np.float64)[:, None] * np.abs(q.astype(np.float64)).sum(axis=1)[:, None]
+             * (w.wscale.cpu().numpy().astype(np.float64)[None, :] / 2))
+    assert np.all(np.abs(y_i8 - y32) <= bound * (1 + 1e-3) + 1e-6 * np.abs(y_ref).max())
+
+
 def test_extreme_shapes(lrq):
     """Smallest and largest shapes the entry points accept."""
     import torch

@@ -16,6 +16,7 @@ import oracle.tlq
 import test_oracle_actquant as t_act
 import test_oracle_actquant_asym as t_asym
 import test_oracle_calib as t_cal
+import test_oracle_levels as t_lev
 import test_oracle_qlinear as t_ql
 import test_oracle_rotation as t_rot
 import test_oracle_rotation_structured as t_str
@@ -261,6 +262,22 @@ def _select_with_inclusive_threshold(J, threshold=1.0):
     return "hadamard" if J <= threshold else "outlier-aware"
 
 
+def _levels_layer_bias_scaled(q, scale, codes, levels, bits, bias=None):
+    idx = codes.astype(np.int64) & (2 ** bits - 1)
+    wv = np.take_along_axis(np.asarray(levels, dtype=np.float64), idx, axis=1)
+    y = q.astype(np.float64) @ wv.T
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y * scale.astype(np.float64)[:, None]            # the bias must not take the token's scale
+
+
+def _levels_layer_by_signed_code_magnitude(q, scale, codes, levels, bits, bias=None):
+    idx = np.abs(codes.astype(np.int64))                     # a negative code must select its own (negative) level
+    wv = np.take_along_axis(np.asarray(levels, dtype=np.float64), np.minimum(idx, 2 ** bits - 1), axis=1)
+    y = (q.astype(np.float64) @ wv.T) * scale.astype(np.float64)[:, None]
+    return y if bias is None else y + np.asarray(bias, dtype=np.float64)[None, :]
+
+
 _ASYM = oracle.actquant.quantize_per_token_asym
 _EXPO = oracle.tlq.tlq_exponents
 _SEARCH = oracle.tlq._search_side
@@ -320,6 +337,11 @@ CASES = {
                                                      (t_tlq.test_idempotent, (4,))]),
     "permutation ranked by magnitude": (oracle.rotation.build_outlier_rotation, _build_with_absmax_ranks,
                                         [(t_str.test_permutation_ranks_channels_by_max_minus_min_of_the_rotated_calibration_data, ())]),
+    "levels layer scales the bias": (_qlinear_mod.qlinear_levels_from_parts, _levels_layer_bias_scaled,
+                                     [(t_lev.test_against_exact_rational_arithmetic, (4,))]),
+    "levels layer drops the code's sign": (_qlinear_mod.qlinear_levels_from_parts, _levels_layer_by_signed_code_magnitude,
+                                           [(t_lev.test_reduces_to_the_fake_quant_product_with_dequantized_weights, ()),
+                                            (t_lev.test_distance_to_the_int8_table_path_is_the_table_rounding, (4,))]),
     "threshold rule inclusive": (oracle.calib.select_rotation, _select_with_inclusive_threshold, [(t_cal.test_threshold_rule, ())]),
     "smoothing factor as a product": (oracle.calib.smoothing_factor, _smoothing_product,
                                       [(t_cal.test_half_migration_equalises_activation_and_weight_ranges, ()),
