@@ -166,8 +166,8 @@ size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bi
  * lrq_ars_rotate_quant - rotate and quantize an activation tile for a given per-layer rotation choice.
  * Paper: Method, "Adaptive Rotation Scheme" (rotation choice), Preliminaries Eq. 1 in its symmetric
  * per-token form (Experiment, "Implementation Details": per-token dynamic activation quantization).
- *   X         bf16 [M,K].            rot: see lrq_rotation.       act_bits: 4 | 8.
- *   q         int8 [M,K] out: codes in [-qmax, qmax], qmax = 2^(act_bits-1) - 1 (4-bit codes are held
+ *   X         bf16 [M,K].            rot: see lrq_rotation.       act_bits: 4 | 6 | 8 (the settings of the paper's tables).
+ *   q         int8 [M,K] out: codes in [-qmax, qmax], qmax = 2^(act_bits-1) - 1 (4- and 6-bit codes are held
  *             in int8 containers), q = rint(u * (qmax / amax_t)), round-half-even, amax_t = max_k |u|.
  *   scale     float [M] out: amax_t / (qmax * sqrt(h)) for Hadamard, amax_t / qmax otherwise, so that
  *             q * scale approximates x . (normalised rotation).  An all-zero token gives q = 0, scale 0.

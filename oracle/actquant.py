@@ -18,7 +18,7 @@ import numpy as np
 
 def quantize_per_token(u: np.ndarray, a_bits: int, norm: float = 1.0):
     """u fp64 [M, K] -> (q int8 [M, K], scale fp32 [M])."""
-    assert a_bits in (4, 8)
+    assert a_bits in (4, 6, 8)           # the bit-widths of the paper's tables
     u = np.asarray(u, dtype=np.float64)
     qmax = float(2 ** (a_bits - 1) - 1)
     amax = np.max(np.abs(u), axis=1)
@@ -42,7 +42,7 @@ def quantize_per_token_asym(u: np.ndarray, a_bits: int, norm: float = 1.0):
     Returned in the form the integer GEMM consumes: q = x_q - 2^(b-1) (int8), zero = z + 2^(b-1) (int32), so that
     x_f = scale * (q + zero) with scale = fp32(s / norm).  u fp64 [M, K] -> (q int8 [M, K], scale fp32 [M],
     zero int32 [M])."""
-    assert a_bits in (4, 8)
+    assert a_bits in (4, 6, 8)           # the bit-widths of the paper's tables
     u = np.asarray(u, dtype=np.float64)
     L = float(2 ** a_bits - 1)
     half = 2 ** (a_bits - 1)

@@ -56,7 +56,7 @@ int check_rotation(const lrq_rotation* rot, int K) {
 
 int check_act(const void* X, int M, int K, const lrq_rotation* rot, int act_bits) {
     if (!X || M <= 0 || K <= 0 || !aligned16(X)) return LRQ_EINVAL;
-    if (act_bits != 4 && act_bits != 8) return LRQ_EUNSUPPORTED;
+    if (act_bits != 4 && act_bits != 6 && act_bits != 8) return LRQ_EUNSUPPORTED;
     if (K % 8 != 0) return LRQ_EUNSUPPORTED;
     return check_rotation(rot, K);
 }

@@ -50,7 +50,7 @@ def test_rotate_quant_rejects_bad_arguments_on_the_host(L):
     assert f(None, P, 0, 128, had(128), 8, P, P, None, 0) == lrq.LRQ_EINVAL
     assert f(None, P + 2, 4, 128, had(128), 8, P, P, None, 0) == lrq.LRQ_EINVAL          # misaligned
     assert f(None, P, 4, 128, None, 8, P, P, None, 0) == lrq.LRQ_EINVAL
-    assert f(None, P, 4, 128, had(128), 6, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED        # act bits
+    assert f(None, P, 4, 128, had(128), 5, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED        # act bits
     assert f(None, P, 4, 132, had(4), 8, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED          # K % 8
     assert f(None, P, 4, 1152, had(96), 8, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED        # not a power of two
     assert f(None, P, 4, 1152, had(256), 8, P, P, None, 0) == lrq.LRQ_EUNSUPPORTED       # does not divide K

@@ -33,6 +33,7 @@ def _acts(M, K, seed, n_salient=4, gain=40.0):
     (5, 64, 1, 8), (5, 64, 2, 8), (9, 64, 4, 4), (3, 192, 8, 8), (33, 192, 64, 8),
     (70, 1536, 512, 8), (65, 4608, 512, 8), (40, 3072, 1024, 4), (19, 12288, 4096, 8), (3, 16384, 16384, 8),
     (1, 1152, 128, 8),
+    (131, 1152, 128, 6), (77, 3072, 1024, 6),     # 6-bit activations (the paper's W4A6 settings)
 ])
 def test_hadamard_rotate_quant_bit_exact(lrq, M, K, h, a_bits):
     print(f"case M={M} K={K} h={h} a={a_bits}", flush=True)
@@ -396,7 +397,7 @@ def test_extreme_shapes(lrq):
 
 
 # ------------------------------------------------------------------ fused path
-@pytest.mark.parametrize("cfg_case", ["config1", "dense", "w3a4"])
+@pytest.mark.parametrize("cfg_case", ["config1", "dense", "w3a4", "w4a6"])
 def test_qlinear_end_to_end(lrq, cfg_case):
     import torch
     print(f"case qlinear {cfg_case}", flush=True)
@@ -404,6 +405,8 @@ def test_qlinear_end_to_end(lrq, cfg_case):
         spec = synth.config_layers(1)[0]
     elif cfg_case == "dense":
         spec = synth.LayerSpec("d", 905, 0, 0, 150, 256, 96, 4, 8, "dense", 256, 0.05, 4, 40.0)
+    elif cfg_case == "w4a6":
+        spec = synth.LayerSpec("a6", 907, 0, 0, 201, 1152, 288, 4, 6, "hadamard", 128, 0.05, 8, 40.0)
     else:
         spec = synth.LayerSpec("w3", 906, 0, 0, 333, 1152, 416, 3, 4, "hadamard", 128, 0.05, 8, 40.0)
     X, W, R, bias = synth.layer_tensors(spec, with_bias=True)
@@ -426,6 +429,7 @@ def test_qlinear_end_to_end(lrq, cfg_case):
     (256, 1152, "hadamard", 128, 8), (37, 1152, "hadamard", 128, 4), (9, 64, "hadamard", 4, 8),
     (70, 1536, "hadamard", 512, 8), (40, 3072, "hadamard", 1024, 4), (19, 12288, "hadamard", 4096, 8),
     (3, 16384, "hadamard", 16384, 8), (11, 256, "none", 0, 8), (70, 128, "dense", 0, 8), (64, 1152, "dense", 0, 4),
+    (100, 1152, "hadamard", 128, 6), (30, 4608, "hadamard", 512, 6),
 ])
 def test_zero_point_rotate_quant_bit_exact(lrq, M, K, rotation, h, a_bits):
     print(f"case asym M={M} K={K} {rotation} h={h} a={a_bits}", flush=True)

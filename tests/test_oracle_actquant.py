@@ -22,7 +22,7 @@ def test_worked_example_by_hand():
     assert q4.tolist() == [[7, -4, 2, 0]] and s4[0] == np.float32(1.0)
 
 
-@pytest.mark.parametrize("a_bits", [4, 8])
+@pytest.mark.parametrize("a_bits", [4, 6, 8])
 def test_brute_force_nearest_grid_point(a_bits):
     rng = np.random.default_rng(a_bits)
     u = rng.standard_normal((6, 40)) * 3.0
@@ -38,7 +38,7 @@ def test_brute_force_nearest_grid_point(a_bits):
                 assert q[t, k] == best
 
 
-@pytest.mark.parametrize("a_bits", [4, 8])
+@pytest.mark.parametrize("a_bits", [4, 6, 8])
 def test_properties(a_bits):
     rng = np.random.default_rng(20 + a_bits)
     u = rng.standard_normal((16, 257)) * np.exp(rng.standard_normal((16, 1)) * 3)

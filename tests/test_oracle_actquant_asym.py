@@ -21,7 +21,7 @@ def test_worked_example_by_hand():
     assert np.allclose(0.2 * (xq + z), [[-1.0, 2.0, 0.0, 0.4, 1.2]])
 
 
-@pytest.mark.parametrize("a_bits", [4, 8])
+@pytest.mark.parametrize("a_bits", [4, 6, 8])
 def test_brute_force_eq1_in_exact_rationals(a_bits):
     rng = np.random.default_rng(40 + a_bits)
     u = rng.standard_normal((5, 33)) * 3.0 + rng.standard_normal((5, 1)) * 4.0      # rows with non-zero mean
@@ -41,7 +41,7 @@ def test_brute_force_eq1_in_exact_rationals(a_bits):
                 assert int(q[t, k]) + half == want
 
 
-@pytest.mark.parametrize("a_bits", [4, 8])
+@pytest.mark.parametrize("a_bits", [4, 6, 8])
 def test_properties(a_bits):
     rng = np.random.default_rng(50 + a_bits)
     u = rng.standard_normal((12, 200)) * np.exp(rng.standard_normal((12, 1))) + rng.standard_normal((12, 1)) * 5
