@@ -80,10 +80,12 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-__device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
-    unsigned u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+// two floats -> two bf16 (round-to-nearest-even, v_cvt_pk_bf16_f32), a in the low half
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 
 // One K block of the main loop.  The A tiles rotate through three LDS buffers: block kb multiplies from `cur`
@@ -156,7 +158,7 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
 // BM rows x (4 waves x NTW x 32) columns per workgroup; MT = BM / 32 MFMA row tiles per wave.  Two shapes
 // are used: 128 x 256 (NTW = 2) and 256 x 128 (NTW = 1); both keep 128 accumulator registers per lane, i.e.
 // two workgroups per CU.  The second halves the decode work per MFMA and doubles the LDS reads per MFMA.
-template <int BITS, int BM, int NTW>
+template <int BITS, int BM, int NTW, bool ZP>
 __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
     const uint8_t* __restrict__ gcodes, const int8_t* __restrict__ lut, const float* __restrict__ wscale,
@@ -168,8 +170,8 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     constexpr int ALOADS = BM * 4 / 256;        // 16-byte chunks of the A tile per thread
     constexpr int LDS_BYTES = (3 * ABUF > WAVES * EPI_WAVE) ? 3 * ABUF : WAVES * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
-    __shared__ float sc[BM];
-    __shared__ int zr[BM];          // per-token zero-points (zero-point form only)
+    __shared__ __attribute__((aligned(16))) float sc[BM];
+    __shared__ __attribute__((aligned(16))) int zr[BM];          // per-token zero-points (zero-point form only)
 
     // XCD-aware tile order.  Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2), so
     // XCD x is handed a contiguous range of a linear tile order; that order walks 8-row-tile groups n-fastest
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     if (t < BM) {
         const int r = m0 + t;
         sc[t] = r < M ? scale[r] : 0.0f;
-        zr[t] = (zero && r < M) ? zero[r] : 0;
+        zr[t] = (ZP && r < M) ? zero[r] : 0;
     }
 
     v16i acc[MT][NTW];
@@ -294,9 +296,8 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     if (kb < KB)                // odd number of K blocks
         kblock<BITS, MT, NTW, ALOADS>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
 
-    // ---- epilogue: rescale in fp32, stage one 32-row slab per wave in LDS (wave-private, so only wave-level
-    // ordering is needed after the K loop's final barrier), store 16 bytes per lane.
-    // Lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of every 32x32 accumulator tile.
+    // ---- epilogue: rescale in fp32.  Lane holds column (lane % 32) and rows 8 g + 4 (lane / 32) + (0..3), g = 0..3, of
+    // every 32 x 32 accumulator tile (four consecutive rows per group of four accumulator registers).
     float wsc[NTW], bs[NTW];
     int csum[NTW];
 #pragma unroll
@@ -305,26 +306,46 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         if (n >= N) n = N - 1;
         wsc[j] = wscale[n];
         bs[j] = bias ? bias[n] : 0.0f;
-        csum[j] = zero ? colsum[n] : 0;
+        csum[j] = ZP ? colsum[n] : 0;
     }
-    // integer sum of one output: accumulator plus zero_t * colsum_n (64-bit: the product can exceed 32 bits)
-    auto total = [&](int a, int lr, int j) -> float {
-        return zero ? (float)((long long)a + (long long)zr[lr] * (long long)csum[j]) : (float)a;
+    // y of accumulator register 4 g + x of tile (i, j); the zero-point form adds zero_t * colsum_n to the integer sum
+    // (64-bit: the product can exceed 32 bits)
+    auto rescale4 = [&](int i, int j, int g, float (&y)[4]) {
+        const int lr0 = i * 32 + 8 * g + 4 * (lane / 32);
+        const float4 s4 = *reinterpret_cast<const float4*>(&sc[lr0]);
+        const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
+        int zv[4] = {0, 0, 0, 0};
+        if constexpr (ZP) {
+            const int4 z4 = *reinterpret_cast<const int4*>(&zr[lr0]);
+            zv[0] = z4.x; zv[1] = z4.y; zv[2] = z4.z; zv[3] = z4.w;
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int a = acc[i][j][4 * g + x];
+            const float tot = ZP ? (float)((long long)a + (long long)zv[x] * (long long)csum[j]) : (float)a;
+            y[x] = (tot * sv[x]) * wsc[j] + bs[j];
+        }
     };
-    unsigned char* slab = smem + wv * EPI_WAVE;
     const int ncol0 = n0 + wv * WN;                 // first column of this wave
-    const bool vec = (N % (out_fp32 ? 4 : 8)) == 0; // rows of Y are 16-byte aligned
+    unsigned char* slab = smem + wv * EPI_WAVE;
     if (!out_fp32) {
+        // bf16: one 32-row slab per wave staged in LDS (wave-private, so only wave-level ordering is needed after the
+        // K loop's final barrier); every lane then stores 16 contiguous bytes, a row segment of the wave is WN * 2 bytes
         uint16_t* Yh = reinterpret_cast<uint16_t*>(Y);
+        const bool vec = N % 8 == 0;                // rows of Y are 16-byte aligned
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
 #pragma unroll
             for (int j = 0; j < NTW; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int lr = 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-                    const float y = (total(acc[i][j][r], i * 32 + lr, j) * sc[i * 32 + lr]) * wsc[j] + bs[j];
-                    *reinterpret_cast<uint16_t*>(&slab[lr * EPI_ROW + (j * 32 + lane % 32) * 2]) = (uint16_t)f32_to_bf16_rne(y);
+                for (int g = 0; g < 4; ++g) {
+                    float y[4];
+                    rescale4(i, j, g, y);
+                    const unsigned d[2] = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        *reinterpret_cast<uint16_t*>(&slab[(8 * g + 4 * (lane / 32) + x) * EPI_ROW + (j * 32 + lane % 32) * 2]) =
+                            (uint16_t)(d[x / 2] >> (16 * (x % 2)));
                 }
             wave_sync();
             // 32 rows x (WN * 2) bytes: WN / 8 lanes per row, 16 bytes per lane
@@ -348,16 +369,20 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
             wave_sync();
         }
     } else {
+        // fp32: the same staging, one 32 x 32 tile at a time
         float* Yf = reinterpret_cast<float*>(Y);
+        const bool vec = N % 4 == 0;
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
             for (int j = 0; j < NTW; ++j) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int lr = 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-                    const float y = (total(acc[i][j][r], i * 32 + lr, j) * sc[i * 32 + lr]) * wsc[j] + bs[j];
-                    *reinterpret_cast<float*>(&slab[lr * EPI_ROW + (lane % 32) * 4]) = y;
+                for (int g = 0; g < 4; ++g) {
+                    float y[4];
+                    rescale4(i, j, g, y);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        *reinterpret_cast<float*>(&slab[(8 * g + 4 * (lane / 32) + x) * EPI_ROW + (lane % 32) * 4]) = y[x];
                 }
                 wave_sync();
 #pragma unroll
@@ -386,8 +411,12 @@ hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, const int
                   const lrq_tlq_weight& w, const float* bias, int fp32, void* Y) {
     constexpr int BN = WAVES * 32 * NTW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + BN - 1) / BN;
-    hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
-                       w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
+    if (zero)
+        hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
+                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
+    else
+        hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW, false>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
+                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
     return hipGetLastError();
 }
 
