@@ -766,9 +766,9 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
                                  int8_t* q, float* scale, int32_t* zero, const float* prescale) {
     const QuantSpec qs = make_spec(act_bits, h, zero, prescale);
     if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
-        // R whole rows per workgroup, about five waves (finer granularity measured faster than nine)
+        // R whole rows per workgroup, at most four waves (finer granularity measured faster than nine; 7 rows of 1152 fill four waves)
         const int lpr = K / E32;
-        static const int tgt = [] { const char* e = getenv("LRQ_ROT_THREADS"); return e ? atoi(e) : 288; }();
+        static const int tgt = [] { const char* e = getenv("LRQ_ROT_THREADS"); return e ? atoi(e) : 256; }();
         int R = tgt / lpr;
         if (R < 1) R = 1;
         if (R > 32) R = 32;
