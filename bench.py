@@ -198,6 +198,22 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     total_ops = sum(l["spec"].ops for l in layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
+    # the same steps on one set of buffers (inputs, workspaces and outputs stay in the 256 MB Infinity Cache when the
+    # working set is small): reported next to the rotated-buffer figure, which is the one in `value`
+    hot = None
+    if copies > 1:
+        nh = max(20, args.steps // 4)
+        for i in range(5):
+            step(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(nh):
+            step(0)
+        torch.cuda.synchronize()
+        hot_ms = (time.perf_counter() - t0) * 1e3 / nh
+        hot = dict(ms_per_step=round(hot_ms, 4), value=round(total_ops / (hot_ms * 1e-3) / 1e12, 2), steps=nh,
+                   note="same buffers every step (working set resident in the Infinity Cache); `value` rotates among "
+                        "%d buffer sets" % copies)
 
     # ---------------------------------------------------------------- per-kernel durations (HIP events on the launch stream)
     ksteps = int(min(300, max(3, min(args.steps, round(0.25 / (ms_per_step * 1e-3))))))
@@ -290,6 +306,8 @@ def main():
                roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
 
+    if hot:
+        out["hot_cache"] = hot
     if args.calibration:
         out["calibration"] = calibration_timings(lrq, layers[0], dev)
     if args.clocks:
