@@ -140,11 +140,20 @@ class Rotation:
     R2: object = None       # torch bf16 [K/block, block, block] on the device
     prescale: object = None # any kind: torch fp32 [K] on the device multiplied into x before the rotation
 
+    def __setattr__(self, name, value):
+        object.__setattr__(self, name, value)
+        object.__setattr__(self, "_cs", None)       # any change drops the cached C struct
+
     def c_struct(self) -> _Rotation:
-        kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE,
-                 "blockperm": LRQ_ROT_BLOCKPERM}
-        return _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R), int(self.block), _ptr(self.R1),
-                         _ptr(self.perm), _ptr(self.R2), _ptr(self.prescale))
+        """The C struct of this choice (built once per state: marshalling is most of a small call's host time)."""
+        cs = self.__dict__.get("_cs")
+        if cs is None:
+            kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE,
+                     "blockperm": LRQ_ROT_BLOCKPERM}
+            cs = _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R), int(self.block), _ptr(self.R1),
+                           _ptr(self.perm), _ptr(self.R2), _ptr(self.prescale))
+            object.__setattr__(self, "_cs", cs)
+        return cs
 
 
 class TLQWeight:
@@ -171,10 +180,19 @@ class TLQWeight:
         self.colsum = torch.empty(N, dtype=torch.int32, **kw)
         self.levels = torch.empty((N, 16), dtype=torch.bfloat16, **kw)
 
+    def __setattr__(self, name, value):
+        object.__setattr__(self, name, value)
+        object.__setattr__(self, "_cs", None)       # any change drops the cached C struct
+
     def c_struct(self) -> _TlqWeight:
-        return _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
-                          _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
-                          _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum), _ptr(self.levels))
+        """The C struct over these arrays (built once per state)."""
+        cs = self.__dict__.get("_cs")
+        if cs is None:
+            cs = _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
+                            _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
+                            _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum), _ptr(self.levels))
+            object.__setattr__(self, "_cs", cs)
+        return cs
 
 
 def tlq_quantize_pack(W, bits: int, I: int = 7, alpha_grid=None, beta_grid=None, out: Optional[TLQWeight] = None,
