@@ -6,7 +6,8 @@
 // accumulation of v_mfma_f32_32x32x16_bf16 rounds.  This is the fidelity reference of the int8 path: the same
 // codes, the paper's value map, half the matrix rate.
 //
-// Workgroup = 4 waves, tile 128 rows x 256 columns; a wave owns 64 columns (two 32-column tiles) of all 128 rows.
+// Workgroup = 4 waves, tile 128 rows x 256 (or 128) columns; a wave owns 64 (32) columns - NTW 32-column tiles - of all
+// 128 rows.
 // Activation codes are widened to bf16 once per workgroup on their way into LDS (two buffers); the packed weight
 // codes go from global memory into registers (same tiling as the int8 GEMM reads) and are decoded there through a
 // per-lane 16-entry table of bf16 levels, held as a high-byte and a low-byte table for byte permutes.
@@ -25,7 +26,7 @@ typedef short v8s __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, MT = BM / 32, NTW = 2, WN = 32 * NTW, BN = 4 * WN;
+constexpr int BM = 128, MT = BM / 32;
 constexpr int BK = kGemmBlockK;                 // 64
 constexpr int PLANE = 32 * 16 + 32;             // one (row tile, 8-value chunk) plane: 32 rows x 16 bytes, padded
 constexpr int ABUF = MT * 8 * PLANE;            // one A tile as bf16: 128 rows x 64 k
@@ -84,12 +85,13 @@ __device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
     return u >> 16;
 }
 
-template <int BITS>
-__global__ __launch_bounds__(256, 2) void qgemm_levels_kernel(const int8_t* __restrict__ q, const float* __restrict__ scale,
+template <int BITS, int NTW>
+__global__ __launch_bounds__(256, NTW == 1 ? 3 : 2) void qgemm_levels_kernel(const int8_t* __restrict__ q, const float* __restrict__ scale,
                                                               int M, int K, int N, const uint8_t* __restrict__ gcodes,
                                                               const uint16_t* __restrict__ levels,
                                                               const float* __restrict__ bias, int out_fp32,
                                                               void* __restrict__ Y, int tiles_m, int tiles_n) {
+    constexpr int WN = 32 * NTW, BN = 4 * WN;
     constexpr int LDS_BYTES = 2 * ABUF > 4 * EPI_WAVE ? 2 * ABUF : 4 * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
     __shared__ float sc[BM];
@@ -291,14 +293,18 @@ __global__ __launch_bounds__(256, 2) void qgemm_levels_kernel(const int8_t* __re
 hipError_t launch_qgemm_levels(hipStream_t st, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight& w,
                                const float* bias, int out_dtype, void* Y) {
     const int fp32 = out_dtype == LRQ_OUT_FP32;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + BN - 1) / BN;
+    // 128 x 256 tiles (two workgroups per CU) for long K loops; 128 x 128 (three per CU) for short ones and for N that
+    // wastes much of a 256-wide tile - the same rule as the int8 GEMM's
+    const bool narrow = K <= 2048 || (w.N % 256 != 0 && w.N <= 2048);
+    const int bn = narrow ? 128 : 256;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + bn - 1) / bn;
     const dim3 grid(tiles_m * tiles_n), block(256);
-    if (w.bits == 4)
-        hipLaunchKernelGGL(qgemm_levels_kernel<4>, grid, block, 0, st, q, scale, M, K, w.N, w.gemm_codes, w.levels, bias, fp32,
-                           Y, tiles_m, tiles_n);
-    else
-        hipLaunchKernelGGL(qgemm_levels_kernel<3>, grid, block, 0, st, q, scale, M, K, w.N, w.gemm_codes, w.levels, bias, fp32,
-                           Y, tiles_m, tiles_n);
+#define LRQ_GO(B, T)                                                                                                       \
+    hipLaunchKernelGGL((qgemm_levels_kernel<B, T>), grid, block, 0, st, q, scale, M, K, w.N, w.gemm_codes, w.levels, bias, \
+                       fp32, Y, tiles_m, tiles_n)
+    if (w.bits == 4) { if (narrow) LRQ_GO(4, 1); else LRQ_GO(4, 2); }
+    else { if (narrow) LRQ_GO(3, 1); else LRQ_GO(3, 2); }
+#undef LRQ_GO
     return hipGetLastError();
 }
 
