@@ -4,7 +4,7 @@
  * The library implements one W-A-quantized linear layer of a Diffusion Transformer:
  *   activations  -> (optional smoothing pre-scale) -> Adaptive Rotation Scheme (Hadamard, or the
  *                   outlier-aware rotation in dense or structured R1.P.R2 form, chosen per layer)
- *                   -> per-token uniform quantization to 4/8-bit codes
+ *                   -> per-token uniform quantization to 4/6/8-bit codes
  *   weights      -> packed 3/4-bit Twin-Log Quantization (TLQ) codes, decoded through a per-channel
  *                   level table into int8 MFMA operands inside the GEMM
  *   output       -> int32 accumulators rescaled per token x per channel.
@@ -20,6 +20,11 @@
  *   - Return value: LRQ_OK (0) or a negative lrq_status.  All argument validation happens on the host
  *     before anything is launched, so a failing call has enqueued nothing.
  *   - Pointers must be aligned to 16 bytes (what any device allocator returns).
+ *   - No entry point allocates or frees device memory, so calls can be recorded into a HIP graph.  The first
+ *     launch of a kernel that needs more than 64 KB of LDS raises that kernel's limit (hipFuncSetAttribute),
+ *     once per kernel and device: run each call shape once outside stream capture before capturing it.
+ *   - Calls may come from several host threads; calls that share a workspace or an output must be ordered
+ *     by the caller (same stream, or events).
  */
 #ifndef LRQ_H_
 #define LRQ_H_
