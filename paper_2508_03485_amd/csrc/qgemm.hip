@@ -155,9 +155,10 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
     __syncthreads();
 }
 
-// BM rows x (4 waves x NTW x 32) columns per workgroup; MT = BM / 32 MFMA row tiles per wave.  Two shapes
-// are used: 128 x 256 (NTW = 2) and 256 x 128 (NTW = 1); both keep 128 accumulator registers per lane, i.e.
-// two workgroups per CU.  The second halves the decode work per MFMA and doubles the LDS reads per MFMA.
+// BM rows x (4 waves x NTW x 32) columns per workgroup; MT = BM / 32 MFMA row tiles per wave.  Shapes in use
+// (launch_qgemm picks): 128 x 256 (NTW = 2, 128 accumulator registers per lane, two workgroups per CU), 128 x 128
+// (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens; 256 x 128 (half the decode work
+// per MFMA, twice the LDS reads per MFMA) is kept for experiments.  ZP: zero-point form (epilogue term).
 template <int BITS, int BM, int NTW, bool ZP>
 __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
