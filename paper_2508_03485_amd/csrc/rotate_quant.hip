@@ -539,6 +539,37 @@ __global__ __launch_bounds__(256) void dense_rotate_f64_kernel(const uint16_t* _
     }
 }
 
+// Dense rotation of a few token rows (conditioning vectors): a 128-row matrix-core tile would be almost empty and the
+// launch a handful of workgroups walking all of K, so here every thread owns one output column of one row and runs the
+// same ascending-k chain of fused multiply-adds itself (x row in LDS as doubles, read as broadcasts; R read 128
+// contiguous bytes per wave and k).
+constexpr int kFewRows = 64;
+__global__ __launch_bounds__(128) void dense_rotate_fewrows_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ R,
+                                                                   int K, double* __restrict__ U, const float* __restrict__ ps) {
+    extern __shared__ double xrow[];
+    const int t = threadIdx.x, row = blockIdx.y, col = blockIdx.x * 128 + t;
+    for (int k = t; k < K; k += 128) {
+        double v = (double)__uint_as_float((unsigned)X[(size_t)row * K + k] << 16);
+        if (ps) v *= (double)ps[k];
+        xrow[k] = v;
+    }
+    __syncthreads();
+    if (col >= K) return;
+    const uint16_t* r = R + col;
+    double u = 0.0;
+    // 32 loads in flight per batch: the chain itself is short (one FMA per k), the loads' latency is what has to be hidden
+    int k = 0;
+    for (; k + 32 <= K; k += 32) {
+        unsigned short rv[32];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) rv[i] = r[(size_t)(k + i) * K];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) u = fma(xrow[k + i], (double)__uint_as_float((unsigned)rv[i] << 16), u);
+    }
+    for (; k < K; ++k) u = fma(xrow[k], (double)__uint_as_float((unsigned)r[(size_t)k * K] << 16), u);
+    U[(size_t)row * K + col] = u;
+}
+
 // Block-diagonal product on the fp64 matrix cores: dst[:, block g] = src[:, block g] . R_g with R [K/B, B, B]
 // bf16 (B = K is the dense rotation, one block).  v_mfma_f64_16x16x4_f64 accumulates its four k in ascending
 // order, one fused multiply-add each, so chaining the instructions over ascending k gives the same bits as the
@@ -849,7 +880,10 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
                                      int act_bits, double* U, int8_t* q, float* scale, int32_t* zero,
                                      const float* prescale) {
     static const int use_mfma = [] { const char* e = getenv("LRQ_DENSE_MFMA"); return e ? atoi(e) : 1; }();
-    if (use_mfma && K % MT_ == 0) {
+    if (M <= kFewRows && (size_t)K * sizeof(double) <= 48 * 1024) {
+        hipLaunchKernelGGL(dense_rotate_fewrows_kernel, dim3((K + 127) / 128, M), dim3(128), (size_t)K * sizeof(double), st, X, R,
+                           K, U, prescale);
+    } else if (use_mfma && K % MT_ == 0) {
         dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
         hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), grid, dim3(256), 0, st, X, R, M, K, K, U, prescale);
     } else {

@@ -68,7 +68,8 @@ def test_no_rotation_quant(lrq):
     assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
 
 
-@pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8), (200, 192, 8)])
+@pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8), (200, 192, 8),
+                                        (2, 1152, 4), (8, 192, 8), (1, 3072, 8), (64, 384, 8), (65, 384, 8)])       # up to 64 rows: the column-per-thread kernel
 def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
     print(f"case dense M={M} K={K} a={a_bits}", flush=True)
     X = _acts(M, K, 3 + K)
@@ -191,7 +192,7 @@ def test_smoothing_factor(lrq, alpha):
 
 @pytest.mark.parametrize("M,K,kind,h", [(70, 1152, "hadamard", 128), (130, 4608, "hadamard", 512), (33, 192, "hadamard", 64),
                                         (50, 4096, "hadamard", 4096), (64, 256, "none", 0), (90, 256, "dense", 0),
-                                        (75, 192, "dense", 0), (140, 384, "blockperm", 128)])
+                                        (75, 192, "dense", 0), (3, 1152, "dense", 0), (140, 384, "blockperm", 128)])
 def test_prescaled_rotate_quant_bit_exact(lrq, M, K, kind, h):
     """The reciprocal smoothing factor multiplied into x ahead of every rotation kind."""
     print(f"case prescale M={M} K={K} {kind} h={h}", flush=True)
