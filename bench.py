@@ -65,7 +65,10 @@ def parse():
     ap.add_argument("--cpu-channels", type=int, default=4608, help="output channels per layer in the oracle sample")
     ap.add_argument("--cache-bytes", type=int, default=768 << 20,
                     help="cycle through enough buffer copies that a step's working set exceeds this")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.levels and args.asym:
+        ap.error("--levels and --asym cannot be combined (the levels path has no zero-point form)")
+    return args
 
 
 def main():
