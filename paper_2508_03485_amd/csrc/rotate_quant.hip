@@ -586,27 +586,29 @@ __global__ __launch_bounds__(128) void dense_rotate_fewrows_kernel(const uint16_
 typedef double v4d __attribute__((ext_vector_type(4)));
 constexpr int MT_ = 128;
 
-template <bool SRC_F32, bool OUT_F32>
+// MR: rows of the workgroup tile, 128 or 64 (wave tile MR / 2 x 64); the tile rows start at row_begin + blockIdx.y * MR.
+template <bool SRC_F32, bool OUT_F32, int MR = MT_>
 __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const void* __restrict__ src,
                                                                                  const uint16_t* __restrict__ R, int M, int K,
                                                                                  int B, void* __restrict__ dst,
-                                                                                 const float* __restrict__ ps) {
+                                                                                 const float* __restrict__ ps, int row_begin) {
     constexpr int KS = SRC_F32 ? 32 : 64;           // k per step
     constexpr int XS = 144, RS = 288;               // row strides in bytes
-    constexpr int XT = MT_ * XS, RT = KS * RS;      // tile bytes
-    static_assert(MT_ == 128, "tile loads are written out for 128 rows");
-    constexpr int XL = 4;                           // 16-byte chunks of the left tile per thread (128 rows x 128 bytes)
+    constexpr int XT = MR * XS, RT = KS * RS;       // tile bytes
+    static_assert(MR == 128 || MR == 64, "tile loads are written out for 128 or 64 rows");
+    constexpr int XL = MR / 32;                     // 16-byte chunks of the left tile per thread (MR rows x 128 bytes)
+    constexpr int RI = MR / 32;                     // 16-row accumulator tiles per wave
     constexpr int RL = KS * 16 / 256;               // 16-byte chunks of the R tile per thread (KS rows x 256 bytes)
     __shared__ __attribute__((aligned(16))) unsigned char Xs[2][XT];
     __shared__ __attribute__((aligned(16))) unsigned char Rs[2][RT];
     __shared__ float Ps[2][KS];
     const int t = threadIdx.x, lane = t % 64, wv = t / 64;
     const int wm = wv / 2, wn = wv % 2;
-    const int row0 = blockIdx.y * MT_, col0 = blockIdx.x * MT_;
+    const int row0 = row_begin + blockIdx.y * MR, col0 = blockIdx.x * MT_;
     const int g = col0 / B, kbase = g * B, cb = col0 - kbase;
-    v4d acc[4][4];
+    v4d acc[RI][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4d{0.0, 0.0, 0.0, 0.0};
     constexpr int XE = SRC_F32 ? 4 : 2;             // bytes per left element
@@ -645,8 +647,11 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
         const int kn = kb + 1 < nk ? kb + 1 : kb;
         uint4 xn0 = *reinterpret_cast<const uint4*>(xsrc[0] + (size_t)kn * KS * XE);
         uint4 xn1 = *reinterpret_cast<const uint4*>(xsrc[1] + (size_t)kn * KS * XE);
-        uint4 xn2 = *reinterpret_cast<const uint4*>(xsrc[2] + (size_t)kn * KS * XE);
-        uint4 xn3 = *reinterpret_cast<const uint4*>(xsrc[3] + (size_t)kn * KS * XE);
+        uint4 xn2 = xn0, xn3 = xn0;
+        if constexpr (XL == 4) {
+            xn2 = *reinterpret_cast<const uint4*>(xsrc[2] + (size_t)kn * KS * XE);
+            xn3 = *reinterpret_cast<const uint4*>(xsrc[3] + (size_t)kn * KS * XE);
+        }
         uint4 rn0 = *reinterpret_cast<const uint4*>(rsrc[0] + (size_t)kn * KS * B * 2);
         uint4 rn1 = *reinterpret_cast<const uint4*>(rsrc[1] + (size_t)kn * KS * B * 2);
         uint4 rn2 = rn0, rn3 = rn0;
@@ -656,26 +661,26 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
         }
         float pn = 1.0f;
         if (ps && t < KS) pn = ps[kbase + kn * KS + t];
-        const unsigned char* xa = &Xs[cur][(wm * 64 + lane % 16) * XS + (lane / 16) * XE];
+        const unsigned char* xa = &Xs[cur][(wm * (MR / 2) + lane % 16) * XS + (lane / 16) * XE];
         const unsigned char* rb = &Rs[cur][(lane / 16) * RS + (wn * 64 + lane % 16) * 2];
 #pragma unroll 2
         for (int ks = 0; ks < KS / 4; ++ks) {
-            double a[4], b[4];
+            double a[RI], b[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < RI; ++i) {
                 if constexpr (SRC_F32) a[i] = (double)*reinterpret_cast<const float*>(xa + i * 16 * XS + ks * 4 * XE);
                 else a[i] = (double)__uint_as_float((unsigned)*reinterpret_cast<const uint16_t*>(xa + i * 16 * XS + ks * 4 * XE) << 16);
             }
             if (ps) {
                 const double pv = (double)Ps[cur][ks * 4 + lane / 16];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] *= pv;
+                for (int i = 0; i < RI; ++i) a[i] *= pv;
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 b[j] = (double)__uint_as_float((unsigned)*reinterpret_cast<const uint16_t*>(rb + ks * 4 * RS + j * 32) << 16);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < RI; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
@@ -686,8 +691,10 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
             unsigned char* rw = Rs[cur ^ 1];
             *reinterpret_cast<uint4*>(xw + xdst[0]) = xn0;
             *reinterpret_cast<uint4*>(xw + xdst[1]) = xn1;
-            *reinterpret_cast<uint4*>(xw + xdst[2]) = xn2;
-            *reinterpret_cast<uint4*>(xw + xdst[3]) = xn3;
+            if constexpr (XL == 4) {
+                *reinterpret_cast<uint4*>(xw + xdst[2]) = xn2;
+                *reinterpret_cast<uint4*>(xw + xdst[3]) = xn3;
+            }
             *reinterpret_cast<uint4*>(rw + rdst[0]) = rn0;
             *reinterpret_cast<uint4*>(rw + rdst[1]) = rn1;
             if constexpr (RL == 4) {
@@ -699,10 +706,10 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
         __syncthreads();
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RI; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = row0 + wm * 64 + i * 16 + 4 * r + lane / 16;
+            const int row = row0 + wm * (MR / 2) + i * 16 + 4 * r + lane / 16;
             if (row < M) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -884,8 +891,21 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
         hipLaunchKernelGGL(dense_rotate_fewrows_kernel, dim3((K + 127) / 128, M), dim3(128), (size_t)K * sizeof(double), st, X, R,
                            K, U, prescale);
     } else if (use_mfma && K % MT_ == 0) {
-        dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
-        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), grid, dim3(256), 0, st, X, R, M, K, K, U, prescale);
+        // 512 workgroups are resident at a time (two per CU).  When the tiles make a few rounds and the last one would be
+        // less than half full, the rows of that last round are cut into 64-row tiles and launched after the full
+        // rounds: twice as many workgroups, each alone on its CU (8192 x 1152: 576 tiles = 504 + 144 half tiles).
+        const int tiles_n = K / MT_, tiles_m = (M + MT_ - 1) / MT_, resident = 512;
+        const long tiles = (long)tiles_n * tiles_m;
+        int full_m = tiles_m;
+        if (tiles > resident && tiles < 4L * resident && tiles % resident != 0 && tiles % resident < resident / 2)
+            full_m = (int)((tiles / resident) * resident / tiles_n);
+        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), dim3(tiles_n, full_m), dim3(256), 0, st, X, R, M, K,
+                           K, U, prescale, 0);
+        if (full_m < tiles_m) {
+            const int row_begin = full_m * MT_;
+            hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false, 64>), dim3(tiles_n, (M - row_begin + 63) / 64),
+                               dim3(256), 0, st, X, R, M, K, K, U, prescale, row_begin);
+        }
     } else {
         dim3 grid(K / DT, (M + DT - 1) / DT);
         hipLaunchKernelGGL(dense_rotate_f64_kernel, grid, dim3(256), 0, st, X, R, M, K, U, prescale);
@@ -904,7 +924,7 @@ hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int 
                                          int8_t* q, float* scale, int32_t* zero, const float* prescale) {
     float* Z = reinterpret_cast<float*>(U);
     const dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
-    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z, prescale);
+    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z, prescale, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = allow_large_lds(reinterpret_cast<const void*>(permute_rows_f32_kernel), 158 * 1024);
@@ -914,7 +934,7 @@ hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int 
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<true, false>), grid, dim3(256), 0, st, Zp, R2, M, K, B, U,
-                       static_cast<const float*>(nullptr));
+                       static_cast<const float*>(nullptr), 0);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const QuantSpec qs = make_spec(act_bits, 1, zero);
