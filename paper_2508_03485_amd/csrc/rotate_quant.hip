@@ -773,6 +773,52 @@ __global__ void quant_from_f64_kernel(const double* __restrict__ U, int K, Quant
     }
 }
 
+// The same for K <= 8192: one 8-element chunk per thread, held in registers between the reduction and the rounding, so
+// that U is read once, 16 bytes at a time.
+__global__ void quant_from_f64_once_kernel(const double* __restrict__ U, int K, QuantSpec qs, int8_t* __restrict__ q,
+                                           float* __restrict__ scale) {
+    __shared__ double red[16];
+    const int t = threadIdx.x;
+    const size_t base = (size_t)blockIdx.x * K;
+    const bool have = t < (K >> 3);
+    double v[8];
+    if (have) {
+        const double2* src = reinterpret_cast<const double2*>(U + base + (size_t)t * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const double2 d = src[i];
+            v[2 * i] = d.x;
+            v[2 * i + 1] = d.y;
+        }
+    }
+    RowQ p;
+    if (!qs.asym) {
+        double m = 0.0;
+        if (have) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m = fmax(m, fabs(v[i]));
+        }
+        p = rowq_sym(block_max(m, red), qs);
+    } else {
+        double hi = -INFINITY, lo = INFINITY;
+        if (have) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { hi = fmax(hi, v[i]); lo = fmin(lo, v[i]); }
+        }
+        hi = block_max(hi, red);
+        lo = block_min(lo, red);
+        p = rowq_asym(hi, lo, qs);
+    }
+    if (have) {
+        if (qs.asym) store8_codes<true>(q + base + (size_t)t * 8, v, p, qs.half);
+        else store8_codes<false>(q + base + (size_t)t * 8, v, p, qs.half);
+    }
+    if (t == 0) {
+        scale[blockIdx.x] = p.scale;
+        if (qs.asym) qs.zero[blockIdx.x] = p.izero;
+    }
+}
+
 int ilog2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -787,6 +833,8 @@ int threads_for_row(int K) {
 
 }  // namespace
 
+static void launch_quant_from_f64(hipStream_t st, const double* U, int M, int K, const QuantSpec& qs, int8_t* q, float* scale);
+
 static QuantSpec make_spec(int act_bits, int h, int32_t* zero, const float* prescale = nullptr) {
     QuantSpec qs;
     qs.asym = zero != nullptr;
@@ -798,6 +846,11 @@ static QuantSpec make_spec(int act_bits, int h, int32_t* zero, const float* pres
     qs.zero = zero;
     qs.prescale = prescale;
     return qs;
+}
+
+static void launch_quant_from_f64(hipStream_t st, const double* U, int M, int K, const QuantSpec& qs, int8_t* q, float* scale) {
+    if (K <= 8192) hipLaunchKernelGGL(quant_from_f64_once_kernel, dim3(M), dim3(threads_for_row(K)), 0, st, U, K, qs, q, scale);
+    else hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qs, q, scale);
 }
 
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
@@ -913,7 +966,7 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const QuantSpec qs = make_spec(act_bits, 1, zero);
-    hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qs, q, scale);
+    launch_quant_from_f64(st, U, M, K, qs, q, scale);
     return hipGetLastError();
 }
 
@@ -938,7 +991,7 @@ hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int 
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const QuantSpec qs = make_spec(act_bits, 1, zero);
-    hipLaunchKernelGGL(quant_from_f64_kernel, dim3(M), dim3(256), 0, st, U, K, qs, q, scale);
+    launch_quant_from_f64(st, U, M, K, qs, q, scale);
     return hipGetLastError();
 }
 
