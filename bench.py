@@ -27,6 +27,60 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak
 FP64_VEC_PEAK_TFLOPS = 78.6
 
 
+class Probes:
+    """The benchmark's own measurement kernels (libbench_probes.so, built next to liblrq.so): a pure int8 MFMA loop
+    and a plain device copy, timed with events."""
+
+    def __init__(self):
+        import ctypes
+        from paper_2508_03485_amd.build import PROBES
+        if not os.path.exists(PROBES):
+            raise ImportError(f"{PROBES} is not built: run `python -m paper_2508_03485_amd.build`")
+        self.L = ctypes.CDLL(PROBES)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        self.L.bench_probe_mfma_i8.restype = ci
+        self.L.bench_probe_mfma_i8.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+        self.L.bench_probe_copy.restype = ci
+        self.L.bench_probe_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
+
+    def launch_mfma(self, blocks, iters, pattern, out, ops=None):
+        import torch
+        rc = self.L.bench_probe_mfma_i8(torch.cuda.current_stream().cuda_stream, blocks, iters, pattern, out.data_ptr(), ops)
+        assert rc == 0
+
+    def mfma_i8_tops(self, pattern=1, blocks=2048, iters=4096, reps=5):
+        """Sustained int8 MFMA rate in TOP/s; pattern 0 = constant operands, 1 = pseudo-random operands."""
+        import ctypes
+        import torch
+        out = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ops = ctypes.c_double(0.0)
+        self.launch_mfma(blocks, iters, pattern, out, ctypes.byref(ops))
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            self.launch_mfma(blocks, iters, pattern, out)
+        b.record()
+        torch.cuda.synchronize()
+        return ops.value * reps / (a.elapsed_time(b) * 1e-3) / 1e12
+
+    def copy_gbs(self, nbytes=1 << 30, reps=10):
+        """Device copy bandwidth in GB/s counting read + written bytes."""
+        import torch
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        st = torch.cuda.current_stream().cuda_stream
+        assert self.L.bench_probe_copy(st, src.data_ptr(), dst.data_ptr(), nbytes) == 0
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            self.L.bench_probe_copy(st, src.data_ptr(), dst.data_ptr(), nbytes)
+        b.record()
+        torch.cuda.synchronize()
+        return 2.0 * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,7 +88,8 @@ def parse():
                     help="timed steps; 0 (default) = as many as fill about 0.6 s, found with a short pilot run "
                          "(the chip needs a few milliseconds of load to reach its steady clocks)")
     ap.add_argument("--warmup", type=int, default=-1, help="untimed warm-up steps; -1 (default) = a tenth of the timed steps")
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="synthetic workload; the default is the largest configuration (config 4), the one the metric is quoted on")
     ap.add_argument("--blocks", type=int, default=0, help="c5 only: number of transformer blocks (0 = all 28)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--structured", type=int, default=0, metavar="B",
@@ -84,12 +139,13 @@ def main():
         from paper_2508_03485_amd.build import build
         build()
     lrq.lib()
+    probes = Probes()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.probes_only:
-        print(json.dumps(dict(copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1), copy_bytes_per_launch=1 << 30,
-                              mfma_i8_tops_constant_operands=round(lrq.probe_mfma_i8(0), 1),
-                              mfma_i8_tops_random_operands=round(lrq.probe_mfma_i8(1), 1))))
+        print(json.dumps(dict(copy_gbs=round(probes.copy_gbs(1 << 30, 5), 1), copy_bytes_per_launch=1 << 30,
+                              mfma_i8_tops_constant_operands=round(probes.mfma_i8_tops(0), 1),
+                              mfma_i8_tops_random_operands=round(probes.mfma_i8_tops(1), 1))))
         return
     cfg = int(args.workload[1])
     specs = synth.config_layers(cfg)
@@ -225,7 +281,7 @@ def main():
     for i in range(ksteps):
         # a ~0.5 ms lead-in kernel keeps the host ahead of the device, so that an interval between two events holds
         # one kernel and no host-side launch gap (short kernels would otherwise be timed at the host's launch rate)
-        lrq.lib().lrq_probe_mfma_i8(torch.cuda.current_stream().cuda_stream, 2048, 512, 1, lead.data_ptr(), None)
+        probes.launch_mfma(2048, 512, 1, lead)
         c = (args.warmup + args.steps + i) % copies
         for li, l in enumerate(layers):
             s = l["spec"]
@@ -314,12 +370,12 @@ def main():
     if args.calibration:
         out["calibration"] = calibration_timings(lrq, layers[0], dev)
     if args.clocks:
-        out["sustained_clocks"] = sustained_clocks(lrq, max(layers, key=lambda l: l["spec"].ops), dev)
+        out["sustained_clocks"] = sustained_clocks(lrq, probes, max(layers, key=lambda l: l["spec"].ops), dev)
 
     # what this device sustains on a pure int8 MFMA loop and on a plain copy kernel (context for the published peaks)
-    out["measured_ceilings"] = dict(mfma_i8_tops_constant_operands=round(lrq.probe_mfma_i8(0), 1),
-                                    mfma_i8_tops_random_operands=round(lrq.probe_mfma_i8(1), 1),
-                                    copy_gbs=round(lrq.probe_copy(1 << 30, 5), 1),
+    out["measured_ceilings"] = dict(mfma_i8_tops_constant_operands=round(probes.mfma_i8_tops(0), 1),
+                                    mfma_i8_tops_random_operands=round(probes.mfma_i8_tops(1), 1),
+                                    copy_gbs=round(probes.copy_gbs(1 << 30, 5), 1),
                                     note="pure 32x32x32 int8 MFMA loops (operand toggling lowers the sustained clock); "
                                          "1 GiB device copy, read + written bytes")
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -335,7 +391,7 @@ def main():
     print(json.dumps(out))
 
 
-def sustained_clocks(lrq, layer, dev):
+def sustained_clocks(lrq, probes, layer, dev):
     """Shader clock reported by `rocm-smi --showclocks` while one kernel runs back to back (about 2 s of queued
     launches, sampled after 1 s): the workload's largest GEMM on its real codes and on all-zero activation codes, the
     pure MFMA probe with pseudo-random and with constant operands, and the layer's rotate+quantize."""
@@ -348,12 +404,10 @@ def sustained_clocks(lrq, layer, dev):
     qz = torch.zeros_like(q)
     Y = torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev)
     scratch = torch.zeros(64, dtype=torch.int32, device=dev)
-    st = torch.cuda.current_stream().cuda_stream
-    L = lrq.lib()
     cases = [("qgemm, the layer's own codes", lambda: lrq.qgemm(q, sc, w, out=Y)),
              ("qgemm, all-zero activation codes", lambda: lrq.qgemm(qz, sc, w, out=Y)),
-             ("int8 MFMA loop, pseudo-random operands", lambda: L.lrq_probe_mfma_i8(st, 4096, 2048, 1, scratch.data_ptr(), None)),
-             ("int8 MFMA loop, constant operands", lambda: L.lrq_probe_mfma_i8(st, 4096, 2048, 0, scratch.data_ptr(), None)),
+             ("int8 MFMA loop, pseudo-random operands", lambda: probes.launch_mfma(4096, 2048, 1, scratch)),
+             ("int8 MFMA loop, constant operands", lambda: probes.launch_mfma(4096, 2048, 0, scratch)),
              ("rotate + quantize", lambda: lrq.ars_rotate_quant(X, rot, s.a_bits, q=q, scale=sc))]
 
     def sclk():

@@ -60,8 +60,9 @@ typedef enum { LRQ_OUT_BF16 = 0, LRQ_OUT_FP32 = 1 } lrq_out_dtype;
  *                     [K/block, block, block] (block g acts on channels g*block ...); P is the staggered
  *                     channel permutation in gather form, (z . P)[:, j] = z[:, perm[j]], perm int32 [K]
  *                     (a permutation of 0..K-1: the library does not verify that, it only clamps every
- *                     index into range).  The intermediate x . R1 is rounded once to fp32.  block must be a
- *                     multiple of 128 that divides K.  Costs O(K * block) per token instead of O(K^2).
+ *                     index into range).  Both products are plain fp64 sums in ascending k; nothing is rounded
+ *                     between the stages.  block must be a multiple of 128 that divides K.  Costs
+ *                     O(K * block) per token instead of O(K^2).
  *   LRQ_ROT_NONE      u = x.
  */
 typedef struct {
@@ -98,6 +99,9 @@ typedef struct {
  *   levels     bf16 [N, 16] or NULL (then not written, and the *_levels calls refuse the struct):
  *              levels[n][c & (2^bits-1)] is the level +-round(2^r 2^I) 2^(f-I) itself, rounded to nearest-even
  *              bf16 - exact for 0 <= I <= 7, where a level has at most 8 significant bits.
+ *   err_pos/err_neg double [N] or NULL (then not written): the value of the search objective sum (W_f - W)^2 of each
+ *              twin at the chosen clip factors (+inf for a twin without a valid candidate).  The sum runs in a fixed
+ *              order - 256 interleaved partial sums over ascending k, then the partial sums in ascending order.
  */
 typedef struct {
     int N, K;
@@ -115,6 +119,8 @@ typedef struct {
     uint8_t* gemm_codes;
     int32_t* colsum;     /* int32 [N]: sum_k lut[n][code[n,k]], the weight of an activation zero-point */
     uint16_t* levels;    /* bf16 [N,16] or NULL: the levels themselves, operands of the *_levels calls  */
+    double* err_pos;     /* double [N] or NULL: search objective of the positive twin at its chosen factors */
+    double* err_neg;     /* double [N] or NULL: the same for the negative twin                              */
 } lrq_tlq_weight;
 
 /* Human-readable text of a status code (static storage). */
@@ -298,18 +304,6 @@ int lrq_smooth_factor(void* stream, const void* Xcal, int T, const float* W, int
 size_t lrq_fluctuation_workspace_bytes(void);
 int lrq_fluctuation_metric(void* stream, const void* X, int M, int K, double* J_out, void* ws, size_t ws_bytes);
 int lrq_ars_select(double J, double threshold);
-
-/*
- * Measurement probes (no counterpart in the paper; they calibrate the roofline on the device at hand).
- * lrq_probe_mfma_i8: `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent
- *   v_mfma_i32_32x32x32_i8; pattern 0 = all operand bytes 1, pattern 1 = pseudo-random operand bytes (the
- *   sustained matrix clock depends on operand toggling).  *ops_per_launch (host, may be NULL) receives the
- *   int8 operations one launch performs (2 per multiply-accumulate).  out: int[1] device scratch.  Time it
- *   from the caller.
- * lrq_probe_copy: plain 16-byte-per-lane device copy of `bytes` (multiple of 16) from src to dst.
- */
-int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out, double* ops_per_launch);
-int lrq_probe_copy(void* stream, const void* src, void* dst, size_t bytes);
 
 #ifdef __cplusplus
 }

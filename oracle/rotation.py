@@ -89,13 +89,13 @@ def rotate_blockdiag(x: np.ndarray, Rb: np.ndarray) -> np.ndarray:
 
 def rotate_blockperm(x: np.ndarray, R1: np.ndarray, perm: np.ndarray, R2: np.ndarray) -> np.ndarray:
     """u = ((x . R1) . P) . R2 with block-diagonal R1, R2 ([nb, B, B] each, bf16-valued) and the channel
-    permutation P in gather form, (z . P)[:, j] = z[:, perm[j]].
-    The intermediate z = x . R1 is rounded once to fp32 (the runtime keeps it in that format); with bf16-valued
-    R2 every product of the second stage is then exact in fp64, so u is again defined bit for bit."""
+    permutation P in gather form, (z . P)[:, j] = z[:, perm[j]] (Method, ARS case equation, second branch).
+    Both block products are the plain fp64 sums of rotate_blockdiag (ascending k, one rounded multiply and one
+    rounded add per term); nothing is rounded between the stages."""
     perm = np.asarray(perm)
     K = x.shape[1]
     assert perm.shape == (K,) and np.array_equal(np.sort(perm), np.arange(K)), "perm must be a permutation of 0..K-1"
-    z = rotate_blockdiag(x, R1).astype(np.float32).astype(np.float64)
+    z = rotate_blockdiag(x, R1)
     return rotate_blockdiag(z[:, perm], R2)
 
 

@@ -20,8 +20,10 @@ Readings of what the paper leaves open (all per output channel, weights per-chan
     as a diagnostic;
   * alpha, beta come from caller-supplied grids scanned in the given order; a candidate whose
     clipped maximum does not exceed the minimum is skipped; the objective is the per-channel,
-    per-sign squared error sum (W_f - W)^2 with the exact Eq. dequant levels; the first
-    minimum wins; a side with no element or no valid candidate takes s = 1,
+    per-sign squared error sum (W_f - W)^2 with the exact Eq. dequant levels, summed in a stated
+    order (_ordered_sum: 256 interleaved partial sums over ascending k, then the partials in
+    ascending order) so that which of two close candidates is smaller does not depend on who adds;
+    the first minimum wins; a side with no element or no valid candidate takes s = 1,
     z = round(W_min) (0 if empty);
   * optional extension, not in the paper: a lower clip factor gamma on W_min, searched jointly with alpha (beta):
         s = (alpha * W_max - gamma * W_min) / intervals,  z = round(gamma * W_min / s)
@@ -48,6 +50,8 @@ class TLQParams:
     beta: np.ndarray    # fp32 [N]  chosen clip factor of the negative side
     gamma_pos: np.ndarray = None   # fp32 [N]  chosen lower clip factors (all ones without the extension)
     gamma_neg: np.ndarray = None
+    err_pos: np.ndarray = None     # fp64 [N]  the search objective at the chosen factors (inf: no valid candidate)
+    err_neg: np.ndarray = None
 
 
 def _log2_abs(W):
@@ -62,9 +66,27 @@ def _encode_side(ell, s, z, lo, hi):
     return np.clip(np.rint(ell / s[:, None]) - z[:, None], lo, hi)
 
 
+_STRIDE = 256
+
+
+def _ordered_sum(v):
+    """Row sums of v [N, K] in the order the search objective is defined in: partial sum j (j = 0..255) adds
+    v[:, j], v[:, j + 256], v[:, j + 512], ... one after the other; the total adds partial 0, 1, ..., 255 one
+    after the other.  Every step is one fp64 addition (positions past K contribute nothing)."""
+    N, K = v.shape
+    part = np.zeros((N, _STRIDE))
+    for a in range(0, K, _STRIDE):
+        blk = v[:, a:a + _STRIDE]
+        part[:, :blk.shape[1]] = part[:, :blk.shape[1]] + blk
+    tot = np.zeros(N)
+    for j in range(_STRIDE):
+        tot = tot + part[:, j]
+    return tot
+
+
 def _search_side(ell, absw, mask, grid, n_intervals, q_lo, q_hi, gamma_grid=(1.0,)):
     """Grid search of one clip factor (and the optional lower clip) for one sign.
-    Returns (s, z, chosen_factor, chosen_gamma)."""
+    Returns (s, z, chosen_factor, chosen_gamma, objective at the choice)."""
     N = ell.shape[0]
     has = mask.any(axis=1)
     wmax = np.max(np.where(mask, ell, -np.inf), axis=1)
@@ -86,14 +108,14 @@ def _search_side(ell, absw, mask, grid, n_intervals, q_lo, q_hi, gamma_grid=(1.0
             q = _encode_side(ell, s, z, q_lo, q_hi)
             lev = np.exp2(s[:, None] * (q + z[:, None]))
             d = np.where(mask, lev - absw, 0.0)
-            err = np.sum(d * d, axis=1)
+            err = _ordered_sum(d * d)
             better = valid & (err < best_err)
             best_err = np.where(better, err, best_err)
             best_s = np.where(better, s, best_s)
             best_z = np.where(better, z, best_z)
             best_c = np.where(better, c32, best_c)
             best_g = np.where(better, g32, best_g)
-    return best_s, best_z.astype(np.int32), best_c, best_g
+    return best_s, best_z.astype(np.int32), best_c, best_g, best_err
 
 
 def tlq_calibrate(W, bits, alpha_grid, beta_grid, neg_lo=1, chunk=256, gamma_grid=None):
@@ -105,13 +127,14 @@ def tlq_calibrate(W, bits, alpha_grid, beta_grid, neg_lo=1, chunk=256, gamma_gri
     half = 2 ** (bits - 1)
     gg = (1.0,) if gamma_grid is None else gamma_grid
     out = [np.empty(N), np.empty(N, np.int32), np.empty(N), np.empty(N, np.int32),
-           np.empty(N, np.float32), np.empty(N, np.float32), np.empty(N, np.float32), np.empty(N, np.float32)]
+           np.empty(N, np.float32), np.empty(N, np.float32), np.empty(N, np.float32), np.empty(N, np.float32),
+           np.empty(N), np.empty(N)]
     for a in range(0, N, chunk):
         w = W[a:a + chunk]
         absw, ell = _log2_abs(w)
-        sp, zp, al, gp = _search_side(ell, absw, w > 0, alpha_grid, float(half - 1), 0.0, float(half - 1), gg)
-        sn, zn, be, gn = _search_side(ell, absw, w < 0, beta_grid, float(half), float(neg_lo), float(half), gg)
-        for dst, src in zip(out, (sp, zp, sn, zn, al, be, gp, gn)):
+        sp, zp, al, gp, ep = _search_side(ell, absw, w > 0, alpha_grid, float(half - 1), 0.0, float(half - 1), gg)
+        sn, zn, be, gn, en = _search_side(ell, absw, w < 0, beta_grid, float(half), float(neg_lo), float(half), gg)
+        for dst, src in zip(out, (sp, zp, sn, zn, al, be, gp, gn, ep, en)):
             dst[a:a + chunk] = src
     return TLQParams(bits, *out)
 

@@ -20,8 +20,8 @@ LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
 
 EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes",
            "lrq_tlq_workspace_bytes", "lrq_tlq_quantize_pack", "lrq_ars_workspace_bytes",
-           "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm", "lrq_probe_mfma_i8",
-           "lrq_probe_copy", "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
+           "lrq_ars_rotate_quant", "lrq_workspace_bytes", "lrq_qlinear", "lrq_qgemm",
+           "lrq_ars_rotate_quant_asym", "lrq_qgemm_asym", "lrq_workspace_bytes_asym",
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
            "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
@@ -45,7 +45,8 @@ class _TlqWeight(ctypes.Structure):
                 ("codes", ctypes.c_void_p), ("s_pos", ctypes.c_void_p), ("s_neg", ctypes.c_void_p),
                 ("z_pos", ctypes.c_void_p), ("z_neg", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("beta", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("wscale", ctypes.c_void_p),
-                ("gemm_codes", ctypes.c_void_p), ("colsum", ctypes.c_void_p), ("levels", ctypes.c_void_p)]
+                ("gemm_codes", ctypes.c_void_p), ("colsum", ctypes.c_void_p), ("levels", ctypes.c_void_p),
+                ("err_pos", ctypes.c_void_p), ("err_neg", ctypes.c_void_p)]
 
 
 _lib = None
@@ -102,10 +103,6 @@ def lib() -> ctypes.CDLL:
     L.lrq_smooth_workspace_bytes.restype, L.lrq_smooth_workspace_bytes.argtypes = sz, [ci]
     L.lrq_smooth_factor.restype = ci
     L.lrq_smooth_factor.argtypes = [vp, vp, ci, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp, sz]
-    L.lrq_probe_mfma_i8.restype = ci
-    L.lrq_probe_mfma_i8.argtypes = [vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
-    L.lrq_probe_copy.restype = ci
-    L.lrq_probe_copy.argtypes = [vp, vp, vp, sz]
     _lib = L
     return L
 
@@ -179,6 +176,8 @@ class TLQWeight:
         self.gemm_codes = torch.zeros(ng, dtype=torch.uint8, **kw)
         self.colsum = torch.empty(N, dtype=torch.int32, **kw)
         self.levels = torch.empty((N, 16), dtype=torch.bfloat16, **kw)
+        self.err_pos = torch.empty(N, dtype=torch.float64, **kw)
+        self.err_neg = torch.empty(N, dtype=torch.float64, **kw)
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -190,7 +189,8 @@ class TLQWeight:
         if cs is None:
             cs = _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
                             _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
-                            _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum), _ptr(self.levels))
+                            _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum), _ptr(self.levels),
+                            _ptr(self.err_pos), _ptr(self.err_neg))
             object.__setattr__(self, "_cs", cs)
         return cs
 
@@ -367,36 +367,3 @@ def ars_select(J: float, threshold: float = 1.0) -> str:
     k = lib().lrq_ars_select(float(J), float(threshold))
     _check(min(k, 0), "lrq_ars_select")
     return {LRQ_ROT_HADAMARD: "hadamard", LRQ_ROT_BLOCKPERM: "blockperm"}[k]
-
-
-def probe_mfma_i8(pattern: int = 1, blocks: int = 2048, iters: int = 4096, reps: int = 5) -> float:
-    """Sustained int8 MFMA rate of the device in TOP/s (lrq_probe_mfma_i8 timed with events);
-    pattern 0 = constant operands, 1 = pseudo-random operands."""
-    import torch
-    out = torch.zeros(1, dtype=torch.int32, device="cuda")
-    ops = ctypes.c_double(0.0)
-    _check(lib().lrq_probe_mfma_i8(_stream(), blocks, iters, pattern, _ptr(out), ctypes.byref(ops)), "lrq_probe_mfma_i8")
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(reps):
-        lib().lrq_probe_mfma_i8(_stream(), blocks, iters, pattern, _ptr(out), None)
-    b.record()
-    torch.cuda.synchronize()
-    return ops.value * reps / (a.elapsed_time(b) * 1e-3) / 1e12
-
-
-def probe_copy(nbytes: int = 1 << 30, reps: int = 10) -> float:
-    """Device copy bandwidth in GB/s counting read + written bytes (lrq_probe_copy timed with events)."""
-    import torch
-    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
-    dst = torch.empty_like(src)
-    _check(lib().lrq_probe_copy(_stream(), _ptr(src), _ptr(dst), nbytes), "lrq_probe_copy")
-    torch.cuda.synchronize()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(reps):
-        lib().lrq_probe_copy(_stream(), _ptr(src), _ptr(dst), nbytes)
-    b.record()
-    torch.cuda.synchronize()
-    return 2.0 * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9

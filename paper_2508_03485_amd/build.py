@@ -7,7 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblrq.so")
-SOURCES = ["lrq_api.hip", "rotate_quant.hip", "tlq_pack.hip", "qgemm.hip", "qgemm_levels.hip", "ars_calib.hip", "probes.hip"]
+PROBES = os.path.join(HERE, "libbench_probes.so")    # measurement probes of bench.py, not part of liblrq
+SOURCES = ["lrq_api.hip", "rotate_quant.hip", "tlq_pack.hip", "qgemm.hip", "qgemm_levels.hip", "ars_calib.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -37,6 +38,10 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
+    cmd = [HIPCC, *FLAGS, "-shared", os.path.join(CSRC, "bench_probes.hip"), "-o", PROBES]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed on bench_probes.hip:\n" + r.stdout)
     return LIB
 
 

@@ -1,9 +1,11 @@
-// Measurement probes: a pure int8 MFMA loop and a plain copy kernel.  They give the sustained matrix
-// rate and the copy bandwidth of the device the benchmark runs on, next to which the published peaks
-// (and the fractions of them that the real kernels reach) can be read.
-#include "lrq_internal.h"
+// Measurement probes of the benchmark (a shared object of their own, loaded by bench.py only - not part of liblrq):
+// a pure int8 MFMA loop and a plain copy kernel.  They give the sustained matrix rate and the copy bandwidth of the
+// device the benchmark runs on, next to which the published peaks (and the fractions of them that the real kernels
+// reach) can be read, and the copy calibrates the byte counters of rocprofv3.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
-namespace lrq {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -55,16 +57,26 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const v4u* __restrict__
 
 }  // namespace
 
-hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int pattern, int* out) {
-    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, pattern, out);
-    return hipGetLastError();
+extern "C" {
+
+// `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent v_mfma_i32_32x32x32_i8; pattern 0 = all operand
+// bytes 1, pattern 1 = pseudo-random operand bytes.  *ops_per_launch (host, may be NULL) receives the int8 operations one
+// launch performs (2 per multiply-accumulate).  out: int[1] device scratch.  Returns 0 or -1.
+__attribute__((visibility("default"))) int bench_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out,
+                                                                double* ops_per_launch) {
+    if (blocks <= 0 || iters <= 0 || !out || (pattern != 0 && pattern != 1)) return -1;
+    if (ops_per_launch) *ops_per_launch = 2.0 * 32 * 32 * 32 * 8.0 * iters * 4.0 * blocks;
+    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, pattern, out);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-hipError_t launch_copy_probe(hipStream_t st, const void* src, void* dst, size_t bytes) {
+// Plain 16-byte-per-lane device copy of `bytes` (multiple of 16) from src to dst.  Returns 0 or -1.
+__attribute__((visibility("default"))) int bench_probe_copy(void* stream, const void* src, void* dst, size_t bytes) {
+    if (!src || !dst || bytes < 16) return -1;
     const size_t n16 = bytes / 16;
-    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st,
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const v4u*>(src), static_cast<v4u*>(dst), n16);
-    return hipGetLastError();
+    return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
-}  // namespace lrq
+}  // extern "C"

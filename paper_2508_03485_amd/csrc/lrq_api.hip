@@ -78,9 +78,9 @@ struct ArsWs {
 ArsWs ars_layout(int M, int K, const lrq_rotation* rot) {
     ArsWs l{0, 0, 0};
     if (rot && rot->kind == LRQ_ROT_DENSE) l.total = round256((size_t)M * K * sizeof(double));
-    if (rot && rot->kind == LRQ_ROT_BLOCKPERM) {       // U doubles (its first half doubles as Z), then Zp floats
+    if (rot && rot->kind == LRQ_ROT_BLOCKPERM) {       // U doubles (first Z = x.R1, finally u), then Zp doubles
         l.zp_off = round256((size_t)M * K * sizeof(double));
-        l.total = l.zp_off + round256((size_t)M * K * sizeof(float));
+        l.total = l.zp_off + round256((size_t)M * K * sizeof(double));
     }
     return l;
 }
@@ -100,7 +100,7 @@ int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rota
             e = lrq::launch_blockperm_rotate_quant(
                 st, x, M, K, rot->block, static_cast<const uint16_t*>(rot->R1), rot->perm,
                 static_cast<const uint16_t*>(rot->R2), act_bits, static_cast<double*>(ws),
-                reinterpret_cast<float*>(static_cast<char*>(ws) + ars_layout(M, K, rot).zp_off), q, scale, zero,
+                reinterpret_cast<double*>(static_cast<char*>(ws) + ars_layout(M, K, rot).zp_off), q, scale, zero,
                 rot->prescale);
             break;
         default:
@@ -127,7 +127,7 @@ const char* lrq_status_string(int status) {
     }
 }
 
-int lrq_version(void) { return 300; }   // 0.3.0: lrq_tlq_weight grew the bf16 level table (0.2.0: lrq_rotation grew its structured-rotation and pre-scale fields)
+int lrq_version(void) { return 400; }   // 0.4.0: lrq_tlq_weight grew err_pos / err_neg; the probes left the library
 
 size_t lrq_tlq_codes_bytes(int N, int K, int bits) {
     if (N <= 0 || K <= 0 || (bits != 3 && bits != 4) || K % 8 != 0) return 0;
@@ -352,17 +352,6 @@ int lrq_fluctuation_metric(void* stream, const void* X, int M, int K, double* J_
 int lrq_ars_select(double J, double threshold) {
     if (J != J || threshold != threshold) return LRQ_EINVAL;
     return J < threshold ? LRQ_ROT_HADAMARD : LRQ_ROT_BLOCKPERM;
-}
-
-int lrq_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out, double* ops_per_launch) {
-    if (blocks <= 0 || iters <= 0 || !out || (pattern != 0 && pattern != 1)) return LRQ_EINVAL;
-    if (ops_per_launch) *ops_per_launch = 2.0 * 32 * 32 * 32 * 8.0 * iters * 4.0 * blocks;
-    return lrq::launch_mfma_probe(static_cast<hipStream_t>(stream), blocks, iters, pattern, out) == hipSuccess ? LRQ_OK : LRQ_EHIP;
-}
-
-int lrq_probe_copy(void* stream, const void* src, void* dst, size_t bytes) {
-    if (!src || !dst || bytes < 16 || !aligned16(src) || !aligned16(dst)) return LRQ_EINVAL;
-    return lrq::launch_copy_probe(static_cast<hipStream_t>(stream), src, dst, bytes) == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 
 }  // extern "C"

@@ -35,10 +35,10 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
                                      int act_bits, double* U, int8_t* q, float* scale, int32_t* zero,
                                      const float* prescale);
 
-// u = ((x.R1).P).R2 with block-diagonal R1, R2 (bf16 [K/B,B,B]), fp32 intermediate, perm in gather form; U [M,K]
-// doubles and Zp [M,K] floats are scratch.  B % 128 == 0, B | K.
+// u = ((x.R1).P).R2 with block-diagonal R1, R2 (bf16 [K/B,B,B]), fp64 throughout, perm in gather form; U [M,K]
+// and Zp [M,K] doubles are scratch.  B % 128 == 0, B | K.
 hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
-                                         const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
+                                         const int32_t* perm, const uint16_t* R2, int act_bits, double* U, double* Zp,
                                          int8_t* q, float* scale, int32_t* zero, const float* prescale);
 
 // Calibration: greedy block rotations R1, R2 and staggered permutation from calibration activations; metric J.
@@ -68,9 +68,6 @@ hipError_t launch_qgemm_levels(hipStream_t st, const int8_t* q, const float* sca
 // Raises a kernel's dynamic-LDS limit (hipFuncAttributeMaxDynamicSharedMemorySize) the first time it is asked for on
 // the current device; later calls for the same (kernel, device) return at once.  Safe from several host threads.
 hipError_t allow_large_lds(const void* kernel, int bytes);
-
-hipError_t launch_mfma_probe(hipStream_t st, int blocks, int iters, int pattern, int* out);
-hipError_t launch_copy_probe(hipStream_t st, const void* src, void* dst, size_t bytes);
 
 // ---- private GEMM weight layout ----
 // Channels are grouped in tiles of 32, K in blocks of 64.  One (channel tile, K block) unit holds, for

@@ -8,8 +8,6 @@
 // The epilogue rescales in fp32 and goes through LDS so that every lane stores 16 contiguous bytes.
 #include "lrq_internal.h"
 
-#include <cstdlib>
-
 namespace lrq {
 namespace {
 
@@ -18,13 +16,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WAVES = 4;
 constexpr int BK = kGemmBlockK;     // 64
-#ifndef LRQ_PLANE_PAD
-#define LRQ_PLANE_PAD 32
-#endif
-#ifndef LRQ_AF_DIST
-#define LRQ_AF_DIST 2
-#endif
-constexpr int PLANE = 32 * 16 + LRQ_PLANE_PAD; // bytes of one (row tile, 16-byte k chunk) plane in LDS, padded
+constexpr int PLANE_PAD = 32;          // padding of a plane (swept 0 / 16 / 32 / 48: 32 leaves the fewest bank conflicts)
+constexpr int AF_DIST = 2;             // A fragments are read this many MFMA groups ahead of their use (swept 1 - 3)
+constexpr int PLANE = 32 * 16 + PLANE_PAD;     // bytes of one (row tile, 16-byte k chunk) plane in LDS, padded
 constexpr int EPI_ROW = 64 * 2 + 16;   // bytes of one staged output row of a wave (up to 64 bf16 / 32 fp32) + pad
 constexpr int EPI_WAVE = 32 * EPI_ROW; // one 32-row slab per wave
 
@@ -100,7 +94,7 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
                                        BRaw<BITS> (&bCur)[NTW], const BRaw<BITS> (&bNxt)[NTW], int kb, int KB,
                                        const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
                                        const uint8_t* const (&bptr)[NTW], const unsigned (&L)[NTW][4], unsigned C,
-                                       v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off, v4i (&afp)[LRQ_AF_DIST]) {
+                                       v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off, v4i (&afp)[AF_DIST]) {
     constexpr int UNIT = 64 * 16;
     const unsigned char* Acur = smem + cur;
 #pragma unroll
@@ -111,7 +105,7 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
     for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * BK);
     v4i af[2 * MT], bd1[NTW];
     constexpr int DPB = (NTW * 4 + MT - 1) / MT;       // operand dwords decoded per MFMA row tile
-    constexpr int DIST = LRQ_AF_DIST;                   // A fragments are read this many MFMA groups ahead
+    constexpr int DIST = AF_DIST;                   // A fragments are read this many MFMA groups ahead
 #pragma unroll
     for (int p = 0; p < DIST; ++p) af[p] = afp[p];
 #pragma unroll
@@ -148,17 +142,15 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
 #pragma unroll
             for (int j = 0; j < NTW; ++j) bCur[j] = load_braw<BITS>(bptr[j] + (size_t)kbn * UNIT);
         }
-#ifndef LRQ_NO_SCHED_BARRIER
         __builtin_amdgcn_sched_barrier(0);
-#endif
     }
     __syncthreads();
 }
 
 // BM rows x (4 waves x NTW x 32) columns per workgroup; MT = BM / 32 MFMA row tiles per wave.  Shapes in use
 // (launch_qgemm picks): 128 x 256 (NTW = 2, 128 accumulator registers per lane, two workgroups per CU), 128 x 128
-// (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens; 256 x 128 (half the decode work
-// per MFMA, twice the LDS reads per MFMA) is kept for experiments.  ZP: zero-point form (epilogue term).
+// (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens (a 256 x 128 shape - half the decode
+// work per MFMA, twice the LDS reads per MFMA - measured slower on every workload).  ZP: zero-point form (epilogue term).
 template <int BITS, int BM, int NTW, bool ZP>
 __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
@@ -277,9 +269,9 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     __syncthreads();
 
     const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
-    v4i afp[LRQ_AF_DIST];
+    v4i afp[AF_DIST];
 #pragma unroll
-    for (int p = 0; p < LRQ_AF_DIST; ++p)
+    for (int p = 0; p < AF_DIST; ++p)
         afp[p] = *reinterpret_cast<const v4i*>(&smem[((p % MT) * 4 + (p / MT) * 2) * PLANE + rd_off]);
 
     int o0 = 0, o1 = ABUF, o2 = 2 * ABUF;       // LDS buffers of tiles kb, kb+1, kb+2
@@ -429,19 +421,12 @@ hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, con
     // Tile shape.  128 x 256 (two workgroups per CU) is the fastest on long K loops; 128 x 128 (three per CU)
     // hides the prologue / epilogue of short K loops better and wastes less on N that is not a multiple of 256;
     // 64 x 128 serves inputs of a few tokens (conditioning vectors), where taller tiles multiply padding.
-    // LRQ_GEMM_SHAPE = 128 | 1281 | 256 | 64 forces 128x256 | 128x128 | 256x128 | 64x128 (experiments).
-    static const int env = [] { const char* e = getenv("LRQ_GEMM_SHAPE"); return e ? atoi(e) : 0; }();
     const bool narrow = K <= 2048 || (w.N % 256 != 0 && w.N <= 2048);
-    const int bm = env ? env : (M <= 64 ? 64 : (narrow ? 1281 : 128));
-    if (bm == 64) {
+    if (M <= 64) {
         if (w.bits == 4) return launch<4, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
         return launch<3, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
     }
-    if (bm == 256) {
-        if (w.bits == 4) return launch<4, 256, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
-        return launch<3, 256, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
-    }
-    if (bm == 1281) {
+    if (narrow) {
         if (w.bits == 4) return launch<4, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
         return launch<3, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
     }

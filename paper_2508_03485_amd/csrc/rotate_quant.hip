@@ -6,8 +6,6 @@
 // integer codes do not depend on the order in which a kernel schedules its work.
 #include "lrq_internal.h"
 
-#include <cstdlib>
-
 namespace lrq {
 namespace {
 
@@ -570,29 +568,27 @@ __global__ __launch_bounds__(128) void dense_rotate_fewrows_kernel(const uint16_
     U[(size_t)row * K + col] = u;
 }
 
-// Block-diagonal product on the fp64 matrix cores: dst[:, block g] = src[:, block g] . R_g with R [K/B, B, B]
-// bf16 (B = K is the dense rotation, one block).  v_mfma_f64_16x16x4_f64 accumulates its four k in ascending
-// order, one fused multiply-add each, so chaining the instructions over ascending k gives the same bits as the
-// scalar chain above whenever every product is exact in fp64 - bf16 x bf16 and fp32 x bf16 both are (a GPU test
-// compares the two kernels' U bit for bit).
-// SRC_F32: the left operand is fp32 [M, K] instead of bf16.  OUT_F32: the result is rounded once to fp32.
+// Block-diagonal product on the fp64 matrix cores: dst[:, block g] = src[:, block g] . R_g with src bf16 [M, K] and
+// R [K/B, B, B] bf16 (B = K is the dense rotation, one block).  v_mfma_f64_16x16x4_f64 accumulates its four k in
+// ascending order, one fused multiply-add each, so chaining the instructions over ascending k gives the same bits as
+// the scalar chain above, and - every product of two bf16 values (times an fp32 pre-scale) being exact in fp64 - the
+// same bits as a sum with separately rounded multiply and add (a GPU test compares U with the definition bit for bit).
 // Workgroup = 4 waves (2 x 2), tile 128 x 128, wave tile 64 x 64 (16 accumulator tiles); B must be a multiple of
 // 128 so that a column tile lies inside one block.
-// The operand tiles stay in LDS in their storage format (bf16 / fp32, 2 / 4 bytes per element) and are widened to
-// fp64 when a fragment is read: a K step holds 64 (bf16 source) or 32 (fp32 source) k per barrier, the global ->
-// LDS path is a plain 16-byte copy, and LDS traffic is a quarter of what fp64 tiles would cost.
+// The operand tiles stay in LDS as bf16 and are widened to fp64 when a fragment is read: a K step holds 64 k per
+// barrier, the global -> LDS path is a plain 16-byte copy, and LDS traffic is a quarter of what fp64 tiles would cost.
 // Row strides: 144 bytes for the left tile (36 dwords: the 16 rows a fragment read touches land on 16 distinct banks,
 // the four k of a read on consecutive ones) and 288 bytes for the R tile (its four k rows 8 banks apart).
 typedef double v4d __attribute__((ext_vector_type(4)));
 constexpr int MT_ = 128;
 
 // MR: rows of the workgroup tile, 128 or 64 (wave tile MR / 2 x 64); the tile rows start at row_begin + blockIdx.y * MR.
-template <bool SRC_F32, bool OUT_F32, int MR = MT_>
-__global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const void* __restrict__ src,
+template <int MR = MT_>
+__global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const uint16_t* __restrict__ src,
                                                                                  const uint16_t* __restrict__ R, int M, int K,
-                                                                                 int B, void* __restrict__ dst,
+                                                                                 int B, double* __restrict__ dst,
                                                                                  const float* __restrict__ ps, int row_begin) {
-    constexpr int KS = SRC_F32 ? 32 : 64;           // k per step
+    constexpr int KS = 64;                          // k per step
     constexpr int XS = 144, RS = 288;               // row strides in bytes
     constexpr int XT = MR * XS, RT = KS * RS;       // tile bytes
     static_assert(MR == 128 || MR == 64, "tile loads are written out for 128 or 64 rows");
@@ -611,7 +607,7 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
     for (int i = 0; i < RI; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4d{0.0, 0.0, 0.0, 0.0};
-    constexpr int XE = SRC_F32 ? 4 : 2;             // bytes per left element
+    constexpr int XE = 2;                           // bytes per left element
     constexpr int XCH = 128 / 16;                   // chunks per left-tile row (128 bytes of data)
     const unsigned char* xsrc[XL];
     int xdst[XL];
@@ -620,7 +616,7 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
         const int c = t + 256 * i, row = c / XCH, cc = c % XCH;
         int grow = row0 + row;
         if (grow >= M) grow = M - 1;
-        xsrc[i] = static_cast<const unsigned char*>(src) + ((size_t)grow * K + kbase) * XE + cc * 16;
+        xsrc[i] = reinterpret_cast<const unsigned char*>(src) + ((size_t)grow * K + kbase) * XE + cc * 16;
         xdst[i] = row * XS + cc * 16;
     }
     const unsigned char* rsrc[RL];
@@ -668,8 +664,7 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
             double a[RI], b[4];
 #pragma unroll
             for (int i = 0; i < RI; ++i) {
-                if constexpr (SRC_F32) a[i] = (double)*reinterpret_cast<const float*>(xa + i * 16 * XS + ks * 4 * XE);
-                else a[i] = (double)__uint_as_float((unsigned)*reinterpret_cast<const uint16_t*>(xa + i * 16 * XS + ks * 4 * XE) << 16);
+                a[i] = (double)__uint_as_float((unsigned)*reinterpret_cast<const uint16_t*>(xa + i * 16 * XS + ks * 4 * XE) << 16);
             }
             if (ps) {
                 const double pv = (double)Ps[cur][ks * 4 + lane / 16];
@@ -714,31 +709,90 @@ __global__ __launch_bounds__(256, 2) void blockdiag_rotate_mfma_f64_kernel(const
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const size_t o = (size_t)row * K + col0 + wn * 64 + j * 16 + lane % 16;
-                    if constexpr (OUT_F32) static_cast<float*>(dst)[o] = (float)acc[i][j][r];
-                    else static_cast<double*>(dst)[o] = acc[i][j][r];
+                    dst[o] = acc[i][j][r];
                 }
             }
         }
 }
 
-// out[row, j] = in[row, perm[j]] for fp32 rows: the row is staged in LDS so that global reads and writes are both
+// out[row, j] = in[row, perm[j]] for fp64 rows: the row is staged in LDS so that global reads and writes are both
 // contiguous.  Indices are clamped into [0, K) (a malformed perm gives wrong values, never an out-of-range access).
-__global__ __launch_bounds__(256) void permute_rows_f32_kernel(const float* __restrict__ in, const int32_t* __restrict__ perm,
-                                                                int M, int K, float* __restrict__ out) {
-    extern __shared__ __attribute__((aligned(16))) float prow[];
+__global__ __launch_bounds__(256) void permute_rows_f64_kernel(const double* __restrict__ in, const int32_t* __restrict__ perm,
+                                                                int M, int K, double* __restrict__ out) {
+    extern __shared__ __attribute__((aligned(16))) double prow[];
     const int t = threadIdx.x;
     for (int row = blockIdx.x; row < M; row += gridDim.x) {
-        const float4* src = reinterpret_cast<const float4*>(in + (size_t)row * K);
-        for (int c = t; c < K / 4; c += 256) reinterpret_cast<float4*>(prow)[c] = src[c];
+        const double2* src = reinterpret_cast<const double2*>(in + (size_t)row * K);
+        for (int c = t; c < K / 2; c += 256) reinterpret_cast<double2*>(prow)[c] = src[c];
         __syncthreads();
-        float4* dst = reinterpret_cast<float4*>(out + (size_t)row * K);
-        for (int c = t; c < K / 4; c += 256) {
-            const int4 pi = reinterpret_cast<const int4*>(perm)[c];
+        double2* dst = reinterpret_cast<double2*>(out + (size_t)row * K);
+        for (int c = t; c < K / 2; c += 256) {
+            const int2 pi = reinterpret_cast<const int2*>(perm)[c];
             const int i0 = min(max(pi.x, 0), K - 1), i1 = min(max(pi.y, 0), K - 1);
-            const int i2 = min(max(pi.z, 0), K - 1), i3 = min(max(pi.w, 0), K - 1);
-            dst[c] = make_float4(prow[i0], prow[i1], prow[i2], prow[i3]);
+            dst[c] = make_double2(prow[i0], prow[i1]);
         }
         __syncthreads();
+    }
+}
+
+// Second stage of the structured rotation: dst[:, block g] = src[:, block g] . R_g for fp64 src and bf16 R
+// [K/B, B, B].  A product of an fp64 value and a bf16 value is not exact in fp64, so here multiply and add round
+// separately, term by term in ascending k - the plain sum the definition states - and the fused multiply-adds of the
+// matrix cores cannot be used.  64 x 64 output tile per workgroup, 4 x 4 outputs per thread, 16 k per LDS stage.
+__global__ __launch_bounds__(256) void blockdiag_rotate_seq_f64_kernel(const double* __restrict__ src,
+                                                                        const uint16_t* __restrict__ R, int M, int K, int B,
+                                                                        double* __restrict__ dst) {
+    __shared__ double Xs[DK][DT + 1];
+    __shared__ double Rs[DK][DT];
+    const int t = threadIdx.x;
+    const int row0 = blockIdx.y * DT, col0 = blockIdx.x * DT;
+    const int g = col0 / B, kbase = g * B, cb = col0 - kbase;
+    const int ty = t / 16, tx = t % 16;
+    double acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+    const int xr = t / 4, xk = (t % 4) * 4;      // src tile: 64 rows x 16 k, 4 doubles per thread
+    const int rk = t / 16, rc = (t % 16) * 4;    // R tile: 16 k x 64 cols, 4 bf16 per thread
+    int xrow = row0 + xr;
+    if (xrow >= M) xrow = M - 1;
+    const uint16_t* Rg = R + (size_t)g * B * B;
+    for (int k0 = 0; k0 < B; k0 += DK) {
+        const double2 x0 = *reinterpret_cast<const double2*>(src + (size_t)xrow * K + kbase + k0 + xk);
+        const double2 x1 = *reinterpret_cast<const double2*>(src + (size_t)xrow * K + kbase + k0 + xk + 2);
+        const uint2 ra = *reinterpret_cast<const uint2*>(Rg + (size_t)(k0 + rk) * B + cb + rc);
+        Xs[xk + 0][xr] = x0.x;
+        Xs[xk + 1][xr] = x0.y;
+        Xs[xk + 2][xr] = x1.x;
+        Xs[xk + 3][xr] = x1.y;
+        Rs[rk][rc + 0] = (double)__uint_as_float(ra.x << 16);
+        Rs[rk][rc + 1] = (double)__uint_as_float(ra.x & 0xffff0000u);
+        Rs[rk][rc + 2] = (double)__uint_as_float(ra.y << 16);
+        Rs[rk][rc + 3] = (double)__uint_as_float(ra.y & 0xffff0000u);
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < DK; ++kk) {
+            double a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = Xs[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Rs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __dadd_rn(acc[i][j], __dmul_rn(a[i], b[j]));
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = row0 + ty * 4 + i;
+        if (r < M) {
+            double* o = dst + (size_t)r * K + col0 + tx * 4;
+            *reinterpret_cast<double2*>(o) = make_double2(acc[i][0], acc[i][1]);
+            *reinterpret_cast<double2*>(o + 2) = make_double2(acc[i][2], acc[i][3]);
+        }
     }
 }
 
@@ -859,8 +913,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
     if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
         // R whole rows per workgroup, at most four waves (finer granularity measured faster than nine; 7 rows of 1152 fill four waves)
         const int lpr = K / E32;
-        static const int tgt = [] { const char* e = getenv("LRQ_ROT_THREADS"); return e ? atoi(e) : 256; }();
-        int R = tgt / lpr;
+        int R = 256 / lpr;
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
@@ -876,8 +929,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
     }
     if (h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512) {
         const int lpr = K / E32;
-        static const int tgt2 = [] { const char* e = getenv("LRQ_ROT2_THREADS"); return e ? atoi(e) : 256; }();
-        int R = tgt2 / lpr;                      // about four waves per workgroup; whole rows only
+        int R = 256 / lpr;                       // about four waves per workgroup; whole rows only
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
@@ -890,8 +942,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         if (per_cu < 1) per_cu = 1;
         // the largest block runs as persistent workgroups that load the next row group while transforming the current
         // one (measured: 566 vs 690 us at 35100 x 12288; at h = 2048 the plain form is the faster one, 208 vs 288 us)
-        static const int allow_persist = [] { const char* e = getenv("LRQ_ROT2_PERSIST"); return e ? atoi(e) : 1; }();
-        const bool persist = allow_persist && h >= 4096 && groups > 256 * per_cu;
+        const bool persist = h >= 4096 && groups > 256 * per_cu;
         const dim3 grid(persist ? 256 * per_cu : groups), block(nt);
 #define LRQ_ATTR(L, P, A, S) { hipError_t e = allow_large_lds(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A, S>), 158 * 1024); if (e != hipSuccess) return e; }
 #define LRQ_ATTR2(L, P) { if (qs.asym && qs.prescale) LRQ_ATTR(L, P, true, true) else if (qs.asym) LRQ_ATTR(L, P, true, false) else if (qs.prescale) LRQ_ATTR(L, P, false, true) else LRQ_ATTR(L, P, false, false) }
@@ -939,11 +990,10 @@ hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, i
 hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K,
                                      int act_bits, double* U, int8_t* q, float* scale, int32_t* zero,
                                      const float* prescale) {
-    static const int use_mfma = [] { const char* e = getenv("LRQ_DENSE_MFMA"); return e ? atoi(e) : 1; }();
     if (M <= kFewRows && (size_t)K * sizeof(double) <= 48 * 1024) {
         hipLaunchKernelGGL(dense_rotate_fewrows_kernel, dim3((K + 127) / 128, M), dim3(128), (size_t)K * sizeof(double), st, X, R,
                            K, U, prescale);
-    } else if (use_mfma && K % MT_ == 0) {
+    } else if (K % MT_ == 0) {
         // 512 workgroups are resident at a time (two per CU).  When the tiles make a few rounds and the last one would be
         // less than half full, the rows of that last round are cut into 64-row tiles and launched after the full
         // rounds: twice as many workgroups, each alone on its CU (8192 x 1152: 576 tiles = 504 + 144 half tiles).
@@ -952,11 +1002,11 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
         int full_m = tiles_m;
         if (tiles > resident && tiles < 4L * resident && tiles % resident != 0 && tiles % resident < resident / 2)
             full_m = (int)((tiles / resident) * resident / tiles_n);
-        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false>), dim3(tiles_n, full_m), dim3(256), 0, st, X, R, M, K,
+        hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<MT_>), dim3(tiles_n, full_m), dim3(256), 0, st, X, R, M, K,
                            K, U, prescale, 0);
         if (full_m < tiles_m) {
             const int row_begin = full_m * MT_;
-            hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, false, 64>), dim3(tiles_n, (M - row_begin + 63) / 64),
+            hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<64>), dim3(tiles_n, (M - row_begin + 63) / 64),
                                dim3(256), 0, st, X, R, M, K, K, U, prescale, row_begin);
         }
     } else {
@@ -970,24 +1020,25 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
     return hipGetLastError();
 }
 
-// Structured outlier-aware rotation u = ((x . R1) . P) . R2: block-diagonal product to fp32 (Z, in the first half of
-// U's storage), row permutation into Zp, block-diagonal product to fp64 U, then the per-token quantizer.
+// Structured outlier-aware rotation u = ((x . R1) . P) . R2, fp64 throughout: block-diagonal product on the fp64
+// matrix cores into Z (U's storage; its products are exact, so the fused accumulation is the plain sum), row
+// permutation into Zp, second block-diagonal product with separately rounded multiply and add back into U, then the
+// per-token quantizer.
 hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,
-                                         const int32_t* perm, const uint16_t* R2, int act_bits, double* U, float* Zp,
+                                         const int32_t* perm, const uint16_t* R2, int act_bits, double* U, double* Zp,
                                          int8_t* q, float* scale, int32_t* zero, const float* prescale) {
-    float* Z = reinterpret_cast<float*>(U);
+    double* Z = U;
     const dim3 grid(K / MT_, (M + MT_ - 1) / MT_);
-    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<false, true>), grid, dim3(256), 0, st, X, R1, M, K, B, Z, prescale, 0);
+    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<MT_>), grid, dim3(256), 0, st, X, R1, M, K, B, Z, prescale, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    e = allow_large_lds(reinterpret_cast<const void*>(permute_rows_f32_kernel), 158 * 1024);
+    e = allow_large_lds(reinterpret_cast<const void*>(permute_rows_f64_kernel), 158 * 1024);
     if (e != hipSuccess) return e;
     const int pgrid = M < 4096 ? M : 4096;
-    hipLaunchKernelGGL(permute_rows_f32_kernel, dim3(pgrid), dim3(256), (size_t)K * sizeof(float), st, Z, perm, M, K, Zp);
+    hipLaunchKernelGGL(permute_rows_f64_kernel, dim3(pgrid), dim3(256), (size_t)K * sizeof(double), st, Z, perm, M, K, Zp);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((blockdiag_rotate_mfma_f64_kernel<true, false>), grid, dim3(256), 0, st, Zp, R2, M, K, B, U,
-                       static_cast<const float*>(nullptr), 0);
+    hipLaunchKernelGGL(blockdiag_rotate_seq_f64_kernel, dim3(K / DT, (M + DT - 1) / DT), dim3(256), 0, st, Zp, R2, M, K, B, U);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const QuantSpec qs = make_spec(act_bits, 1, zero);

@@ -29,6 +29,17 @@ __device__ __forceinline__ double wave_mind(double v) {
     return v;
 }
 
+// Sum of the workgroup's NT per-thread values in ascending thread order, one fp64 addition after the other (the order
+// the search objective is defined in); red must hold NT doubles.  Every thread returns the same bits.
+__device__ __forceinline__ double block_sum_ascending(double v, double* red) {
+    red[threadIdx.x] = v;
+    __syncthreads();
+    double r = 0.0;
+    for (int i = 0; i < NT; ++i) r = r + red[i];
+    __syncthreads();
+    return r;
+}
+
 __device__ __forceinline__ double block_sum(double v, double* red) {
     v = wave_sum(v);
     if (threadIdx.x % kWave == 0) red[threadIdx.x / kWave] = v;
@@ -46,11 +57,14 @@ __device__ __forceinline__ double clampd(double v, double lo, double hi) { retur
 // same (s, z, factor).  sgn = +1 scans the positive weights, -1 the negative ones.
 // ggrid / ngamma: optional grid of the lower clip factor (extension: s = (c W_max - g W_min) / intervals,
 // z = round(g W_min / s)), scanned inside the loop over c; ngamma = 0 is the paper's formula (g = 1).
+// The objective of a candidate is summed in a fixed order: thread j adds the terms of k = j, j + NT, j + 2 NT, ...
+// one after the other, then the NT partial sums are added in ascending j - so which of two close candidates is the
+// smaller one does not depend on the reduction tree.
 __device__ void search_side(const float* __restrict__ w, const double* __restrict__ ell, int K, double sgn,
                             bool has, double wmax, double wmin, const float* __restrict__ grid, int ngrid,
                             const float* __restrict__ ggrid, int ngamma,
                             double nint, double qlo, double qhi, double* red, double& s_out, double& z_out,
-                            float& c_out, float& g_out) {
+                            float& c_out, float& g_out, double& err_out) {
     double best_err = INFINITY, best_s = 1.0, best_z = has ? rint(wmin) : 0.0;
     float best_c = 1.0f, best_g = 1.0f;
     const int ng = ngamma > 0 ? ngamma : 1;
@@ -69,10 +83,10 @@ __device__ void search_side(const float* __restrict__ w, const double* __restric
             if (wk * sgn > 0.0) {
                 const double qv = clampd(rint(ell[k] / s) - z, qlo, qhi);
                 const double d = exp2(s * (qv + z)) - fabs(wk);
-                err += d * d;
+                err = err + d * d;
             }
         }
-        err = block_sum(err, red);
+        err = block_sum_ascending(err, red);
         if (err < best_err) {
             best_err = err;
             best_s = s;
@@ -85,6 +99,7 @@ __device__ void search_side(const float* __restrict__ w, const double* __restric
     z_out = best_z;
     c_out = best_c;
     g_out = best_g;
+    err_out = best_err;
 }
 
 // Round-to-nearest-even bf16 of a double.  The detour over fp32 could round twice only when the fp32 value lands
@@ -105,11 +120,12 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     double* __restrict__ s_neg, int32_t* __restrict__ z_pos, int32_t* __restrict__ z_neg,
     float* __restrict__ alpha, float* __restrict__ beta, int8_t* __restrict__ lut, float* __restrict__ wscale,
     uint8_t* __restrict__ gemm_codes, int32_t* __restrict__ colsum, const float* __restrict__ ggrid, int ngamma,
-    float* __restrict__ gamma_pos, float* __restrict__ gamma_neg, uint16_t* __restrict__ levels) {
+    float* __restrict__ gamma_pos, float* __restrict__ gamma_neg, uint16_t* __restrict__ levels,
+    double* __restrict__ err_pos, double* __restrict__ err_neg) {
     extern __shared__ double sm[];
     double* ell = sm;                                   // K doubles: log2|w|
-    double* red = sm + K;                               // 64 doubles of reduction scratch
-    int8_t* code = reinterpret_cast<int8_t*>(red + 64); // K signed codes
+    double* red = sm + K;                               // NT doubles of reduction scratch
+    int8_t* code = reinterpret_cast<int8_t*>(red + NT); // K signed codes
     const int n = blockIdx.x, t = threadIdx.x;
     const float* w = W + (size_t)n * K;
     const int half = 1 << (bits - 1), nlev = 1 << bits;
@@ -136,18 +152,20 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     if (!has_p) pmax = pmin = 0.0;
     if (!has_n) nmax = nmin = 0.0;
 
-    double sp, zp, sn, zn;
+    double sp, zp, sn, zn, ep, en;
     float al, be, gp, gn;
     search_side(w, ell, K, 1.0, has_p, pmax, pmin, agrid, na, ggrid, ngamma, (double)(half - 1), 0.0, (double)(half - 1),
-                red, sp, zp, al, gp);
+                red, sp, zp, al, gp, ep);
     search_side(w, ell, K, -1.0, has_n, nmax, nmin, bgrid, nb, ggrid, ngamma, (double)half, 1.0, (double)half, red, sn, zn,
-                be, gn);
+                be, gn, en);
 
     if (t == 0) {
         s_pos[n] = sp; s_neg[n] = sn; z_pos[n] = (int32_t)zp; z_neg[n] = (int32_t)zn;
         alpha[n] = al; beta[n] = be;
         if (gamma_pos) gamma_pos[n] = gp;
         if (gamma_neg) gamma_neg[n] = gn;
+        if (err_pos) err_pos[n] = ep;
+        if (err_neg) err_neg[n] = en;
     }
 
     // level table: e(c) = s+(c + z+) for c >= 0, s-(-c + z-) for c < 0; exponent split and integerisation
@@ -238,14 +256,15 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
                                     const float* alpha_grid, int n_alpha, const float* beta_grid, int n_beta,
                                     const lrq_tlq_weight& out, const float* gamma_grid, int n_gamma, float* gamma_pos,
                                     float* gamma_neg) {
-    const size_t lds = (size_t)K * sizeof(double) + 64 * sizeof(double) + (size_t)K;
+    const size_t lds = (size_t)K * sizeof(double) + NT * sizeof(double) + (size_t)K;
     {
         const hipError_t e = allow_large_lds(reinterpret_cast<const void*>(tlq_quantize_pack_kernel), 158 * 1024);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
                        beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
-                       out.lut, out.wscale, out.gemm_codes, out.colsum, gamma_grid, n_gamma, gamma_pos, gamma_neg, out.levels);
+                       out.lut, out.wscale, out.gemm_codes, out.colsum, gamma_grid, n_gamma, gamma_pos, gamma_neg, out.levels,
+                       out.err_pos, out.err_neg);
     return hipGetLastError();
 }
 

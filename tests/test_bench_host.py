@@ -21,7 +21,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_defaults_follow_the_contract(monkeypatch):
     monkeypatch.setattr(sys, "argv", ["bench.py"])
     a = bench.parse()
-    assert a.gpus == 1 and a.workload == "c2"             # the configuration the metric is quoted on
+    assert a.gpus == 1 and a.workload == "c4"             # the largest configuration: the one the metric is quoted on
     assert a.steps == 0 and a.warmup == -1                # sized from a pilot run
     monkeypatch.setattr(sys, "argv", ["bench.py", "--gpus", "1", "--steps", "7", "--warmup", "3"])
     a = bench.parse()

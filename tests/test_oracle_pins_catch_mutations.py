@@ -155,10 +155,15 @@ def _zigzag_without_turning(ranges, B):
 
 
 def _blockperm_scatter(x, R1, perm, R2):
-    z = oracle.rotation.rotate_blockdiag(x, R1).astype(np.float32).astype(np.float64)
+    z = oracle.rotation.rotate_blockdiag(x, R1)
     zp = np.empty_like(z)
     zp[:, np.asarray(perm)] = z                    # scatter instead of gather
     return oracle.rotation.rotate_blockdiag(zp, R2)
+
+
+def _blockperm_narrow_intermediate(x, R1, perm, R2):
+    z = oracle.rotation.rotate_blockdiag(x, R1).astype(np.float32).astype(np.float64)   # a storage format leaking in
+    return oracle.rotation.rotate_blockdiag(z[:, np.asarray(perm)], R2)
 
 
 def _blockdiag_transposed(x, Rb):
@@ -313,6 +318,10 @@ CASES = {
     "permutation applied as a scatter": (oracle.rotation.rotate_blockperm, _blockperm_scatter,
                                          [(t_str.test_equals_the_materialised_dense_product, ()),
                                           (t_str.test_identity_blocks_leave_only_the_permutation, ())]),
+    "intermediate of the structured rotation rounded to fp32": (
+        oracle.rotation.rotate_blockperm, _blockperm_narrow_intermediate,
+        [(t_str.test_nothing_is_rounded_between_the_two_stages, ()),
+         (t_str.test_equals_the_materialised_dense_product, ())]),
     "rotation blocks transposed": (oracle.rotation.rotate_blockdiag, _blockdiag_transposed,
                                    [(t_str.test_blockdiag_equals_block_diagonal_matrix_product, ()),
                                     (t_str.test_equals_the_materialised_dense_product, ())]),

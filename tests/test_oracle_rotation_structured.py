@@ -59,12 +59,13 @@ def test_equals_the_materialised_dense_product():
     D = scipy.linalg.block_diag(*R1) @ P @ scipy.linalg.block_diag(*R2)
     x = oracle.bf16_bits_to_f64(synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)))
     u = rot.rotate_blockperm(x, R1, perm, R2)
-    assert np.allclose(u, x @ D, rtol=0, atol=1e-5 * np.abs(x @ D).max())      # fp32 rounding of the intermediate
+    assert np.allclose(u, x @ D, rtol=0, atol=1e-12 * np.abs(x @ D).max())     # fp64 round-off only
     wrong = x @ (scipy.linalg.block_diag(*R1) @ P.T @ scipy.linalg.block_diag(*R2))
     assert not np.allclose(u, wrong, rtol=0, atol=1e-2)
 
 
-def test_intermediate_is_rounded_to_fp32_once():
+def test_nothing_is_rounded_between_the_two_stages():
+    # second stage = identity: the result is the first block product itself, every fp64 bit of it
     rng = np.random.default_rng(5)
     nb, B = 2, 8
     R1 = _rand_blocks(rng, nb, B)
@@ -72,8 +73,30 @@ def test_intermediate_is_rounded_to_fp32_once():
     x = oracle.bf16_bits_to_f64(synth.f32_to_bf16_bits(rng.standard_normal((6, nb * B)).astype(np.float32)))
     z = rot.rotate_blockdiag(x, R1)
     u = rot.rotate_blockperm(x, R1, np.arange(nb * B), eye)
-    assert np.array_equal(u, z.astype(np.float32).astype(np.float64))
-    assert not np.array_equal(u, z)
+    assert np.array_equal(u, z)
+    assert not np.array_equal(u, z.astype(np.float32).astype(np.float64))   # a narrower intermediate would show
+
+
+def test_second_stage_sums_term_by_term_in_ascending_k():
+    # scalar re-evaluation of one output: multiply and add rounded separately, k ascending within the block
+    rng = np.random.default_rng(8)
+    nb, B, M = 2, 8, 3
+    K = nb * B
+    R1, R2 = _rand_blocks(rng, nb, B), _rand_blocks(rng, nb, B)
+    perm = rng.permutation(K)
+    x = oracle.bf16_bits_to_f64(synth.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)))
+    u = rot.rotate_blockperm(x, R1, perm, R2)
+    for t, j in ((0, 0), (1, 9), (2, 15)):
+        g, jj = divmod(j, B)
+        acc = 0.0
+        for k in range(B):
+            src = int(perm[g * B + k])                   # channel of z that lands at position g*B + k
+            gs, ks = divmod(src, B)
+            zv = 0.0
+            for i in range(B):
+                zv = zv + float(x[t, gs * B + i]) * float(R1[gs, i, ks])
+            acc = acc + zv * float(R2[g, k, jj])
+        assert u[t, j] == acc
 
 
 def test_rejects_a_non_permutation():

@@ -129,6 +129,46 @@ def test_search_picks_the_first_minimum_of_the_grid(bits):
             assert float(chosen) == firsts[0]
 
 
+@pytest.mark.parametrize("K", [1, 255, 256, 257, 600, 1152])
+def test_objective_is_summed_in_its_stated_order(K):
+    # 256 interleaved partial sums over ascending k, then partial 0, 1, ..., 255: a scalar loop in that order gives
+    # the same bits; values of very different magnitude make any other association visible
+    rng = np.random.default_rng(K)
+    v = (rng.random((3, K)) * 10.0 ** rng.integers(-12, 4, size=(3, K)))
+    got = oracle.tlq._ordered_sum(v)
+    for n in range(3):
+        part = [0.0] * 256
+        for k in range(K):
+            part[k % 256] = part[k % 256] + float(v[n, k])
+        tot = 0.0
+        for j in range(256):
+            tot = tot + part[j]
+        assert got[n] == tot
+    if K >= 600:
+        ascending = [sum(float(x) for x in v[n]) for n in range(3)]       # plain left-to-right sum: other bits
+        assert any(got[n] != ascending[n] for n in range(3))
+        assert np.allclose(got, ascending, rtol=1e-12, atol=0)
+
+
+def test_reported_objective_is_the_ordered_sum_at_the_chosen_factors():
+    W = _weights(4, 600, 77)
+    p = oracle.tlq_calibrate(W, 4, GRID, GRID)
+    for n in range(4):
+        for sel, s, z, lo, hi, want in ((W[n] > 0, p.s_pos[n], p.z_pos[n], 0, 7, p.err_pos[n]),
+                                        (W[n] < 0, p.s_neg[n], p.z_neg[n], 1, 8, p.err_neg[n])):
+            part = [0.0] * 256
+            for k in range(600):
+                if sel[k]:
+                    w = abs(float(W[n, k]))
+                    q = min(max(round(math.log2(w) / s) - int(z), lo), hi)
+                    d = 2.0 ** (s * (q + int(z))) - w
+                    part[k % 256] = part[k % 256] + d * d
+            tot = 0.0
+            for j in range(256):
+                tot = tot + part[j]
+            assert want == pytest.approx(tot, rel=1e-13)       # log2 / exp2 of two libraries; the order is pinned above
+
+
 def test_equal_minima_keep_the_first_grid_entry():
     # a side whose weights are all 4.0 is reproduced exactly by several clip factors (zero error each):
     # the factor that comes first in the caller's grid order wins
