@@ -41,7 +41,8 @@ typedef enum {
     LRQ_EINVAL = -1,       /* null pointer, non-positive size, misaligned pointer, inconsistent struct   */
     LRQ_EUNSUPPORTED = -2, /* bit-width, block size or shape outside what the kernels implement          */
     LRQ_EWORKSPACE = -3,   /* workspace pointer null or smaller than the *_workspace_bytes() answer      */
-    LRQ_EHIP = -4          /* the HIP runtime reported an error while launching                           */
+    LRQ_EHIP = -4,         /* the HIP runtime reported an error while launching                           */
+    LRQ_ESCRATCH = -5      /* lrq_qlinear_static: the layer does not fit the library's built-in scratch buffer */
 } lrq_status;
 
 typedef enum { LRQ_ROT_NONE = 0, LRQ_ROT_HADAMARD = 1, LRQ_ROT_DENSE = 2, LRQ_ROT_BLOCKPERM = 3 } lrq_rotation_kind;
@@ -208,6 +209,27 @@ size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act
 int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
                 const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y,
                 void* ws, size_t ws_bytes);
+
+/*
+ * lrq_qlinear_static - lrq_qlinear for callers that cannot allocate device memory or carry a workspace around:
+ * code running under HIP stream capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and bit-identical results as lrq_qlinear, minus the workspace: the activation codes, the token scales
+ * and the rotation scratch live in a buffer of lrq_static_scratch_bytes() = 64 MiB that is part of the library's
+ * code object (every device the library runs on holds one copy until the process ends).  The call allocates and
+ * frees nothing.
+ *   - A layer whose lrq_workspace_bytes(M, N, K, rot, act_bits) exceeds the buffer is refused with LRQ_ESCRATCH and
+ *     nothing is launched (Hadamard layers fit up to M * K of about 6.7e7: all layers of the 8192- and 4608-token
+ *     workloads; dense rotations up to M * K of about 7e6).
+ *   - Every call on a device uses that device's one buffer: calls that may overlap on one device (different
+ *     streams, or several host threads) race on it and must be ordered by the caller.  The buffer keeps the previous
+ *     call's contents; the kernels overwrite what they read, nothing relies on its state.
+ *   - lrq_init() resolves the buffer's device address for the current device (lrq_qlinear_static does the same on
+ *     its first call on a device): call it once per device before a stream capture.  Returns LRQ_OK or LRQ_EHIP.
+ */
+int lrq_init(void);
+size_t lrq_static_scratch_bytes(void);
+int lrq_qlinear_static(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                       const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y);
 
 /*
  * lrq_qgemm - the GEMM + rescale stage of lrq_qlinear alone, on activation codes already produced by

@@ -14,7 +14,7 @@ from typing import Optional, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LRQ_LIB", os.path.join(_HERE, "liblrq.so"))   # LRQ_LIB: developer override
 
-LRQ_OK, LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP = 0, -1, -2, -3, -4
+LRQ_OK, LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP, LRQ_ESCRATCH = 0, -1, -2, -3, -4, -5
 LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE, LRQ_ROT_BLOCKPERM = 0, 1, 2, 3
 LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
 
@@ -25,7 +25,7 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
            "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
-           "lrq_qlinear_levels")
+           "lrq_qlinear_levels", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
 
 
 class LrqError(RuntimeError):
@@ -81,6 +81,10 @@ def lib() -> ctypes.CDLL:
     L.lrq_qlinear.restype = ci
     L.lrq_qlinear.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, ctypes.POINTER(_TlqWeight), vp, ci,
                               vp, vp, sz]
+    L.lrq_init.restype, L.lrq_init.argtypes = ci, []
+    L.lrq_static_scratch_bytes.restype, L.lrq_static_scratch_bytes.argtypes = sz, []
+    L.lrq_qlinear_static.restype = ci
+    L.lrq_qlinear_static.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
     L.lrq_qgemm.restype = ci
     L.lrq_qgemm.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
     L.lrq_ars_rotate_quant_asym.restype = ci
@@ -288,6 +292,20 @@ def qlinear(X, rot: Rotation, act_bits: int, w: TLQWeight, bias=None, out_dtype=
     st = getattr(lib(), name)(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
                               _out_code(out_dtype), _ptr(out), _ptr(workspace), workspace.numel())
     _check(st, name)
+    return out
+
+
+def qlinear_static(X, rot: Rotation, act_bits: int, w: TLQWeight, out, bias=None):
+    """lrq_qlinear_static: lrq_qlinear on the library's built-in scratch buffer (no workspace, no allocation: `out`
+    must be given).  Returns `out`."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    assert out.shape == (M, w.N) and out.is_contiguous()
+    r, cs = rot.c_struct(), w.c_struct()
+    st = lib().lrq_qlinear_static(_stream(), _ptr(X), M, K, ctypes.byref(r), act_bits, ctypes.byref(cs), _ptr(bias),
+                                  _out_code(out.dtype), _ptr(out))
+    _check(st, "lrq_qlinear_static")
     return out
 
 

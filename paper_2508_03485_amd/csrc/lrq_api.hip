@@ -72,6 +72,31 @@ int check_weight(const lrq_tlq_weight* w) {
     return LRQ_OK;
 }
 
+// ---- built-in scratch of lrq_qlinear_static -------------------------------------------------------------------
+// One fixed array per device, part of the code object: callers that cannot allocate (stream capture, serving loops)
+// get the activation codes / scales / rotation scratch of a layer from here instead of from a workspace argument.
+// `scratch` is a host-side stand-in for the symbol; the device address is resolved once per device with
+// hipGetSymbolAddress and only that address is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current device's copy of `scratch` (resolved on first use).
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LRQ_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LRQ_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LRQ_OK;
+}
+
 struct ArsWs {
     size_t u_off, zp_off, total;
 };
@@ -123,11 +148,12 @@ const char* lrq_status_string(int status) {
         case LRQ_EUNSUPPORTED: return "unsupported bit-width, block size or shape";
         case LRQ_EWORKSPACE: return "workspace missing or too small";
         case LRQ_EHIP: return "HIP runtime error at launch";
+        case LRQ_ESCRATCH: return "the layer needs more scratch memory than the library's built-in buffer holds (use the call that takes a workspace)";
         default: return "unknown status";
     }
 }
 
-int lrq_version(void) { return 400; }   // 0.4.0: lrq_tlq_weight grew err_pos / err_neg; the probes left the library
+int lrq_version(void) { return 400; }   // 0.4.0: lrq_tlq_weight grew err_pos / err_neg; lrq_qlinear_static; the probes left the library
 
 size_t lrq_tlq_codes_bytes(int N, int K, int bits) {
     if (N <= 0 || K <= 0 || (bits != 3 && bits != 4) || K % 8 != 0) return 0;
@@ -297,6 +323,24 @@ int lrq_qlinear_levels(void* stream, const void* X, int M, int K, const lrq_rota
 int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
                 const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
     return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, Gemm::kInt8);
+}
+
+int lrq_init(void) {
+    void* p = nullptr;
+    return static_scratch(&p);
+}
+
+size_t lrq_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int lrq_qlinear_static(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
+                       const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y) {
+    // sizes first: a layer that does not fit is refused before anything else is looked at or launched
+    if (M <= 0 || K <= 0 || !w || w->N <= 0) return LRQ_EINVAL;
+    if (lrq_workspace_bytes(M, w->N, K, rot, act_bits) > kStaticScratchBytes) return LRQ_ESCRATCH;
+    void* ws = nullptr;
+    const int st = static_scratch(&ws);
+    if (st != LRQ_OK) return st;
+    return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, kStaticScratchBytes, Gemm::kInt8);
 }
 
 int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits,
