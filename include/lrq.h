@@ -45,7 +45,9 @@ typedef enum {
     LRQ_ESCRATCH = -5      /* lrq_qlinear_static: the layer does not fit the library's built-in scratch buffer */
 } lrq_status;
 
-typedef enum { LRQ_ROT_NONE = 0, LRQ_ROT_HADAMARD = 1, LRQ_ROT_DENSE = 2, LRQ_ROT_BLOCKPERM = 3 } lrq_rotation_kind;
+typedef enum {
+    LRQ_ROT_NONE = 0, LRQ_ROT_HADAMARD = 1, LRQ_ROT_DENSE = 2, LRQ_ROT_BLOCKPERM = 3, LRQ_ROT_DENSE_F64 = 4
+} lrq_rotation_kind;
 typedef enum { LRQ_OUT_BF16 = 0, LRQ_OUT_FP32 = 1 } lrq_out_dtype;
 
 /*
@@ -55,7 +57,12 @@ typedef enum { LRQ_OUT_BF16 = 0, LRQ_OUT_FP32 = 1 } lrq_out_dtype;
  *                     had_block = h, a power of two dividing K (Preliminaries, Eq. hadamard).  The
  *                     transform is taken unnormalised (+-1 entries) and 1/sqrt(h) goes into the scale.
  *   LRQ_ROT_DENSE     u = x . R with R a K x K bf16 matrix (row-major, device): any orthogonal matrix,
- *                     e.g. the paper's greedy outlier-aware product R1.P.R2 materialised.
+ *                     e.g. the paper's greedy outlier-aware product R1.P.R2 materialised.  The codes are those of
+ *                     the fp64 sum over ascending k; the bulk of the product runs on the bf16 matrix cores and
+ *                     every rounding decision that their error bound does not settle is recomputed in fp64.
+ *   LRQ_ROT_DENSE_F64 the same rotation evaluated entirely in fp64 (about ten times slower; same codes and scales,
+ *                     and it leaves u as doubles [M, K] at the head of the rotation workspace): the reference the
+ *                     fast evaluation is checked against.
  *   LRQ_ROT_BLOCKPERM u = ((x . R1) . P) . R2: the outlier-aware branch in the structured form the paper
  *                     prints.  R1, R2 are block-diagonal with blocks of `block` channels, stored as bf16
  *                     [K/block, block, block] (block g acts on channels g*block ...); P is the staggered
@@ -188,6 +195,18 @@ size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bi
  */
 int lrq_ars_rotate_quant(void* stream, const void* X, int M, int K, const lrq_rotation* rot,
                          int act_bits, int8_t* q, float* scale, void* ws, size_t ws_bytes);
+
+/*
+ * Diagnostics of the LRQ_ROT_DENSE evaluation (host only, launches nothing): byte offsets, inside the workspace that
+ * lrq_ars_rotate_quant was given, of what its matrix-core evaluation leaves behind -
+ *   offsets[0]  float  [M, K]  the approximation u~ of u = x . R (bf16 matrix cores, fp64 accumulation of 64-k runs)
+ *   offsets[1]  double [M]     the bound eps_t on |u~ - u| that holds for every element of token t
+ *   offsets[2]  int32  [M]     how many elements of token t the bound left undecided and were recomputed in fp64
+ *   offsets[3]  int32  [M]     1 for a token that was recomputed as a whole (0 otherwise)
+ * Returns LRQ_OK, or LRQ_EUNSUPPORTED when that evaluation does not serve the shape (then the fp64 evaluation runs:
+ * M <= 64, K % 128 != 0, K > 16384, M * K >= 2^31; also whenever a pre-scale or the zero-point form is used).
+ */
+int lrq_ars_dense_diagnostics(int M, int K, size_t offsets[4]);
 
 /* Workspace of lrq_qlinear (bytes): activation codes, scales and rotation scratch. */
 size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act_bits);

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("LRQ_LIB", os.path.join(_HERE, "liblrq.so"))   # LRQ_LIB: developer override
 
 LRQ_OK, LRQ_EINVAL, LRQ_EUNSUPPORTED, LRQ_EWORKSPACE, LRQ_EHIP, LRQ_ESCRATCH = 0, -1, -2, -3, -4, -5
-LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE, LRQ_ROT_BLOCKPERM = 0, 1, 2, 3
+LRQ_ROT_NONE, LRQ_ROT_HADAMARD, LRQ_ROT_DENSE, LRQ_ROT_BLOCKPERM, LRQ_ROT_DENSE_F64 = 0, 1, 2, 3, 4
 LRQ_OUT_BF16, LRQ_OUT_FP32 = 0, 1
 
 EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_gemm_codes_bytes",
@@ -25,7 +25,7 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
            "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
-           "lrq_qlinear_levels", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
+           "lrq_qlinear_levels", "lrq_ars_dense_diagnostics", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
 
 
 class LrqError(RuntimeError):
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.lrq_ars_workspace_bytes.argtypes = [ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_ars_rotate_quant.restype = ci
     L.lrq_ars_rotate_quant.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, vp, vp, vp, sz]
+    L.lrq_ars_dense_diagnostics.restype = ci
+    L.lrq_ars_dense_diagnostics.argtypes = [ci, ci, ctypes.POINTER(sz * 4)]
     L.lrq_workspace_bytes.restype = sz
     L.lrq_workspace_bytes.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_qlinear.restype = ci
@@ -131,10 +133,10 @@ def _ptr(t) -> Optional[int]:
 
 @dataclass
 class Rotation:
-    """Per-layer rotation choice: kind in {"none", "hadamard", "dense", "blockperm"}."""
+    """Per-layer rotation choice: kind in {"none", "hadamard", "dense", "blockperm", "dense_f64"}."""
     kind: str = "hadamard"
     had_block: int = 0
-    R: object = None        # torch bf16 [K, K] on the device for kind == "dense"
+    R: object = None        # torch bf16 [K, K] on the device for kind == "dense" / "dense_f64"
     block: int = 0          # kind == "blockperm": block size of R1, R2
     R1: object = None       # torch bf16 [K/block, block, block] on the device
     perm: object = None     # torch int32 [K] on the device (gather form)
@@ -150,7 +152,7 @@ class Rotation:
         cs = self.__dict__.get("_cs")
         if cs is None:
             kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE,
-                     "blockperm": LRQ_ROT_BLOCKPERM}
+                     "blockperm": LRQ_ROT_BLOCKPERM, "dense_f64": LRQ_ROT_DENSE_F64}
             cs = _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R), int(self.block), _ptr(self.R1),
                            _ptr(self.perm), _ptr(self.R2), _ptr(self.prescale))
             object.__setattr__(self, "_cs", cs)
@@ -266,6 +268,19 @@ def ars_rotate_quant(X, rot: Rotation, act_bits: int, q=None, scale=None, worksp
                                     _ptr(workspace), nws)
     _check(st, "lrq_ars_rotate_quant")
     return q, scale
+
+
+def ars_dense_diagnostics(workspace, M: int, K: int):
+    """Views into the workspace an LRQ_ROT_DENSE call of lrq_ars_rotate_quant used (lrq_ars_dense_diagnostics):
+    (u~ fp32 [M, K], eps fp64 [M], undecided-element counts int32 [M], whole-row flags int32 [M])."""
+    import torch
+    offs = (ctypes.c_size_t * 4)()
+    _check(lib().lrq_ars_dense_diagnostics(M, K, ctypes.byref(offs)), "lrq_ars_dense_diagnostics")
+    u = workspace[offs[0]:offs[0] + M * K * 4].view(torch.float32).view(M, K)
+    eps = workspace[offs[1]:offs[1] + M * 8].view(torch.float64)
+    cnt = workspace[offs[2]:offs[2] + M * 4].view(torch.int32)
+    whole = workspace[offs[3]:offs[3] + M * 4].view(torch.int32)
+    return u, eps, cnt, whole
 
 
 def _out_code(dtype) -> int:

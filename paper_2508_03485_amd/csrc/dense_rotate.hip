@@ -1,0 +1,561 @@
+// Dense outlier-aware rotation u = x . R (Method, ARS case equation, second branch with R materialised) followed by the
+// per-token quantizer, with the bulk of the product on the bf16 matrix cores.
+//
+// The codes are defined in fp64: u[t, j] = sum over ascending k of x[t, k] R[k, j] (every product of two bf16 values is
+// exact, every addition rounds once), amax_t = max_j |u|, code = rint(u * (qmax / amax_t)).  A bf16 MFMA with fp32
+// accumulation cannot give u to that accuracy, but it gives an approximation u~ with a bound eps_t on |u~ - u| that holds
+// for every element of the row, and almost every rounding decision is already settled by u~:
+//   * the row maximum is attained among the elements with |u~| >= max |u~| - 2 eps_t (normally one or two); those are
+//     recomputed exactly (the definition's own chain of fused multiply-adds) and give amax_t bit for bit;
+//   * an element whose u~ * inv lies farther than eps_t * inv (plus fp64 round-off) from the nearest half-integer rounds to
+//     the same code as the exact value; the others (a few per thousand) are recomputed exactly.
+// Rows where this does not pay (more uncertain elements than the lists hold: tiny |u| against large |x|) are recomputed
+// as a whole.  Nothing depends on how the error is distributed - only on the bound, which is derived below from a
+// stated model of the matrix instruction's rounding and checked by a GPU test against the exact values.
+//
+// Error bound.  A run of m = CHUNK / 16 chained v_mfma_f32_32x32x16_bf16 starts from a zero accumulator and is then
+// added to an fp64 accumulator (exact to 2^-53), so only the roundings inside a run count.  Model of one instruction,
+// D = C + sum_{i<16} a_i b_i: every addend is aligned to the largest one and truncated below 2^-26 of it, the sum is
+// rounded or truncated to 24 bits: |D - exact| <= (17 * 2^-26 + 2^-23) * (|C| + sum |a_i b_i|) < ETA * (|C| + sum |a_i b_i|),
+// ETA = 2^-21 (measured on this chip: at most 5.8 * 2^-24 over adversarial exponent mixes).  Over a run, |C| is at most
+// the sum of |a b| of the run's earlier steps, so the run's error is at most ETA * m * S_run, and the whole element's
+// ETA * m * S, S = sum_k |x_k| |R_kj|.  S is bounded per row without touching R's columns one by one:
+//   S <= rho * sqrt(sum_{|x_k| < theta} x_k^2)  +  sum_{|x_k| >= theta} |x_k| * max_j |R_kj|
+// (Cauchy-Schwarz on the many small entries, rho = max_j ||R[:, j]||_2; the few large ones - salient channels - term by
+// term), theta = 4 * mean |x|.  u~ is stored as fp32: one more rounding, 2^-24 |u~| <= 2^-24 S.
+#include "lrq_internal.h"
+
+namespace lrq {
+namespace {
+
+constexpr int kWave = 64;
+constexpr double kMagic = 6755399441055744.0;   // 1.5 * 2^52: adding it rounds to an integer, ties to even
+constexpr int CAPC = 4;                          // amax candidates kept per row
+constexpr float kBoundSlack = 1.004f;            // covers the fp32 arithmetic in which the bound itself is evaluated
+
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ float wave_sumf(float v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_maxf(float v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ int wave_sumi(int v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// ---- statistics of a K x K bf16 matrix A, one workgroup per row: maxabs[row] = max_j |A[row, j]| (if maxabs) and
+// *sumsq_max = max over rows of sum_j A[row, j]^2 (if sumsq_max; float bits, atomic max - zero it first).  Run on R it
+// gives max_j |R_kj| per k; run on R transposed it gives rho^2.  zero_words: the launch on R also clears the scalars.
+__global__ __launch_bounds__(256) void matrix_row_stats_kernel(const uint16_t* __restrict__ A, int K, float* __restrict__ maxabs,
+                                                               unsigned* __restrict__ sumsq_max, unsigned* __restrict__ zero_words,
+                                                               int n_zero) {
+    __shared__ float red[8];
+    const int t = threadIdx.x, row = blockIdx.x;
+    if (zero_words && row == 0 && t < n_zero) zero_words[t] = 0u;
+    const uint4* src = reinterpret_cast<const uint4*>(A + (size_t)row * K);
+    float mx = 0.0f, ss = 0.0f;
+    for (int c = t; c < K / 8; c += 256) {
+        const uint4 v = src[c];
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = bf16_lo(w[i]), b = bf16_hi(w[i]);
+            mx = fmaxf(mx, fmaxf(fabsf(a), fabsf(b)));
+            ss += a * a + b * b;
+        }
+    }
+    mx = wave_maxf(mx);
+    ss = wave_sumf(ss);
+    if (t % kWave == 0) { red[t / kWave] = mx; red[4 + t / kWave] = ss; }
+    __syncthreads();
+    if (t == 0) {
+        mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        ss = (red[4] + red[5]) + (red[6] + red[7]);
+        if (maxabs) maxabs[row] = mx;
+        if (sumsq_max) atomicMax(sumsq_max, __float_as_uint(ss));      // non-negative floats order like their bit patterns
+    }
+}
+
+// Rt[j, k] = R[k, j], 64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ R, int K, uint16_t* __restrict__ Rt) {
+    __shared__ uint16_t tile[64][66];
+    const int t = threadIdx.x, k0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+    {
+        const int r = t / 4, c = (t % 4) * 16;
+        const uint4 a = *reinterpret_cast<const uint4*>(R + (size_t)(k0 + r) * K + j0 + c);
+        const uint4 b = *reinterpret_cast<const uint4*>(R + (size_t)(k0 + r) * K + j0 + c + 8);
+        const unsigned w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            tile[r][c + 2 * i] = (uint16_t)(w[i] & 0xffffu);
+            tile[r][c + 2 * i + 1] = (uint16_t)(w[i] >> 16);
+        }
+    }
+    __syncthreads();
+    {
+        const int r = t / 4, c = (t % 4) * 16;      // output row j0 + r, columns k0 + c ...
+        unsigned w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = (unsigned)tile[c + 2 * i][r] | ((unsigned)tile[c + 2 * i + 1][r] << 16);
+        uint4* dst = reinterpret_cast<uint4*>(Rt + (size_t)(j0 + r) * K + k0 + c);
+        dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    }
+}
+
+// ---- u~ = x . R on the bf16 matrix cores.  Workgroup = 8 waves (4 x 2), tile 128 tokens x 128 columns, wave tile
+// 32 x 64 (two 32 x 32 accumulator tiles); both operand tiles (x rows and R columns, i.e. rows of Rt) go global ->
+// registers -> LDS one 64-k stage ahead, rows padded to 144 bytes so that the 16-byte fragment reads of 16 consecutive
+// rows fall on distinct banks.  Every CHUNK k the fp32 accumulators are added to fp64 ones and cleared.
+constexpr int DT_M = 128, DT_N = 128, DT_K = 64, DT_ROW = 144;
+
+template <int CHUNK>
+__global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt,
+                                                                    int M, int K, float* __restrict__ Ut, int tiles_m, int tiles_n) {
+    static_assert(CHUNK == 32 || CHUNK == 64 || CHUNK == 128, "run length of the fp32 accumulation");
+    __shared__ __attribute__((aligned(16))) unsigned char As[2][DT_M * DT_ROW];
+    __shared__ __attribute__((aligned(16))) unsigned char Bs[2][DT_N * DT_ROW];
+    // tile order: workgroup ids go round-robin over the 8 XCDs; each XCD walks a contiguous range of an order that keeps
+    // 8 row tiles together and runs over the column tiles fastest, so that an XCD's L2 sees each x panel and each R
+    // panel several times in a row
+    const int ntiles = tiles_m * tiles_n;
+    int tile;
+    {
+        const int x = blockIdx.x % 8, i = blockIdx.x / 8;
+        const int base = ntiles / 8, rem = ntiles % 8;
+        tile = x * base + (x < rem ? x : rem) + i;
+    }
+    int tm, tn;
+    {
+        constexpr int GM = 8;
+        const int per_group = GM * tiles_n;
+        const int group = tile / per_group, first_m = group * GM;
+        const int gsize = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+        const int r = tile % per_group;
+        tm = first_m + r % gsize;
+        tn = r / gsize;
+    }
+    const int m0 = tm * DT_M, n0 = tn * DT_N;
+    const int t = threadIdx.x, lane = t % kWave, wv = t / kWave;
+    const int wm = wv / 2, wn = wv % 2;
+
+    // loader: 1024 16-byte chunks per operand tile, two per thread
+    const unsigned char* asrc[2];
+    const unsigned char* bsrc[2];
+    int ldst[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = t + 512 * i, row = c / 8, cc = c % 8;
+        int gr = m0 + row;
+        if (gr >= M) gr = M - 1;
+        asrc[i] = reinterpret_cast<const unsigned char*>(X + (size_t)gr * K) + cc * 16;
+        bsrc[i] = reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + row) * K) + cc * 16;
+        ldst[i] = row * DT_ROW + cc * 16;
+    }
+    v16f acc[2];
+    double wide[2][16];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc[j][r] = 0.0f; wide[j][r] = 0.0; }
+
+    uint4 an[2], bn[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        *reinterpret_cast<uint4*>(&As[0][ldst[i]]) = *reinterpret_cast<const uint4*>(asrc[i]);
+        *reinterpret_cast<uint4*>(&Bs[0][ldst[i]]) = *reinterpret_cast<const uint4*>(bsrc[i]);
+    }
+    __syncthreads();
+    const int nk = K / DT_K;
+    const int a_off = (wm * 32 + lane % 32) * DT_ROW + (lane / 32) * 16;
+    const int b_off = (wn * 64 + lane % 32) * DT_ROW + (lane / 32) * 16;
+    for (int kb = 0; kb < nk; ++kb) {
+        const int cur = kb & 1;
+        const int kn = kb + 1 < nk ? kb + 1 : kb;       // the last stage re-reads itself into the idle buffer
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            an[i] = *reinterpret_cast<const uint4*>(asrc[i] + (size_t)kn * DT_K * 2);
+            bn[i] = *reinterpret_cast<const uint4*>(bsrc[i] + (size_t)kn * DT_K * 2);
+        }
+#pragma unroll
+        for (int s = 0; s < DT_K / 16; ++s) {
+            const v8s a = *reinterpret_cast<const v8s*>(&As[cur][a_off + s * 32]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const v8s b = *reinterpret_cast<const v8s*>(&Bs[cur][b_off + j * 32 * DT_ROW + s * 32]);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+            }
+            if constexpr (CHUNK == 32) {
+                if (s % 2 == 1) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { wide[j][r] += (double)acc[j][r]; acc[j][r] = 0.0f; }
+                }
+            }
+        }
+        if (CHUNK == 64 || (CHUNK == 128 && (kb % 2 == 1 || kb == nk - 1))) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { wide[j][r] += (double)acc[j][r]; acc[j][r] = 0.0f; }
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<uint4*>(&As[cur ^ 1][ldst[i]]) = an[i];
+            *reinterpret_cast<uint4*>(&Bs[cur ^ 1][ldst[i]]) = bn[i];
+        }
+        __syncthreads();
+    }
+    // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+            if (row < M) Ut[(size_t)row * K + n0 + wn * 64 + j * 32 + lane % 32] = (float)wide[j][r];
+        }
+}
+
+// ---- per row (one wave each): the bound eps_t, then the candidates for the row maximum.
+// mode[row] = 1 marks a row that is recomputed as a whole (more candidates than the list holds).
+__global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_t* __restrict__ X, const float* __restrict__ Ut,
+                                                                   int M, int K, const float* __restrict__ rowmaxR,
+                                                                   const unsigned* __restrict__ rho2_bits, float err_factor,
+                                                                   double* __restrict__ eps, unsigned long long* __restrict__ amax_bits,
+                                                                   int* __restrict__ ccount, uint16_t* __restrict__ cidx,
+                                                                   int* __restrict__ mode) {
+    const int lane = threadIdx.x % kWave, row = blockIdx.x * 4 + threadIdx.x / kWave;
+    if (row >= M) return;
+    const uint4* xs = reinterpret_cast<const uint4*>(X + (size_t)row * K);
+    float s1 = 0.0f;
+    for (int c = lane; c < K / 8; c += kWave) {
+        const uint4 v = xs[c];
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s1 += fabsf(bf16_lo(w[i])) + fabsf(bf16_hi(w[i]));
+    }
+    s1 = wave_sumf(s1);
+    const float theta = 4.0f * s1 / (float)K;
+    float small2 = 0.0f, big = 0.0f;
+    for (int c = lane; c < K / 8; c += kWave) {
+        const uint4 v = xs[c];
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+        const float4 r0 = reinterpret_cast<const float4*>(rowmaxR)[2 * c], r1 = reinterpret_cast<const float4*>(rowmaxR)[2 * c + 1];
+        const float rm[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = fabsf(bf16_lo(w[i])), b = fabsf(bf16_hi(w[i]));
+            if (a >= theta) big += a * rm[2 * i]; else small2 += a * a;
+            if (b >= theta) big += b * rm[2 * i + 1]; else small2 += b * b;
+        }
+    }
+    small2 = wave_sumf(small2);
+    big = wave_sumf(big);
+    const float rho = sqrtf(__uint_as_float(*rho2_bits)) * kBoundSlack;
+    const float S = (rho * sqrtf(small2) * kBoundSlack + big) * kBoundSlack;       // >= sum_k |x_k| |R_kj| for every j
+    const double e = (double)S * (double)err_factor;
+    // row maximum of |u~| and the elements within 2 eps of it
+    const float4* us = reinterpret_cast<const float4*>(Ut + (size_t)row * K);
+    float mx = 0.0f;
+    for (int c = lane; c < K / 4; c += kWave) {
+        const float4 v = us[c];
+        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    mx = wave_maxf(mx);
+    int whole = 0, n = 0;
+    if (!(S > 0.0f)) {
+        // x is all zero (or not finite): u is exactly zero, nothing to decide
+    } else {
+        const double lim = (double)mx - 2.0 * e;
+        int mine = 0;
+        for (int c = lane; c < K / 4; c += kWave) {
+            const float4 v = us[c];
+            mine += ((double)fabsf(v.x) >= lim) + ((double)fabsf(v.y) >= lim) + ((double)fabsf(v.z) >= lim) + ((double)fabsf(v.w) >= lim);
+        }
+        n = wave_sumi(mine);
+        if (n > CAPC) {
+            whole = 1;
+            n = 0;
+        } else {
+            // at most CAPC hits in the row: the lanes that have one take their slots in lane order
+            // exclusive prefix of `mine` over the lanes
+            int before = 0;
+            for (int l = 0; l < kWave; ++l) {
+                const int m_l = __shfl(mine, l, kWave);
+                if (l < lane) before += m_l;
+            }
+            if (mine) {
+                int slot = before;
+                for (int c = lane; c < K / 4; c += kWave) {
+                    const float4 v = us[c];
+                    const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if ((double)fabsf(vv[i]) >= lim) cidx[(size_t)row * CAPC + slot++] = (uint16_t)(c * 4 + i);
+                }
+            }
+        }
+    }
+    if (lane == 0) {
+        eps[row] = e;
+        amax_bits[row] = 0ull;
+        ccount[row] = n;
+        mode[row] = whole;
+    }
+}
+
+// ---- the definition's chain for single elements: u = sum over ascending k of x[row, k] * R[k, col], one fused
+// multiply-add per term (the products are exact).  Rt holds R's columns contiguously, so both streams are read 128
+// bytes at a time per lane.
+__device__ __forceinline__ double exact_element(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt, int K, int row, int col) {
+    const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)row * K);
+    const uint4* rp = reinterpret_cast<const uint4*>(Rt + (size_t)col * K);
+    double u = 0.0;
+    for (int c = 0; c < K / 8; c += 8) {
+        uint4 xv[8], rv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { xv[i] = xp[c + i]; rv[i] = rp[c + i]; }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const unsigned xw[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+            const unsigned rw[4] = {rv[i].x, rv[i].y, rv[i].z, rv[i].w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                u = fma((double)bf16_lo(xw[d]), (double)bf16_lo(rw[d]), u);
+                u = fma((double)bf16_hi(xw[d]), (double)bf16_hi(rw[d]), u);
+            }
+        }
+    }
+    return u;
+}
+
+// amax candidates: thread i -> slot i / M of row i % M (slot 0 of every row first, so that the waves are full)
+__global__ __launch_bounds__(256) void dense_exact_amax_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt,
+                                                               int M, int K, const int* __restrict__ ccount,
+                                                               const uint16_t* __restrict__ cidx,
+                                                               unsigned long long* __restrict__ amax_bits) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)M * CAPC) return;
+    const int slot = (int)(i / M), row = (int)(i % M);
+    if (slot >= ccount[row]) return;
+    const double u = exact_element(X, Rt, K, row, (int)cidx[(size_t)row * CAPC + slot]);
+    atomicMax(&amax_bits[row], (unsigned long long)__double_as_longlong(fabs(u)));
+}
+
+// ---- codes from u~ with the exact amax; the elements the bound leaves undecided go to the row's list (one wave per row)
+__global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __restrict__ Ut, int M, int K, double qmax,
+                                                               const double* __restrict__ eps,
+                                                               const unsigned long long* __restrict__ amax_bits,
+                                                               int8_t* __restrict__ q, float* __restrict__ scale,
+                                                               int* __restrict__ fcount, uint16_t* __restrict__ fidx, int capf,
+                                                               int* __restrict__ mode) {
+    extern __shared__ int lds_cnt[];            // one counter per wave
+    const int wv = threadIdx.x / kWave, lane = threadIdx.x % kWave, row = blockIdx.x * 4 + wv;
+    if (lane == 0) lds_cnt[wv] = 0;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (row >= M) return;
+    if (mode[row]) {                            // recomputed as a whole later
+        if (lane == 0) fcount[row] = 0;
+        return;
+    }
+    const double amax = __longlong_as_double((long long)amax_bits[row]);
+    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    const double delta = eps[row] * inv * (1.0 + 1e-6) + 1e-12;
+    const double keep = 0.5 - delta;            // |p - rint(p)| below this: the code is settled
+    const float4* us = reinterpret_cast<const float4*>(Ut + (size_t)row * K);
+    uint16_t* myidx = fidx + (size_t)row * capf;
+    for (int c = lane; c < K / 8; c += kWave) {
+        const float4 v0 = us[2 * c], v1 = us[2 * c + 1];
+        const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        unsigned b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double p = (double)v[i] * inv;
+            double r = (p + kMagic) - kMagic;
+            if (!(fabs(p - r) < keep)) {
+                const int slot = atomicAdd(&lds_cnt[wv], 1);
+                if (slot < capf) myidx[slot] = (uint16_t)(c * 8 + i);
+            }
+            r = fmin(fmax(r, -qmax), qmax);
+            b[i] = (unsigned)__double2loint(r + kMagic) & 0xffu;
+        }
+        *reinterpret_cast<uint2*>(q + (size_t)row * K + (size_t)c * 8) =
+            make_uint2(b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24), b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane == 0) {
+        const int n = lds_cnt[wv];
+        scale[row] = (float)(amax / qmax);
+        if (n > capf) {
+            mode[row] = 1;
+            fcount[row] = 0;
+        } else {
+            fcount[row] = n;
+        }
+    }
+}
+
+// ---- exclusive prefix sum of the per-row counts, offs[0 .. M] (one workgroup; M is at most a few 10^5)
+__global__ __launch_bounds__(1024) void dense_scan_counts_kernel(const int* __restrict__ cnt, int M, int* __restrict__ offs) {
+    __shared__ int part[1024];
+    const int t = threadIdx.x, per = (M + 1023) / 1024;
+    const int a = t * per, b = a + per < M ? a + per : M;
+    int s = 0;
+    for (int i = a; i < b; ++i) s += cnt[i];
+    part[t] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        const int v = t >= o ? part[t - o] : 0;
+        __syncthreads();
+        part[t] += v;
+        __syncthreads();
+    }
+    int run = part[t] - s;
+    for (int i = a; i < b; ++i) {
+        offs[i] = run;
+        run += cnt[i];
+    }
+    if (t == 1023) offs[M] = part[1023];
+}
+
+// ---- undecided elements: exact value, exact code.  Thread i takes list entry i (row found by bisection of offs).
+__global__ __launch_bounds__(256) void dense_exact_codes_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt,
+                                                                int M, int K, double qmax, const int* __restrict__ offs,
+                                                                const uint16_t* __restrict__ fidx, int capf,
+                                                                const unsigned long long* __restrict__ amax_bits,
+                                                                int8_t* __restrict__ q) {
+    const int total = offs[M];
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        int lo = 0, hi = M;                     // largest row with offs[row] <= i
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) / 2;
+            if (offs[mid] <= i) lo = mid; else hi = mid;
+        }
+        const int row = lo, col = (int)fidx[(size_t)row * capf + (i - offs[row])];
+        const double u = exact_element(X, Rt, K, row, col);
+        const double amax = __longlong_as_double((long long)amax_bits[row]);
+        const double inv = amax > 0.0 ? qmax / amax : 0.0;
+        q[(size_t)row * K + col] = (int8_t)__double2loint(u * inv + kMagic);
+    }
+}
+
+// ---- rows recomputed as a whole (one workgroup per row, rows with mode == 0 leave at once): every column's chain,
+// twice - once for the maximum, once for the codes - with the row of x in LDS; R is read row by row, coalesced.
+__global__ __launch_bounds__(256) void dense_exact_rows_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ R,
+                                                               int K, double qmax, const int* __restrict__ mode,
+                                                               int8_t* __restrict__ q, float* __restrict__ scale) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int row = blockIdx.x, t = threadIdx.x;
+    if (!mode[row]) return;
+    uint16_t* xr = reinterpret_cast<uint16_t*>(lds_raw);
+    double* red = reinterpret_cast<double*>(lds_raw + (((size_t)K * 2 + 15) & ~(size_t)15));
+    for (int k = t; k < K; k += 256) xr[k] = X[(size_t)row * K + k];
+    __syncthreads();
+    double inv = 0.0;
+    for (int pass = 0; pass < 2; ++pass) {
+        double mx = 0.0;
+        for (int col = t; col < K; col += 256) {
+            const uint16_t* r = R + col;
+            double u = 0.0;
+            for (int k = 0; k < K; ++k)
+                u = fma((double)__uint_as_float((unsigned)xr[k] << 16), (double)__uint_as_float((unsigned)r[(size_t)k * K] << 16), u);
+            if (pass == 0) mx = fmax(mx, fabs(u));
+            else q[(size_t)row * K + col] = (int8_t)__double2loint(u * inv + kMagic);
+        }
+        if (pass == 0) {
+#pragma unroll
+            for (int o = kWave / 2; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
+            if (t % kWave == 0) red[t / kWave] = mx;
+            __syncthreads();
+            const double amax = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+            inv = amax > 0.0 ? qmax / amax : 0.0;
+            if (t == 0) scale[row] = (float)(amax / qmax);
+        }
+    }
+}
+
+}  // namespace
+
+DenseFastWs dense_fast_layout(int M, int K) {
+    DenseFastWs w;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { const size_t at = o; o += round256(bytes); return at; };
+    w.capf = ((32 + K / 64) + 7) & ~7;
+    w.ut = take((size_t)M * K * sizeof(float));
+    w.rt = take((size_t)K * K * sizeof(uint16_t));
+    w.rowmax = take((size_t)K * sizeof(float));
+    w.scalars = take(256);
+    w.eps = take((size_t)M * sizeof(double));
+    w.amax = take((size_t)M * sizeof(unsigned long long));
+    w.ccount = take((size_t)M * sizeof(int));
+    w.cidx = take((size_t)M * CAPC * sizeof(uint16_t));
+    w.fcount = take((size_t)M * sizeof(int));
+    w.fidx = take((size_t)M * w.capf * sizeof(uint16_t));
+    w.foffs = take(((size_t)M + 1) * sizeof(int));
+    w.mode = take((size_t)M * sizeof(int));
+    w.total = o;
+    return w;
+}
+
+bool dense_fast_applies(int M, int K, bool zero_point, bool prescale) {
+    return !zero_point && !prescale && M > 64 && K % 128 == 0 && K <= 16384 && (size_t)M * K < ((size_t)1 << 31);
+}
+
+// run length of the fp32 accumulation between promotions to fp64
+constexpr int kChunk = 64;
+
+hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K, int act_bits,
+                                          void* ws, int8_t* q, float* scale) {
+    const DenseFastWs L = dense_fast_layout(M, K);
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float* Ut = reinterpret_cast<float*>(base + L.ut);
+    uint16_t* Rt = reinterpret_cast<uint16_t*>(base + L.rt);
+    float* rowmax = reinterpret_cast<float*>(base + L.rowmax);
+    unsigned* scalars = reinterpret_cast<unsigned*>(base + L.scalars);       // [0]: rho^2 as float bits
+    double* eps = reinterpret_cast<double*>(base + L.eps);
+    unsigned long long* amax = reinterpret_cast<unsigned long long*>(base + L.amax);
+    int* ccount = reinterpret_cast<int*>(base + L.ccount);
+    uint16_t* cidx = reinterpret_cast<uint16_t*>(base + L.cidx);
+    int* fcount = reinterpret_cast<int*>(base + L.fcount);
+    uint16_t* fidx = reinterpret_cast<uint16_t*>(base + L.fidx);
+    int* foffs = reinterpret_cast<int*>(base + L.foffs);
+    int* mode = reinterpret_cast<int*>(base + L.mode);
+    const double qmax = (double)((1 << (act_bits - 1)) - 1);
+    // ETA * m for the runs of the matrix instruction, 2^-24 for the fp32 store of u~
+    const float err_factor = (float)(ldexp(1.0, -21) * (kChunk / 16) + ldexp(1.0, -24));
+
+    hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, R, K, rowmax, static_cast<unsigned*>(nullptr), scalars, 64);
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3(K / 64, K / 64), dim3(256), 0, st, R, K, Rt);
+    hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, Rt, K, static_cast<float*>(nullptr), scalars,
+                       static_cast<unsigned*>(nullptr), 0);
+    const int tiles_m = (M + DT_M - 1) / DT_M, tiles_n = K / DT_N;
+    hipLaunchKernelGGL((dense_rotate_bf16_kernel<kChunk>), dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, tiles_m, tiles_n);
+    hipLaunchKernelGGL(dense_row_candidates_kernel, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, M, K, rowmax, scalars, err_factor,
+                       eps, amax, ccount, cidx, mode);
+    hipLaunchKernelGGL(dense_exact_amax_kernel, dim3((unsigned)(((long)M * CAPC + 255) / 256)), dim3(256), 0, st, X, Rt, M, K,
+                       ccount, cidx, amax);
+    hipLaunchKernelGGL(dense_quant_flag_kernel, dim3((M + 3) / 4), dim3(256), 4 * sizeof(int), st, Ut, M, K, qmax, eps, amax, q,
+                       scale, fcount, fidx, L.capf, mode);
+    hipLaunchKernelGGL(dense_scan_counts_kernel, dim3(1), dim3(1024), 0, st, fcount, M, foffs);
+    hipLaunchKernelGGL(dense_exact_codes_kernel, dim3(2048), dim3(256), 0, st, X, Rt, M, K, qmax, foffs, fidx, L.capf, amax, q);
+    const size_t rows_lds = (((size_t)K * 2 + 15) & ~(size_t)15) + 4 * sizeof(double);
+    hipLaunchKernelGGL(dense_exact_rows_kernel, dim3(M), dim3(256), rows_lds, st, X, R, K, qmax, mode, q, scale);
+    return hipGetLastError();
+}
+
+}  // namespace lrq

@@ -42,6 +42,7 @@ int check_rotation(const lrq_rotation* rot, int K) {
             if (!is_pow2(rot->had_block) || K % rot->had_block != 0) return LRQ_EUNSUPPORTED;
             return K <= kMaxRowLds ? LRQ_OK : LRQ_EUNSUPPORTED;
         case LRQ_ROT_DENSE:
+        case LRQ_ROT_DENSE_F64:
             if (!rot->R || !aligned16(rot->R)) return LRQ_EINVAL;
             return K % 64 == 0 ? LRQ_OK : LRQ_EUNSUPPORTED;
         case LRQ_ROT_BLOCKPERM:
@@ -102,7 +103,14 @@ struct ArsWs {
 };
 ArsWs ars_layout(int M, int K, const lrq_rotation* rot) {
     ArsWs l{0, 0, 0};
-    if (rot && rot->kind == LRQ_ROT_DENSE) l.total = round256((size_t)M * K * sizeof(double));
+    if (rot && (rot->kind == LRQ_ROT_DENSE || rot->kind == LRQ_ROT_DENSE_F64)) {
+        // U doubles for the evaluation in fp64; the matrix-core evaluation lays its own buffers over the same bytes
+        l.total = round256((size_t)M * K * sizeof(double));
+        if (rot->kind == LRQ_ROT_DENSE && lrq::dense_fast_applies(M, K, false, rot->prescale != nullptr)) {
+            const size_t fast = lrq::dense_fast_layout(M, K).total;
+            if (fast > l.total) l.total = fast;
+        }
+    }
     if (rot && rot->kind == LRQ_ROT_BLOCKPERM) {       // U doubles (first Z = x.R1, finally u), then Zp doubles
         l.zp_off = round256((size_t)M * K * sizeof(double));
         l.total = l.zp_off + round256((size_t)M * K * sizeof(double));
@@ -129,8 +137,11 @@ int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rota
                 rot->prescale);
             break;
         default:
-            e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
-                                               static_cast<double*>(ws), q, scale, zero, rot->prescale);
+            if (rot->kind == LRQ_ROT_DENSE && lrq::dense_fast_applies(M, K, zero != nullptr, rot->prescale != nullptr))
+                e = lrq::launch_dense_rotate_quant_fast(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits, ws, q, scale);
+            else
+                e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
+                                                   static_cast<double*>(ws), q, scale, zero, rot->prescale);
             break;
     }
     return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
@@ -208,6 +219,17 @@ size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bi
     (void)act_bits;
     if (M <= 0 || K <= 0) return 0;
     return ars_layout(M, K, rot).total;
+}
+
+int lrq_ars_dense_diagnostics(int M, int K, size_t offsets[4]) {
+    if (M <= 0 || K <= 0 || !offsets) return LRQ_EINVAL;
+    if (!lrq::dense_fast_applies(M, K, false, false)) return LRQ_EUNSUPPORTED;
+    const lrq::DenseFastWs l = lrq::dense_fast_layout(M, K);
+    offsets[0] = l.ut;
+    offsets[1] = l.eps;
+    offsets[2] = l.fcount;
+    offsets[3] = l.mode;
+    return LRQ_OK;
 }
 
 static int ars_impl(void* stream, const void* X, int M, int K, const lrq_rotation* rot, int act_bits, int8_t* q,

@@ -35,6 +35,18 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
                                      int act_bits, double* U, int8_t* q, float* scale, int32_t* zero,
                                      const float* prescale);
 
+// The same rotation + quantizer with the bulk product on the bf16 matrix cores, a certified error bound and exact
+// recomputation of the undecided elements (symmetric quantizer without pre-scale only; dense_fast_applies says when).
+// Bit-identical codes and scales.  ws: dense_fast_layout(M, K).total bytes.
+struct DenseFastWs {
+    size_t ut, rt, rowmax, scalars, eps, amax, ccount, cidx, fcount, fidx, foffs, mode, total;
+    int capf;       // undecided elements a row's list holds
+};
+DenseFastWs dense_fast_layout(int M, int K);
+bool dense_fast_applies(int M, int K, bool zero_point, bool prescale);
+hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K, int act_bits,
+                                          void* ws, int8_t* q, float* scale);
+
 // u = ((x.R1).P).R2 with block-diagonal R1, R2 (bf16 [K/B,B,B]), fp64 throughout, perm in gather form; U [M,K]
 // and Zp [M,K] doubles are scratch.  B % 128 == 0, B | K.
 hipError_t launch_blockperm_rotate_quant(hipStream_t st, const uint16_t* X, int M, int K, int B, const uint16_t* R1,

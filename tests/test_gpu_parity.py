@@ -69,23 +69,89 @@ def test_no_rotation_quant(lrq):
 
 
 @pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8), (200, 192, 8),
-                                        (2, 1152, 4), (8, 192, 8), (1, 3072, 8), (64, 384, 8), (65, 384, 8)])       # up to 64 rows: the column-per-thread kernel
+                                        (2, 1152, 4), (8, 192, 8), (1, 3072, 8), (64, 384, 8), (65, 384, 8),      # up to 64 rows: the column-per-thread kernel
+                                        (300, 1152, 8), (129, 3072, 6), (257, 2048, 4)])
 def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
     print(f"case dense M={M} K={K} a={a_bits}", flush=True)
     X = _acts(M, K, 3 + K)
     R = synth.make_rotation(K, (901, K, 0))
     import torch
     q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "dense", R_bits=R)
-    rot = lrq.Rotation("dense", 0, bf16_to_dev(R))
+    u_ref = oracle.rotate_dense(oracle.bf16_bits_to_f64(X), oracle.bf16_bits_to_f64(R))
+    Rd = bf16_to_dev(R)
+    # the evaluation in fp64: codes, scales and the rotated activations themselves (fp64 scratch at the head of the
+    # workspace) - same bits as the definition's ascending-k accumulation, i.e. the kernel's summation order is the oracle's
+    rot = lrq.Rotation("dense_f64", 0, Rd)
     ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, a_bits), dtype=torch.uint8, device="cuda")
     q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, workspace=ws)
     assert np.array_equal(q.cpu().numpy(), q_ref)
     assert np.array_equal(s.cpu().numpy(), s_ref)
-    # the rotated activations themselves (fp64 scratch at the head of the workspace): same bits as the
-    # definition's ascending-k accumulation, i.e. the kernel's summation order is the oracle's
     u = ws[:M * K * 8].view(torch.float64).view(M, K).cpu().numpy()
-    u_ref = oracle.rotate_dense(oracle.bf16_bits_to_f64(X), oracle.bf16_bits_to_f64(R))
     assert np.array_equal(u, u_ref)
+    # the default evaluation (bf16 matrix cores + error bound + exact recomputation where the bound does not decide;
+    # shapes it does not serve fall back to the one above): the same codes and scales
+    rot = lrq.Rotation("dense", 0, Rd)
+    ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, a_bits), dtype=torch.uint8, device="cuda")
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, workspace=ws)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    if M > 64 and K % 128 == 0:
+        ut, eps, cnt, whole = (a.cpu().numpy() for a in lrq.ars_dense_diagnostics(ws, M, K))
+        err = np.abs(ut.astype(np.float64) - u_ref).max(axis=1)
+        assert np.all(err <= eps), f"error bound violated: worst ratio {np.max(err / eps)}"
+        print(f"  max |u~ - u| / eps = {np.max(err / np.maximum(eps, 1e-300)):.3f}, undecided fraction "
+              f"{cnt.sum() / (M * K):.2e}, whole rows {int(whole.sum())}", flush=True)
+        assert whole.sum() == 0 and cnt.sum() < 0.05 * M * K        # the bound decides almost everything on this data
+
+
+def test_dense_rotation_rows_the_bound_cannot_decide(lrq):
+    """Rows built so that the matrix-core evaluation cannot settle them: exact ties on a rounding boundary, rows whose
+    rotated values are tiny against their inputs (heavy cancellation), an all-zero row, a single spike, and equal
+    maxima - every one must still give the oracle's codes (through the exact recomputation)."""
+    import torch
+    M, K = 130, 256
+    X = oracle.bf16_bits_to_f64(_acts(M, K, 4242)).astype(np.float32)
+    R = np.zeros((K, K), np.float32)
+    R[np.arange(K), (np.arange(K) * 7 + 3) % K] = 1.0          # a permutation matrix: u holds x's values exactly
+    R[5, :] = 0.0; R[5, (5 * 7 + 3) % K] = 0.5
+    X[0] = 0.0
+    X[1] = 0.0; X[1, 9] = -3.0
+    X[2, :] = 1.0                                              # every element is the maximum
+    X[3, :] = 0.5; X[3, 0] = 127.0                             # u * inv = 0.5 exactly: ties, rounded to even
+    X[4, :] = 2.5; X[4, 1] = 127.0                             # 2.5 -> 2
+    X[5, :] = 1.5; X[5, 2] = -127.0
+    Xb = synth.f32_to_bf16_bits(X)
+    Rb = synth.f32_to_bf16_bits(R)
+    for a_bits in (8, 4):
+        q_ref, s_ref = oracle.ars_rotate_quant(Xb, a_bits, "dense", R_bits=Rb)
+        rot = lrq.Rotation("dense", 0, bf16_to_dev(Rb))
+        ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, a_bits), dtype=torch.uint8, device="cuda")
+        q, s = lrq.ars_rotate_quant(bf16_to_dev(Xb), rot, a_bits, workspace=ws)
+        assert np.array_equal(q.cpu().numpy(), q_ref)
+        assert np.array_equal(s.cpu().numpy(), s_ref)
+        _, _, cnt, whole = (a.cpu().numpy() for a in lrq.ars_dense_diagnostics(ws, M, K))
+        assert whole[2] == 1                                   # 256 equal maxima: recomputed as a whole
+        if a_bits == 8:
+            assert cnt[3] >= K - 1 or whole[3] == 1            # the ties were not decided by the approximation
+    # heavy cancellation: R's lower half is its upper half negated and the second half of x repeats the first up to one
+    # element that differs in its last bit, so u is 2^-7 of a single product while sum |x| |R| is large: the bound
+    # decides nothing and every row is recomputed as a whole
+    g = synth.rng_for(913, 1)
+    A = oracle.bf16_bits_to_f64(synth.f32_to_bf16_bits(g.standard_normal((K // 2, K)).astype(np.float32)))
+    Rb = synth.f32_to_bf16_bits(np.concatenate([A, -A], axis=0).astype(np.float32))
+    half = synth.f32_to_bf16_bits(g.standard_normal((M, K // 2)).astype(np.float32))
+    other = half.copy()
+    other[np.arange(M), np.arange(M) % (K // 2)] ^= 1
+    Xb = np.concatenate([half, other], axis=1)
+    q_ref, s_ref = oracle.ars_rotate_quant(Xb, 8, "dense", R_bits=Rb)
+    rot = lrq.Rotation("dense", 0, bf16_to_dev(Rb))
+    ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, 8), dtype=torch.uint8, device="cuda")
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(Xb), rot, 8, workspace=ws)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    assert np.abs(q_ref).max() == 127 and (q_ref != 0).mean() > 0.5
+    _, _, _, whole = (a.cpu().numpy() for a in lrq.ars_dense_diagnostics(ws, M, K))
+    assert whole.sum() == M
 
 
 def _blockperm_inputs(lrq, K, B, seed):
