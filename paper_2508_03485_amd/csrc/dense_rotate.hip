@@ -35,6 +35,7 @@ constexpr float kBoundSlack = 1.004f;            // covers the fp32 arithmetic i
 
 typedef short v8s __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
@@ -116,17 +117,63 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 }
 
 // ---- u~ = x . R on the bf16 matrix cores.  Workgroup = 8 waves (4 x 2), tile 128 tokens x 128 columns, wave tile
-// 32 x 64 (two 32 x 32 accumulator tiles); both operand tiles (x rows and R columns, i.e. rows of Rt) go global ->
-// registers -> LDS one 64-k stage ahead, rows padded to 144 bytes so that the 16-byte fragment reads of 16 consecutive
-// rows fall on distinct banks.  Every CHUNK k the fp32 accumulators are added to fp64 ones and cleared.
-constexpr int DT_M = 128, DT_N = 128, DT_K = 64, DT_ROW = 144;
+// 32 x 64 (two 32 x 32 accumulator tiles: with the fp64 copies that is 96 registers, which leaves room to keep two
+// 64-k stages of both operands in flight in registers).  Both operand tiles (x rows and R columns, i.e. rows of Rt)
+// go global -> registers -> LDS: stage s is loaded two iterations before it is stored to one of three LDS buffers and
+// three before it is multiplied.  LDS rows are padded to 144 bytes so that the 16-byte fragment reads of 16
+// consecutive rows fall on distinct banks.  A run of CHUNK = 64 k (one stage) starts on a zero accumulator (the
+// instruction's constant-zero addend, no clearing) and ends by adding the fp32 tiles to the fp64 ones.
+// (X, Rt and Ut are deliberately not declared __restrict__: with that promise the compiler moves the prefetch loads past
+// the compiler barrier that keeps them ahead of the arithmetic, down to their LDS stores.)
+constexpr int DT_M = 128, DT_N = 128, DT_K = 64, DT_ROW = 144, DT_BUF = DT_M * DT_ROW;
+constexpr int kChunk = DT_K;        // run length of the fp32 accumulation between promotions to fp64
 
-template <int CHUNK>
-__global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt,
-                                                                    int M, int K, float* __restrict__ Ut, int tiles_m, int tiles_n) {
-    static_assert(CHUNK == 32 || CHUNK == 64 || CHUNK == 128, "run length of the fp32 accumulation");
-    __shared__ __attribute__((aligned(16))) unsigned char As[2][DT_M * DT_ROW];
-    __shared__ __attribute__((aligned(16))) unsigned char Bs[2][DT_N * DT_ROW];
+struct Stage {                      // one thread's share of a 64-k stage of both operand tiles
+    v4u a0, a1, b0, b1;
+};
+__device__ __forceinline__ Stage load_stage(const unsigned char* a0, const unsigned char* a1, const unsigned char* b0,
+                                            const unsigned char* b1, int kb, int nk) {
+    const size_t o = (size_t)(kb < nk ? kb : nk - 1) * DT_K * 2;       // past the end: a harmless re-read, never multiplied
+    Stage s;
+    s.a0 = *reinterpret_cast<const v4u*>(a0 + o);
+    s.a1 = *reinterpret_cast<const v4u*>(a1 + o);
+    s.b0 = *reinterpret_cast<const v4u*>(b0 + o);
+    s.b1 = *reinterpret_cast<const v4u*>(b1 + o);
+    return s;
+}
+__device__ __forceinline__ void store_stage(const Stage s, unsigned char* As, unsigned char* Bs, int buf, int d0, int d1) {
+    *reinterpret_cast<v4u*>(&As[buf * DT_BUF + d0]) = s.a0;
+    *reinterpret_cast<v4u*>(&As[buf * DT_BUF + d1]) = s.a1;
+    *reinterpret_cast<v4u*>(&Bs[buf * DT_BUF + d0]) = s.b0;
+    *reinterpret_cast<v4u*>(&Bs[buf * DT_BUF + d1]) = s.b1;
+}
+// one stage: a run of four chained matrix instructions per accumulator tile from a zero addend, then added to the fp64 tiles
+__device__ __forceinline__ void multiply_stage(const unsigned char* A, const unsigned char* B, double (&wide)[2][16]) {
+    v16f acc[2];
+#pragma unroll
+    for (int s = 0; s < DT_K / 16; ++s) {
+        const v8s a = *reinterpret_cast<const v8s*>(A + s * 32);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const v8s b = *reinterpret_cast<const v8s*>(B + j * 32 * DT_ROW + s * 32);
+            if (s == 0) {
+                const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
+            } else {
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) wide[j][r] += (double)acc[j][r];
+}
+
+__global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K, float* Ut,
+                                                                    int tiles_m, int tiles_n) {
+    __shared__ __attribute__((aligned(16))) unsigned char As[3 * DT_BUF];
+    __shared__ __attribute__((aligned(16))) unsigned char Bs[3 * DT_BUF];
     // tile order: workgroup ids go round-robin over the 8 XCDs; each XCD walks a contiguous range of an order that keeps
     // 8 row tiles together and runs over the column tiles fastest, so that an XCD's L2 sees each x panel and each R
     // panel several times in a row
@@ -151,73 +198,54 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
     const int t = threadIdx.x, lane = t % kWave, wv = t / kWave;
     const int wm = wv / 2, wn = wv % 2;
 
-    // loader: 1024 16-byte chunks per operand tile, two per thread
-    const unsigned char* asrc[2];
-    const unsigned char* bsrc[2];
-    int ldst[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int c = t + 512 * i, row = c / 8, cc = c % 8;
-        int gr = m0 + row;
-        if (gr >= M) gr = M - 1;
-        asrc[i] = reinterpret_cast<const unsigned char*>(X + (size_t)gr * K) + cc * 16;
-        bsrc[i] = reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + row) * K) + cc * 16;
-        ldst[i] = row * DT_ROW + cc * 16;
-    }
-    v16f acc[2];
+    // loader: 1024 16-byte chunks per operand tile and stage, two per thread (rows r0 and r0 + 64)
+    const int r0 = t / 8, cc = t % 8;
+    int g0 = m0 + r0, g1 = m0 + r0 + 64;
+    if (g0 >= M) g0 = M - 1;
+    if (g1 >= M) g1 = M - 1;
+    const unsigned char* pa0 = reinterpret_cast<const unsigned char*>(X + (size_t)g0 * K) + cc * 16;
+    const unsigned char* pa1 = reinterpret_cast<const unsigned char*>(X + (size_t)g1 * K) + cc * 16;
+    const unsigned char* pb0 = reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0) * K) + cc * 16;
+    const unsigned char* pb1 = reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0 + 64) * K) + cc * 16;
+    const int d0 = r0 * DT_ROW + cc * 16, d1 = d0 + 64 * DT_ROW;
+    const int nk = K / DT_K;
+
     double wide[2][16];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { acc[j][r] = 0.0f; wide[j][r] = 0.0; }
-
-    uint4 an[2], bn[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        *reinterpret_cast<uint4*>(&As[0][ldst[i]]) = *reinterpret_cast<const uint4*>(asrc[i]);
-        *reinterpret_cast<uint4*>(&Bs[0][ldst[i]]) = *reinterpret_cast<const uint4*>(bsrc[i]);
-    }
-    __syncthreads();
-    const int nk = K / DT_K;
+        for (int r = 0; r < 16; ++r) wide[j][r] = 0.0;
     const int a_off = (wm * 32 + lane % 32) * DT_ROW + (lane / 32) * 16;
     const int b_off = (wn * 64 + lane % 32) * DT_ROW + (lane / 32) * 16;
-    for (int kb = 0; kb < nk; ++kb) {
-        const int cur = kb & 1;
-        const int kn = kb + 1 < nk ? kb + 1 : kb;       // the last stage re-reads itself into the idle buffer
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            an[i] = *reinterpret_cast<const uint4*>(asrc[i] + (size_t)kn * DT_K * 2);
-            bn[i] = *reinterpret_cast<const uint4*>(bsrc[i] + (size_t)kn * DT_K * 2);
-        }
-#pragma unroll
-        for (int s = 0; s < DT_K / 16; ++s) {
-            const v8s a = *reinterpret_cast<const v8s*>(&As[cur][a_off + s * 32]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const v8s b = *reinterpret_cast<const v8s*>(&Bs[cur][b_off + j * 32 * DT_ROW + s * 32]);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
-            }
-            if constexpr (CHUNK == 32) {
-                if (s % 2 == 1) {
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) { wide[j][r] += (double)acc[j][r]; acc[j][r] = 0.0f; }
-                }
-            }
-        }
-        if (CHUNK == 64 || (CHUNK == 128 && (kb % 2 == 1 || kb == nk - 1))) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) { wide[j][r] += (double)acc[j][r]; acc[j][r] = 0.0f; }
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<uint4*>(&As[cur ^ 1][ldst[i]]) = an[i];
-            *reinterpret_cast<uint4*>(&Bs[cur ^ 1][ldst[i]]) = bn[i];
-        }
+
+    // prologue: stages 0, 1 in LDS buffers 0, 1; stages 2 (even) and 3 (odd) in registers
+    Stage ev = load_stage(pa0, pa1, pb0, pb1, 0, nk);
+    Stage od = load_stage(pa0, pa1, pb0, pb1, 1, nk);
+    store_stage(ev, As, Bs, 0, d0, d1);
+    store_stage(od, As, Bs, 1, d0, d1);
+    ev = load_stage(pa0, pa1, pb0, pb1, 2, nk);
+    od = load_stage(pa0, pa1, pb0, pb1, 3, nk);
+    __syncthreads();
+    int b0 = 0, b1 = 1, b2 = 2;                          // LDS buffers of stages kb, kb + 1, kb + 2
+    for (int kb = 0; kb < nk; kb += 2) {                 // K % 128 == 0: an even number of stages
+        store_stage(ev, As, Bs, b2, d0, d1);             // stage kb + 2, loaded two iterations ago
+        ev = load_stage(pa0, pa1, pb0, pb1, kb + 4, nk);
+        asm volatile("" ::: "memory");                   // keeps the loads above ahead of the arithmetic below
+        __builtin_amdgcn_sched_barrier(0);
+        multiply_stage(&As[b0 * DT_BUF + a_off], &Bs[b0 * DT_BUF + b_off], wide);
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        store_stage(od, As, Bs, b0, d0, d1);             // stage kb + 3 into the buffer that stage kb just left
+        od = load_stage(pa0, pa1, pb0, pb1, kb + 5, nk);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        multiply_stage(&As[b1 * DT_BUF + a_off], &Bs[b1 * DT_BUF + b_off], wide);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        const int f = b0;                                // stages kb + 2, kb + 3, kb + 4 live in b2, b0, b1
+        b0 = b2;
+        b2 = b1;
+        b1 = f;
     }
     // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
 #pragma unroll
@@ -231,35 +259,60 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
 
 // ---- per row (one wave each): the bound eps_t, then the candidates for the row maximum.
 // mode[row] = 1 marks a row that is recomputed as a whole (more candidates than the list holds).
+// RES: K <= 4096, the row of x and of u~ stay in registers between the passes (each is read once).
+template <bool RES>
 __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_t* __restrict__ X, const float* __restrict__ Ut,
                                                                    int M, int K, const float* __restrict__ rowmaxR,
                                                                    const unsigned* __restrict__ rho2_bits, float err_factor,
                                                                    double* __restrict__ eps, unsigned long long* __restrict__ amax_bits,
                                                                    int* __restrict__ ccount, uint16_t* __restrict__ cidx,
                                                                    int* __restrict__ mode) {
+    constexpr int NX = RES ? 8 : 1, NU = RES ? 16 : 1;
     const int lane = threadIdx.x % kWave, row = blockIdx.x * 4 + threadIdx.x / kWave;
     if (row >= M) return;
     const uint4* xs = reinterpret_cast<const uint4*>(X + (size_t)row * K);
-    float s1 = 0.0f;
-    for (int c = lane; c < K / 8; c += kWave) {
-        const uint4 v = xs[c];
-        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+    const float4* us = reinterpret_cast<const float4*>(Ut + (size_t)row * K);
+    const int nxc = K / 8, nuc = K / 4;
+    uint4 xr[NX];
+    float4 ur[NU];
+    if constexpr (RES) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) s1 += fabsf(bf16_lo(w[i])) + fabsf(bf16_hi(w[i]));
+        for (int i = 0; i < NX; ++i) xr[i] = lane + kWave * i < nxc ? xs[lane + kWave * i] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int i = 0; i < NU; ++i) ur[i] = lane + kWave * i < nuc ? us[lane + kWave * i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    auto xchunk = [&](int i, int c) { return RES ? xr[i] : xs[c]; };
+    auto uchunk = [&](int i, int c) { return RES ? ur[i] : us[c]; };
+    const int xiters = RES ? NX : (nxc + kWave - 1) / kWave, uiters = RES ? NU : (nuc + kWave - 1) / kWave;
+
+    float s1 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < xiters; ++i) {
+        const int c = lane + kWave * i;
+        if (c < nxc) {
+            const uint4 v = xchunk(RES ? i : 0, c);
+            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) s1 += fabsf(bf16_lo(w[d])) + fabsf(bf16_hi(w[d]));
+        }
     }
     s1 = wave_sumf(s1);
     const float theta = 4.0f * s1 / (float)K;
     float small2 = 0.0f, big = 0.0f;
-    for (int c = lane; c < K / 8; c += kWave) {
-        const uint4 v = xs[c];
-        const unsigned w[4] = {v.x, v.y, v.z, v.w};
-        const float4 r0 = reinterpret_cast<const float4*>(rowmaxR)[2 * c], r1 = reinterpret_cast<const float4*>(rowmaxR)[2 * c + 1];
-        const float rm[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float a = fabsf(bf16_lo(w[i])), b = fabsf(bf16_hi(w[i]));
-            if (a >= theta) big += a * rm[2 * i]; else small2 += a * a;
-            if (b >= theta) big += b * rm[2 * i + 1]; else small2 += b * b;
+    for (int i = 0; i < xiters; ++i) {
+        const int c = lane + kWave * i;
+        if (c < nxc) {
+            const uint4 v = xchunk(RES ? i : 0, c);
+            const unsigned w[4] = {v.x, v.y, v.z, v.w};
+            const float4 r0 = reinterpret_cast<const float4*>(rowmaxR)[2 * c], r1 = reinterpret_cast<const float4*>(rowmaxR)[2 * c + 1];
+            const float rm[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const float a = fabsf(bf16_lo(w[d])), b = fabsf(bf16_hi(w[d]));
+                if (a >= theta) big += a * rm[2 * d]; else small2 += a * a;
+                if (b >= theta) big += b * rm[2 * d + 1]; else small2 += b * b;
+            }
         }
     }
     small2 = wave_sumf(small2);
@@ -268,22 +321,27 @@ __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_
     const float S = (rho * sqrtf(small2) * kBoundSlack + big) * kBoundSlack;       // >= sum_k |x_k| |R_kj| for every j
     const double e = (double)S * (double)err_factor;
     // row maximum of |u~| and the elements within 2 eps of it
-    const float4* us = reinterpret_cast<const float4*>(Ut + (size_t)row * K);
     float mx = 0.0f;
-    for (int c = lane; c < K / 4; c += kWave) {
-        const float4 v = us[c];
-        mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+#pragma unroll
+    for (int i = 0; i < uiters; ++i) {
+        const int c = lane + kWave * i;
+        if (c < nuc) {
+            const float4 v = uchunk(RES ? i : 0, c);
+            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
     }
     mx = wave_maxf(mx);
     int whole = 0, n = 0;
-    if (!(S > 0.0f)) {
-        // x is all zero (or not finite): u is exactly zero, nothing to decide
-    } else {
-        const double lim = (double)mx - 2.0 * e;
+    if (S > 0.0f) {                              // otherwise x is all zero (or not finite) and there is nothing to decide
+        const float lim = (float)((double)mx - 2.0 * e) * (1.0f - 1e-6f);       // rounded down: never misses a candidate
         int mine = 0;
-        for (int c = lane; c < K / 4; c += kWave) {
-            const float4 v = us[c];
-            mine += ((double)fabsf(v.x) >= lim) + ((double)fabsf(v.y) >= lim) + ((double)fabsf(v.z) >= lim) + ((double)fabsf(v.w) >= lim);
+#pragma unroll
+        for (int i = 0; i < uiters; ++i) {
+            const int c = lane + kWave * i;
+            if (c < nuc) {
+                const float4 v = uchunk(RES ? i : 0, c);
+                mine += (fabsf(v.x) >= lim) + (fabsf(v.y) >= lim) + (fabsf(v.z) >= lim) + (fabsf(v.w) >= lim);
+            }
         }
         n = wave_sumi(mine);
         if (n > CAPC) {
@@ -291,20 +349,24 @@ __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_
             n = 0;
         } else {
             // at most CAPC hits in the row: the lanes that have one take their slots in lane order
-            // exclusive prefix of `mine` over the lanes
             int before = 0;
-            for (int l = 0; l < kWave; ++l) {
+            for (unsigned long long hits = __ballot(mine > 0); hits; hits &= hits - 1) {     // at most CAPC lanes
+                const int l = __ffsll((long long)hits) - 1;
                 const int m_l = __shfl(mine, l, kWave);
                 if (l < lane) before += m_l;
             }
             if (mine) {
                 int slot = before;
-                for (int c = lane; c < K / 4; c += kWave) {
-                    const float4 v = us[c];
-                    const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if ((double)fabsf(vv[i]) >= lim) cidx[(size_t)row * CAPC + slot++] = (uint16_t)(c * 4 + i);
+                for (int i = 0; i < uiters; ++i) {
+                    const int c = lane + kWave * i;
+                    if (c < nuc) {
+                        const float4 v = uchunk(RES ? i : 0, c);
+                        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int d = 0; d < 4; ++d)
+                            if (fabsf(vv[d]) >= lim) cidx[(size_t)row * CAPC + slot++] = (uint16_t)(c * 4 + d);
+                    }
                 }
             }
         }
@@ -318,41 +380,102 @@ __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_
 }
 
 // ---- the definition's chain for single elements: u = sum over ascending k of x[row, k] * R[k, col], one fused
-// multiply-add per term (the products are exact).  Rt holds R's columns contiguously, so both streams are read 128
-// bytes at a time per lane.
-__device__ __forceinline__ double exact_element(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt, int K, int row, int col) {
-    const uint4* xp = reinterpret_cast<const uint4*>(X + (size_t)row * K);
-    const uint4* rp = reinterpret_cast<const uint4*>(Rt + (size_t)col * K);
-    double u = 0.0;
-    for (int c = 0; c < K / 8; c += 8) {
-        uint4 xv[8], rv[8];
+// multiply-add per term (the products are exact).  Every lane of a wave owns one element, but the wave fetches the
+// operands together: in one load instruction eight neighbouring lanes read the eight 16-byte pieces of one element's
+// next 128 bytes (64 k) of its x row / R column (Rt holds R's columns contiguously), so every cache line is requested
+// once and used in full - a lane reading its own stream 16 bytes at a time asks for each line eight times over and the
+// chain then runs at a tenth of its arithmetic rate.  The pieces go through a wave-private LDS buffer (element rows
+// padded to 144 bytes: conflict-free 16-byte reads) to the lane that owns the element; the loads of the next 64 k are
+// in flight while the current ones are summed.
+constexpr int XE_ROW = 144, XE_BUF = 64 * XE_ROW;        // one operand's staging buffer of a wave (9216 bytes)
+
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+struct Pieces {
+    v4u x[8], r[8];
+};
+// (xp / rp are not __restrict__: see dense_rotate_bf16_kernel)
+__device__ __forceinline__ Pieces load_pieces(const unsigned char* const (&xp)[8], const unsigned char* const (&rp)[8], size_t off) {
+    Pieces p;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) { xv[i] = xp[c + i]; rv[i] = rp[c + i]; }
+    for (int q = 0; q < 8; ++q) {
+        p.x[q] = *reinterpret_cast<const v4u*>(xp[q] + off);
+        p.r[q] = *reinterpret_cast<const v4u*>(rp[q] + off);
+    }
+    return p;
+}
+
+// All 64 lanes must call this together (lanes without an element pass any valid row / col and ignore the result).
+// K % 64 == 0.  lds: this wave's 2 * XE_BUF bytes.
+__device__ __forceinline__ double exact_element_wave(const uint16_t* X, const uint16_t* Rt, int K, int row, int col,
+                                                     unsigned char* lds) {
+    const int lane = threadIdx.x % kWave;
+    const unsigned char* xp[8];
+    const unsigned char* rp[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = 8 * q + lane / 8;                 // the element whose piece (lane % 8) this lane fetches in load q
+        const int er = __shfl(row, e, kWave), ec = __shfl(col, e, kWave);
+        xp[q] = reinterpret_cast<const unsigned char*>(X + (size_t)er * K) + (lane % 8) * 16;
+        rp[q] = reinterpret_cast<const unsigned char*>(Rt + (size_t)ec * K) + (lane % 8) * 16;
+    }
+    unsigned char* xs = lds;
+    unsigned char* rs = lds + XE_BUF;
+    const int wr = (lane / 8) * XE_ROW + (lane % 8) * 16;        // + 8 q rows for load q
+    const int rd = lane * XE_ROW;
+    const int nb = K / 64;
+    double u = 0.0;
+    Pieces nxt = load_pieces(xp, rp, 0);
+    for (int b = 0; b < nb; ++b) {
+        // stage batch b (the previous batch was read into registers before this point)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            *reinterpret_cast<v4u*>(xs + wr + 8 * q * XE_ROW) = nxt.x[q];
+            *reinterpret_cast<v4u*>(rs + wr + 8 * q * XE_ROW) = nxt.r[q];
+        }
+        wave_lds_sync();
+        nxt = load_pieces(xp, rp, (size_t)(b + 1 < nb ? b + 1 : b) * 128);     // past the end: a harmless re-read
+        asm volatile("" ::: "memory");                   // keeps these loads ahead of the arithmetic below
+        __builtin_amdgcn_sched_barrier(0);
+        v4u xv[8], rv[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const unsigned xw[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
-            const unsigned rw[4] = {rv[i].x, rv[i].y, rv[i].z, rv[i].w};
+            xv[i] = *reinterpret_cast<const v4u*>(xs + rd + i * 16);
+            rv[i] = *reinterpret_cast<const v4u*>(rs + rd + i * 16);
+        }
+        wave_lds_sync();                                 // the reads are issued before the next batch is staged
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                u = fma((double)bf16_lo(xw[d]), (double)bf16_lo(rw[d]), u);
-                u = fma((double)bf16_hi(xw[d]), (double)bf16_hi(rw[d]), u);
+                u = fma((double)bf16_lo(xv[i][d]), (double)bf16_lo(rv[i][d]), u);
+                u = fma((double)bf16_hi(xv[i][d]), (double)bf16_hi(rv[i][d]), u);
             }
-        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     return u;
 }
 
 // amax candidates: thread i -> slot i / M of row i % M (slot 0 of every row first, so that the waves are full)
-__global__ __launch_bounds__(256) void dense_exact_amax_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt,
-                                                               int M, int K, const int* __restrict__ ccount,
-                                                               const uint16_t* __restrict__ cidx,
+__global__ __launch_bounds__(256) void dense_exact_amax_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K,
+                                                               const int* __restrict__ ccount, const uint16_t* __restrict__ cidx,
                                                                unsigned long long* __restrict__ amax_bits) {
+    __shared__ __attribute__((aligned(16))) unsigned char stage[4 * 2 * XE_BUF];
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long)M * CAPC) return;
-    const int slot = (int)(i / M), row = (int)(i % M);
-    if (slot >= ccount[row]) return;
-    const double u = exact_element(X, Rt, K, row, (int)cidx[(size_t)row * CAPC + slot]);
-    atomicMax(&amax_bits[row], (unsigned long long)__double_as_longlong(fabs(u)));
+    int row = 0, col = 0;
+    bool have = false;
+    if (i < (long)M * CAPC) {
+        const int slot = (int)(i / M);
+        row = (int)(i % M);
+        have = slot < ccount[row];
+        col = have ? (int)cidx[(size_t)row * CAPC + slot] : 0;
+    }
+    if (__ballot(have) == 0ull) return;                  // nothing in this wave
+    const double u = exact_element_wave(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
+    if (have) atomicMax(&amax_bits[row], (unsigned long long)__double_as_longlong(fabs(u)));
 }
 
 // ---- codes from u~ with the exact amax; the elements the bound leaves undecided go to the row's list (one wave per row)
@@ -410,47 +533,70 @@ __global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __re
     }
 }
 
-// ---- exclusive prefix sum of the per-row counts, offs[0 .. M] (one workgroup; M is at most a few 10^5)
+// ---- exclusive prefix sum of the per-row counts, offs[0 .. M] (one workgroup of 1024 threads; 16384 counts per pass
+// through LDS so that global reads and writes are coalesced)
 __global__ __launch_bounds__(1024) void dense_scan_counts_kernel(const int* __restrict__ cnt, int M, int* __restrict__ offs) {
+    __shared__ int buf[16384];
     __shared__ int part[1024];
-    const int t = threadIdx.x, per = (M + 1023) / 1024;
-    const int a = t * per, b = a + per < M ? a + per : M;
-    int s = 0;
-    for (int i = a; i < b; ++i) s += cnt[i];
-    part[t] = s;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        const int v = t >= o ? part[t - o] : 0;
+    const int t = threadIdx.x;
+    int carry = 0;
+    for (int base = 0; base < M; base += 16384) {
+        for (int i = t; i < 16384; i += 1024) buf[i] = base + i < M ? cnt[base + i] : 0;
         __syncthreads();
-        part[t] += v;
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += buf[t * 16 + i];
+        part[t] = s;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {
+            const int v = t >= o ? part[t - o] : 0;
+            __syncthreads();
+            part[t] += v;
+            __syncthreads();
+        }
+        int run = carry + part[t] - s;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int c = buf[t * 16 + i];
+            buf[t * 16 + i] = run;
+            run += c;
+        }
+        carry += part[1023];
+        __syncthreads();
+        for (int i = t; i < 16384; i += 1024)
+            if (base + i < M) offs[base + i] = buf[i];
         __syncthreads();
     }
-    int run = part[t] - s;
-    for (int i = a; i < b; ++i) {
-        offs[i] = run;
-        run += cnt[i];
-    }
-    if (t == 1023) offs[M] = part[1023];
+    if (t == 0) offs[M] = carry;
 }
 
 // ---- undecided elements: exact value, exact code.  Thread i takes list entry i (row found by bisection of offs).
-__global__ __launch_bounds__(256) void dense_exact_codes_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ Rt,
-                                                                int M, int K, double qmax, const int* __restrict__ offs,
-                                                                const uint16_t* __restrict__ fidx, int capf,
-                                                                const unsigned long long* __restrict__ amax_bits,
+__global__ __launch_bounds__(256) void dense_exact_codes_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K, double qmax,
+                                                                const int* __restrict__ offs, const uint16_t* __restrict__ fidx,
+                                                                int capf, const unsigned long long* __restrict__ amax_bits,
                                                                 int8_t* __restrict__ q) {
+    __shared__ __attribute__((aligned(16))) unsigned char stage[4 * 2 * XE_BUF];
     const int total = offs[M];
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
-        int lo = 0, hi = M;                     // largest row with offs[row] <= i
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) / 2;
-            if (offs[mid] <= i) lo = mid; else hi = mid;
+    const int lane = threadIdx.x % kWave;
+    for (int base = blockIdx.x * 256 + (threadIdx.x - lane); base < total; base += gridDim.x * 256) {     // wave-uniform
+        const int i = base + lane;
+        const bool have = i < total;
+        int row = 0, col = 0;
+        if (have) {
+            int lo = 0, hi = M;                         // largest row with offs[row] <= i
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) / 2;
+                if (offs[mid] <= i) lo = mid; else hi = mid;
+            }
+            row = lo;
+            col = (int)fidx[(size_t)row * capf + (i - offs[row])];
         }
-        const int row = lo, col = (int)fidx[(size_t)row * capf + (i - offs[row])];
-        const double u = exact_element(X, Rt, K, row, col);
-        const double amax = __longlong_as_double((long long)amax_bits[row]);
-        const double inv = amax > 0.0 ? qmax / amax : 0.0;
-        q[(size_t)row * K + col] = (int8_t)__double2loint(u * inv + kMagic);
+        const double u = exact_element_wave(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
+        if (have) {
+            const double amax = __longlong_as_double((long long)amax_bits[row]);
+            const double inv = amax > 0.0 ? qmax / amax : 0.0;
+            q[(size_t)row * K + col] = (int8_t)__double2loint(u * inv + kMagic);
+        }
     }
 }
 
@@ -516,9 +662,6 @@ bool dense_fast_applies(int M, int K, bool zero_point, bool prescale) {
     return !zero_point && !prescale && M > 64 && K % 128 == 0 && K <= 16384 && (size_t)M * K < ((size_t)1 << 31);
 }
 
-// run length of the fp32 accumulation between promotions to fp64
-constexpr int kChunk = 64;
-
 hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K, int act_bits,
                                           void* ws, int8_t* q, float* scale) {
     const DenseFastWs L = dense_fast_layout(M, K);
@@ -544,9 +687,13 @@ hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, con
     hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, Rt, K, static_cast<float*>(nullptr), scalars,
                        static_cast<unsigned*>(nullptr), 0);
     const int tiles_m = (M + DT_M - 1) / DT_M, tiles_n = K / DT_N;
-    hipLaunchKernelGGL((dense_rotate_bf16_kernel<kChunk>), dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, tiles_m, tiles_n);
-    hipLaunchKernelGGL(dense_row_candidates_kernel, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, M, K, rowmax, scalars, err_factor,
-                       eps, amax, ccount, cidx, mode);
+    hipLaunchKernelGGL(dense_rotate_bf16_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, tiles_m, tiles_n);
+    if (K <= 4096)
+        hipLaunchKernelGGL(dense_row_candidates_kernel<true>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, M, K, rowmax, scalars,
+                           err_factor, eps, amax, ccount, cidx, mode);
+    else
+        hipLaunchKernelGGL(dense_row_candidates_kernel<false>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, M, K, rowmax, scalars,
+                           err_factor, eps, amax, ccount, cidx, mode);
     hipLaunchKernelGGL(dense_exact_amax_kernel, dim3((unsigned)(((long)M * CAPC + 255) / 256)), dim3(256), 0, st, X, Rt, M, K,
                        ccount, cidx, amax);
     hipLaunchKernelGGL(dense_quant_flag_kernel, dim3((M + 3) / 4), dim3(256), 4 * sizeof(int), st, Ut, M, K, qmax, eps, amax, q,

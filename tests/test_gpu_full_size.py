@@ -175,20 +175,24 @@ def test_levels_path_at_full_size(lrq, cfg, layer):
 
 
 def test_dense_rotation_whose_last_round_of_tiles_is_sparse(lrq):
-    """2100 x 4096: 32 x 17 = 544 tiles of 128 x 128, 32 more than the 512 resident at a time, so the launch cuts the
-    last rows (2048 ...) into 64-row tiles; sampled rows from both regions, and the ragged last rows, bit for bit."""
+    """2100 x 4096: 32 x 17 = 544 tiles of 128 x 128, 32 more than the 512 resident at a time, so the fp64 evaluation
+    cuts the last rows (2048 ...) into 64-row tiles; sampled rows from both regions, and the ragged last rows, bit for
+    bit - codes, scales and the fp64 rotated activations; the default (matrix-core) evaluation gives the same codes."""
     import torch
     M, K = 2100, 4096
     X = synth.make_activations(M, K, (931, M, K), 0.05, 8, 40.0)
     R = synth.make_rotation(K, (931, K, 0))
-    rot = lrq.Rotation("dense", 0, bf16_to_dev(R))
-    ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, 8), dtype=torch.uint8, device="cuda")
-    q, sc = lrq.ars_rotate_quant(bf16_to_dev(X), rot, 8, workspace=ws)
-    torch.cuda.synchronize()
     rows = np.array(sorted(set(_sample(M, 24, (931,)).tolist()) | {2047, 2048, 2049, 2099, 2111 % M, 1, 127, 128}))
-    ridx = torch.from_numpy(rows).to(q.device)
     q_ref, s_ref = oracle.ars_rotate_quant(X[rows], 8, "dense", R_bits=R)
-    assert np.array_equal(q[ridx].cpu().numpy(), q_ref)
-    assert np.array_equal(sc[ridx].cpu().numpy(), s_ref)
-    u = ws[:M * K * 8].view(torch.float64).view(M, K)[ridx].cpu().numpy()
-    assert np.array_equal(u, oracle.rotate_dense(oracle.bf16_bits_to_f64(X[rows]), oracle.bf16_bits_to_f64(R)))
+    Rd, Xd = bf16_to_dev(R), bf16_to_dev(X)
+    for kind in ("dense_f64", "dense"):
+        rot = lrq.Rotation(kind, 0, Rd)
+        ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, 8), dtype=torch.uint8, device="cuda")
+        q, sc = lrq.ars_rotate_quant(Xd, rot, 8, workspace=ws)
+        torch.cuda.synchronize()
+        ridx = torch.from_numpy(rows).to(q.device)
+        assert np.array_equal(q[ridx].cpu().numpy(), q_ref), kind
+        assert np.array_equal(sc[ridx].cpu().numpy(), s_ref), kind
+        if kind == "dense_f64":
+            u = ws[:M * K * 8].view(torch.float64).view(M, K)[ridx].cpu().numpy()
+            assert np.array_equal(u, oracle.rotate_dense(oracle.bf16_bits_to_f64(X[rows]), oracle.bf16_bits_to_f64(R)))
