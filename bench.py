@@ -345,6 +345,21 @@ def main():
                            unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4), traffic=None,
                            avg_launch_ms=round(t / len(had), 4))
 
+    # outlier-aware dense rotation + quantizer (whole lrq_ars_rotate_quant call of the layers that take it): the bulk
+    # product runs on the bf16 matrix cores, algorithmic flops 2*M*K*K per launch
+    dense = [(li, l) for li, l in enumerate(layers) if l["spec"].rotation == "dense" and not isinstance(l["rot"].R, type(None))
+             and l["rot"].kind == "dense" and l["spec"].M > 64]
+    roofline_dense = None
+    if dense:
+        fl = sum(2.0 * l["spec"].M * l["spec"].K * l["spec"].K for _, l in dense)
+        t = sum(rot_ms[li] for li, _ in dense)
+        tf = fl / (t * 1e-3) / 1e12
+        roofline_dense = dict(bound="mfma", kernel="dense rotation + quantize (bf16 MFMA product, fp64 accumulation of 64-k runs, "
+                              "error bound, exact recomputation of undecided elements)", achieved=round(tf, 2),
+                              peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=round(tf / BF16_MFMA_PEAK_TFLOPS, 4), traffic=None,
+                              avg_launch_ms=round(t / len(dense), 4),
+                              note="time of the whole call (nine kernels), flops of the product alone")
+
     out = dict(metric="fused W-TLQ/A-ARS qlinear TOPS + % int8 MFMA peak; rotate+quant HBM GB/s",
                value=round(tops, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
@@ -362,7 +377,7 @@ def main():
                            value_map="levels round(2^r 2^I) 2^(f-I) as bf16 operands" if args.levels else "per-channel int8 level table",
                            step=("lrq_qlinear_levels per layer: rotate + quantize + TLQ decode + bf16 MFMA GEMM + rescale, bf16 out" if args.levels else
                                  "lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out")),
-               roofline=roofline, roofline_rotate_quant=roofline_rq, per_layer=per_layer,
+               roofline=roofline, roofline_rotate_quant=roofline_rq, roofline_dense_rotation=roofline_dense, per_layer=per_layer,
                offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
 
     if hot:
@@ -386,6 +401,8 @@ def main():
                 out["roofline"]["traffic"] = tr.get("qgemm")
             if out["roofline_rotate_quant"]:
                 out["roofline_rotate_quant"]["traffic"] = tr.get("rotate_quant")
+            if out["roofline_dense_rotation"] and not args.structured:
+                out["roofline_dense_rotation"]["traffic"] = tr.get("dense_rotation")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, args.cpu_rows, args.cpu_channels)
     print(json.dumps(out))
