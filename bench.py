@@ -114,6 +114,9 @@ def parse():
     ap.add_argument("--levels", action="store_true",
                     help="run the GEMM on the TLQ levels themselves (lrq_qlinear_levels: bf16 matrix cores, the paper's value "
                          "map without the int8 level table) - the fidelity-reference path, priced against the bf16 peak")
+    ap.add_argument("--packed4", action="store_true",
+                    help="layers with 4-bit activations keep their codes two per byte between rotate+quantize and the GEMM "
+                         "(lrq_qlinear_packed4)")
     ap.add_argument("--probes-only", action="store_true",
                     help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
@@ -207,6 +210,9 @@ def main():
             l["X"].append(l["X"][0].clone())
         l["Y"] = [torch.empty((s.M, s.N), dtype=torch.bfloat16, device=dev) for _ in range(copies)]
         nws = lrq.workspace_bytes(s.M, s.N, s.K, l["rot"], s.a_bits, asym=args.asym)
+        if args.packed4 and s.a_bits == 4:
+            import ctypes
+            nws = max(nws, lrq.lib().lrq_workspace_bytes_packed4(s.M, s.N, s.K, ctypes.byref(l["rot"].c_struct())))
         l["ws"] = [torch.empty(nws, dtype=torch.uint8, device=dev) for _ in range(copies)]
         l["q"] = [torch.empty((s.M, s.K), dtype=torch.int8, device=dev) for _ in range(copies)]
         l["sc"] = [torch.empty(s.M, dtype=torch.float32, device=dev) for _ in range(copies)]
@@ -214,11 +220,16 @@ def main():
         na = lrq.ars_workspace_bytes(s.M, s.K, l["rot"], s.a_bits)
         l["aws"] = torch.empty(na, dtype=torch.uint8, device=dev) if na else None
 
+    packed = args.packed4 and not (args.asym or args.levels)
+
     def step(i):
         c = i % copies
         for l in layers:
-            lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym,
-                        levels=args.levels)
+            if packed and l["spec"].a_bits == 4:
+                lrq.qlinear_packed4(l["X"][c], l["rot"], l["w"], out=l["Y"][c], workspace=l["ws"][c])
+            else:
+                lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym,
+                            levels=args.levels)
 
     if args.graph:
         eager_step = step
@@ -287,11 +298,17 @@ def main():
             s = l["spec"]
             a, b, d = (torch.cuda.Event(enable_timing=True) for _ in range(3))
             a.record()
-            lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"],
-                                 asym=args.asym, zero=l["zr"][c] if args.asym else None)
-            b.record()
-            lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c], zero=l["zr"][c] if args.asym else None,
-                      levels=args.levels)
+            if packed and s.a_bits == 4:
+                q4 = l["q"][c].view(torch.uint8).view(-1)[:s.M * s.K // 2].view(s.M, s.K // 2)
+                lrq.ars_rotate_quant_packed4(l["X"][c], l["rot"], q4=q4, scale=l["sc"][c], workspace=l["ws"][c])
+                b.record()
+                lrq.qgemm_packed4(q4, l["sc"][c], l["w"], out=l["Y"][c])
+            else:
+                lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"],
+                                     asym=args.asym, zero=l["zr"][c] if args.asym else None)
+                b.record()
+                lrq.qgemm(l["q"][c], l["sc"][c], l["w"], out=l["Y"][c], zero=l["zr"][c] if args.asym else None,
+                          levels=args.levels)
             d.record()
             ev.append((li, a, b, d))
     torch.cuda.synchronize()
@@ -372,7 +389,7 @@ def main():
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
                            outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
                            smoothing_prescale=bool(args.smooth), hip_graph=bool(args.graph),
-                           tlq_lower_clip=bool(args.lower_clip),
+                           tlq_lower_clip=bool(args.lower_clip), packed_4bit_activation_codes=bool(args.packed4),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            value_map="levels round(2^r 2^I) 2^(f-I) as bf16 operands" if args.levels else "per-channel int8 level table",
                            step=("lrq_qlinear_levels per layer: rotate + quantize + TLQ decode + bf16 MFMA GEMM + rescale, bf16 out" if args.levels else

@@ -292,6 +292,26 @@ int lrq_qlinear_asym(void* stream, const void* X, int M, int K, const lrq_rotati
                      const lrq_tlq_weight* w, const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes);
 
 /*
+ * Packed 4-bit activation codes (the W4A4 / W3A4 settings of the paper's tables; the paper leaves the storage of the
+ * codes open).  Same quantizer as lrq_ars_rotate_quant with act_bits = 4 - symmetric, codes in [-7, 7] - but two codes
+ * per byte, half the bytes between the two stages of the layer:
+ *   q4  uint8 [M, K/2]: every 8 consecutive codes of a token make 4 bytes; byte j of the group holds code[j] + 8 in its
+ *       low nibble and code[4 + j] + 8 in its high nibble (nibbles in 1 .. 15, "excess-8").
+ * lrq_qgemm_packed4 widens the nibbles to bytes on their way into LDS and removes the offset in the epilogue
+ * (acc - 8 * colsum_n), so its outputs equal lrq_qgemm's on the unpacked codes bit for bit.  Hadamard rotations (and no
+ * rotation) pack inside the rotate kernel; the other kinds quantize to int8 codes in the workspace and pack in a second
+ * pass.  Requires K % 16 == 0 (K % 64 == 0 for the GEMM); everything else as for the unpacked calls.
+ */
+size_t lrq_ars_workspace_bytes_packed4(int M, int K, const lrq_rotation* rot);
+int lrq_ars_rotate_quant_packed4(void* stream, const void* X, int M, int K, const lrq_rotation* rot, uint8_t* q4, float* scale,
+                                 void* ws, size_t ws_bytes);
+int lrq_qgemm_packed4(void* stream, const uint8_t* q4, const float* scale, int M, int K, const lrq_tlq_weight* w,
+                      const float* bias, int out_dtype, void* Y);
+size_t lrq_workspace_bytes_packed4(int M, int N, int K, const lrq_rotation* rot);
+int lrq_qlinear_packed4(void* stream, const void* X, int M, int K, const lrq_rotation* rot, const lrq_tlq_weight* w,
+                        const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes);
+
+/*
  * Calibration of the outlier-aware branch (paper: Method, "Adaptive Rotation Scheme": greedy rotations
  * R^i = E_c* R~ Q E_c*, R^ = prod_i R^i, built block-wise; staggered permutation P; second rotation).
  * Runs once per layer, off the inference path.

@@ -42,7 +42,7 @@ from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits  # noqa: F401
 from .rotation import (hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_dense, rotate_blockdiag,  # noqa: F401
                        rotate_blockperm, zigzag_permutation, greedy_block_rotation, build_outlier_rotation)
 from .calib import fluctuation_J, select_rotation, smoothing_factor, smooth_weights  # noqa: F401
-from .actquant import quantize_per_token, quantize_per_token_asym  # noqa: F401
+from .actquant import quantize_per_token, quantize_per_token_asym, pack_act_codes4, unpack_act_codes4  # noqa: F401
 from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
                   tlq_level_values, tlq_lut, pack_codes, unpack_codes)
 from .qlinear import (ars_rotate_quant, ars_rotate_quant_asym, qlinear, qlinear_from_parts,  # noqa: F401

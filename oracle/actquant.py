@@ -59,3 +59,24 @@ def quantize_per_token_asym(u: np.ndarray, a_bits: int, norm: float = 1.0):
     zero = (z + half).astype(np.int32)
     scale = (s / np.float64(norm)).astype(np.float32)
     return q, scale, zero
+
+
+def pack_act_codes4(q: np.ndarray) -> np.ndarray:
+    """Storage of 4-bit activation codes two per byte (the paper's W4A4 / W3A4 settings; it leaves the storage open,
+    this is the build's format): q int8 [M, K] with values in [-7, 7], K a multiple of 8 -> uint8 [M, K/2].
+    Every 8 consecutive codes of a token make 4 bytes; byte j of the group holds q[j] + 8 in its low nibble and
+    q[4 + j] + 8 in its high nibble."""
+    q = np.asarray(q)
+    M, K = q.shape
+    assert K % 8 == 0 and q.min(initial=0) >= -7 and q.max(initial=0) <= 7
+    g = q.astype(np.int64).reshape(M, K // 8, 8) + 8
+    return (g[:, :, :4] | (g[:, :, 4:] << 4)).astype(np.uint8).reshape(M, K // 2)
+
+
+def unpack_act_codes4(q4: np.ndarray) -> np.ndarray:
+    """Inverse of pack_act_codes4: uint8 [M, K/2] -> int8 [M, K]."""
+    q4 = np.asarray(q4, dtype=np.uint8)
+    M, H = q4.shape
+    g = q4.astype(np.int64).reshape(M, H // 4, 4)
+    out = np.concatenate([(g & 15) - 8, (g >> 4) - 8], axis=2)
+    return out.reshape(M, 2 * H).astype(np.int8)

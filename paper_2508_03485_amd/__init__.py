@@ -25,7 +25,8 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
            "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
-           "lrq_qlinear_levels", "lrq_ars_dense_diagnostics", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
+           "lrq_qlinear_levels", "lrq_ars_dense_diagnostics", "lrq_ars_workspace_bytes_packed4",
+           "lrq_ars_rotate_quant_packed4", "lrq_qgemm_packed4", "lrq_workspace_bytes_packed4", "lrq_qlinear_packed4", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
 
 
 class LrqError(RuntimeError):
@@ -78,6 +79,16 @@ def lib() -> ctypes.CDLL:
     L.lrq_ars_rotate_quant.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, vp, vp, vp, sz]
     L.lrq_ars_dense_diagnostics.restype = ci
     L.lrq_ars_dense_diagnostics.argtypes = [ci, ci, ctypes.POINTER(sz * 4)]
+    L.lrq_ars_workspace_bytes_packed4.restype = sz
+    L.lrq_ars_workspace_bytes_packed4.argtypes = [ci, ci, ctypes.POINTER(_Rotation)]
+    L.lrq_ars_rotate_quant_packed4.restype = ci
+    L.lrq_ars_rotate_quant_packed4.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), vp, vp, vp, sz]
+    L.lrq_qgemm_packed4.restype = ci
+    L.lrq_qgemm_packed4.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
+    L.lrq_workspace_bytes_packed4.restype = sz
+    L.lrq_workspace_bytes_packed4.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation)]
+    L.lrq_qlinear_packed4.restype = ci
+    L.lrq_qlinear_packed4.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ctypes.POINTER(_TlqWeight), vp, ci, vp, vp, sz]
     L.lrq_workspace_bytes.restype = sz
     L.lrq_workspace_bytes.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_qlinear.restype = ci
@@ -268,6 +279,56 @@ def ars_rotate_quant(X, rot: Rotation, act_bits: int, q=None, scale=None, worksp
                                     _ptr(workspace), nws)
     _check(st, "lrq_ars_rotate_quant")
     return q, scale
+
+
+def ars_rotate_quant_packed4(X, rot: Rotation, q4=None, scale=None, workspace=None):
+    """lrq_ars_rotate_quant_packed4: X bf16 [M, K] -> (q4 uint8 [M, K/2] packed 4-bit codes, scale fp32 [M])."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    if q4 is None:
+        q4 = torch.empty((M, K // 2), dtype=torch.uint8, device=X.device)
+    if scale is None:
+        scale = torch.empty(M, dtype=torch.float32, device=X.device)
+    r = rot.c_struct()
+    need = lib().lrq_ars_workspace_bytes_packed4(M, K, ctypes.byref(r))
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    st = lib().lrq_ars_rotate_quant_packed4(_stream(), _ptr(X), M, K, ctypes.byref(r), _ptr(q4), _ptr(scale), _ptr(workspace),
+                                            0 if workspace is None else workspace.numel())
+    _check(st, "lrq_ars_rotate_quant_packed4")
+    return q4, scale
+
+
+def qgemm_packed4(q4, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
+    """lrq_qgemm_packed4: the decode + GEMM + rescale stage on packed 4-bit activation codes [M, K/2]."""
+    import torch
+    assert q4.is_cuda and q4.dtype == torch.uint8 and q4.is_contiguous()
+    M, K = q4.shape[0], q4.shape[1] * 2
+    out_dtype = out_dtype or (out.dtype if out is not None else torch.bfloat16)
+    if out is None:
+        out = torch.empty((M, w.N), dtype=out_dtype, device=q4.device)
+    cs = w.c_struct()
+    st = lib().lrq_qgemm_packed4(_stream(), _ptr(q4), _ptr(scale), M, K, ctypes.byref(cs), _ptr(bias), _out_code(out_dtype), _ptr(out))
+    _check(st, "lrq_qgemm_packed4")
+    return out
+
+
+def qlinear_packed4(X, rot: Rotation, w: TLQWeight, bias=None, out_dtype=None, out=None, workspace=None):
+    """lrq_qlinear_packed4: the fused layer with 4-bit activation codes packed two per byte between its stages."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    out_dtype = out_dtype or (out.dtype if out is not None else torch.bfloat16)
+    if out is None:
+        out = torch.empty((M, w.N), dtype=out_dtype, device=X.device)
+    r, cs = rot.c_struct(), w.c_struct()
+    if workspace is None:
+        workspace = torch.empty(lib().lrq_workspace_bytes_packed4(M, w.N, K, ctypes.byref(r)), dtype=torch.uint8, device=X.device)
+    st = lib().lrq_qlinear_packed4(_stream(), _ptr(X), M, K, ctypes.byref(r), ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
+                                   _ptr(out), _ptr(workspace), workspace.numel())
+    _check(st, "lrq_qlinear_packed4")
+    return out
 
 
 def ars_dense_diagnostics(workspace, M: int, K: int):

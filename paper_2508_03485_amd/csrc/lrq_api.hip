@@ -347,6 +347,84 @@ int lrq_qlinear(void* stream, const void* X, int M, int K, const lrq_rotation* r
     return qlinear_impl(stream, X, M, K, rot, act_bits, w, bias, out_dtype, Y, ws, ws_bytes, Gemm::kInt8);
 }
 
+// ---- packed 4-bit activation codes -------------------------------------------------------------------------------
+static bool packs_in_kernel(const lrq_rotation* rot, int K) {
+    return !rot->prescale && ((rot->kind == LRQ_ROT_HADAMARD && lrq::hadamard_packs_in_kernel(K, rot->had_block)) ||
+                              (rot->kind == LRQ_ROT_NONE && lrq::hadamard_packs_in_kernel(K, 1)));
+}
+
+size_t lrq_ars_workspace_bytes_packed4(int M, int K, const lrq_rotation* rot) {
+    if (M <= 0 || K <= 0 || !rot) return 0;
+    // rotations whose kernels do not pack themselves quantize to int8 codes in the workspace first
+    return (packs_in_kernel(rot, K) ? 0 : round256((size_t)M * K)) + ars_layout(M, K, rot).total;
+}
+
+static int rotate_quant_packed4(hipStream_t st, const void* X, int M, int K, const lrq_rotation* rot, uint8_t* q4, float* scale,
+                                void* ws) {
+    if (packs_in_kernel(rot, K)) {
+        const int h = rot->kind == LRQ_ROT_HADAMARD ? rot->had_block : 1;
+        return lrq::launch_hadamard_quant(st, static_cast<const uint16_t*>(X), M, K, h, 4, reinterpret_cast<int8_t*>(q4), scale,
+                                          nullptr, nullptr, true) == hipSuccess ? LRQ_OK : LRQ_EHIP;
+    }
+    int8_t* q8 = static_cast<int8_t*>(ws);
+    const int st8 = run_rotate_quant(st, X, M, K, rot, 4, q8, scale, nullptr, static_cast<char*>(ws) + round256((size_t)M * K));
+    if (st8 != LRQ_OK) return st8;
+    return lrq::launch_pack_nibbles(st, q8, M, K, q4) == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_ars_rotate_quant_packed4(void* stream, const void* X, int M, int K, const lrq_rotation* rot, uint8_t* q4, float* scale,
+                                 void* ws, size_t ws_bytes) {
+    int st = check_act(X, M, K, rot, 4);
+    if (st != LRQ_OK) return st;
+    if (K % 16 != 0) return LRQ_EUNSUPPORTED;
+    if (!q4 || !scale || !aligned16(q4)) return LRQ_EINVAL;
+    const size_t need = lrq_ars_workspace_bytes_packed4(M, K, rot);
+    if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) return LRQ_EWORKSPACE;
+    return rotate_quant_packed4(static_cast<hipStream_t>(stream), X, M, K, rot, q4, scale, ws);
+}
+
+static int check_gemm_common(const lrq_tlq_weight* w, int K, int out_dtype) {
+    int st = check_weight(w);
+    if (st != LRQ_OK) return st;
+    if (w->K != K) return LRQ_EINVAL;
+    if (out_dtype != LRQ_OUT_BF16 && out_dtype != LRQ_OUT_FP32) return LRQ_EUNSUPPORTED;
+    return K % lrq::kGemmBlockK != 0 ? LRQ_EUNSUPPORTED : LRQ_OK;
+}
+
+int lrq_qgemm_packed4(void* stream, const uint8_t* q4, const float* scale, int M, int K, const lrq_tlq_weight* w,
+                      const float* bias, int out_dtype, void* Y) {
+    if (!q4 || !scale || !Y || M <= 0 || K <= 0 || !aligned16(q4) || !aligned16(Y)) return LRQ_EINVAL;
+    const int st = check_gemm_common(w, K, out_dtype);
+    if (st != LRQ_OK) return st;
+    return lrq::launch_qgemm(static_cast<hipStream_t>(stream), reinterpret_cast<const int8_t*>(q4), scale, nullptr, M, K, *w, bias,
+                             out_dtype, Y, true) == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+size_t lrq_workspace_bytes_packed4(int M, int N, int K, const lrq_rotation* rot) {
+    (void)N;
+    if (M <= 0 || K <= 0 || !rot) return 0;
+    return round256((size_t)M * K / 2) + round256((size_t)M * sizeof(float)) + lrq_ars_workspace_bytes_packed4(M, K, rot);
+}
+
+int lrq_qlinear_packed4(void* stream, const void* X, int M, int K, const lrq_rotation* rot, const lrq_tlq_weight* w,
+                        const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+    int st = check_act(X, M, K, rot, 4);
+    if (st != LRQ_OK) return st;
+    if (!Y || !aligned16(Y)) return LRQ_EINVAL;
+    st = check_gemm_common(w, K, out_dtype);
+    if (st != LRQ_OK) return st;
+    if (!ws || ws_bytes < lrq_workspace_bytes_packed4(M, w->N, K, rot) || !aligned16(ws)) return LRQ_EWORKSPACE;
+    char* base = static_cast<char*>(ws);
+    uint8_t* q4 = reinterpret_cast<uint8_t*>(base);
+    float* scale = reinterpret_cast<float*>(base + round256((size_t)M * K / 2));
+    void* rot_ws = base + round256((size_t)M * K / 2) + round256((size_t)M * sizeof(float));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = rotate_quant_packed4(s, X, M, K, rot, q4, scale, rot_ws);
+    if (st != LRQ_OK) return st;
+    return lrq::launch_qgemm(s, reinterpret_cast<const int8_t*>(q4), scale, nullptr, M, K, *w, bias, out_dtype, Y, true) == hipSuccess
+               ? LRQ_OK : LRQ_EHIP;
+}
+
 int lrq_init(void) {
     void* p = nullptr;
     return static_scratch(&p);

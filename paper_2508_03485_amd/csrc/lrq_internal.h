@@ -20,13 +20,19 @@ struct QuantSpec {
     double L, half, sqrt_h; // zero-point form: 2^a - 1, 2^(a-1), sqrt(h)
     int32_t* zero;          // zero-point form: output [M]
     const float* prescale;  // per-channel factor applied to x before the rotation ([K], nullptr = none)
+    int packed;             // 1: 4-bit codes are written two per byte (excess-8 nibbles, see lrq.h), row stride K / 2
 };
 
 // u = x.(I (x) H_h) in fp64, per-token statistics, round to codes.  K % 8 == 0, h | K, h power of two.
 // zero == nullptr selects the symmetric quantizer, otherwise the zero-point form (zero receives z + 2^(a-1)).
 // prescale (every launcher): nullptr, or fp32 [K] multiplied into x channel-wise before the rotation.
+// packed (symmetric 4-bit codes only): q receives the packed nibbles ([M, K/2] bytes); only the shapes for which
+// hadamard_packs_in_kernel is true may be launched that way.
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale, int32_t* zero, const float* prescale);
+                                 int8_t* q, float* scale, int32_t* zero, const float* prescale, bool packed = false);
+bool hadamard_packs_in_kernel(int K, int h);
+// q int8 [M, K] (codes in [-7, 7]) -> packed nibbles [M, K/2]
+hipError_t launch_pack_nibbles(hipStream_t st, const int8_t* q, int M, int K, uint8_t* q4);
 // u = x (no rotation), same quantizer.
 hipError_t launch_plain_quant(hipStream_t st, const uint16_t* X, int M, int K, int act_bits,
                               int8_t* q, float* scale, int32_t* zero, const float* prescale);
@@ -70,8 +76,9 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
                                     float* gamma_neg);
 
 // zero == nullptr: symmetric codes; otherwise the epilogue adds zero_t * colsum_n to the integer sum.
+// packed4: q holds packed 4-bit activation codes ([M, K/2] bytes, excess-8 nibbles); zero must then be nullptr.
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
-                        const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y);
+                        const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y, bool packed4 = false);
 
 // Y = scale_t * sum_k q * levels (+ bias) on the bf16 matrix cores; w.levels must be set.
 hipError_t launch_qgemm_levels(hipStream_t st, const int8_t* q, const float* scale, int M, int K, const lrq_tlq_weight& w,

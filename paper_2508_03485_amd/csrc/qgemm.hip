@@ -89,20 +89,42 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // bCur holds B block kb (its MFMA step 0 already decoded in bd0; reloaded with block kb+2 once step 1 is decoded),
 // bNxt holds block kb+1 whose step 0 is decoded into bd0 while step 1 multiplies.
 // Decode work is spread evenly between the MFMAs so that it issues in their shadow.
-template <int BITS, int MT, int NTW, int ALOADS>
+// Packed 4-bit activation codes (A4P): a 16-byte chunk holds 32 codes, eight per dword, byte j of a dword = code[j] + 8 in
+// the low nibble and code[4 + j] + 8 in the high nibble.  It is widened on its way into LDS to two 16-byte chunks of
+// bytes in [1, 15]; the constant offset 8 leaves through the epilogue as a zero-point of -8 (times the channel's level sum).
+template <bool A4P>
+__device__ __forceinline__ void stage_a(unsigned char* dst, v4i a) {
+    if constexpr (!A4P) {
+        *reinterpret_cast<v4i*>(dst) = a;
+    } else {
+        v4i lo, hi;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const unsigned w = (unsigned)a[d];
+            const unsigned l = w & 0x0f0f0f0fu, h = (w >> 4) & 0x0f0f0f0fu;
+            if (d < 2) { lo[2 * d] = (int)l; lo[2 * d + 1] = (int)h; }
+            else { hi[2 * (d - 2)] = (int)l; hi[2 * (d - 2) + 1] = (int)h; }
+        }
+        *reinterpret_cast<v4i*>(dst) = lo;
+        *reinterpret_cast<v4i*>(dst + PLANE) = hi;
+    }
+}
+
+template <int BITS, int MT, int NTW, int ALOADS, bool A4P>
 __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int nx, v4i (&aS)[ALOADS],
                                        BRaw<BITS> (&bCur)[NTW], const BRaw<BITS> (&bNxt)[NTW], int kb, int KB,
                                        const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
                                        const uint8_t* const (&bptr)[NTW], const unsigned (&L)[NTW][4], unsigned C,
                                        v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off, v4i (&afp)[AF_DIST]) {
     constexpr int UNIT = 64 * 16;
+    constexpr int ABK = A4P ? BK / 2 : BK;          // bytes of a token row per K block
     const unsigned char* Acur = smem + cur;
 #pragma unroll
-    for (int i = 0; i < ALOADS; ++i) *reinterpret_cast<v4i*>(&smem[st + aoff[i]]) = aS[i];
+    for (int i = 0; i < ALOADS; ++i) stage_a<A4P>(&smem[st + aoff[i]], aS[i]);
     const int ka = kb + 4 < KB ? kb + 4 : KB - 1;
     const int kbn = kb + 2 < KB ? kb + 2 : KB - 1;
 #pragma unroll
-    for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * BK);
+    for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * ABK);
     v4i af[2 * MT], bd1[NTW];
     constexpr int DPB = (NTW * 4 + MT - 1) / MT;       // operand dwords decoded per MFMA row tile
     constexpr int DIST = AF_DIST;                   // A fragments are read this many MFMA groups ahead
@@ -151,16 +173,19 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
 // (launch_qgemm picks): 128 x 256 (NTW = 2, 128 accumulator registers per lane, two workgroups per CU), 128 x 128
 // (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens (a 256 x 128 shape - half the decode
 // work per MFMA, twice the LDS reads per MFMA - measured slower on every workload).  ZP: zero-point form (epilogue term).
-template <int BITS, int BM, int NTW, bool ZP>
+template <int BITS, int BM, int NTW, bool ZP, bool A4P = false>
 __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,
     const uint8_t* __restrict__ gcodes, const int8_t* __restrict__ lut, const float* __restrict__ wscale,
     const float* __restrict__ bias, int out_fp32, void* __restrict__ Y, int tiles_m, int tiles_n,
-    const int32_t* __restrict__ zero, const int32_t* __restrict__ colsum) {
+    const int32_t* __restrict__ zero, const int32_t* __restrict__ colsum, int const_zero) {
+    static_assert(!A4P || ZP, "the packed form needs the zero-point term of the epilogue");
     constexpr int MT = BM / 32;
     constexpr int WN = 32 * NTW, BN = WAVES * WN;
     constexpr int ABUF = MT * 4 * PLANE;
-    constexpr int ALOADS = BM * 4 / 256;        // 16-byte chunks of the A tile per thread
+    constexpr int ACHUNKS = A4P ? BM * 2 : BM * 4;                 // 16-byte chunks of the A tile in global memory
+    constexpr int ALOADS = ACHUNKS >= 256 ? ACHUNKS / 256 : 1;      // per thread (fewer chunks than threads: some are fetched twice)
+    constexpr int ABK = A4P ? BK / 2 : BK;
     constexpr int LDS_BYTES = (3 * ABUF > WAVES * EPI_WAVE) ? 3 * ABUF : WAVES * EPI_WAVE;
     __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
     __shared__ __attribute__((aligned(16))) float sc[BM];
@@ -212,16 +237,17 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     int aoff[ALOADS];
 #pragma unroll
     for (int i = 0; i < ALOADS; ++i) {
-        const int cid = t + 256 * i, row = cid / 4, c = cid % 4;
+        const int cid = (t + 256 * i) % ACHUNKS;
+        const int row = A4P ? cid / 2 : cid / 4, c = A4P ? 2 * (cid % 2) : cid % 4;      // c: first 16-byte chunk in LDS
         int gr = m0 + row;
         if (gr >= M) gr = M - 1;
-        aptr[i] = q + (size_t)gr * K + c * 16;
+        aptr[i] = A4P ? q + (size_t)gr * (K / 2) + (c / 2) * 16 : q + (size_t)gr * K + c * 16;
         aoff[i] = ((row / 32) * 4 + c) * PLANE + (row % 32) * 16;
     }
     if (t < BM) {
         const int r = m0 + t;
         sc[t] = r < M ? scale[r] : 0.0f;
-        zr[t] = (ZP && r < M) ? zero[r] : 0;
+        zr[t] = (ZP && r < M) ? (zero ? zero[r] : const_zero) : 0;
     }
 
     v16i acc[MT][NTW];
@@ -244,22 +270,22 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
             a0[i] = *reinterpret_cast<const v4i*>(aptr[i]);
-            a1[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k1 * BK);
+            a1[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k1 * ABK);
         }
         // same issue order as the steady state of the K loop (A set, B block, A set, B block), so that the wait
         // counters the compiler derives at the loop head are the loop's own and not a conservative merge
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * BK);
+        for (int i = 0; i < ALOADS; ++i) aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * ABK);
 #pragma unroll
         for (int j = 0; j < NTW; ++j) bE[j] = load_braw<BITS>(bptr[j]);
 #pragma unroll
-        for (int i = 0; i < ALOADS; ++i) aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k3 * BK);
+        for (int i = 0; i < ALOADS; ++i) aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k3 * ABK);
 #pragma unroll
         for (int j = 0; j < NTW; ++j) bO[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
-            *reinterpret_cast<v4i*>(&smem[aoff[i]]) = a0[i];
-            *reinterpret_cast<v4i*>(&smem[ABUF + aoff[i]]) = a1[i];
+            stage_a<A4P>(&smem[aoff[i]], a0[i]);
+            stage_a<A4P>(&smem[ABUF + aoff[i]], a1[i]);
         }
 #pragma unroll
         for (int j = 0; j < NTW; ++j)
@@ -279,15 +305,15 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     // two K blocks per trip with no branch in between: with a conditional second block the compiler has to assume the
     // shorter path at the loop head and drains the whole load queue there (s_waitcnt vmcnt(0)) on every trip
     for (; kb + 1 < KB; kb += 2) {
-        kblock<BITS, MT, NTW, ALOADS>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
-        kblock<BITS, MT, NTW, ALOADS>(smem, o1, o0, o2, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        kblock<BITS, MT, NTW, ALOADS, A4P>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        kblock<BITS, MT, NTW, ALOADS, A4P>(smem, o1, o0, o2, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
         const int t0 = o0;      // two blocks done: tiles kb+2, kb+3, kb+4 live in o2, o0, o1
         o0 = o2;
         o2 = o1;
         o1 = t0;
     }
     if (kb < KB)                // odd number of K blocks
-        kblock<BITS, MT, NTW, ALOADS>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        kblock<BITS, MT, NTW, ALOADS, A4P>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
 
     // ---- epilogue: rescale in fp32.  Lane holds column (lane % 32) and rows 8 g + 4 (lane / 32) + (0..3), g = 0..3, of
     // every 32 x 32 accumulator tile (four consecutive rows per group of four accumulator registers).
@@ -401,37 +427,42 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 
 template <int BITS, int BM, int NTW>
 hipError_t launch(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
-                  const lrq_tlq_weight& w, const float* bias, int fp32, void* Y) {
+                  const lrq_tlq_weight& w, const float* bias, int fp32, void* Y, bool packed4) {
     constexpr int BN = WAVES * 32 * NTW;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (w.N + BN - 1) / BN;
-    if (zero)
+    if (packed4)
+        hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW, true, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
+                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, static_cast<const int32_t*>(nullptr),
+                           w.colsum, -8);
+    else if (zero)
         hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW, true>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
-                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
+                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum, 0);
     else
         hipLaunchKernelGGL((qgemm_kernel<BITS, BM, NTW, false>), dim3(tiles_m * tiles_n), dim3(256), 0, st, q, scale, M, K, w.N,
-                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum);
+                           w.gemm_codes, w.lut, w.wscale, bias, fp32, Y, tiles_m, tiles_n, zero, w.colsum, 0);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_qgemm(hipStream_t st, const int8_t* q, const float* scale, const int32_t* zero, int M, int K,
-                        const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y) {
+                        const lrq_tlq_weight& w, const float* bias, int out_dtype, void* Y, bool packed4) {
+    if (packed4 && zero) return hipErrorInvalidValue;
     const int fp32 = out_dtype == LRQ_OUT_FP32;
     // Tile shape.  128 x 256 (two workgroups per CU) is the fastest on long K loops; 128 x 128 (three per CU)
     // hides the prologue / epilogue of short K loops better and wastes less on N that is not a multiple of 256;
     // 64 x 128 serves inputs of a few tokens (conditioning vectors), where taller tiles multiply padding.
     const bool narrow = K <= 2048 || (w.N % 256 != 0 && w.N <= 2048);
     if (M <= 64) {
-        if (w.bits == 4) return launch<4, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
-        return launch<3, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+        if (w.bits == 4) return launch<4, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y, packed4);
+        return launch<3, 64, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y, packed4);
     }
     if (narrow) {
-        if (w.bits == 4) return launch<4, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
-        return launch<3, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+        if (w.bits == 4) return launch<4, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y, packed4);
+        return launch<3, 128, 1>(st, q, scale, zero, M, K, w, bias, fp32, Y, packed4);
     }
-    if (w.bits == 4) return launch<4, 128, 2>(st, q, scale, zero, M, K, w, bias, fp32, Y);
-    return launch<3, 128, 2>(st, q, scale, zero, M, K, w, bias, fp32, Y);
+    if (w.bits == 4) return launch<4, 128, 2>(st, q, scale, zero, M, K, w, bias, fp32, Y, packed4);
+    return launch<3, 128, 2>(st, q, scale, zero, M, K, w, bias, fp32, Y, packed4);
 }
 
 }  // namespace lrq

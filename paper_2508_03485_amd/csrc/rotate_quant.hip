@@ -133,6 +133,12 @@ __device__ __forceinline__ unsigned pack4(const double* v, const RowQ& p, double
     return (hi << 16) | lo;
 }
 
+// Packed 4-bit codes: eight codes q[0..7] in [-7, 7] make one dword; byte j holds q[j] + 8 in its low nibble and
+// q[4 + j] + 8 in its high nibble.  lo4 / hi4: the int8 codes q[0..3] / q[4..7], one per byte.
+__device__ __forceinline__ unsigned pack_nibbles8(unsigned lo4, unsigned hi4) {
+    return ((lo4 ^ 0x08080808u) & 0x0f0f0f0fu) | (((hi4 ^ 0x08080808u) & 0x0f0f0f0fu) << 4);
+}
+
 template <bool ASYM>
 __device__ __forceinline__ void store8_codes(int8_t* __restrict__ dst, const double v[8], const RowQ& p, double half) {
     *reinterpret_cast<uint2*>(dst) = make_uint2(pack4<ASYM>(v, p, half), pack4<ASYM>(v + 4, p, half));
@@ -290,9 +296,15 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
     unsigned out[8];
 #pragma unroll
     for (int g = 0; g < 8; ++g) out[g] = pack4<ASYM>(v + 4 * g, p, qs.half);
-    uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
-    dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
-    dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
+    if (!ASYM && qs.packed) {
+        *reinterpret_cast<uint4*>(q + (size_t)row * (K / 2) + (size_t)slot * (E32 / 2)) =
+            make_uint4(pack_nibbles8(out[0], out[1]), pack_nibbles8(out[2], out[3]), pack_nibbles8(out[4], out[5]),
+                       pack_nibbles8(out[6], out[7]));
+    } else {
+        uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
+        dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
+        dst[1] = make_uint4(out[4], out[5], out[6], out[7]);
+    }
     if (slot == 0) {
         scale[row] = p.scale;
         if constexpr (ASYM) qs.zero[row] = p.izero;
@@ -464,9 +476,15 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
         __syncthreads();
         if (live) {
             const uint4* src = reinterpret_cast<const uint4*>(cbuf + j * 32 + (j >> 5) * 16);
-            uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
-            dst[0] = src[0];
-            dst[1] = src[1];
+            if (!ASYM && qs.packed) {
+                const uint4 a = src[0], c = src[1];
+                *reinterpret_cast<uint4*>(q + (size_t)row * (K / 2) + (size_t)slot * (E32 / 2)) =
+                    make_uint4(pack_nibbles8(a.x, a.y), pack_nibbles8(a.z, a.w), pack_nibbles8(c.x, c.y), pack_nibbles8(c.z, c.w));
+            } else {
+                uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
+                dst[0] = src[0];
+                dst[1] = src[1];
+            }
             if (slot == 0) {
                 scale[row] = p.scale;
                 if constexpr (ASYM) qs.zero[row] = p.izero;
@@ -873,6 +891,14 @@ __global__ void quant_from_f64_once_kernel(const double* __restrict__ U, int K, 
     }
 }
 
+// int8 codes [M, K] -> packed nibbles [M, K / 2], 16 codes per thread (K % 16 == 0)
+__global__ __launch_bounds__(256) void pack_nibbles_kernel(const int8_t* __restrict__ q, size_t n16, uint8_t* __restrict__ q4) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n16) return;
+    const uint4 v = reinterpret_cast<const uint4*>(q)[i];
+    reinterpret_cast<uint2*>(q4)[i] = make_uint2(pack_nibbles8(v.x, v.y), pack_nibbles8(v.z, v.w));
+}
+
 int ilog2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -889,6 +915,16 @@ int threads_for_row(int K) {
 
 static void launch_quant_from_f64(hipStream_t st, const double* U, int M, int K, const QuantSpec& qs, int8_t* q, float* scale);
 
+static bool e32_shape(int K, int h) { return h <= 128 && K % 128 == 0 && K / E32 <= 576; }
+static bool twopass_shape(int K, int h) { return h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512; }
+bool hadamard_packs_in_kernel(int K, int h) { return e32_shape(K, h) || twopass_shape(K, h); }
+
+hipError_t launch_pack_nibbles(hipStream_t st, const int8_t* q, int M, int K, uint8_t* q4) {
+    const size_t n16 = (size_t)M * K / 16;
+    hipLaunchKernelGGL(pack_nibbles_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, q, n16, q4);
+    return hipGetLastError();
+}
+
 static QuantSpec make_spec(int act_bits, int h, int32_t* zero, const float* prescale = nullptr) {
     QuantSpec qs;
     qs.asym = zero != nullptr;
@@ -899,6 +935,7 @@ static QuantSpec make_spec(int act_bits, int h, int32_t* zero, const float* pres
     qs.half = (double)(1 << (act_bits - 1));
     qs.zero = zero;
     qs.prescale = prescale;
+    qs.packed = 0;
     return qs;
 }
 
@@ -908,9 +945,13 @@ static void launch_quant_from_f64(hipStream_t st, const double* U, int M, int K,
 }
 
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale, int32_t* zero, const float* prescale) {
-    const QuantSpec qs = make_spec(act_bits, h, zero, prescale);
-    if (h <= 128 && K % 128 == 0 && K / E32 <= 576) {
+                                 int8_t* q, float* scale, int32_t* zero, const float* prescale, bool packed) {
+    QuantSpec qs = make_spec(act_bits, h, zero, prescale);
+    if (packed) {
+        if (zero || act_bits != 4 || !hadamard_packs_in_kernel(K, h)) return hipErrorInvalidValue;
+        qs.packed = 1;
+    }
+    if (e32_shape(K, h)) {
         // R whole rows per workgroup, at most four waves (finer granularity measured faster than nine; 7 rows of 1152 fill four waves)
         const int lpr = K / E32;
         int R = 256 / lpr;
@@ -927,7 +968,7 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
 #undef LRQ_CASE
         return hipGetLastError();
     }
-    if (h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512) {
+    if (twopass_shape(K, h)) {
         const int lpr = K / E32;
         int R = 256 / lpr;                       // about four waves per workgroup; whole rows only
         if (R < 1) R = 1;

@@ -87,3 +87,19 @@ def test_rotate_then_quantize_one_hot_closed_form():
     q, s = oracle.ars_rotate_quant(synth.f32_to_bf16_bits(x), 8, "hadamard", h)
     assert np.array_equal(q[0], (127 * oracle.hadamard_matrix(h)[c]).astype(np.int8))
     assert s[0] == np.float32(244.0 / (127.0 * np.sqrt(128.0)))
+
+
+def test_packed_4bit_codes_hand_example_and_round_trip():
+    # codes -7 .. 0 -> nibbles 1 .. 8; byte j = nibble[j] | nibble[4 + j] << 4
+    q = np.array([[-7, -6, -5, -4, -3, -2, -1, 0, 7, 0, 1, -1, 2, 3, 4, 5]], dtype=np.int8)
+    want = np.array([[0x51, 0x62, 0x73, 0x84, 0xAF, 0xB8, 0xC9, 0xD7]], dtype=np.uint8)
+    got = oracle.pack_act_codes4(q)
+    assert got.dtype == np.uint8 and np.array_equal(got, want)
+    assert np.array_equal(oracle.unpack_act_codes4(want), q)
+    rng = np.random.default_rng(5)
+    q = rng.integers(-7, 8, size=(9, 64)).astype(np.int8)
+    p = oracle.pack_act_codes4(q)
+    assert p.shape == (9, 32) and np.array_equal(oracle.unpack_act_codes4(p), q)
+    assert ((p & 15) >= 1).all() and ((p >> 4) >= 1).all()           # nibble 0 (code -8) never occurs
+    with pytest.raises(AssertionError):
+        oracle.pack_act_codes4(np.full((1, 8), -8, dtype=np.int8))     # outside the symmetric 4-bit range
