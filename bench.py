@@ -117,6 +117,9 @@ def parse():
     ap.add_argument("--packed4", action="store_true",
                     help="layers with 4-bit activations keep their codes two per byte between rotate+quantize and the GEMM "
                          "(lrq_qlinear_packed4)")
+    ap.add_argument("--fp8", action="store_true",
+                    help="layers with 4-bit activations run with FP8 E4M3 operands on both sides (lrq_qlinear_fp8: levels with "
+                         "three mantissa bits, v_mfma_f32_32x32x64_f8f6f4)")
     ap.add_argument("--probes-only", action="store_true",
                     help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
@@ -220,13 +223,16 @@ def main():
         na = lrq.ars_workspace_bytes(s.M, s.K, l["rot"], s.a_bits)
         l["aws"] = torch.empty(na, dtype=torch.uint8, device=dev) if na else None
 
-    packed = args.packed4 and not (args.asym or args.levels)
+    packed = args.packed4 and not (args.asym or args.levels or args.fp8)
+    fp8 = args.fp8 and not (args.asym or args.levels)
 
     def step(i):
         c = i % copies
         for l in layers:
             if packed and l["spec"].a_bits == 4:
                 lrq.qlinear_packed4(l["X"][c], l["rot"], l["w"], out=l["Y"][c], workspace=l["ws"][c])
+            elif fp8 and l["spec"].a_bits == 4:
+                lrq.qlinear_fp8(l["X"][c], l["rot"], l["w"], out=l["Y"][c], workspace=l["ws"][c])
             else:
                 lrq.qlinear(l["X"][c], l["rot"], l["spec"].a_bits, l["w"], out=l["Y"][c], workspace=l["ws"][c], asym=args.asym,
                             levels=args.levels)
@@ -303,6 +309,11 @@ def main():
                 lrq.ars_rotate_quant_packed4(l["X"][c], l["rot"], q4=q4, scale=l["sc"][c], workspace=l["ws"][c])
                 b.record()
                 lrq.qgemm_packed4(q4, l["sc"][c], l["w"], out=l["Y"][c])
+            elif fp8 and s.a_bits == 4:
+                q8 = l["q"][c].view(torch.uint8)
+                lrq.ars_rotate_quant_fp8(l["X"][c], l["rot"], q8=q8, scale=l["sc"][c], workspace=l["aws"])
+                b.record()
+                lrq.qgemm_fp8(q8, l["sc"][c], l["w"], out=l["Y"][c])
             else:
                 lrq.ars_rotate_quant(l["X"][c], l["rot"], s.a_bits, q=l["q"][c], scale=l["sc"][c], workspace=l["aws"],
                                      asym=args.asym, zero=l["zr"][c] if args.asym else None)
@@ -344,7 +355,7 @@ def main():
     # dominant kernel: the decode + MFMA GEMM.  Algorithmic ops per launch = 2*M*N*K.
     gemm_total_ms = sum(gemm_ms)
     gemm_tops = total_ops / (gemm_total_ms * 1e-3) / 1e12
-    mfma_peak = BF16_MFMA_PEAK_TFLOPS if args.levels else INT8_MFMA_PEAK_TOPS
+    mfma_peak = BF16_MFMA_PEAK_TFLOPS if args.levels else INT8_MFMA_PEAK_TOPS      # the FP8 peak equals the int8 one (5.0 PFLOP/s)
     roofline = dict(bound="mfma", kernel=("qgemm_levels_kernel (decode + bf16 MFMA + rescale)" if args.levels else
                                           "qgemm_kernel (decode + int8 MFMA + rescale)"), achieved=round(gemm_tops, 2),
                     peak=mfma_peak, unit="TFLOP/s", frac=round(gemm_tops / mfma_peak, 4),
@@ -380,7 +391,7 @@ def main():
     out = dict(metric="fused W-TLQ/A-ARS qlinear TOPS + % int8 MFMA peak; rotate+quant HBM GB/s",
                value=round(tops, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
-               dtype="bf16" if args.levels else "int8", data="synthetic",
+               dtype="bf16" if args.levels else ("fp8" if args.fp8 else "int8"), data="synthetic",
                config=dict(workload={1: "config1: single 256x1152->1152 W4A8 Hadamard",
                                      2: "config2: PixArt-style block linears, 8192 tokens, hidden 1152, W4A8, Hadamard",
                                      3: "config3: FLUX-style block linears, 4608 tokens, hidden 3072, W4A4, Hadamard",
@@ -390,6 +401,7 @@ def main():
                            outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
                            smoothing_prescale=bool(args.smooth), hip_graph=bool(args.graph),
                            tlq_lower_clip=bool(args.lower_clip), packed_4bit_activation_codes=bool(args.packed4),
+                           fp8_operands=bool(args.fp8),
                            activation_quantizer="zero-point (Eq. 1)" if args.asym else "symmetric absmax",
                            value_map="levels round(2^r 2^I) 2^(f-I) as bf16 operands" if args.levels else "per-channel int8 level table",
                            step=("lrq_qlinear_levels per layer: rotate + quantize + TLQ decode + bf16 MFMA GEMM + rescale, bf16 out" if args.levels else

@@ -107,6 +107,12 @@ typedef struct {
  *   levels     bf16 [N, 16] or NULL (then not written, and the *_levels calls refuse the struct):
  *              levels[n][c & (2^bits-1)] is the level +-round(2^r 2^I) 2^(f-I) itself, rounded to nearest-even
  *              bf16 - exact for 0 <= I <= 7, where a level has at most 8 significant bits.
+ *   lut_fp8    uint8 [N, 16] or NULL, wscale_fp8 float [N] or NULL (then not written, and the *_fp8 calls refuse the
+ *              struct): the levels with I = 3 mantissa bits, +-round(2^r 2^3) 2^(f-3) - four significant bits, an FP8
+ *              E4M3 number's worth ("Hardware Implementation": I is a free parameter of the integerisation) - divided
+ *              by the power of two wscale_fp8[n] = 2^(floor(log2 max_c |level|) - 7) and rounded to E4M3 (nearest
+ *              even; exact for levels within 2^13 of the largest, subnormal spacing 2^-9 below, zero below 2^-10).
+ *              lut_fp8[n][c & (2^bits-1)] is the E4M3 bit pattern, operand of the FP8 matrix instruction.
  *   err_pos/err_neg double [N] or NULL (then not written): the value of the search objective sum (W_f - W)^2 of each
  *              twin at the chosen clip factors (+inf for a twin without a valid candidate).  The sum runs in a fixed
  *              order - 256 interleaved partial sums over ascending k, then the partial sums in ascending order.
@@ -127,6 +133,8 @@ typedef struct {
     uint8_t* gemm_codes;
     int32_t* colsum;     /* int32 [N]: sum_k lut[n][code[n,k]], the weight of an activation zero-point */
     uint16_t* levels;    /* bf16 [N,16] or NULL: the levels themselves, operands of the *_levels calls  */
+    uint8_t* lut_fp8;    /* uint8 [N,16] or NULL: E4M3 bit patterns of the I = 3 levels / wscale_fp8            */
+    float* wscale_fp8;   /* float [N] or NULL: the power-of-two scale of lut_fp8                                 */
     double* err_pos;     /* double [N] or NULL: search objective of the positive twin at its chosen factors */
     double* err_neg;     /* double [N] or NULL: the same for the negative twin                              */
 } lrq_tlq_weight;
@@ -310,6 +318,25 @@ int lrq_qgemm_packed4(void* stream, const uint8_t* q4, const float* scale, int M
 size_t lrq_workspace_bytes_packed4(int M, int N, int K, const lrq_rotation* rot);
 int lrq_qlinear_packed4(void* stream, const void* X, int M, int K, const lrq_rotation* rot, const lrq_tlq_weight* w,
                         const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes);
+
+/*
+ * The layer with FP8 E4M3 operands on both sides (v_mfma_f32_32x32x64_f8f6f4; the alternative value map of
+ * "Hardware Implementation" with I = 3: no int8 table, the levels keep their own four bits).  Only for 4-bit activation
+ * codes: an integer in [-7, 7] is an E4M3 value, a 6- or 8-bit code is not.
+ *   lrq_ars_rotate_quant_fp8  as lrq_ars_rotate_quant with act_bits = 4, but q8 uint8 [M, K] receives the codes as E4M3
+ *                             bit patterns (same scale).  Workspace: lrq_ars_workspace_bytes(M, K, rot, 4).
+ *   lrq_qgemm_fp8             Y[t,n] = scale_t * wscale_fp8_n * sum_k q[t,k] * value(lut_fp8_n[code[n,k]])  (+ bias_n).
+ *                             Every product is exact in fp32; the fp32 accumulation of the matrix instruction rounds
+ *                             (order unspecified), so outputs carry a relative error of about sqrt(K) 2^-24.
+ *   lrq_qlinear_fp8           both stages; workspace lrq_workspace_bytes(M, N, K, rot, 4).
+ * Requires w->lut_fp8 and w->wscale_fp8 (LRQ_EINVAL otherwise), K % 64 == 0; errors as for the int8 calls.
+ */
+int lrq_ars_rotate_quant_fp8(void* stream, const void* X, int M, int K, const lrq_rotation* rot, uint8_t* q8, float* scale,
+                             void* ws, size_t ws_bytes);
+int lrq_qgemm_fp8(void* stream, const uint8_t* q8, const float* scale, int M, int K, const lrq_tlq_weight* w,
+                  const float* bias, int out_dtype, void* Y);
+int lrq_qlinear_fp8(void* stream, const void* X, int M, int K, const lrq_rotation* rot, const lrq_tlq_weight* w,
+                    const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes);
 
 /*
  * Calibration of the outlier-aware branch (paper: Method, "Adaptive Rotation Scheme": greedy rotations

@@ -24,6 +24,7 @@ What follows the paper and where:
                  clamp-round quantizers (Eq. log-based quantizer), search-based
                  clipping (Eq. hyperparameters clip), dequantization (Eq. dequant),
                  exponent split and integerisation ("Hardware Implementation").
+* fp8.py       - FP8 E4M3 conversion (the operand format of the FP8 value map: levels with I = 3 mantissa bits).
 * qlinear.py   - the quantized linear layer Y = s_x * s_w * (I_x . I_w) assembled
                  from the above (last equation of "Hardware Implementation").
 
@@ -44,6 +45,8 @@ from .rotation import (hadamard_matrix, fwht_blocks, rotate_hadamard, rotate_den
 from .calib import fluctuation_J, select_rotation, smoothing_factor, smooth_weights  # noqa: F401
 from .actquant import quantize_per_token, quantize_per_token_asym, pack_act_codes4, unpack_act_codes4  # noqa: F401
 from .tlq import (TLQParams, tlq_calibrate, tlq_encode, tlq_exponents, tlq_dequant,  # noqa: F401
-                  tlq_level_values, tlq_lut, pack_codes, unpack_codes)
+                  tlq_level_values, tlq_lut, tlq_lut_fp8, pack_codes, unpack_codes)
+from .fp8 import e4m3_bits_to_f64, f64_to_e4m3_bits  # noqa: F401
 from .qlinear import (ars_rotate_quant, ars_rotate_quant_asym, qlinear, qlinear_from_parts,  # noqa: F401
-                      qlinear_from_parts_asym, qlinear_levels_from_parts, reference_linear)
+                      qlinear_from_parts_asym, qlinear_levels_from_parts, qlinear_fp8_from_parts, act_codes_to_e4m3,
+                      reference_linear)

@@ -86,6 +86,30 @@ def qlinear_levels_from_parts(q, scale, codes, levels, bits, bias=None):
     return y
 
 
+def act_codes_to_e4m3(q):
+    """4-bit activation codes (integers in [-7, 7]) as FP8 E4M3 bit patterns: every such integer has at most three
+    significant bits, so the conversion is exact."""
+    from .fp8 import e4m3_bits_to_f64, f64_to_e4m3_bits
+    q = np.asarray(q)
+    assert np.abs(q).max(initial=0) <= 7
+    bits = f64_to_e4m3_bits(q.astype(np.float64))
+    assert np.array_equal(e4m3_bits_to_f64(bits), q.astype(np.float64))
+    return bits
+
+
+def qlinear_fp8_from_parts(q, scale, codes, lut_fp8, wscale_fp8, bits, bias=None):
+    """The layer with FP8 E4M3 operands on both sides (4-bit activation codes; levels from tlq_lut_fp8):
+    Y[t, n] = scale_t wscale_n sum_k q[t, k] value(lut_fp8[n, code[n, k]]) (+ bias_n), the sum exact in fp64
+    (a product has at most seven significant bits)."""
+    from .fp8 import e4m3_bits_to_f64
+    idx = codes.astype(np.int64) & (2 ** bits - 1)
+    wv = np.take_along_axis(e4m3_bits_to_f64(lut_fp8), idx, axis=1)                      # [N, K]
+    y = (q.astype(np.float64) @ wv.T) * scale.astype(np.float64)[:, None] * np.asarray(wscale_fp8, dtype=np.float64)[None, :]
+    if bias is not None:
+        y = y + np.asarray(bias, dtype=np.float64)[None, :]
+    return y
+
+
 def qlinear(X_bits, W, w_bits, a_bits, rotation, had_block=None, R_bits=None, I=7,
             alpha_grid=None, beta_grid=None, bias=None):
     """Whole path: TLQ calibrate + encode the (already rotated) weights, rotate + quantize the

@@ -192,6 +192,21 @@ def tlq_lut(p: TLQParams, I=7):
     return lut, wscale
 
 
+def tlq_lut_fp8(p: TLQParams):
+    """The levels as FP8 E4M3 operands ("Hardware Implementation" with I = 3: a level round(2^r 2^3) 2^(f-3) has four
+    significant bits, an E4M3 number's worth).  Per channel the levels are divided by a power of two
+    wscale = 2^(floor(log2 max|v|) - 7), which puts the largest one in [128, 256) - inside E4M3's range (448) - and
+    then rounded to E4M3 (nearest even): exact for every level within 2^13 of the largest, rounded to the subnormal
+    spacing 2^-9 below that, zero below 2^-10.  Returns (lut uint8 [N, 2^b] of E4M3 bit patterns indexed by
+    c & (2^b - 1), wscale fp32 [N]).  This normalisation is not in the paper (its datapath shifts per element)."""
+    from .fp8 import f64_to_e4m3_bits
+    v = tlq_level_values(p, 3)
+    vmax = np.max(np.abs(v), axis=1)
+    e = np.floor(np.log2(np.where(vmax > 0, vmax, 1.0))) - 7.0
+    wscale = np.exp2(e)
+    return f64_to_e4m3_bits(v / wscale[:, None]), wscale.astype(np.float32)
+
+
 def tlq_dequant(codes, p: TLQParams):
     """W_f of Eq. dequant from signed codes (sign of the code = mask)."""
     v = tlq_level_values(p, I=-1)

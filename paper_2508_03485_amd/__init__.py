@@ -26,7 +26,8 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
            "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
            "lrq_qlinear_levels", "lrq_ars_dense_diagnostics", "lrq_ars_workspace_bytes_packed4",
-           "lrq_ars_rotate_quant_packed4", "lrq_qgemm_packed4", "lrq_workspace_bytes_packed4", "lrq_qlinear_packed4", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
+           "lrq_ars_rotate_quant_packed4", "lrq_qgemm_packed4", "lrq_workspace_bytes_packed4", "lrq_qlinear_packed4",
+           "lrq_ars_rotate_quant_fp8", "lrq_qgemm_fp8", "lrq_qlinear_fp8", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
 
 
 class LrqError(RuntimeError):
@@ -47,6 +48,7 @@ class _TlqWeight(ctypes.Structure):
                 ("z_pos", ctypes.c_void_p), ("z_neg", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("beta", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("wscale", ctypes.c_void_p),
                 ("gemm_codes", ctypes.c_void_p), ("colsum", ctypes.c_void_p), ("levels", ctypes.c_void_p),
+                ("lut_fp8", ctypes.c_void_p), ("wscale_fp8", ctypes.c_void_p),
                 ("err_pos", ctypes.c_void_p), ("err_neg", ctypes.c_void_p)]
 
 
@@ -89,6 +91,12 @@ def lib() -> ctypes.CDLL:
     L.lrq_workspace_bytes_packed4.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation)]
     L.lrq_qlinear_packed4.restype = ci
     L.lrq_qlinear_packed4.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ctypes.POINTER(_TlqWeight), vp, ci, vp, vp, sz]
+    L.lrq_ars_rotate_quant_fp8.restype = ci
+    L.lrq_ars_rotate_quant_fp8.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), vp, vp, vp, sz]
+    L.lrq_qgemm_fp8.restype = ci
+    L.lrq_qgemm_fp8.argtypes = [vp, vp, vp, ci, ci, ctypes.POINTER(_TlqWeight), vp, ci, vp]
+    L.lrq_qlinear_fp8.restype = ci
+    L.lrq_qlinear_fp8.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ctypes.POINTER(_TlqWeight), vp, ci, vp, vp, sz]
     L.lrq_workspace_bytes.restype = sz
     L.lrq_workspace_bytes.argtypes = [ci, ci, ci, ctypes.POINTER(_Rotation), ci]
     L.lrq_qlinear.restype = ci
@@ -193,6 +201,8 @@ class TLQWeight:
         self.gemm_codes = torch.zeros(ng, dtype=torch.uint8, **kw)
         self.colsum = torch.empty(N, dtype=torch.int32, **kw)
         self.levels = torch.empty((N, 16), dtype=torch.bfloat16, **kw)
+        self.lut_fp8 = torch.empty((N, 16), dtype=torch.uint8, **kw)
+        self.wscale_fp8 = torch.empty(N, dtype=torch.float32, **kw)
         self.err_pos = torch.empty(N, dtype=torch.float64, **kw)
         self.err_neg = torch.empty(N, dtype=torch.float64, **kw)
 
@@ -207,7 +217,7 @@ class TLQWeight:
             cs = _TlqWeight(self.N, self.K, self.bits, self.I, _ptr(self.codes), _ptr(self.s_pos), _ptr(self.s_neg),
                             _ptr(self.z_pos), _ptr(self.z_neg), _ptr(self.alpha), _ptr(self.beta), _ptr(self.lut),
                             _ptr(self.wscale), _ptr(self.gemm_codes), _ptr(self.colsum), _ptr(self.levels),
-                            _ptr(self.err_pos), _ptr(self.err_neg))
+                            _ptr(self.lut_fp8), _ptr(self.wscale_fp8), _ptr(self.err_pos), _ptr(self.err_neg))
             object.__setattr__(self, "_cs", cs)
         return cs
 
@@ -328,6 +338,56 @@ def qlinear_packed4(X, rot: Rotation, w: TLQWeight, bias=None, out_dtype=None, o
     st = lib().lrq_qlinear_packed4(_stream(), _ptr(X), M, K, ctypes.byref(r), ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
                                    _ptr(out), _ptr(workspace), workspace.numel())
     _check(st, "lrq_qlinear_packed4")
+    return out
+
+
+def ars_rotate_quant_fp8(X, rot: Rotation, q8=None, scale=None, workspace=None):
+    """lrq_ars_rotate_quant_fp8: X bf16 [M, K] -> (q8 uint8 [M, K] 4-bit codes as FP8 E4M3 bit patterns, scale fp32 [M])."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    if q8 is None:
+        q8 = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    if scale is None:
+        scale = torch.empty(M, dtype=torch.float32, device=X.device)
+    r = rot.c_struct()
+    need = lib().lrq_ars_workspace_bytes(M, K, ctypes.byref(r), 4)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    st = lib().lrq_ars_rotate_quant_fp8(_stream(), _ptr(X), M, K, ctypes.byref(r), _ptr(q8), _ptr(scale), _ptr(workspace),
+                                        0 if workspace is None else workspace.numel())
+    _check(st, "lrq_ars_rotate_quant_fp8")
+    return q8, scale
+
+
+def qgemm_fp8(q8, scale, w: TLQWeight, bias=None, out_dtype=None, out=None):
+    """lrq_qgemm_fp8: decode + FP8 MFMA GEMM + rescale on activation codes held as E4M3 bytes [M, K]."""
+    import torch
+    assert q8.is_cuda and q8.dtype == torch.uint8 and q8.is_contiguous()
+    M, K = q8.shape
+    out_dtype = out_dtype or (out.dtype if out is not None else torch.bfloat16)
+    if out is None:
+        out = torch.empty((M, w.N), dtype=out_dtype, device=q8.device)
+    cs = w.c_struct()
+    st = lib().lrq_qgemm_fp8(_stream(), _ptr(q8), _ptr(scale), M, K, ctypes.byref(cs), _ptr(bias), _out_code(out_dtype), _ptr(out))
+    _check(st, "lrq_qgemm_fp8")
+    return out
+
+
+def qlinear_fp8(X, rot: Rotation, w: TLQWeight, bias=None, out_dtype=None, out=None, workspace=None):
+    """lrq_qlinear_fp8: the fused layer with FP8 E4M3 operands on both sides (4-bit activation codes)."""
+    import torch
+    assert X.is_cuda and X.dtype == torch.bfloat16 and X.is_contiguous()
+    M, K = X.shape
+    out_dtype = out_dtype or (out.dtype if out is not None else torch.bfloat16)
+    if out is None:
+        out = torch.empty((M, w.N), dtype=out_dtype, device=X.device)
+    r, cs = rot.c_struct(), w.c_struct()
+    if workspace is None:
+        workspace = torch.empty(lib().lrq_workspace_bytes(M, w.N, K, ctypes.byref(r), 4), dtype=torch.uint8, device=X.device)
+    st = lib().lrq_qlinear_fp8(_stream(), _ptr(X), M, K, ctypes.byref(r), ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
+                               _ptr(out), _ptr(workspace), workspace.numel())
+    _check(st, "lrq_qlinear_fp8")
     return out
 
 

@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblrq.so")
 PROBES = os.path.join(HERE, "libbench_probes.so")    # measurement probes of bench.py, not part of liblrq
-SOURCES = ["lrq_api.hip", "rotate_quant.hip", "tlq_pack.hip", "qgemm.hip", "qgemm_levels.hip", "ars_calib.hip", "dense_rotate.hip"]
+SOURCES = ["lrq_api.hip", "rotate_quant.hip", "tlq_pack.hip", "qgemm.hip", "qgemm_levels.hip", "ars_calib.hip", "dense_rotate.hip", "qgemm_fp8.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

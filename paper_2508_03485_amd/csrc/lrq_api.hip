@@ -70,6 +70,7 @@ int check_weight(const lrq_tlq_weight* w) {
         return LRQ_EINVAL;
     if (!aligned16(w->codes) || !aligned16(w->lut) || !aligned16(w->gemm_codes)) return LRQ_EINVAL;
     if (w->levels && !aligned16(w->levels)) return LRQ_EINVAL;
+    if (w->lut_fp8 && !aligned16(w->lut_fp8)) return LRQ_EINVAL;
     return LRQ_OK;
 }
 
@@ -423,6 +424,60 @@ int lrq_qlinear_packed4(void* stream, const void* X, int M, int K, const lrq_rot
     if (st != LRQ_OK) return st;
     return lrq::launch_qgemm(s, reinterpret_cast<const int8_t*>(q4), scale, nullptr, M, K, *w, bias, out_dtype, Y, true) == hipSuccess
                ? LRQ_OK : LRQ_EHIP;
+}
+
+// ---- FP8 E4M3 operands on both sides --------------------------------------------------------------------------------
+static int rotate_quant_fp8(hipStream_t st, const void* X, int M, int K, const lrq_rotation* rot, uint8_t* q8, float* scale,
+                            void* ws) {
+    if (packs_in_kernel(rot, K)) {
+        const int h = rot->kind == LRQ_ROT_HADAMARD ? rot->had_block : 1;
+        return lrq::launch_hadamard_quant(st, static_cast<const uint16_t*>(X), M, K, h, 4, reinterpret_cast<int8_t*>(q8), scale,
+                                          nullptr, nullptr, false, true) == hipSuccess ? LRQ_OK : LRQ_EHIP;
+    }
+    // the other kinds write int8 codes, converted in place
+    const int st8 = run_rotate_quant(st, X, M, K, rot, 4, reinterpret_cast<int8_t*>(q8), scale, nullptr, ws);
+    if (st8 != LRQ_OK) return st8;
+    return lrq::launch_codes_to_fp8(st, reinterpret_cast<int8_t*>(q8), (size_t)M * K) == hipSuccess ? LRQ_OK : LRQ_EHIP;
+}
+
+int lrq_ars_rotate_quant_fp8(void* stream, const void* X, int M, int K, const lrq_rotation* rot, uint8_t* q8, float* scale,
+                             void* ws, size_t ws_bytes) {
+    int st = check_act(X, M, K, rot, 4);
+    if (st != LRQ_OK) return st;
+    if (K % 16 != 0) return LRQ_EUNSUPPORTED;
+    if (!q8 || !scale || !aligned16(q8)) return LRQ_EINVAL;
+    const size_t need = ars_layout(M, K, rot).total;
+    if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) return LRQ_EWORKSPACE;
+    return rotate_quant_fp8(static_cast<hipStream_t>(stream), X, M, K, rot, q8, scale, ws);
+}
+
+int lrq_qgemm_fp8(void* stream, const uint8_t* q8, const float* scale, int M, int K, const lrq_tlq_weight* w,
+                  const float* bias, int out_dtype, void* Y) {
+    if (!q8 || !scale || !Y || M <= 0 || K <= 0 || !aligned16(q8) || !aligned16(Y)) return LRQ_EINVAL;
+    const int st = check_gemm_common(w, K, out_dtype);
+    if (st != LRQ_OK) return st;
+    if (!w->lut_fp8 || !w->wscale_fp8) return LRQ_EINVAL;
+    return lrq::launch_qgemm_fp8(static_cast<hipStream_t>(stream), q8, scale, M, K, *w, bias, out_dtype, Y) == hipSuccess ? LRQ_OK
+                                                                                                                         : LRQ_EHIP;
+}
+
+int lrq_qlinear_fp8(void* stream, const void* X, int M, int K, const lrq_rotation* rot, const lrq_tlq_weight* w,
+                    const float* bias, int out_dtype, void* Y, void* ws, size_t ws_bytes) {
+    int st = check_act(X, M, K, rot, 4);
+    if (st != LRQ_OK) return st;
+    if (!Y || !aligned16(Y)) return LRQ_EINVAL;
+    st = check_gemm_common(w, K, out_dtype);
+    if (st != LRQ_OK) return st;
+    if (!w->lut_fp8 || !w->wscale_fp8) return LRQ_EINVAL;
+    if (!ws || ws_bytes < lrq_workspace_bytes(M, w->N, K, rot, 4) || !aligned16(ws)) return LRQ_EWORKSPACE;
+    char* base = static_cast<char*>(ws);
+    uint8_t* q8 = reinterpret_cast<uint8_t*>(base);
+    float* scale = reinterpret_cast<float*>(base + round256((size_t)M * K));
+    void* rot_ws = base + round256((size_t)M * K) + round256((size_t)M * sizeof(float));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = rotate_quant_fp8(s, X, M, K, rot, q8, scale, rot_ws);
+    if (st != LRQ_OK) return st;
+    return lrq::launch_qgemm_fp8(s, q8, scale, M, K, *w, bias, out_dtype, Y) == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 
 int lrq_init(void) {

@@ -21,6 +21,7 @@ struct QuantSpec {
     int32_t* zero;          // zero-point form: output [M]
     const float* prescale;  // per-channel factor applied to x before the rotation ([K], nullptr = none)
     int packed;             // 1: 4-bit codes are written two per byte (excess-8 nibbles, see lrq.h), row stride K / 2
+    int fp8;                // 1: 4-bit codes are written as FP8 E4M3 bit patterns
 };
 
 // u = x.(I (x) H_h) in fp64, per-token statistics, round to codes.  K % 8 == 0, h | K, h power of two.
@@ -29,7 +30,13 @@ struct QuantSpec {
 // packed (symmetric 4-bit codes only): q receives the packed nibbles ([M, K/2] bytes); only the shapes for which
 // hadamard_packs_in_kernel is true may be launched that way.
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale, int32_t* zero, const float* prescale, bool packed = false);
+                                 int8_t* q, float* scale, int32_t* zero, const float* prescale, bool packed = false,
+                                 bool fp8 = false);
+// int8 codes in [-7, 7] -> FP8 E4M3 bit patterns, in place (n bytes, n % 16 == 0)
+hipError_t launch_codes_to_fp8(hipStream_t st, int8_t* q, size_t n);
+// Y = scale_t * wscale_fp8_n * sum_k q * lut_fp8 (+ bias) on the FP8 matrix cores; q8: E4M3 bit patterns [M, K]
+hipError_t launch_qgemm_fp8(hipStream_t st, const uint8_t* q8, const float* scale, int M, int K, const lrq_tlq_weight& w,
+                            const float* bias, int out_dtype, void* Y);
 bool hadamard_packs_in_kernel(int K, int h);
 // q int8 [M, K] (codes in [-7, 7]) -> packed nibbles [M, K/2]
 hipError_t launch_pack_nibbles(hipStream_t st, const int8_t* q, int M, int K, uint8_t* q4);

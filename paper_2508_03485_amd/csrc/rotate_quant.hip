@@ -139,6 +139,16 @@ __device__ __forceinline__ unsigned pack_nibbles8(unsigned lo4, unsigned hi4) {
     return ((lo4 ^ 0x08080808u) & 0x0f0f0f0fu) | (((hi4 ^ 0x08080808u) & 0x0f0f0f0fu) << 4);
 }
 
+// Four int8 codes in [-7, 7] (one per byte) -> their FP8 E4M3 bit patterns: two 8-entry byte tables (0 .. 7 and the
+// negative values by their low three bits) and a pick by the code's bit 3, which is set exactly for the negative ones.
+__device__ __forceinline__ unsigned fp8x4_from_codes(unsigned w) {
+    const unsigned idx = w & 0x07070707u;
+    const unsigned pick = ((w >> 1) & 0x04040404u) | 0x03020100u;
+    const unsigned pos = __builtin_amdgcn_perm(0x4e4c4a48u, 0x44403800u, idx);     // 0, 1, 2, 3 | 4, 5, 6, 7
+    const unsigned neg = __builtin_amdgcn_perm(0xb8c0c4c8u, 0xcaccce00u, idx);   // -, -7, -6, -5 | -4, -3, -2, -1
+    return __builtin_amdgcn_perm(neg, pos, pick);
+}
+
 template <bool ASYM>
 __device__ __forceinline__ void store8_codes(int8_t* __restrict__ dst, const double v[8], const RowQ& p, double half) {
     *reinterpret_cast<uint2*>(dst) = make_uint2(pack4<ASYM>(v, p, half), pack4<ASYM>(v + 4, p, half));
@@ -296,6 +306,10 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
     unsigned out[8];
 #pragma unroll
     for (int g = 0; g < 8; ++g) out[g] = pack4<ASYM>(v + 4 * g, p, qs.half);
+    if (!ASYM && qs.fp8) {
+#pragma unroll
+        for (int g = 0; g < 8; ++g) out[g] = fp8x4_from_codes(out[g]);
+    }
     if (!ASYM && qs.packed) {
         *reinterpret_cast<uint4*>(q + (size_t)row * (K / 2) + (size_t)slot * (E32 / 2)) =
             make_uint4(pack_nibbles8(out[0], out[1]), pack_nibbles8(out[2], out[3]), pack_nibbles8(out[4], out[5]),
@@ -480,6 +494,11 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
                 const uint4 a = src[0], c = src[1];
                 *reinterpret_cast<uint4*>(q + (size_t)row * (K / 2) + (size_t)slot * (E32 / 2)) =
                     make_uint4(pack_nibbles8(a.x, a.y), pack_nibbles8(a.z, a.w), pack_nibbles8(c.x, c.y), pack_nibbles8(c.z, c.w));
+            } else if (!ASYM && qs.fp8) {
+                const uint4 a = src[0], c = src[1];
+                uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
+                dst[0] = make_uint4(fp8x4_from_codes(a.x), fp8x4_from_codes(a.y), fp8x4_from_codes(a.z), fp8x4_from_codes(a.w));
+                dst[1] = make_uint4(fp8x4_from_codes(c.x), fp8x4_from_codes(c.y), fp8x4_from_codes(c.z), fp8x4_from_codes(c.w));
             } else {
                 uint4* dst = reinterpret_cast<uint4*>(q + (size_t)row * K + (size_t)slot * E32);
                 dst[0] = src[0];
@@ -899,6 +918,14 @@ __global__ __launch_bounds__(256) void pack_nibbles_kernel(const int8_t* __restr
     reinterpret_cast<uint2*>(q4)[i] = make_uint2(pack_nibbles8(v.x, v.y), pack_nibbles8(v.z, v.w));
 }
 
+// int8 codes in [-7, 7] -> FP8 E4M3 bit patterns in place, 16 codes per thread
+__global__ __launch_bounds__(256) void codes_to_fp8_kernel(int8_t* __restrict__ q, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n16) return;
+    const uint4 v = reinterpret_cast<const uint4*>(q)[i];
+    reinterpret_cast<uint4*>(q)[i] = make_uint4(fp8x4_from_codes(v.x), fp8x4_from_codes(v.y), fp8x4_from_codes(v.z), fp8x4_from_codes(v.w));
+}
+
 int ilog2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -919,6 +946,12 @@ static bool e32_shape(int K, int h) { return h <= 128 && K % 128 == 0 && K / E32
 static bool twopass_shape(int K, int h) { return h >= 256 && h <= 4096 && K % 128 == 0 && K / E32 <= 512; }
 bool hadamard_packs_in_kernel(int K, int h) { return e32_shape(K, h) || twopass_shape(K, h); }
 
+hipError_t launch_codes_to_fp8(hipStream_t st, int8_t* q, size_t n) {
+    const size_t n16 = n / 16;
+    hipLaunchKernelGGL(codes_to_fp8_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, q, n16);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack_nibbles(hipStream_t st, const int8_t* q, int M, int K, uint8_t* q4) {
     const size_t n16 = (size_t)M * K / 16;
     hipLaunchKernelGGL(pack_nibbles_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, st, q, n16, q4);
@@ -936,6 +969,7 @@ static QuantSpec make_spec(int act_bits, int h, int32_t* zero, const float* pres
     qs.zero = zero;
     qs.prescale = prescale;
     qs.packed = 0;
+    qs.fp8 = 0;
     return qs;
 }
 
@@ -945,11 +979,12 @@ static void launch_quant_from_f64(hipStream_t st, const double* U, int M, int K,
 }
 
 hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K, int h, int act_bits,
-                                 int8_t* q, float* scale, int32_t* zero, const float* prescale, bool packed) {
+                                 int8_t* q, float* scale, int32_t* zero, const float* prescale, bool packed, bool fp8) {
     QuantSpec qs = make_spec(act_bits, h, zero, prescale);
-    if (packed) {
-        if (zero || act_bits != 4 || !hadamard_packs_in_kernel(K, h)) return hipErrorInvalidValue;
-        qs.packed = 1;
+    if (packed || fp8) {
+        if ((packed && fp8) || zero || act_bits != 4 || !hadamard_packs_in_kernel(K, h)) return hipErrorInvalidValue;
+        qs.packed = packed;
+        qs.fp8 = fp8;
     }
     if (e32_shape(K, h)) {
         // R whole rows per workgroup, at most four waves (finer granularity measured faster than nine; 7 rows of 1152 fill four waves)

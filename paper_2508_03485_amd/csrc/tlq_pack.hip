@@ -114,6 +114,21 @@ __device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
     return (uint16_t)(u >> 16);
 }
 
+// Round-to-nearest-even FP8 E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest value
+// 448, subnormals in steps of 2^-9) of a double, saturating.
+__device__ __forceinline__ uint8_t f64_to_e4m3_rne(double x) {
+    const unsigned sgn = x < 0.0 ? 0x80u : 0u;
+    const double a = fmin(fabs(x), 448.0);
+    if (!(a > 0.0)) return (uint8_t)sgn;
+    int e = ilogb(a);
+    e = e < -6 ? -6 : e;                                   // below 2^-6 everything shares the subnormal spacing
+    double n = rint(ldexp(a, 3 - e));                      // multiples of 2^(e - 3): 8 .. 16 for a normal, 0 .. 8 below
+    if (n >= 16.0) { n = 8.0; ++e; }
+    if (e > 8 || (e == 8 && n > 14.0)) return (uint8_t)(sgn | 0x7eu);
+    if (n < 8.0) return (uint8_t)(sgn | (unsigned)n);      // subnormal (n = 8 at e = -6 is the smallest normal)
+    return (uint8_t)(sgn | ((unsigned)(e + 7) << 3) | ((unsigned)n - 8u));
+}
+
 __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     const float* __restrict__ W, int N, int K, int bits, int I, const float* __restrict__ agrid, int na,
     const float* __restrict__ bgrid, int nb, uint8_t* __restrict__ codes_out, double* __restrict__ s_pos,
@@ -121,7 +136,7 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     float* __restrict__ alpha, float* __restrict__ beta, int8_t* __restrict__ lut, float* __restrict__ wscale,
     uint8_t* __restrict__ gemm_codes, int32_t* __restrict__ colsum, const float* __restrict__ ggrid, int ngamma,
     float* __restrict__ gamma_pos, float* __restrict__ gamma_neg, uint16_t* __restrict__ levels,
-    double* __restrict__ err_pos, double* __restrict__ err_neg) {
+    double* __restrict__ err_pos, double* __restrict__ err_neg, uint8_t* __restrict__ lut_fp8, float* __restrict__ wscale_fp8) {
     extern __shared__ double sm[];
     double* ell = sm;                                   // K doubles: log2|w|
     double* red = sm + K;                               // NT doubles of reduction scratch
@@ -198,6 +213,27 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
     }
     if (t == 0) wscale[n] = ws;
 
+    // the same levels with I = 3 as FP8 E4M3 operands: divided by the power of two that puts the largest in [128, 256)
+    if (lut_fp8 && wscale_fp8) {
+        __syncthreads();
+        double v3 = 0.0;
+        if (t < nlev) {
+            const int c = t < half ? t : t - nlev;
+            const double e = c >= 0 ? sp * ((double)c + zp) : sn * ((double)(-c) + zn);
+            const double f = floor(e), r = e - f;
+            const double mag = ldexp(rint(exp2(r) * 8.0), (int)f - 3);
+            v3 = c >= 0 ? mag : -mag;
+            red[t] = mag;
+        }
+        __syncthreads();
+        double m3 = 0.0;
+        for (int i = 0; i < nlev; ++i) m3 = fmax(m3, red[i]);
+        const int ex = (m3 > 0.0 ? ilogb(m3) : 0) - 7;
+        if (t < 16) lut_fp8[(size_t)n * 16 + t] = t < nlev ? f64_to_e4m3_rne(ldexp(v3, -ex)) : (uint8_t)0;
+        if (t == 0) wscale_fp8[n] = ldexpf(1.0f, ex);
+        __syncthreads();
+    }
+
     // codes (Eq. log-based quantizer); the negative twin is clamped to [1, 2^(b-1)]
     for (int k = t; k < K; k += NT) {
         const double wk = (double)w[k];
@@ -264,7 +300,7 @@ hipError_t launch_tlq_quantize_pack(hipStream_t st, const float* W, int N, int K
     hipLaunchKernelGGL(tlq_quantize_pack_kernel, dim3(N), dim3(NT), lds, st, W, N, K, bits, I, alpha_grid, n_alpha,
                        beta_grid, n_beta, out.codes, out.s_pos, out.s_neg, out.z_pos, out.z_neg, out.alpha, out.beta,
                        out.lut, out.wscale, out.gemm_codes, out.colsum, gamma_grid, n_gamma, gamma_pos, gamma_neg, out.levels,
-                       out.err_pos, out.err_neg);
+                       out.err_pos, out.err_neg, out.lut_fp8, out.wscale_fp8);
     return hipGetLastError();
 }
 

@@ -11,11 +11,13 @@ import oracle
 import oracle.actquant
 import oracle.bf16
 import oracle.calib
+import oracle.fp8
 import oracle.rotation
 import oracle.tlq
 import test_oracle_actquant as t_act
 import test_oracle_actquant_asym as t_asym
 import test_oracle_calib as t_cal
+import test_oracle_fp8 as t_fp8
 import test_oracle_levels as t_lev
 import test_oracle_qlinear as t_ql
 import test_oracle_rotation as t_rot
@@ -164,6 +166,25 @@ def _blockperm_scatter(x, R1, perm, R2):
 def _blockperm_narrow_intermediate(x, R1, perm, R2):
     z = oracle.rotation.rotate_blockdiag(x, R1).astype(np.float32).astype(np.float64)   # a storage format leaking in
     return oracle.rotation.rotate_blockdiag(z[:, np.asarray(perm)], R2)
+
+
+def _e4m3_rounding_towards_zero(x):
+    x = np.asarray(x, dtype=np.float64)
+    a = np.minimum(np.abs(x), 448.0)
+    pos = oracle.fp8.e4m3_bits_to_f64(np.arange(0x7f, dtype=np.uint8))
+    idx = np.searchsorted(pos, a, side="right") - 1               # largest representable magnitude <= |x|: truncation
+    return (np.arange(0x7f, dtype=np.uint8)[idx] | (np.signbit(x).astype(np.uint8) << 7)).astype(np.uint8)
+
+
+def _lut_fp8_top_level_at_448(p):
+    v = oracle.tlq.tlq_level_values(p, 3)
+    wscale = np.max(np.abs(v), axis=1) / 448.0                    # uses the whole range, but is no power of two
+    return oracle.fp8.f64_to_e4m3_bits(v / wscale[:, None]), wscale.astype(np.float32)
+
+
+def _pack_act_adjacent_pairs(q):
+    q = np.asarray(q).astype(np.int64) + 8
+    return (q[:, 0::2] | (q[:, 1::2] << 4)).astype(np.uint8)        # neighbours share a byte instead of j and 4 + j
 
 
 def _blockdiag_transposed(x, Rb):
@@ -322,6 +343,12 @@ CASES = {
         oracle.rotation.rotate_blockperm, _blockperm_narrow_intermediate,
         [(t_str.test_nothing_is_rounded_between_the_two_stages, ()),
          (t_str.test_equals_the_materialised_dense_product, ())]),
+    "FP8 conversion truncates": (oracle.fp8.f64_to_e4m3_bits, _e4m3_rounding_towards_zero,
+                                 [(t_fp8.test_conversion_is_the_nearest_value_ties_to_even_and_saturates, ())]),
+    "FP8 level table scaled by a non power of two": (oracle.tlq.tlq_lut_fp8, _lut_fp8_top_level_at_448,
+                                                     [(t_fp8.test_fp8_level_table, (4,))]),
+    "packed activation codes pair neighbours": (oracle.actquant.pack_act_codes4, _pack_act_adjacent_pairs,
+                                                [(t_act.test_packed_4bit_codes_hand_example_and_round_trip, ())]),
     "rotation blocks transposed": (oracle.rotation.rotate_blockdiag, _blockdiag_transposed,
                                    [(t_str.test_blockdiag_equals_block_diagonal_matrix_product, ()),
                                     (t_str.test_equals_the_materialised_dense_product, ())]),
