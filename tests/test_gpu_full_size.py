@@ -196,3 +196,67 @@ def test_dense_rotation_whose_last_round_of_tiles_is_sparse(lrq):
         if kind == "dense_f64":
             u = ws[:M * K * 8].view(torch.float64).view(M, K)[ridx].cpu().numpy()
             assert np.array_equal(u, oracle.rotate_dense(oracle.bf16_bits_to_f64(X[rows]), oracle.bf16_bits_to_f64(R)))
+
+
+def _config_5_blocks():
+    specs = synth.config_layers(5)
+    blocks = {}
+    for s in specs:
+        blocks.setdefault(s.name.split(".")[0], []).append(s)
+    return specs, blocks
+
+
+def test_config_5_dense_layers_and_two_more_blocks(lrq):
+    """Every config-5 layer above the fluctuation threshold (among them two-token adaLN calls, which take the fp64
+    evaluation, and 8192-token ones, which take the matrix-core one), plus all five layers of a middle and of the
+    last block: sampled rows and channels, the bar of _check_layer."""
+    specs, blocks = _config_5_blocks()
+    dense = [s for s in specs if s.rotation == "dense"]
+    assert {s.M for s in dense} >= {2, specs[0].M}, "want both token counts among the dense layers"
+    assert len({(s.K, s.N) for s in dense}) >= 4, "want the dense layers to span the shapes of a block"
+    names = sorted(blocks, key=lambda b: int(b[1:]))
+    picked = dense + blocks[names[len(names) // 2]] + blocks[names[-1]]
+    seen = set()
+    for s in picked:
+        if s.name not in seen:
+            seen.add(s.name)
+            _check_layer(lrq, s)
+
+
+@pytest.mark.parametrize("part", [0, 1, 2, 3])
+def test_config_5_weight_tables_of_every_layer(lrq, part):
+    """All 140 weight matrices of config 5 go through the pack kernel; the packed codes, level tables and channel
+    scales of a seeded sample of channels of each are compared (the channels are independent under per-channel TLQ)."""
+    import torch
+    specs, _ = _config_5_blocks()
+    gd = to_dev(GRID)
+    mine = specs[part::4]
+    print(f"config 5 weight tables, part {part}: {len(mine)} layers", flush=True)
+    for s in mine:
+        W = synth.make_weights(s.N, s.K, s.key)
+        chans = _sample(s.N, 24, s.key)
+        w = lrq.tlq_quantize_pack(to_dev(W), s.w_bits, 7, gd, gd)
+        cidx = torch.from_numpy(chans).to(w.codes.device)
+        codes_s, lut_s, ws_s = w.codes[cidx].cpu().numpy(), w.lut[cidx].cpu().numpy(), w.wscale[cidx].cpu().numpy()
+        p = oracle.tlq_calibrate(W[chans], s.w_bits, GRID, GRID)
+        assert np.array_equal(codes_s, oracle.pack_codes(oracle.tlq_encode(W[chans], p), s.w_bits)), s.name
+        lut, wscale = oracle.tlq_lut(p, 7)
+        assert np.array_equal(lut_s[:, :2 ** s.w_bits], lut), s.name
+        assert np.all(np.abs(ws_s.view(np.int32) - wscale.view(np.int32)) <= 1), s.name
+
+
+@pytest.mark.parametrize("which", ["qkv", "fc2", "adaLN"])
+def test_config_5_weight_codes_in_full(lrq, which):
+    """One W3 matrix of each of three shapes (K -> 3K, 4K -> K, K -> 6K), every channel, packed codes and tables."""
+    specs, blocks = _config_5_blocks()
+    names = sorted(blocks, key=lambda b: int(b[1:]))
+    s = [x for x in blocks[names[len(names) // 3]] if x.name.endswith("." + which)][0]
+    print(f"config 5 full weight check {s.name} N={s.N} K={s.K} W{s.w_bits}", flush=True)
+    W = synth.make_weights(s.N, s.K, s.key)
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), s.w_bits, 7, gd, gd)
+    p = oracle.tlq_calibrate(W, s.w_bits, GRID, GRID)
+    assert np.array_equal(w.codes.cpu().numpy(), oracle.pack_codes(oracle.tlq_encode(W, p), s.w_bits))
+    lut, wscale = oracle.tlq_lut(p, 7)
+    assert np.array_equal(w.lut.cpu().numpy()[:, :2 ** s.w_bits], lut)
+    assert np.all(np.abs(w.wscale.cpu().numpy().view(np.int32) - wscale.view(np.int32)) <= 1)
