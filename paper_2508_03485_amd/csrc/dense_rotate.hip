@@ -117,61 +117,83 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 }
 
 // ---- u~ = x . R on the bf16 matrix cores.  Workgroup = 8 waves (4 x 2), tile 128 tokens x 128 columns, wave tile
-// 32 x 64 (two 32 x 32 accumulator tiles: with the fp64 copies that is 96 registers, which leaves room to keep two
-// 64-k stages of both operands in flight in registers).  Both operand tiles (x rows and R columns, i.e. rows of Rt)
-// go global -> registers -> LDS: stage s is loaded two iterations before it is stored to one of three LDS buffers and
-// three before it is multiplied.  LDS rows are padded to 144 bytes so that the 16-byte fragment reads of 16
-// consecutive rows fall on distinct banks.  A run of CHUNK = 64 k (one stage) starts on a zero accumulator (the
-// instruction's constant-zero addend, no clearing) and ends by adding the fp32 tiles to the fp64 ones.
+// 32 x 64 (two 32 x 32 accumulator tiles).  Both operand tiles (x rows and R columns, i.e. rows of Rt) go global ->
+// registers -> LDS: stage s is loaded two iterations before it is stored to one of three LDS buffers and three before
+// it is multiplied.  LDS rows are padded to 144 bytes so that the 16-byte fragment reads of 16 consecutive rows fall
+// on distinct banks.
+// Accumulation has three levels.  A run of CHUNK = 64 k (one stage) is four chained matrix instructions that start on
+// a zero accumulator (the instruction's constant-zero addend, no clearing).  The fp32 tiles of a finished run are
+// added - one vector fp32 addition per value, rounded to nearest - to fp32 group tiles, GROUP runs to a group, and a
+// finished group is added to the fp64 tiles.  Both additions are done during the following stage, spread between its
+// matrix instructions, so they issue while the matrix cores work; the conversion to fp64 (the expensive part: twelve
+// issue cycles per value against eight cycles of matrix work per value and run) happens once per group only.
+// Besides u~ the kernel writes, per row and 64-column segment (a wave's width), the maximum of |u~| (segmax): the
+// search for the row maximum then reads one value per segment instead of the whole row.
 // (X, Rt and Ut are deliberately not declared __restrict__: with that promise the compiler moves the prefetch loads past
 // the compiler barrier that keeps them ahead of the arithmetic, down to their LDS stores.)
 constexpr int DT_M = 128, DT_N = 128, DT_K = 64, DT_ROW = 144, DT_BUF = DT_M * DT_ROW;
-constexpr int kChunk = DT_K;        // run length of the fp32 accumulation between promotions to fp64
+constexpr int DT_SEG = 64;          // columns per segment maximum
+constexpr int kChunk = DT_K;        // run length of the fp32 accumulation inside the matrix instruction
+constexpr int kGroup = 4;           // runs per fp32 group sum
 
-struct Stage {                      // one thread's share of a 64-k stage of both operand tiles
-    v4u a0, a1, b0, b1;
-};
-__device__ __forceinline__ Stage load_stage(const unsigned char* a0, const unsigned char* a1, const unsigned char* b0,
-                                            const unsigned char* b1, int kb, int nk) {
-    const size_t o = (size_t)(kb < nk ? kb : nk - 1) * DT_K * 2;       // past the end: a harmless re-read, never multiplied
-    Stage s;
-    s.a0 = *reinterpret_cast<const v4u*>(a0 + o);
-    s.a1 = *reinterpret_cast<const v4u*>(a1 + o);
-    s.b0 = *reinterpret_cast<const v4u*>(b0 + o);
-    s.b1 = *reinterpret_cast<const v4u*>(b1 + o);
-    return s;
+// fragments of one 16-k step of a wave: its 32 rows of the x tile, columns 0..31 and 32..63 of its R tile
+__device__ __forceinline__ void read_fragments(const unsigned char* A, const unsigned char* B, int s, v8s (&f)[3]) {
+    f[0] = *reinterpret_cast<const v8s*>(A + s * 32);
+    f[1] = *reinterpret_cast<const v8s*>(B + s * 32);
+    f[2] = *reinterpret_cast<const v8s*>(B + 32 * DT_ROW + s * 32);
 }
-__device__ __forceinline__ void store_stage(const Stage s, unsigned char* As, unsigned char* Bs, int buf, int d0, int d1) {
-    *reinterpret_cast<v4u*>(&As[buf * DT_BUF + d0]) = s.a0;
-    *reinterpret_cast<v4u*>(&As[buf * DT_BUF + d1]) = s.a1;
-    *reinterpret_cast<v4u*>(&Bs[buf * DT_BUF + d0]) = s.b0;
-    *reinterpret_cast<v4u*>(&Bs[buf * DT_BUF + d1]) = s.b1;
-}
-// one stage: a run of four chained matrix instructions per accumulator tile from a zero addend, then added to the fp64 tiles
-__device__ __forceinline__ void multiply_stage(const unsigned char* A, const unsigned char* B, double (&wide)[2][16]) {
+// One stage: its run of matrix instructions into fresh fp32 tiles, and - a quarter after each step - the bookkeeping
+// of the previous stage's tiles `prev`: FIRST: they open a new group (the group tiles take them as they are), else they
+// are added to the group tiles; FLUSH (the previous stage closed a group): the group tiles then join the fp64 tiles.
+// The fragments of step s + 1 are read from LDS before the matrix instructions of step s are issued (LDS latency is
+// longer than a matrix instruction); fr holds those of step 0 on entry and those of the next stage's step 0 (buffer
+// An / Bn, complete since the previous barrier) on return.
+// The staged registers st (this thread's four 16-byte pieces of the stage that is two ahead) go to LDS one per step, at
+// dst[i], and are reloaded from src[i] + goff (the stage that is four ahead) right away: spread like this the LDS writes of
+// the eight waves overlap the matrix work instead of preceding it.
+template <bool FIRST, bool FLUSH>
+__device__ __forceinline__ void multiply_stage(const unsigned char* A, const unsigned char* B, const unsigned char* An,
+                                               const unsigned char* Bn, v8s (&fr)[3], v4u (&st)[4], unsigned char* const (&dst)[4],
+                                               const unsigned char* const (&src)[4], size_t goff, double (&wide)[2][16],
+                                               v16f (&group)[2], v16f (&prev)[2]) {
     v16f acc[2];
+    v8s fo[3];                       // fragments of the odd steps
 #pragma unroll
     for (int s = 0; s < DT_K / 16; ++s) {
-        const v8s a = *reinterpret_cast<const v8s*>(A + s * 32);
+        if (s % 2 == 0) read_fragments(A, B, s + 1, fo);
+        else if (s + 1 < DT_K / 16) read_fragments(A, B, s + 1, fr);
+        else read_fragments(An, Bn, 0, fr);
+        *reinterpret_cast<v4u*>(dst[s]) = st[s];
+        st[s] = *reinterpret_cast<const v4u*>(src[s] + goff);
+        asm volatile("" ::: "memory");                   // keeps the load here, ahead of the arithmetic that follows
+        __builtin_amdgcn_sched_barrier(0);
+        const v8s a = s % 2 == 0 ? fr[0] : fo[0];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const v8s b = *reinterpret_cast<const v8s*>(B + j * 32 * DT_ROW + s * 32);
+            const v8s b = s % 2 == 0 ? fr[1 + j] : fo[1 + j];
             if (s == 0) {
                 const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
                 acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
             } else {
                 acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
             }
+            constexpr int PER = 16 / (DT_K / 16);          // values of a tile of `prev` handled after each instruction
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int r = s * PER + i;
+                const float g = FIRST ? prev[j][r] : group[j][r] + prev[j][r];
+                group[j][r] = g;
+                if (FLUSH) wide[j][r] += (double)g;
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) wide[j][r] += (double)acc[j][r];
+    prev[0] = acc[0];
+    prev[1] = acc[1];
 }
 
 __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K, float* Ut,
-                                                                    int tiles_m, int tiles_n) {
+                                                                    float* segmax, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) unsigned char As[3 * DT_BUF];
     __shared__ __attribute__((aligned(16))) unsigned char Bs[3 * DT_BUF];
     // tile order: workgroup ids go round-robin over the 8 XCDs; each XCD walks a contiguous range of an order that keeps
@@ -198,92 +220,150 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
     const int t = threadIdx.x, lane = t % kWave, wv = t / kWave;
     const int wm = wv / 2, wn = wv % 2;
 
-    // loader: 1024 16-byte chunks per operand tile and stage, two per thread (rows r0 and r0 + 64)
+    // loader: 1024 16-byte pieces per operand tile and stage, two per thread and operand (rows r0 and r0 + 64)
     const int r0 = t / 8, cc = t % 8;
     int g0 = m0 + r0, g1 = m0 + r0 + 64;
     if (g0 >= M) g0 = M - 1;
     if (g1 >= M) g1 = M - 1;
-    const unsigned char* pa0 = reinterpret_cast<const unsigned char*>(X + (size_t)g0 * K) + cc * 16;
-    const unsigned char* pa1 = reinterpret_cast<const unsigned char*>(X + (size_t)g1 * K) + cc * 16;
-    const unsigned char* pb0 = reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0) * K) + cc * 16;
-    const unsigned char* pb1 = reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0 + 64) * K) + cc * 16;
+    const unsigned char* src[4] = {reinterpret_cast<const unsigned char*>(X + (size_t)g0 * K) + cc * 16,
+                                   reinterpret_cast<const unsigned char*>(X + (size_t)g1 * K) + cc * 16,
+                                   reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0) * K) + cc * 16,
+                                   reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0 + 64) * K) + cc * 16};
     const int d0 = r0 * DT_ROW + cc * 16, d1 = d0 + 64 * DT_ROW;
     const int nk = K / DT_K;
+    auto goff = [nk](int kb) { return (size_t)(kb < nk ? kb : nk - 1) * DT_K * 2; };   // past the end: a harmless re-read
 
     double wide[2][16];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) wide[j][r] = 0.0;
-    const int a_off = (wm * 32 + lane % 32) * DT_ROW + (lane / 32) * 16;
-    const int b_off = (wn * 64 + lane % 32) * DT_ROW + (lane / 32) * 16;
-
-    // prologue: stages 0, 1 in LDS buffers 0, 1; stages 2 (even) and 3 (odd) in registers
-    Stage ev = load_stage(pa0, pa1, pb0, pb1, 0, nk);
-    Stage od = load_stage(pa0, pa1, pb0, pb1, 1, nk);
-    store_stage(ev, As, Bs, 0, d0, d1);
-    store_stage(od, As, Bs, 1, d0, d1);
-    ev = load_stage(pa0, pa1, pb0, pb1, 2, nk);
-    od = load_stage(pa0, pa1, pb0, pb1, 3, nk);
-    __syncthreads();
-    int b0 = 0, b1 = 1, b2 = 2;                          // LDS buffers of stages kb, kb + 1, kb + 2
-    for (int kb = 0; kb < nk; kb += 2) {                 // K % 128 == 0: an even number of stages
-        store_stage(ev, As, Bs, b2, d0, d1);             // stage kb + 2, loaded two iterations ago
-        ev = load_stage(pa0, pa1, pb0, pb1, kb + 4, nk);
-        asm volatile("" ::: "memory");                   // keeps the loads above ahead of the arithmetic below
-        __builtin_amdgcn_sched_barrier(0);
-        multiply_stage(&As[b0 * DT_BUF + a_off], &Bs[b0 * DT_BUF + b_off], wide);
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        store_stage(od, As, Bs, b0, d0, d1);             // stage kb + 3 into the buffer that stage kb just left
-        od = load_stage(pa0, pa1, pb0, pb1, kb + 5, nk);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        multiply_stage(&As[b1 * DT_BUF + a_off], &Bs[b1 * DT_BUF + b_off], wide);
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        const int f = b0;                                // stages kb + 2, kb + 3, kb + 4 live in b2, b0, b1
-        b0 = b2;
-        b2 = b1;
-        b1 = f;
-    }
-    // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
+    v16f group[2], prev[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-            if (row < M) Ut[(size_t)row * K + n0 + wn * 64 + j * 32 + lane % 32] = (float)wide[j][r];
+            wide[j][r] = 0.0;
+            group[j][r] = 0.0f;
+            prev[j][r] = 0.0f;
         }
+    const int a_off = (wm * 32 + lane % 32) * DT_ROW + (lane / 32) * 16;
+    const int b_off = (wn * 64 + lane % 32) * DT_ROW + (lane / 32) * 16;
+
+    // prologue: stages 0, 1 in LDS buffers 0, 1; stages 2 (even) and 3 (odd) in registers
+    v4u ev[4], od[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ev[i] = *reinterpret_cast<const v4u*>(src[i] + goff(0));
+        od[i] = *reinterpret_cast<const v4u*>(src[i] + goff(1));
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        unsigned char* base = i < 2 ? As : Bs;
+        const int d = i % 2 == 0 ? d0 : d1;
+        *reinterpret_cast<v4u*>(&base[d]) = ev[i];
+        *reinterpret_cast<v4u*>(&base[DT_BUF + d]) = od[i];
+        ev[i] = *reinterpret_cast<const v4u*>(src[i] + goff(2));
+        od[i] = *reinterpret_cast<const v4u*>(src[i] + goff(3));
+    }
+    __syncthreads();
+    v8s fr[3];
+    read_fragments(&As[a_off], &Bs[b_off], 0, fr);
+    int b0 = 0, b1 = 1, b2 = 2;                          // LDS buffers of stages kb, kb + 1, kb + 2
+    // Stage kb handles the tiles of stage kb - 1 (`prev`).  With GROUP = 4: stage 4 i + 1 opens group i with run 4 i,
+    // stages 4 i + 2, 4 i + 3 add runs 4 i + 1, 4 i + 2, stage 4 i + 4 adds run 4 i + 3 and flushes the group.  Stage 0
+    // has nothing to handle: it "flushes" the zero-initialised tiles, which changes nothing.
+    static_assert(kGroup == 4, "the loop body below is written out for groups of four runs");
+    // two stages: the first multiplies from b0 and refills b2 from the even registers (stage KB + 2, loaded two iterations
+    // ago; they then take stage KB + 4), the second multiplies from b1 and refills b0, the buffer that stage KB just
+    // left, from the odd ones (a macro, not a lambda: captured register arrays would be spilled to scratch memory)
+#define LRQ_DENSE_STAGE_PAIR(FIRST_A, FLUSH_A, FIRST_B, FLUSH_B, KB)                                                     \
+    {                                                                                                                     \
+        unsigned char* const dst_a[4] = {&As[b2 * DT_BUF + d0], &As[b2 * DT_BUF + d1], &Bs[b2 * DT_BUF + d0],             \
+                                         &Bs[b2 * DT_BUF + d1]};                                                          \
+        multiply_stage<FIRST_A, FLUSH_A>(&As[b0 * DT_BUF + a_off], &Bs[b0 * DT_BUF + b_off], &As[b1 * DT_BUF + a_off],    \
+                                         &Bs[b1 * DT_BUF + b_off], fr, ev, dst_a, src, goff((KB) + 4), wide, group, prev); \
+        __builtin_amdgcn_sched_barrier(0);                                                                                \
+        __syncthreads();                                                                                                  \
+        unsigned char* const dst_b[4] = {&As[b0 * DT_BUF + d0], &As[b0 * DT_BUF + d1], &Bs[b0 * DT_BUF + d0],             \
+                                         &Bs[b0 * DT_BUF + d1]};                                                          \
+        multiply_stage<FIRST_B, FLUSH_B>(&As[b1 * DT_BUF + a_off], &Bs[b1 * DT_BUF + b_off], &As[b2 * DT_BUF + a_off],    \
+                                         &Bs[b2 * DT_BUF + b_off], fr, od, dst_b, src, goff((KB) + 5), wide, group, prev); \
+        __builtin_amdgcn_sched_barrier(0);                                                                                \
+        __syncthreads();                                                                                                  \
+        const int f = b0;                                /* stages KB + 2, KB + 3, KB + 4 live in b2, b0, b1 */           \
+        b0 = b2;                                                                                                          \
+        b2 = b1;                                                                                                          \
+        b1 = f;                                                                                                           \
+    }
+    int kb = 0;
+    for (; kb + 3 < nk; kb += 4) {
+        LRQ_DENSE_STAGE_PAIR(false, true, true, false, kb)
+        LRQ_DENSE_STAGE_PAIR(false, false, false, false, kb + 2)
+    }
+    if (kb < nk) LRQ_DENSE_STAGE_PAIR(false, true, true, false, kb)      // K % 256 == 128: two more stages
+#undef LRQ_DENSE_STAGE_PAIR
+    // the last run, and whatever its group holds
+    const bool opens = (nk - 1) % kGroup == 0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) wide[j][r] += (double)(opens ? prev[j][r] : group[j][r] + prev[j][r]);
+
+    // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
+    float vals[16];                                      // per row that this lane touches: max over its two columns
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        const float u0 = (float)wide[0][r], u1 = (float)wide[1][r];
+        if (row < M) {
+            float* dst = Ut + (size_t)row * K + n0 + wn * 64 + lane % 32;
+            dst[0] = u0;
+            dst[32] = u1;
+        }
+        vals[r] = fmaxf(fabsf(u0), fabsf(u1));
+    }
+    // maximum over the 32 lanes of a half-wave: one full exchange, then exchanges that halve the number of values a lane
+    // carries (the lane with bit w set keeps the upper w values, its partner the lower ones); lane l ends with value l % 16
+#pragma unroll
+    for (int r = 0; r < 16; ++r) vals[r] = fmaxf(vals[r], __shfl_xor(vals[r], 16, kWave));
+#pragma unroll
+    for (int w = 8; w >= 1; w >>= 1) {
+        const bool up = (lane & w) != 0;
+#pragma unroll
+        for (int h = 0; h < w; ++h) {
+            const float keep = up ? vals[h + w] : vals[h];
+            const float send = up ? vals[h] : vals[h + w];
+            vals[h] = fmaxf(keep, __shfl_xor(send, w, kWave));
+        }
+    }
+    if ((lane & 16) == 0) {
+        const int r = lane % 16;
+        const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        if (row < M) segmax[(size_t)row * (K / DT_SEG) + (n0 + wn * 64) / DT_SEG] = vals[0];
+    }
 }
 
-// ---- per row (one wave each): the bound eps_t, then the candidates for the row maximum.
+// ---- per row (one wave each): the bound eps_t, then the candidates for the row maximum, found from the segment maxima
+// (only the segments that reach the limit are read from u~).
 // mode[row] = 1 marks a row that is recomputed as a whole (more candidates than the list holds).
-// RES: K <= 4096, the row of x and of u~ stay in registers between the passes (each is read once).
+// RES: K <= 4096, the row of x stays in registers between the passes (it is read once).
 template <bool RES>
 __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_t* __restrict__ X, const float* __restrict__ Ut,
-                                                                   int M, int K, const float* __restrict__ rowmaxR,
+                                                                   const float* __restrict__ segmax, int M, int K,
+                                                                   const float* __restrict__ rowmaxR,
                                                                    const unsigned* __restrict__ rho2_bits, float err_factor,
                                                                    double* __restrict__ eps, unsigned long long* __restrict__ amax_bits,
                                                                    int* __restrict__ ccount, uint16_t* __restrict__ cidx,
                                                                    int* __restrict__ mode) {
-    constexpr int NX = RES ? 8 : 1, NU = RES ? 16 : 1;
+    constexpr int NX = RES ? 8 : 1;
     const int lane = threadIdx.x % kWave, row = blockIdx.x * 4 + threadIdx.x / kWave;
     if (row >= M) return;
     const uint4* xs = reinterpret_cast<const uint4*>(X + (size_t)row * K);
-    const float4* us = reinterpret_cast<const float4*>(Ut + (size_t)row * K);
-    const int nxc = K / 8, nuc = K / 4;
+    const int nxc = K / 8, nseg = K / DT_SEG;
     uint4 xr[NX];
-    float4 ur[NU];
     if constexpr (RES) {
 #pragma unroll
         for (int i = 0; i < NX; ++i) xr[i] = lane + kWave * i < nxc ? xs[lane + kWave * i] : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-        for (int i = 0; i < NU; ++i) ur[i] = lane + kWave * i < nuc ? us[lane + kWave * i] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     }
     auto xchunk = [&](int i, int c) { return RES ? xr[i] : xs[c]; };
-    auto uchunk = [&](int i, int c) { return RES ? ur[i] : us[c]; };
-    const int xiters = RES ? NX : (nxc + kWave - 1) / kWave, uiters = RES ? NU : (nuc + kWave - 1) / kWave;
+    const int xiters = RES ? NX : (nxc + kWave - 1) / kWave;
 
     float s1 = 0.0f;
 #pragma unroll
@@ -321,55 +401,32 @@ __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_
     const float S = (rho * sqrtf(small2) * kBoundSlack + big) * kBoundSlack;       // >= sum_k |x_k| |R_kj| for every j
     const double e = (double)S * (double)err_factor;
     // row maximum of |u~| and the elements within 2 eps of it
+    const float* sm = segmax + (size_t)row * nseg;
     float mx = 0.0f;
-#pragma unroll
-    for (int i = 0; i < uiters; ++i) {
-        const int c = lane + kWave * i;
-        if (c < nuc) {
-            const float4 v = uchunk(RES ? i : 0, c);
-            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-        }
-    }
+    for (int c = lane; c < nseg; c += kWave) mx = fmaxf(mx, sm[c]);
     mx = wave_maxf(mx);
     int whole = 0, n = 0;
     if (S > 0.0f) {                              // otherwise x is all zero (or not finite) and there is nothing to decide
         const float lim = (float)((double)mx - 2.0 * e) * (1.0f - 1e-6f);       // rounded down: never misses a candidate
-        int mine = 0;
-#pragma unroll
-        for (int i = 0; i < uiters; ++i) {
-            const int c = lane + kWave * i;
-            if (c < nuc) {
-                const float4 v = uchunk(RES ? i : 0, c);
-                mine += (fabsf(v.x) >= lim) + (fabsf(v.y) >= lim) + (fabsf(v.z) >= lim) + (fabsf(v.w) >= lim);
-            }
-        }
-        n = wave_sumi(mine);
-        if (n > CAPC) {
-            whole = 1;
-            n = 0;
-        } else {
-            // at most CAPC hits in the row: the lanes that have one take their slots in lane order
-            int before = 0;
-            for (unsigned long long hits = __ballot(mine > 0); hits; hits &= hits - 1) {     // at most CAPC lanes
-                const int l = __ffsll((long long)hits) - 1;
-                const int m_l = __shfl(mine, l, kWave);
-                if (l < lane) before += m_l;
-            }
-            if (mine) {
-                int slot = before;
-#pragma unroll
-                for (int i = 0; i < uiters; ++i) {
-                    const int c = lane + kWave * i;
-                    if (c < nuc) {
-                        const float4 v = uchunk(RES ? i : 0, c);
-                        const float vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                        for (int d = 0; d < 4; ++d)
-                            if (fabsf(vv[d]) >= lim) cidx[(size_t)row * CAPC + slot++] = (uint16_t)(c * 4 + d);
-                    }
+        const float* ur = Ut + (size_t)row * K;
+        for (int base = 0; base < nseg && !whole; base += kWave) {
+            const int c = base + lane;
+            unsigned long long segs = __ballot(c < nseg && sm[c] >= lim);        // segments that hold a candidate
+            while (segs && !whole) {
+                const int seg = base + __ffsll((long long)segs) - 1;
+                segs &= segs - 1;
+                const bool hit = fabsf(ur[seg * DT_SEG + lane]) >= lim;
+                const unsigned long long hits = __ballot(hit);
+                const int cnt = __popcll(hits);
+                if (n + cnt > CAPC) {
+                    whole = 1;
+                } else {
+                    if (hit) cidx[(size_t)row * CAPC + n + __popcll(hits & ((1ull << lane) - 1ull))] = (uint16_t)(seg * DT_SEG + lane);
+                    n += cnt;
                 }
             }
         }
+        if (whole) n = 0;
     }
     if (lane == 0) {
         eps[row] = e;
@@ -644,6 +701,7 @@ DenseFastWs dense_fast_layout(int M, int K) {
     w.capf = ((32 + K / 64) + 7) & ~7;
     w.ut = take((size_t)M * K * sizeof(float));
     w.rt = take((size_t)K * K * sizeof(uint16_t));
+    w.segmax = take((size_t)M * (K / DT_SEG) * sizeof(float));
     w.rowmax = take((size_t)K * sizeof(float));
     w.scalars = take(256);
     w.eps = take((size_t)M * sizeof(double));
@@ -669,6 +727,7 @@ hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, con
     float* Ut = reinterpret_cast<float*>(base + L.ut);
     uint16_t* Rt = reinterpret_cast<uint16_t*>(base + L.rt);
     float* rowmax = reinterpret_cast<float*>(base + L.rowmax);
+    float* segmax = reinterpret_cast<float*>(base + L.segmax);
     unsigned* scalars = reinterpret_cast<unsigned*>(base + L.scalars);       // [0]: rho^2 as float bits
     double* eps = reinterpret_cast<double*>(base + L.eps);
     unsigned long long* amax = reinterpret_cast<unsigned long long*>(base + L.amax);
@@ -679,20 +738,21 @@ hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, con
     int* foffs = reinterpret_cast<int*>(base + L.foffs);
     int* mode = reinterpret_cast<int*>(base + L.mode);
     const double qmax = (double)((1 << (act_bits - 1)) - 1);
-    // ETA * m for the runs of the matrix instruction, 2^-24 for the fp32 store of u~
-    const float err_factor = (float)(ldexp(1.0, -21) * (kChunk / 16) + ldexp(1.0, -24));
+    // ETA * m for the runs of the matrix instruction, 2^-24 for each of the GROUP - 1 fp32 additions of a group and for the
+    // fp32 store of u~
+    const float err_factor = (float)(ldexp(1.0, -21) * (kChunk / 16) + ldexp(1.0, -24) * kGroup);
 
     hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, R, K, rowmax, static_cast<unsigned*>(nullptr), scalars, 64);
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3(K / 64, K / 64), dim3(256), 0, st, R, K, Rt);
     hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, Rt, K, static_cast<float*>(nullptr), scalars,
                        static_cast<unsigned*>(nullptr), 0);
     const int tiles_m = (M + DT_M - 1) / DT_M, tiles_n = K / DT_N;
-    hipLaunchKernelGGL(dense_rotate_bf16_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, tiles_m, tiles_n);
+    hipLaunchKernelGGL(dense_rotate_bf16_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, segmax, tiles_m, tiles_n);
     if (K <= 4096)
-        hipLaunchKernelGGL(dense_row_candidates_kernel<true>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, M, K, rowmax, scalars,
+        hipLaunchKernelGGL(dense_row_candidates_kernel<true>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax, scalars,
                            err_factor, eps, amax, ccount, cidx, mode);
     else
-        hipLaunchKernelGGL(dense_row_candidates_kernel<false>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, M, K, rowmax, scalars,
+        hipLaunchKernelGGL(dense_row_candidates_kernel<false>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax, scalars,
                            err_factor, eps, amax, ccount, cidx, mode);
     hipLaunchKernelGGL(dense_exact_amax_kernel, dim3((unsigned)(((long)M * CAPC + 255) / 256)), dim3(256), 0, st, X, Rt, M, K,
                        ccount, cidx, amax);

@@ -52,7 +52,7 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
 // recomputation of the undecided elements (symmetric quantizer without pre-scale only; dense_fast_applies says when).
 // Bit-identical codes and scales.  ws: dense_fast_layout(M, K).total bytes.
 struct DenseFastWs {
-    size_t ut, rt, rowmax, scalars, eps, amax, ccount, cidx, fcount, fidx, foffs, mode, total;
+    size_t ut, rt, segmax, rowmax, scalars, eps, amax, ccount, cidx, fcount, fidx, foffs, mode, total;
     int capf;       // undecided elements a row's list holds
 };
 DenseFastWs dense_fast_layout(int M, int K);
