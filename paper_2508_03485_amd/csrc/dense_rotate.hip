@@ -13,13 +13,16 @@
 // as a whole.  Nothing depends on how the error is distributed - only on the bound, which is derived below from a
 // stated model of the matrix instruction's rounding and checked by a GPU test against the exact values.
 //
-// Error bound.  A run of m = CHUNK / 16 chained v_mfma_f32_32x32x16_bf16 starts from a zero accumulator and is then
-// added to an fp64 accumulator (exact to 2^-53), so only the roundings inside a run count.  Model of one instruction,
-// D = C + sum_{i<16} a_i b_i: every addend is aligned to the largest one and truncated below 2^-26 of it, the sum is
-// rounded or truncated to 24 bits: |D - exact| <= (17 * 2^-26 + 2^-23) * (|C| + sum |a_i b_i|) < ETA * (|C| + sum |a_i b_i|),
+// Error bound.  A run of m = CHUNK / 16 chained v_mfma_f32_32x32x16_bf16 starts from a zero accumulator.  Model of one
+// instruction, D = C + sum_{i<16} a_i b_i: every addend is aligned to the largest one and truncated below 2^-26 of it, the
+// sum is rounded or truncated to 24 bits: |D - exact| <= (17 * 2^-26 + 2^-23) * (|C| + sum |a_i b_i|) < ETA * (|C| + sum |a_i b_i|),
 // ETA = 2^-21 (measured on this chip: at most 5.8 * 2^-24 over adversarial exponent mixes).  Over a run, |C| is at most
-// the sum of |a b| of the run's earlier steps, so the run's error is at most ETA * m * S_run, and the whole element's
-// ETA * m * S, S = sum_k |x_k| |R_kj|.  S is bounded per row without touching R's columns one by one:
+// the sum of |a b| of the run's earlier steps, so the run's error is at most ETA * m * S_run.  GROUP runs are then summed
+// in fp32 by ordinary vector additions (round to nearest: each errs by at most 2^-24 of its result, which is at most the
+// group's sum of |a b|): (GROUP - 1) * 2^-24 * S_group.  Groups are added to an fp64 accumulator (exact to 2^-53).  In all
+//   |u~ - u| <= (ETA * m + (GROUP - 1) * 2^-24) * S,   S = sum_k |x_k| |R_kj|
+// (second-order terms are far below the slack with which S itself is evaluated), and S is bounded per row without touching
+// R's columns one by one:
 //   S <= rho * sqrt(sum_{|x_k| < theta} x_k^2)  +  sum_{|x_k| >= theta} |x_k| * max_j |R_kj|
 // (Cauchy-Schwarz on the many small entries, rho = max_j ||R[:, j]||_2; the few large ones - salient channels - term by
 // term), theta = 4 * mean |x|.  u~ is stored as fp32: one more rounding, 2^-24 |u~| <= 2^-24 S.
@@ -121,20 +124,21 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __r
 // registers -> LDS: stage s is loaded two iterations before it is stored to one of three LDS buffers and three before
 // it is multiplied.  LDS rows are padded to 144 bytes so that the 16-byte fragment reads of 16 consecutive rows fall
 // on distinct banks.
-// Accumulation has three levels.  A run of CHUNK = 64 k (one stage) is four chained matrix instructions that start on
+// Accumulation has three levels.  A run of CHUNK = 32 k (half a stage) is two chained matrix instructions that start on
 // a zero accumulator (the instruction's constant-zero addend, no clearing).  The fp32 tiles of a finished run are
-// added - one vector fp32 addition per value, rounded to nearest - to fp32 group tiles, GROUP runs to a group, and a
-// finished group is added to the fp64 tiles.  Both additions are done during the following stage, spread between its
-// matrix instructions, so they issue while the matrix cores work; the conversion to fp64 (the expensive part: twelve
-// issue cycles per value against eight cycles of matrix work per value and run) happens once per group only.
+// added - one vector fp32 addition per value, rounded to nearest, eight times more accurate than the addition inside
+// the matrix instruction - to fp32 group tiles, GROUP = 8 runs (256 k) to a group, and a finished group is added to the
+// fp64 tiles.  These additions are spread between the matrix instructions of the following steps, so they issue while
+// the matrix cores work; the conversion to fp64 (the expensive part: twelve issue cycles per value against eight
+// cycles of matrix work per value and 64 k) happens once per group only.
 // Besides u~ the kernel writes, per row and 64-column segment (a wave's width), the maximum of |u~| (segmax): the
 // search for the row maximum then reads one value per segment instead of the whole row.
 // (X, Rt and Ut are deliberately not declared __restrict__: with that promise the compiler moves the prefetch loads past
 // the compiler barrier that keeps them ahead of the arithmetic, down to their LDS stores.)
 constexpr int DT_M = 128, DT_N = 128, DT_K = 64, DT_ROW = 144, DT_BUF = DT_M * DT_ROW;
 constexpr int DT_SEG = 64;          // columns per segment maximum
-constexpr int kChunk = DT_K;        // run length of the fp32 accumulation inside the matrix instruction
-constexpr int kGroup = 4;           // runs per fp32 group sum
+constexpr int kChunk = 32;          // run length of the fp32 accumulation inside the matrix instruction
+constexpr int kGroup = 8;           // runs per fp32 group sum
 
 // fragments of one 16-k step of a wave: its 32 rows of the x tile, columns 0..31 and 32..63 of its R tile
 __device__ __forceinline__ void read_fragments(const unsigned char* A, const unsigned char* B, int s, v8s (&f)[3]) {
@@ -142,9 +146,11 @@ __device__ __forceinline__ void read_fragments(const unsigned char* A, const uns
     f[1] = *reinterpret_cast<const v8s*>(B + s * 32);
     f[2] = *reinterpret_cast<const v8s*>(B + 32 * DT_ROW + s * 32);
 }
-// One stage: its run of matrix instructions into fresh fp32 tiles, and - a quarter after each step - the bookkeeping
-// of the previous stage's tiles `prev`: FIRST: they open a new group (the group tiles take them as they are), else they
-// are added to the group tiles; FLUSH (the previous stage closed a group): the group tiles then join the fp64 tiles.
+// One stage = two runs of CHUNK = 32 k: steps 0, 1 accumulate into fresh fp32 tiles A, steps 2, 3 into fresh tiles B.
+// The bookkeeping of finished runs is spread between the matrix instructions, eight values after each: during steps 0, 1
+// the B tiles of the previous stage (`prev`) are added to the group tiles and, if they close a group (FLUSH), the group
+// tiles join the fp64 tiles; during steps 2, 3 this stage's A tiles are added to the group tiles or, if they open a
+// group (FIRST), replace them.
 // The fragments of step s + 1 are read from LDS before the matrix instructions of step s are issued (LDS latency is
 // longer than a matrix instruction); fr holds those of step 0 on entry and those of the next stage's step 0 (buffer
 // An / Bn, complete since the previous barrier) on return.
@@ -156,7 +162,9 @@ __device__ __forceinline__ void multiply_stage(const unsigned char* A, const uns
                                                const unsigned char* Bn, v8s (&fr)[3], v4u (&st)[4], unsigned char* const (&dst)[4],
                                                const unsigned char* const (&src)[4], size_t goff, double (&wide)[2][16],
                                                v16f (&group)[2], v16f (&prev)[2]) {
-    v16f acc[2];
+    static_assert(DT_K == 2 * kChunk && kChunk == 32, "two runs of two matrix instructions per stage");
+    const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    v16f ta[2], tb[2];
     v8s fo[3];                       // fragments of the odd steps
 #pragma unroll
     for (int s = 0; s < DT_K / 16; ++s) {
@@ -171,25 +179,29 @@ __device__ __forceinline__ void multiply_stage(const unsigned char* A, const uns
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const v8s b = s % 2 == 0 ? fr[1 + j] : fo[1 + j];
-            if (s == 0) {
-                const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
-            } else {
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
-            }
-            constexpr int PER = 16 / (DT_K / 16);          // values of a tile of `prev` handled after each instruction
+            if (s == 0) ta[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
+            if (s == 1) ta[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, ta[j], 0, 0, 0);
+            if (s == 2) tb[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, zero, 0, 0, 0);
+            if (s == 3) tb[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, tb[j], 0, 0, 0);
+            // slot 0..3 of this half of the stage: tile slot / 2, values 8 (slot % 2) ... + 7 (tile 0 first: its last
+            // matrix instruction was issued before tile 1's)
+            const int slot = 2 * (s % 2) + j, tile = slot / 2;
 #pragma unroll
-            for (int i = 0; i < PER; ++i) {
-                const int r = s * PER + i;
-                const float g = FIRST ? prev[j][r] : group[j][r] + prev[j][r];
-                group[j][r] = g;
-                if (FLUSH) wide[j][r] += (double)g;
+            for (int i = 0; i < 8; ++i) {
+                const int r = 8 * (slot % 2) + i;
+                if (s < 2) {
+                    const float g = group[tile][r] + prev[tile][r];
+                    group[tile][r] = g;
+                    if (FLUSH) wide[tile][r] += (double)g;
+                } else {
+                    group[tile][r] = FIRST ? ta[tile][r] : group[tile][r] + ta[tile][r];
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    prev[0] = acc[0];
-    prev[1] = acc[1];
+    prev[0] = tb[0];
+    prev[1] = tb[1];
 }
 
 __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K, float* Ut,
@@ -266,10 +278,10 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
     v8s fr[3];
     read_fragments(&As[a_off], &Bs[b_off], 0, fr);
     int b0 = 0, b1 = 1, b2 = 2;                          // LDS buffers of stages kb, kb + 1, kb + 2
-    // Stage kb handles the tiles of stage kb - 1 (`prev`).  With GROUP = 4: stage 4 i + 1 opens group i with run 4 i,
-    // stages 4 i + 2, 4 i + 3 add runs 4 i + 1, 4 i + 2, stage 4 i + 4 adds run 4 i + 3 and flushes the group.  Stage 0
-    // has nothing to handle: it "flushes" the zero-initialised tiles, which changes nothing.
-    static_assert(kGroup == 4, "the loop body below is written out for groups of four runs");
+    // A group is the eight runs of four stages: stage 4 i opens group i with its first run (FIRST) and, before that, adds
+    // the last run of stage 4 i - 1 to group i - 1 and flushes it (FLUSH).  Stage 0 has nothing to flush: it "flushes" the
+    // zero-initialised tiles, which changes nothing.
+    static_assert(kGroup == 8 && 2 * kChunk == DT_K, "the loop body below is written out for groups of four stages");
     // two stages: the first multiplies from b0 and refills b2 from the even registers (stage KB + 2, loaded two iterations
     // ago; they then take stage KB + 4), the second multiplies from b1 and refills b0, the buffer that stage KB just
     // left, from the odd ones (a macro, not a lambda: captured register arrays would be spilled to scratch memory)
@@ -294,17 +306,16 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
     }
     int kb = 0;
     for (; kb + 3 < nk; kb += 4) {
-        LRQ_DENSE_STAGE_PAIR(false, true, true, false, kb)
+        LRQ_DENSE_STAGE_PAIR(true, true, false, false, kb)
         LRQ_DENSE_STAGE_PAIR(false, false, false, false, kb + 2)
     }
-    if (kb < nk) LRQ_DENSE_STAGE_PAIR(false, true, true, false, kb)      // K % 256 == 128: two more stages
+    if (kb < nk) LRQ_DENSE_STAGE_PAIR(true, true, false, false, kb)      // K % 256 == 128: two more stages
 #undef LRQ_DENSE_STAGE_PAIR
-    // the last run, and whatever its group holds
-    const bool opens = (nk - 1) % kGroup == 0;
+    // the last run, and what its group holds
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) wide[j][r] += (double)(opens ? prev[j][r] : group[j][r] + prev[j][r]);
+        for (int r = 0; r < 16; ++r) wide[j][r] += (double)(group[j][r] + prev[j][r]);
 
     // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
     float vals[16];                                      // per row that this lane touches: max over its two columns
