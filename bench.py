@@ -382,11 +382,30 @@ def main():
         fl = sum(2.0 * l["spec"].M * l["spec"].K * l["spec"].K for _, l in dense)
         t = sum(rot_ms[li] for li, _ in dense)
         tf = fl / (t * 1e-3) / 1e12
-        roofline_dense = dict(bound="mfma", kernel="dense rotation + quantize (bf16 MFMA product, fp64 accumulation of 64-k runs, "
-                              "error bound, exact recomputation of undecided elements)", achieved=round(tf, 2),
+        roofline_dense = dict(bound="mfma", kernel="dense rotation + quantize (bf16 MFMA product in 32-k runs, fp32 group sums, "
+                              "fp64 totals, error bound, exact recomputation of undecided elements)", achieved=round(tf, 2),
                               peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=round(tf / BF16_MFMA_PEAK_TFLOPS, 4), traffic=None,
                               avg_launch_ms=round(t / len(dense), 4),
-                              note="time of the whole call (nine kernels), flops of the product alone")
+                              note="time of the whole call (ten kernels), flops of the product alone")
+        # what the error bound left undecided in the first such layer's last call, and how far the approximate product
+        # really is from the fp64 evaluation (LRQ_ROT_DENSE_F64 leaves u in fp64 at the head of its workspace)
+        l0 = dense[0][1]
+        s0 = l0["spec"]
+        rot64 = lrq.Rotation("dense_f64", 0, l0["rot"].R)
+        ws64 = torch.empty(lrq.ars_workspace_bytes(s0.M, s0.K, rot64, s0.a_bits), dtype=torch.uint8, device=dev)
+        lrq.ars_rotate_quant(l0["X"][0], rot64, s0.a_bits, workspace=ws64)
+        lrq.ars_rotate_quant(l0["X"][0], l0["rot"], s0.a_bits, workspace=l0["aws"])
+        torch.cuda.synchronize()
+        ut, eps, cnt, whole = lrq.ars_dense_diagnostics(l0["aws"], s0.M, s0.K)
+        u64 = ws64[:s0.M * s0.K * 8].view(torch.float64).view(s0.M, s0.K)
+        ratio = 0.0
+        for r0 in range(0, s0.M, 4096):           # in slabs: the difference in fp64 would double the footprint otherwise
+            r1 = min(r0 + 4096, s0.M)
+            ratio = max(ratio, float(((ut[r0:r1].double() - u64[r0:r1]).abs() / eps[r0:r1].view(-1, 1)).max().item()))
+        roofline_dense["diagnostics"] = dict(layer=s0.name, undecided_fraction=round(float(cnt.sum().item()) / (s0.M * s0.K), 6),
+                                             max_undecided_per_row=int(cnt.max().item()), rows_recomputed_whole=int(whole.sum().item()),
+                                             max_error_over_bound=round(ratio, 4))
+        del ws64, u64
 
     out = dict(metric="fused W-TLQ/A-ARS qlinear TOPS + % int8 MFMA peak; rotate+quant HBM GB/s",
                value=round(tops, 2), unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
