@@ -95,6 +95,9 @@ def parse():
     ap.add_argument("--structured", type=int, default=0, metavar="B",
                     help="run the layers that take the dense outlier-aware rotation with its structured form "
                          "X.R1.P.R2 instead (block size B, seeded block rotations and permutation)")
+    ap.add_argument("--no-prepared-rotation", action="store_true",
+                    help="dense rotations: let every call derive R's transpose and statistics itself instead of handing over "
+                         "the result of lrq_ars_dense_prepare (computed once, untimed, like the weight packing)")
     ap.add_argument("--clocks", action="store_true",
                     help="also sample the shader clock (rocm-smi) while single kernels run back to back for ~2 s each and "
                          "report it under 'sustained_clocks' (the int8 matrix peak scales with that clock)")
@@ -167,6 +170,7 @@ def main():
     layers = []
     shape_cache = {}
     pack_ms = 0.0
+    prepare_ms = 0.0
     for s in specs:
         # config 5 re-uses one set of activations per distinct shape (seeded by the first block that has it): the
         # kernels' work does not depend on the values, and 140 separate 8192-token inputs would not fit the run time
@@ -195,6 +199,18 @@ def main():
             shape_cache[skey] = (X, w, R)
         X, w, R = shape_cache[skey]
         rot = R if isinstance(R, lrq.Rotation) else lrq.Rotation(s.rotation, s.had_block, R)
+        if (rot.kind == "dense" and not args.no_prepared_rotation and not args.smooth and not args.asym and s.M > 64
+                and lrq.lib().lrq_ars_dense_prepared_bytes(s.K) > 0):
+            # offline like the weight packing: the rotation is fixed at calibration time, so is everything derived from it
+            if ("prepared", skey) not in shape_cache:
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                shape_cache[("prepared", skey)] = lrq.ars_dense_prepare(R)
+                e1.record()
+                torch.cuda.synchronize()
+                prepare_ms += e0.elapsed_time(e1)
+            rot.prepared = shape_cache[("prepared", skey)]
         if args.smooth:
             if "inv" not in shape_cache.setdefault(("smooth", skey), {}):
                 Wd = torch.from_numpy(synth.make_weights(s.N, s.K, s.key)).to(dev)
@@ -418,6 +434,7 @@ def main():
                                      5: "config5: 28-block PixArt-style stack, W3A4, per-layer ARS"}[cfg],
                            layers=len(layers), ops_per_step=total_ops, buffer_copies=copies,
                            outlier_rotation=(f"structured R1.P.R2, block {args.structured}" if args.structured else "dense K x K"),
+                           dense_rotation_prepared_offline=any(l["rot"].prepared is not None for l in layers),
                            smoothing_prescale=bool(args.smooth), hip_graph=bool(args.graph),
                            tlq_lower_clip=bool(args.lower_clip), packed_4bit_activation_codes=bool(args.packed4),
                            fp8_operands=bool(args.fp8),
@@ -426,7 +443,8 @@ def main():
                            step=("lrq_qlinear_levels per layer: rotate + quantize + TLQ decode + bf16 MFMA GEMM + rescale, bf16 out" if args.levels else
                                  "lrq_qlinear per layer: rotate + quantize + TLQ decode + int8 MFMA GEMM + rescale, bf16 out")),
                roofline=roofline, roofline_rotate_quant=roofline_rq, roofline_dense_rotation=roofline_dense, per_layer=per_layer,
-               offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), input_generation_s=round(gen_s, 1)))
+               offline=dict(tlq_quantize_pack_ms=round(pack_ms, 2), dense_prepare_ms=round(prepare_ms, 3),
+                            input_generation_s=round(gen_s, 1)))
 
     if hot:
         out["hot_cache"] = hot

@@ -84,6 +84,9 @@ typedef struct {
     const float* prescale; /* any kind: NULL, or fp32 [K] (device) multiplied into x channel by channel before the
                               rotation - the reciprocal smoothing factor of lrq_smooth_factor (Experiment,
                               "Implementation Details": difficulty migration from activations to weights)     */
+    const void* R_prepared; /* LRQ_ROT_DENSE: NULL, or the device buffer lrq_ars_dense_prepare filled from this R (a rotation
+                              is fixed at calibration time: its transpose and the statistics the error bound needs are then
+                              computed once instead of in every call).  Must be NULL or refilled if R's contents change.  */
 } lrq_rotation;
 
 /*
@@ -215,6 +218,19 @@ int lrq_ars_rotate_quant(void* stream, const void* X, int M, int K, const lrq_ro
  * M <= 64, K % 128 != 0, K > 16384, M * K >= 2^31; also whenever a pre-scale or the zero-point form is used).
  */
 int lrq_ars_dense_diagnostics(int M, int K, size_t offsets[4]);
+
+/*
+ * Preprocessing of a dense rotation matrix (Method, ARS case equation, outlier-aware branch: R is computed offline, so
+ * what the run-time call derives from R alone can be computed offline too).  lrq_ars_dense_prepare writes R's transpose
+ * and the per-row / per-column statistics of the error bound into `prepared` (device, at least
+ * lrq_ars_dense_prepared_bytes(K) bytes, 256-byte aligned); a lrq_rotation of kind LRQ_ROT_DENSE whose R_prepared points
+ * there skips that work in lrq_ars_rotate_quant / lrq_qlinear (three small launches per call) and gives the same codes.
+ * lrq_ars_dense_prepared_bytes returns 0 for a K the matrix-core evaluation does not serve (K % 128 != 0 or K > 16384);
+ * lrq_ars_dense_prepare then returns LRQ_EUNSUPPORTED.  R: bf16 [K, K] device.  Errors: LRQ_EINVAL (null pointer,
+ * K <= 0, misaligned or short buffer), LRQ_EHIP.
+ */
+size_t lrq_ars_dense_prepared_bytes(int K);
+int lrq_ars_dense_prepare(void* stream, const void* R, int K, void* prepared, size_t prepared_bytes);
 
 /* Workspace of lrq_qlinear (bytes): activation codes, scales and rotation scratch. */
 size_t lrq_workspace_bytes(int M, int N, int K, const lrq_rotation* rot, int act_bits);

@@ -25,7 +25,7 @@ EXPORTS = ("lrq_status_string", "lrq_version", "lrq_tlq_codes_bytes", "lrq_tlq_g
            "lrq_qlinear_asym", "lrq_ars_build_workspace_bytes", "lrq_ars_build_rotation",
            "lrq_fluctuation_workspace_bytes", "lrq_fluctuation_metric", "lrq_ars_select",
            "lrq_smooth_workspace_bytes", "lrq_smooth_factor", "lrq_tlq_quantize_pack_clip", "lrq_qgemm_levels",
-           "lrq_qlinear_levels", "lrq_ars_dense_diagnostics", "lrq_ars_workspace_bytes_packed4",
+           "lrq_qlinear_levels", "lrq_ars_dense_diagnostics", "lrq_ars_dense_prepared_bytes", "lrq_ars_dense_prepare", "lrq_ars_workspace_bytes_packed4",
            "lrq_ars_rotate_quant_packed4", "lrq_qgemm_packed4", "lrq_workspace_bytes_packed4", "lrq_qlinear_packed4",
            "lrq_ars_rotate_quant_fp8", "lrq_qgemm_fp8", "lrq_qlinear_fp8", "lrq_init", "lrq_static_scratch_bytes", "lrq_qlinear_static")
 
@@ -39,7 +39,7 @@ class LrqError(RuntimeError):
 class _Rotation(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_int), ("had_block", ctypes.c_int), ("R", ctypes.c_void_p),
                 ("block", ctypes.c_int), ("R1", ctypes.c_void_p), ("perm", ctypes.c_void_p), ("R2", ctypes.c_void_p),
-                ("prescale", ctypes.c_void_p)]
+                ("prescale", ctypes.c_void_p), ("R_prepared", ctypes.c_void_p)]
 
 
 class _TlqWeight(ctypes.Structure):
@@ -81,6 +81,10 @@ def lib() -> ctypes.CDLL:
     L.lrq_ars_rotate_quant.argtypes = [vp, vp, ci, ci, ctypes.POINTER(_Rotation), ci, vp, vp, vp, sz]
     L.lrq_ars_dense_diagnostics.restype = ci
     L.lrq_ars_dense_diagnostics.argtypes = [ci, ci, ctypes.POINTER(sz * 4)]
+    L.lrq_ars_dense_prepared_bytes.restype = sz
+    L.lrq_ars_dense_prepared_bytes.argtypes = [ci]
+    L.lrq_ars_dense_prepare.restype = ci
+    L.lrq_ars_dense_prepare.argtypes = [vp, vp, ci, vp, sz]
     L.lrq_ars_workspace_bytes_packed4.restype = sz
     L.lrq_ars_workspace_bytes_packed4.argtypes = [ci, ci, ctypes.POINTER(_Rotation)]
     L.lrq_ars_rotate_quant_packed4.restype = ci
@@ -161,6 +165,7 @@ class Rotation:
     perm: object = None     # torch int32 [K] on the device (gather form)
     R2: object = None       # torch bf16 [K/block, block, block] on the device
     prescale: object = None # any kind: torch fp32 [K] on the device multiplied into x before the rotation
+    prepared: object = None # kind == "dense": torch uint8 buffer filled by ars_dense_prepare(R), or None
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -173,7 +178,7 @@ class Rotation:
             kinds = {"none": LRQ_ROT_NONE, "hadamard": LRQ_ROT_HADAMARD, "dense": LRQ_ROT_DENSE,
                      "blockperm": LRQ_ROT_BLOCKPERM, "dense_f64": LRQ_ROT_DENSE_F64}
             cs = _Rotation(kinds[self.kind], int(self.had_block), _ptr(self.R), int(self.block), _ptr(self.R1),
-                           _ptr(self.perm), _ptr(self.R2), _ptr(self.prescale))
+                           _ptr(self.perm), _ptr(self.R2), _ptr(self.prescale), _ptr(self.prepared))
             object.__setattr__(self, "_cs", cs)
         return cs
 
@@ -388,6 +393,19 @@ def qlinear_fp8(X, rot: Rotation, w: TLQWeight, bias=None, out_dtype=None, out=N
     st = lib().lrq_qlinear_fp8(_stream(), _ptr(X), M, K, ctypes.byref(r), ctypes.byref(cs), _ptr(bias), _out_code(out_dtype),
                                _ptr(out), _ptr(workspace), workspace.numel())
     _check(st, "lrq_qlinear_fp8")
+    return out
+
+
+def ars_dense_prepare(R):
+    """lrq_ars_dense_prepare: the preprocessing of a dense rotation matrix R (bf16 [K, K] on the device), to be kept in
+    Rotation.prepared for as long as R's contents stay the same.  Returns a uint8 device tensor."""
+    import torch
+    K = R.shape[0]
+    need = lib().lrq_ars_dense_prepared_bytes(K)
+    if need == 0:
+        raise LrqError(LRQ_EUNSUPPORTED, "lrq_ars_dense_prepared_bytes")
+    out = torch.empty(need, dtype=torch.uint8, device=R.device)
+    _check(lib().lrq_ars_dense_prepare(_stream(), _ptr(R), K, _ptr(out), need), "lrq_ars_dense_prepare")
     return out
 
 

@@ -53,11 +53,6 @@ __device__ __forceinline__ float wave_maxf(float v) {
     for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
     return v;
 }
-__device__ __forceinline__ int wave_sumi(int v) {
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
 
 // ---- statistics of a K x K bf16 matrix A, one workgroup per row: maxabs[row] = max_j |A[row, j]| (if maxabs) and
 // *sumsq_max = max over rows of sum_j A[row, j]^2 (if sumsq_max; float bits, atomic max - zero it first).  Run on R it
@@ -711,10 +706,10 @@ DenseFastWs dense_fast_layout(int M, int K) {
     auto take = [&](size_t bytes) { const size_t at = o; o += round256(bytes); return at; };
     w.capf = ((32 + K / 64) + 7) & ~7;
     w.ut = take((size_t)M * K * sizeof(float));
-    w.rt = take((size_t)K * K * sizeof(uint16_t));
-    w.segmax = take((size_t)M * (K / DT_SEG) * sizeof(float));
+    w.rt = take((size_t)K * K * sizeof(uint16_t));          // rt | rowmax | scalars: the layout of dense_prepared_layout
     w.rowmax = take((size_t)K * sizeof(float));
     w.scalars = take(256);
+    w.segmax = take((size_t)M * (K / DT_SEG) * sizeof(float));
     w.eps = take((size_t)M * sizeof(double));
     w.amax = take((size_t)M * sizeof(unsigned long long));
     w.ccount = take((size_t)M * sizeof(int));
@@ -731,15 +726,45 @@ bool dense_fast_applies(int M, int K, bool zero_point, bool prescale) {
     return !zero_point && !prescale && M > 64 && K % 128 == 0 && K <= 16384 && (size_t)M * K < ((size_t)1 << 31);
 }
 
-hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K, int act_bits,
-                                          void* ws, int8_t* q, float* scale) {
+// What the fast evaluation derives from R alone: Rt bf16 [K, K] | max_j |R_kj| float [K] | scalars (256 bytes: rho^2).
+struct DensePrepared {
+    size_t rt, rowmax, scalars, total;
+};
+static DensePrepared dense_prepared_layout(int K) {
+    DensePrepared p;
+    p.rt = 0;
+    p.rowmax = round256((size_t)K * K * sizeof(uint16_t));
+    p.scalars = p.rowmax + round256((size_t)K * sizeof(float));
+    p.total = p.scalars + 256;
+    return p;
+}
+size_t dense_prepared_bytes(int K) { return dense_prepared_layout(K).total; }
+
+hipError_t launch_dense_prepare(hipStream_t st, const uint16_t* R, int K, void* prepared) {
+    const DensePrepared P = dense_prepared_layout(K);
+    unsigned char* base = static_cast<unsigned char*>(prepared);
+    uint16_t* Rt = reinterpret_cast<uint16_t*>(base + P.rt);
+    float* rowmax = reinterpret_cast<float*>(base + P.rowmax);
+    unsigned* scalars = reinterpret_cast<unsigned*>(base + P.scalars);       // [0]: rho^2 as float bits
+    hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, R, K, rowmax, static_cast<unsigned*>(nullptr), scalars, 64);
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3(K / 64, K / 64), dim3(256), 0, st, R, K, Rt);
+    hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, Rt, K, static_cast<float*>(nullptr), scalars,
+                       static_cast<unsigned*>(nullptr), 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, const void* prepared, int M, int K,
+                                          int act_bits, void* ws, int8_t* q, float* scale) {
     const DenseFastWs L = dense_fast_layout(M, K);
     unsigned char* base = static_cast<unsigned char*>(ws);
     float* Ut = reinterpret_cast<float*>(base + L.ut);
-    uint16_t* Rt = reinterpret_cast<uint16_t*>(base + L.rt);
-    float* rowmax = reinterpret_cast<float*>(base + L.rowmax);
+    // R's transpose and statistics: the caller's prepared copy, or the workspace's own (same layout at L.rt)
+    const DensePrepared P = dense_prepared_layout(K);
+    const unsigned char* pbase = prepared ? static_cast<const unsigned char*>(prepared) : base + L.rt;
+    const uint16_t* Rt = reinterpret_cast<const uint16_t*>(pbase + P.rt);
+    const float* rowmax = reinterpret_cast<const float*>(pbase + P.rowmax);
+    const unsigned* scalars = reinterpret_cast<const unsigned*>(pbase + P.scalars);       // [0]: rho^2 as float bits
     float* segmax = reinterpret_cast<float*>(base + L.segmax);
-    unsigned* scalars = reinterpret_cast<unsigned*>(base + L.scalars);       // [0]: rho^2 as float bits
     double* eps = reinterpret_cast<double*>(base + L.eps);
     unsigned long long* amax = reinterpret_cast<unsigned long long*>(base + L.amax);
     int* ccount = reinterpret_cast<int*>(base + L.ccount);
@@ -753,10 +778,10 @@ hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, con
     // fp32 store of u~
     const float err_factor = (float)(ldexp(1.0, -21) * (kChunk / 16) + ldexp(1.0, -24) * kGroup);
 
-    hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, R, K, rowmax, static_cast<unsigned*>(nullptr), scalars, 64);
-    hipLaunchKernelGGL(transpose_bf16_kernel, dim3(K / 64, K / 64), dim3(256), 0, st, R, K, Rt);
-    hipLaunchKernelGGL(matrix_row_stats_kernel, dim3(K), dim3(256), 0, st, Rt, K, static_cast<float*>(nullptr), scalars,
-                       static_cast<unsigned*>(nullptr), 0);
+    if (!prepared) {       // R's transpose and statistics: computed here, into the same layout inside the workspace
+        const hipError_t e = launch_dense_prepare(st, R, K, base + L.rt);
+        if (e != hipSuccess) return e;
+    }
     const int tiles_m = (M + DT_M - 1) / DT_M, tiles_n = K / DT_N;
     hipLaunchKernelGGL(dense_rotate_bf16_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, segmax, tiles_m, tiles_n);
     if (K <= 4096)

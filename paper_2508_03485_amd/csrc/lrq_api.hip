@@ -44,6 +44,7 @@ int check_rotation(const lrq_rotation* rot, int K) {
         case LRQ_ROT_DENSE:
         case LRQ_ROT_DENSE_F64:
             if (!rot->R || !aligned16(rot->R)) return LRQ_EINVAL;
+            if (rot->R_prepared && (reinterpret_cast<uintptr_t>(rot->R_prepared) & 255) != 0) return LRQ_EINVAL;
             return K % 64 == 0 ? LRQ_OK : LRQ_EUNSUPPORTED;
         case LRQ_ROT_BLOCKPERM:
             if (!rot->R1 || !rot->R2 || !rot->perm || rot->block <= 0) return LRQ_EINVAL;
@@ -139,7 +140,8 @@ int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rota
             break;
         default:
             if (rot->kind == LRQ_ROT_DENSE && lrq::dense_fast_applies(M, K, zero != nullptr, rot->prescale != nullptr))
-                e = lrq::launch_dense_rotate_quant_fast(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits, ws, q, scale);
+                e = lrq::launch_dense_rotate_quant_fast(st, x, static_cast<const uint16_t*>(rot->R), rot->R_prepared, M, K, act_bits,
+                                                        ws, q, scale);
             else
                 e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
                                                    static_cast<double*>(ws), q, scale, zero, rot->prescale);
@@ -220,6 +222,21 @@ size_t lrq_ars_workspace_bytes(int M, int K, const lrq_rotation* rot, int act_bi
     (void)act_bits;
     if (M <= 0 || K <= 0) return 0;
     return ars_layout(M, K, rot).total;
+}
+
+size_t lrq_ars_dense_prepared_bytes(int K) {
+    if (K <= 0 || K % 128 != 0 || K > 16384) return 0;
+    return lrq::dense_prepared_bytes(K);
+}
+
+int lrq_ars_dense_prepare(void* stream, const void* R, int K, void* prepared, size_t prepared_bytes) {
+    if (!R || !prepared || K <= 0) return LRQ_EINVAL;
+    const size_t need = lrq_ars_dense_prepared_bytes(K);
+    if (need == 0) return LRQ_EUNSUPPORTED;
+    if (prepared_bytes < need || (reinterpret_cast<uintptr_t>(prepared) & 255) != 0 || (reinterpret_cast<uintptr_t>(R) & 15) != 0)
+        return LRQ_EINVAL;
+    const hipError_t e = lrq::launch_dense_prepare(static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(R), K, prepared);
+    return e == hipSuccess ? LRQ_OK : LRQ_EHIP;
 }
 
 int lrq_ars_dense_diagnostics(int M, int K, size_t offsets[4]) {

@@ -52,13 +52,17 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
 // recomputation of the undecided elements (symmetric quantizer without pre-scale only; dense_fast_applies says when).
 // Bit-identical codes and scales.  ws: dense_fast_layout(M, K).total bytes.
 struct DenseFastWs {
-    size_t ut, rt, segmax, rowmax, scalars, eps, amax, ccount, cidx, fcount, fidx, foffs, mode, total;
+    size_t ut, rt, rowmax, scalars, segmax, eps, amax, ccount, cidx, fcount, fidx, foffs, mode, total;
     int capf;       // undecided elements a row's list holds
 };
 DenseFastWs dense_fast_layout(int M, int K);
 bool dense_fast_applies(int M, int K, bool zero_point, bool prescale);
-hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, int M, int K, int act_bits,
-                                          void* ws, int8_t* q, float* scale);
+// prepared: NULL, or dense_prepared_bytes(K) bytes that launch_dense_prepare filled from this R (its transpose and the
+// statistics the error bound needs): then the call skips that preprocessing.
+hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, const void* prepared, int M, int K,
+                                          int act_bits, void* ws, int8_t* q, float* scale);
+size_t dense_prepared_bytes(int K);
+hipError_t launch_dense_prepare(hipStream_t st, const uint16_t* R, int K, void* prepared);
 
 // u = ((x.R1).P).R2 with block-diagonal R1, R2 (bf16 [K/B,B,B]), fp64 throughout, perm in gather form; U [M,K]
 // and Zp [M,K] doubles are scratch.  B % 128 == 0, B | K.

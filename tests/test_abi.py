@@ -233,6 +233,24 @@ def test_lower_clip_entry_point_validates_on_the_host(L):
     assert call(4, 5) == lrq.LRQ_EUNSUPPORTED
 
 
+def test_dense_prepare_validates_on_the_host(L):
+    P = 4096
+    assert L.lrq_ars_dense_prepared_bytes(3072) >= 2 * 3072 * 3072 + 4 * 3072
+    assert L.lrq_ars_dense_prepared_bytes(192) == 0          # K % 128 != 0: the fp64 evaluation serves it, nothing to prepare
+    assert L.lrq_ars_dense_prepared_bytes(32768) == 0
+    f = L.lrq_ars_dense_prepare
+    big = 1 << 30
+    assert f(None, None, 256, P, big) == lrq.LRQ_EINVAL
+    assert f(None, P, 256, None, big) == lrq.LRQ_EINVAL
+    assert f(None, P, 0, P, big) == lrq.LRQ_EINVAL
+    assert f(None, P, 192, P, big) == lrq.LRQ_EUNSUPPORTED
+    assert f(None, P, 256, P, 100) == lrq.LRQ_EINVAL          # short buffer
+    assert f(None, P, 256, P + 16, big) == lrq.LRQ_EINVAL     # not 256-byte aligned
+    # a rotation that carries a misaligned prepared buffer is refused before anything is launched
+    bad = ctypes.byref(lrq._Rotation(lrq.LRQ_ROT_DENSE, 0, P, 0, None, None, None, None, P + 16))
+    assert L.lrq_ars_rotate_quant(None, P, 128, 256, bad, 8, P, P, P, big) == lrq.LRQ_EINVAL
+
+
 def test_header_is_plain_c(tmp_path):
     """include/lrq.h is a C header: it compiles as C99 with no torch, HIP or C++ types in its signatures."""
     import shutil

@@ -105,6 +105,33 @@ def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
         assert whole.sum() == 0 and cnt.sum() < 0.05 * M * K        # the bound decides almost everything on this data
 
 
+def test_dense_rotation_with_a_prepared_matrix(lrq):
+    """lrq_ars_dense_prepare: R's transpose and statistics computed once; calls that carry them give the oracle's codes and
+    scales, also through lrq_qlinear, and a K the matrix-core evaluation does not serve is refused."""
+    import torch
+    M, K, N = 200, 1152, 256
+    X = _acts(M, K, 77)
+    R = synth.make_rotation(K, (902, K, 0))
+    q_ref, s_ref = oracle.ars_rotate_quant(X, 8, "dense", R_bits=R)
+    Rd, Xd = bf16_to_dev(R), bf16_to_dev(X)
+    prep = lrq.ars_dense_prepare(Rd)
+    assert prep.numel() == lrq.lib().lrq_ars_dense_prepared_bytes(K)
+    rot = lrq.Rotation("dense", 0, Rd, prepared=prep)
+    for _ in range(2):                                  # the prepared buffer is only read: a second call gives the same
+        q, s = lrq.ars_rotate_quant(Xd, rot, 8)
+        assert np.array_equal(q.cpu().numpy(), q_ref)
+        assert np.array_equal(s.cpu().numpy(), s_ref)
+    W = synth.make_weights(N, K, (902, 1))
+    gd = to_dev(GRID)
+    w = lrq.tlq_quantize_pack(to_dev(W), 4, 7, gd, gd)
+    Y1 = lrq.qlinear(Xd, rot, 8, w, out_dtype=torch.float32)
+    Y0 = lrq.qlinear(Xd, lrq.Rotation("dense", 0, Rd), 8, w, out_dtype=torch.float32)
+    assert torch.equal(Y0, Y1)
+    assert lrq.lib().lrq_ars_dense_prepared_bytes(192) == 0
+    with pytest.raises(lrq.LrqError):
+        lrq.ars_dense_prepare(bf16_to_dev(synth.make_rotation(192, (902, 192, 0))))
+
+
 def test_dense_rotation_rows_the_bound_cannot_decide(lrq):
     """Rows built so that the matrix-core evaluation cannot settle them: exact ties on a rounding boundary, rows whose
     rotated values are tiny against their inputs (heavy cancellation), an all-zero row, a single spike, and equal
