@@ -125,7 +125,7 @@ def parse():
                          "three mantissa bits, v_mfma_f32_32x32x64_f8f6f4)")
     ap.add_argument("--probes-only", action="store_true",
                     help="run only the pure-MFMA and copy probes (calibration of rocprofv3 byte counters)")
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="token rows per layer in the oracle sample")
+    ap.add_argument("--cpu-rows", type=int, default=16384, help="token rows per layer in the oracle sample")
     ap.add_argument("--cpu-channels", type=int, default=4608, help="output channels per layer in the oracle sample")
     ap.add_argument("--cache-bytes", type=int, default=768 << 20,
                     help="cycle through enough buffer copies that a step's working set exceeds this")
@@ -596,9 +596,9 @@ def cpu_baseline(specs, rows, channels):
         ops += 2 * m * n * s.K
     return dict(value=round(ops / t_run / 1e12, 5), unit="TOPS", cores=int(cores), kind="oracle",
                 seconds=round(t_run, 2),
-                sample="first %d token rows x first %d output channels of %d distinct layers (%s); runtime path only "
-                       "(rotate + quantize + integer GEMM + rescale), calibration untimed"
-                       % (rows, channels, len(sample), ", ".join(s.name for s in sample)))
+                sample="first %d token rows (128 where the oracle's k-by-k dense rotation applies) x first %d output channels "
+                       "of %d distinct layers (%s); runtime path only (rotate + quantize + integer GEMM + rescale), "
+                       "calibration untimed" % (rows, channels, len(sample), ", ".join(s.name for s in sample)))
 
 
 if __name__ == "__main__":
