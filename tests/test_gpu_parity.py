@@ -182,6 +182,45 @@ def test_dense_rotation_rows_the_bound_cannot_decide(lrq):
     assert whole.sum() == M
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_dense_rotation_error_bound_on_mixed_exponents(lrq, seed):
+    """Inputs chosen against the rounding model of the matrix instruction rather than for realism: x and a (non-orthogonal) R
+    whose entries are +-m 2^e with exponents spread over 2^-12 ... 2^12 inside every 16-k group, so that most addends of an
+    instruction are truncated against the largest one and the running sums cancel.  The certified bound must still hold
+    for every element, and the codes must still be the oracle's."""
+    import torch
+    M, K = 160, 512
+    g = synth.rng_for(917, seed)
+    def mixed(shape):
+        m = g.integers(128, 256, size=shape).astype(np.float64)          # 8 significant bits: a bf16 value
+        e = g.integers(-12, 13, size=shape).astype(np.float64)
+        sgn = g.choice([-1.0, 1.0], size=shape)
+        return synth.f32_to_bf16_bits((sgn * m * np.exp2(e - 7)).astype(np.float32))
+    Xb, Rb = mixed((M, K)), mixed((K, K))
+    if seed == 2:                                       # one operand at a single magnitude: the other's spread alone
+        Rb = synth.f32_to_bf16_bits(g.choice([-1.0, 1.0], size=(K, K)).astype(np.float32))
+    if seed == 3:
+        # per 16-k group one product of magnitude about 1 and fifteen full-mantissa products about 2^-11 of it, same sign:
+        # their low bits fall below the alignment cut of the instruction, fifteen times per instruction
+        x = np.full((M, K), 255.0 / 128 * 2.0 ** -6)
+        r = np.full((K, K), 253.0 / 128 * 2.0 ** -6)
+        x[:, ::16] = 1.0
+        r[::16, :] = 251.0 / 128
+        x[1::2] *= -1.0
+        Xb, Rb = synth.f32_to_bf16_bits(x.astype(np.float32)), synth.f32_to_bf16_bits(r.astype(np.float32))
+    q_ref, s_ref = oracle.ars_rotate_quant(Xb, 8, "dense", R_bits=Rb)
+    u_ref = oracle.rotate_dense(oracle.bf16_bits_to_f64(Xb), oracle.bf16_bits_to_f64(Rb))
+    rot = lrq.Rotation("dense", 0, bf16_to_dev(Rb))
+    ws = torch.zeros(lrq.ars_workspace_bytes(M, K, rot, 8), dtype=torch.uint8, device="cuda")
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(Xb), rot, 8, workspace=ws)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    ut, eps, cnt, whole = (a.cpu().numpy() for a in lrq.ars_dense_diagnostics(ws, M, K))
+    err = np.abs(ut.astype(np.float64) - u_ref).max(axis=1)
+    print(f"  seed {seed}: max |u~ - u| / eps = {np.max(err / eps):.3f}, whole rows {int(whole.sum())}", flush=True)
+    assert np.all(err <= eps), f"error bound violated: worst ratio {np.max(err / eps)}"
+
+
 def _blockperm_inputs(lrq, K, B, seed):
     R1 = synth.make_block_rotations(K, B, (903, K, seed), 0)
     R2 = synth.make_block_rotations(K, B, (903, K, seed), 1)
