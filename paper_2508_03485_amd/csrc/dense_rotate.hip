@@ -473,6 +473,11 @@ __device__ __forceinline__ Pieces load_pieces(const unsigned char* const (&xp)[8
 
 // All 64 lanes must call this together (lanes without an element pass any valid row / col and ignore the result).
 // K % 64 == 0.  lds: this wave's 2 * XE_BUF bytes.
+// XDIRECT: every lane reads its own x row itself, 16 bytes at a time, and only the R columns go through LDS - for waves whose
+// neighbouring lanes share rows (the list of undecided elements keeps a row's entries together, about nine to a row at
+// config 4): lanes with the same address are served by one request, so the cooperative fetch buys nothing for x there
+// and its trip through LDS is half of the kernel's LDS traffic.
+template <bool XDIRECT>
 __device__ __forceinline__ double exact_element_wave(const uint16_t* X, const uint16_t* Rt, int K, int row, int col,
                                                      unsigned char* lds) {
     const int lane = threadIdx.x % kWave;
@@ -482,7 +487,8 @@ __device__ __forceinline__ double exact_element_wave(const uint16_t* X, const ui
     for (int q = 0; q < 8; ++q) {
         const int e = 8 * q + lane / 8;                 // the element whose piece (lane % 8) this lane fetches in load q
         const int er = __shfl(row, e, kWave), ec = __shfl(col, e, kWave);
-        xp[q] = reinterpret_cast<const unsigned char*>(X + (size_t)er * K) + (lane % 8) * 16;
+        xp[q] = XDIRECT ? reinterpret_cast<const unsigned char*>(X + (size_t)row * K) + q * 16
+                        : reinterpret_cast<const unsigned char*>(X + (size_t)er * K) + (lane % 8) * 16;
         rp[q] = reinterpret_cast<const unsigned char*>(Rt + (size_t)ec * K) + (lane % 8) * 16;
     }
     unsigned char* xs = lds;
@@ -496,17 +502,21 @@ __device__ __forceinline__ double exact_element_wave(const uint16_t* X, const ui
         // stage batch b (the previous batch was read into registers before this point)
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            *reinterpret_cast<v4u*>(xs + wr + 8 * q * XE_ROW) = nxt.x[q];
+            if (!XDIRECT) *reinterpret_cast<v4u*>(xs + wr + 8 * q * XE_ROW) = nxt.x[q];
             *reinterpret_cast<v4u*>(rs + wr + 8 * q * XE_ROW) = nxt.r[q];
+        }
+        v4u xv[8], rv[8];
+        if (XDIRECT) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) xv[i] = nxt.x[i];
         }
         wave_lds_sync();
         nxt = load_pieces(xp, rp, (size_t)(b + 1 < nb ? b + 1 : b) * 128);     // past the end: a harmless re-read
         asm volatile("" ::: "memory");                   // keeps these loads ahead of the arithmetic below
         __builtin_amdgcn_sched_barrier(0);
-        v4u xv[8], rv[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            xv[i] = *reinterpret_cast<const v4u*>(xs + rd + i * 16);
+            if (!XDIRECT) xv[i] = *reinterpret_cast<const v4u*>(xs + rd + i * 16);
             rv[i] = *reinterpret_cast<const v4u*>(rs + rd + i * 16);
         }
         wave_lds_sync();                                 // the reads are issued before the next batch is staged
@@ -537,7 +547,7 @@ __global__ __launch_bounds__(256) void dense_exact_amax_kernel(const uint16_t* X
         col = have ? (int)cidx[(size_t)row * CAPC + slot] : 0;
     }
     if (__ballot(have) == 0ull) return;                  // nothing in this wave
-    const double u = exact_element_wave(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
+    const double u = exact_element_wave<false>(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
     if (have) atomicMax(&amax_bits[row], (unsigned long long)__double_as_longlong(fabs(u)));
 }
 
@@ -654,7 +664,7 @@ __global__ __launch_bounds__(256) void dense_exact_codes_kernel(const uint16_t* 
             row = lo;
             col = (int)fidx[(size_t)row * capf + (i - offs[row])];
         }
-        const double u = exact_element_wave(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
+        const double u = exact_element_wave<true>(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
         if (have) {
             const double amax = __longlong_as_double((long long)amax_bits[row]);
             const double inv = amax > 0.0 ? qmax / amax : 0.0;
