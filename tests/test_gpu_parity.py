@@ -221,6 +221,24 @@ def test_dense_rotation_error_bound_on_mixed_exponents(lrq, seed):
     assert np.all(err <= eps), f"error bound violated: worst ratio {np.max(err / eps)}"
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_dense_rotation_random_shapes(lrq, seed):
+    """Seeded random token counts, widths (every multiple of 128 up to 1536: one to twelve pairs of K stages, with and without
+    the two-stage tail) and bit-widths through the matrix-core evaluation, with and without a prepared R."""
+    g = synth.rng_for(919, seed)
+    M, K, a_bits = int(g.integers(65, 520)), 128 * int(g.integers(1, 13)), int(g.choice([4, 6, 8]))
+    prepared = bool(g.integers(0, 2))
+    print(f"case dense random seed={seed} M={M} K={K} a={a_bits} prepared={prepared}", flush=True)
+    X = _acts(M, K, 800 + seed)
+    R = synth.make_rotation(K, (919, seed, 1))
+    q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "dense", R_bits=R)
+    Rd = bf16_to_dev(R)
+    rot = lrq.Rotation("dense", 0, Rd, prepared=lrq.ars_dense_prepare(Rd) if prepared else None)
+    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+
+
 def _blockperm_inputs(lrq, K, B, seed):
     R1 = synth.make_block_rotations(K, B, (903, K, seed), 0)
     R2 = synth.make_block_rotations(K, B, (903, K, seed), 1)
