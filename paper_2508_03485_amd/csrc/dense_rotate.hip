@@ -36,6 +36,65 @@ constexpr double kMagic = 6755399441055744.0;   // 1.5 * 2^52: adding it rounds 
 constexpr int CAPC = 4;                          // amax candidates kept per row
 constexpr float kBoundSlack = 1.004f;            // covers the fp32 arithmetic in which the bound itself is evaluated
 
+// Monotone map double -> uint64 (unsigned order = numeric order), so that an unsigned atomic maximum is a maximum of doubles.
+// The zero-point form keeps, per row, the key of max u and the key of max (-u); the symmetric form the bits of max |u|.
+__device__ __forceinline__ unsigned long long okey(double v) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    return (b >> 63) ? ~b : b | 0x8000000000000000ull;
+}
+__device__ __forceinline__ double okey_value(unsigned long long k) {
+    return __longlong_as_double((long long)((k >> 63) ? k & 0x7fffffffffffffffull : ~k));
+}
+
+// The per-token quantizer of a row (Preliminaries, Eq. 1).  Symmetric form: inv = qmax / amax, code = rint(u inv).  Zero-point
+// form: range = max - min, L = 2^b - 1, inv = L / range, z = rint(min inv), x_q = clamp(rint(u inv) - z, 0, L), s = range / L,
+// stored as q = x_q - 2^(b-1) and zero = z + 2^(b-1); a constant row takes x_q = 0 and (s, z) = (|c|, sign c), (1, 0) for c = 0.
+struct RowQuant {
+    double inv, zsub;       // code = clamp(rint(u inv) - zsub, -half, half - 1) in the zero-point form
+    float scale;
+    int izero;
+};
+template <bool ASYM>
+__device__ __forceinline__ RowQuant row_quant(unsigned long long kmax, unsigned long long kmin, double qmax) {
+    RowQuant r;
+    if constexpr (!ASYM) {
+        const double amax = __longlong_as_double((long long)kmax);
+        r.inv = amax > 0.0 ? qmax / amax : 0.0;
+        r.zsub = 0.0;
+        r.scale = (float)(amax / qmax);
+        r.izero = 0;
+    } else {
+        const double L = 2.0 * qmax + 1.0, half = qmax + 1.0;       // qmax = 2^(b-1) - 1
+        const double vmax = okey_value(kmax), vmin = -okey_value(kmin), rng = vmax - vmin;
+        double sc, z;
+        if (rng > 0.0) {
+            r.inv = L / rng;
+            sc = rng / L;
+            z = rint(vmin * r.inv);
+            r.zsub = z + half;
+        } else {
+            r.inv = 0.0;
+            sc = vmin != 0.0 ? fabs(vmin) : 1.0;
+            z = vmin > 0.0 ? 1.0 : (vmin < 0.0 ? -1.0 : 0.0);
+            r.zsub = half;                      // every code is x_q = 0, i.e. q = -2^(b-1)
+        }
+        r.scale = (float)sc;
+        r.izero = (int)(z + half);
+    }
+    return r;
+}
+// the code of one exact value (low byte of the result); product, rounding and clamp round separately
+template <bool ASYM>
+__device__ __forceinline__ int exact_code(double u, const RowQuant& p, double qmax) {
+    if constexpr (!ASYM) {
+        return __double2loint(u * p.inv + kMagic);
+    } else {
+        const double r = (u * p.inv + kMagic) - kMagic;
+        const double t = fmin(fmax(r - p.zsub, -(qmax + 1.0)), qmax);
+        return __double2loint(t + kMagic);
+    }
+}
+
 typedef short v8s __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
@@ -199,6 +258,33 @@ __device__ __forceinline__ void multiply_stage(const unsigned char* A, const uns
     prev[1] = tb[1];
 }
 
+// Maximum over the 32 lanes of a half-wave of 16 values per lane: one full exchange, then exchanges that halve the number
+// of values a lane carries (the lane with bit W set keeps the upper W values, its partner the lower ones); lane l ends
+// with value number l % 16 (the return value).  (The halving width is a template parameter: with a loop variable the
+// register array would be indexed dynamically, i.e. through chains of compares and selects.)
+template <int W>
+__device__ __forceinline__ void halve_exchange(float (&vals)[16], int lane) {
+    const bool up = (lane & W) != 0;
+#pragma unroll
+    for (int h = 0; h < W; ++h) {
+        const float keep = up ? vals[h + W] : vals[h];
+        const float send = up ? vals[h] : vals[h + W];
+        vals[h] = fmaxf(keep, __shfl_xor(send, W, kWave));
+    }
+}
+__device__ __forceinline__ float half_wave_max16(float (&vals)[16], int lane) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) vals[r] = fmaxf(vals[r], __shfl_xor(vals[r], 16, kWave));
+    halve_exchange<8>(vals, lane);
+    halve_exchange<4>(vals, lane);
+    halve_exchange<2>(vals, lane);
+    halve_exchange<1>(vals, lane);
+    return vals[0];
+}
+
+// ASYM (zero-point form of the quantizer): the segment values are max u~ and, in the second half of segmax, max (-u~)
+// instead of max |u~|.
+template <bool ASYM>
 __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K, float* Ut,
                                                                     float* segmax, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) unsigned char As[3 * DT_BUF];
@@ -313,7 +399,7 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
         for (int r = 0; r < 16; ++r) wide[j][r] += (double)(group[j][r] + prev[j][r]);
 
     // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
-    float vals[16];                                      // per row that this lane touches: max over its two columns
+    float vals[16], neg[16];                             // per row that this lane touches: max over its two columns
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
@@ -323,26 +409,19 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
             dst[0] = u0;
             dst[32] = u1;
         }
-        vals[r] = fmaxf(fabsf(u0), fabsf(u1));
+        vals[r] = ASYM ? fmaxf(u0, u1) : fmaxf(fabsf(u0), fabsf(u1));
+        neg[r] = ASYM ? fmaxf(-u0, -u1) : 0.0f;
     }
-    // maximum over the 32 lanes of a half-wave: one full exchange, then exchanges that halve the number of values a lane
-    // carries (the lane with bit w set keeps the upper w values, its partner the lower ones); lane l ends with value l % 16
-#pragma unroll
-    for (int r = 0; r < 16; ++r) vals[r] = fmaxf(vals[r], __shfl_xor(vals[r], 16, kWave));
-#pragma unroll
-    for (int w = 8; w >= 1; w >>= 1) {
-        const bool up = (lane & w) != 0;
-#pragma unroll
-        for (int h = 0; h < w; ++h) {
-            const float keep = up ? vals[h + w] : vals[h];
-            const float send = up ? vals[h] : vals[h + w];
-            vals[h] = fmaxf(keep, __shfl_xor(send, w, kWave));
-        }
-    }
+    const float hi = half_wave_max16(vals, lane);
+    const float lo = ASYM ? half_wave_max16(neg, lane) : 0.0f;
     if ((lane & 16) == 0) {
         const int r = lane % 16;
         const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-        if (row < M) segmax[(size_t)row * (K / DT_SEG) + (n0 + wn * 64) / DT_SEG] = vals[0];
+        if (row < M) {
+            const size_t at = (size_t)row * (K / DT_SEG) + (n0 + wn * 64) / DT_SEG;
+            segmax[at] = hi;
+            if (ASYM) segmax[(size_t)M * (K / DT_SEG) + at] = lo;
+        }
     }
 }
 
@@ -350,7 +429,10 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
 // (only the segments that reach the limit are read from u~).
 // mode[row] = 1 marks a row that is recomputed as a whole (more candidates than the list holds).
 // RES: K <= 4096, the row of x stays in registers between the passes (it is read once).
-template <bool RES>
+// ASYM (zero-point form): two searches, for the row's maximum (side 0) and for its minimum (side 1, on the maxima of -u~
+// in the second half of segmax); ccount [M, 2] and cidx [M, 2, CAPC] hold both, amax_bits [M, 2] is cleared for both.
+// The symmetric form uses side 0 only (same strides).
+template <bool RES, bool ASYM>
 __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_t* __restrict__ X, const float* __restrict__ Ut,
                                                                    const float* __restrict__ segmax, int M, int K,
                                                                    const float* __restrict__ rowmaxR,
@@ -406,38 +488,49 @@ __global__ __launch_bounds__(256) void dense_row_candidates_kernel(const uint16_
     const float rho = sqrtf(__uint_as_float(*rho2_bits)) * kBoundSlack;
     const float S = (rho * sqrtf(small2) * kBoundSlack + big) * kBoundSlack;       // >= sum_k |x_k| |R_kj| for every j
     const double e = (double)S * (double)err_factor;
-    // row maximum of |u~| and the elements within 2 eps of it
-    const float* sm = segmax + (size_t)row * nseg;
-    float mx = 0.0f;
-    for (int c = lane; c < nseg; c += kWave) mx = fmaxf(mx, sm[c]);
-    mx = wave_maxf(mx);
-    int whole = 0, n = 0;
-    if (S > 0.0f) {                              // otherwise x is all zero (or not finite) and there is nothing to decide
-        const float lim = (float)((double)mx - 2.0 * e) * (1.0f - 1e-6f);       // rounded down: never misses a candidate
-        const float* ur = Ut + (size_t)row * K;
-        for (int base = 0; base < nseg && !whole; base += kWave) {
-            const int c = base + lane;
-            unsigned long long segs = __ballot(c < nseg && sm[c] >= lim);        // segments that hold a candidate
-            while (segs && !whole) {
-                const int seg = base + __ffsll((long long)segs) - 1;
-                segs &= segs - 1;
-                const bool hit = fabsf(ur[seg * DT_SEG + lane]) >= lim;
-                const unsigned long long hits = __ballot(hit);
-                const int cnt = __popcll(hits);
-                if (n + cnt > CAPC) {
-                    whole = 1;
-                } else {
-                    if (hit) cidx[(size_t)row * CAPC + n + __popcll(hits & ((1ull << lane) - 1ull))] = (uint16_t)(seg * DT_SEG + lane);
-                    n += cnt;
+    // row maximum of |u~| (zero-point form: maximum and minimum of u~) and the elements within 2 eps of it
+    int whole = 0, cnt[2] = {0, 0};
+    const float* ur = Ut + (size_t)row * K;
+#pragma unroll
+    for (int side = 0; side < (ASYM ? 2 : 1); ++side) {
+        const float* sm = segmax + (size_t)side * M * nseg + (size_t)row * nseg;
+        float mx = -INFINITY;
+        for (int c = lane; c < nseg; c += kWave) mx = fmaxf(mx, sm[c]);
+        mx = wave_maxf(mx);
+        int n = 0;
+        if (S > 0.0f && !whole) {                // otherwise x is all zero (or not finite) and there is nothing to decide
+            const float lf = (float)((double)mx - 2.0 * e);
+            const float lim = lf - fabsf(lf) * 1e-6f;                                  // rounded down: never misses a candidate
+            for (int base = 0; base < nseg && !whole; base += kWave) {
+                const int c = base + lane;
+                unsigned long long segs = __ballot(c < nseg && sm[c] >= lim);        // segments that hold a candidate
+                while (segs && !whole) {
+                    const int seg = base + __ffsll((long long)segs) - 1;
+                    segs &= segs - 1;
+                    const float v = ur[seg * DT_SEG + lane];
+                    const bool hit = (ASYM ? (side == 0 ? v : -v) : fabsf(v)) >= lim;
+                    const unsigned long long hits = __ballot(hit);
+                    const int k = __popcll(hits);
+                    if (n + k > CAPC) {
+                        whole = 1;
+                    } else {
+                        if (hit) cidx[((size_t)row * 2 + side) * CAPC + n + __popcll(hits & ((1ull << lane) - 1ull))] = (uint16_t)(seg * DT_SEG + lane);
+                        n += k;
+                    }
                 }
             }
         }
-        if (whole) n = 0;
+        cnt[side] = n;
     }
+    if (whole) cnt[0] = cnt[1] = 0;
     if (lane == 0) {
         eps[row] = e;
-        amax_bits[row] = 0ull;
-        ccount[row] = n;
+        // no search (all-zero row): u is 0 everywhere
+        const bool zero_row = !(S > 0.0f);
+        amax_bits[2 * (size_t)row] = ASYM && zero_row ? okey(0.0) : 0ull;
+        amax_bits[2 * (size_t)row + 1] = ASYM && zero_row ? okey(0.0) : 0ull;
+        ccount[2 * (size_t)row] = cnt[0];
+        ccount[2 * (size_t)row + 1] = cnt[1];
         mode[row] = whole;
     }
 }
@@ -532,32 +625,41 @@ __device__ __forceinline__ double exact_element_wave(const uint16_t* X, const ui
     return u;
 }
 
-// amax candidates: thread i -> slot i / M of row i % M (slot 0 of every row first, so that the waves are full)
+// amax candidates: thread i -> slot i / M of row i % M (slot 0 of every row first, so that the waves are full); the
+// zero-point form runs the slots of side 0 (maximum), then those of side 1 (minimum, kept as the maximum of -u).
+template <bool ASYM>
 __global__ __launch_bounds__(256) void dense_exact_amax_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K,
                                                                const int* __restrict__ ccount, const uint16_t* __restrict__ cidx,
                                                                unsigned long long* __restrict__ amax_bits) {
     __shared__ __attribute__((aligned(16))) unsigned char stage[4 * 2 * XE_BUF];
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    int row = 0, col = 0;
+    int row = 0, col = 0, side = 0;
     bool have = false;
-    if (i < (long)M * CAPC) {
-        const int slot = (int)(i / M);
-        row = (int)(i % M);
-        have = slot < ccount[row];
-        col = have ? (int)cidx[(size_t)row * CAPC + slot] : 0;
+    if (i < (long)M * CAPC * (ASYM ? 2 : 1)) {
+        side = (int)(i / ((long)M * CAPC));
+        const long j = i - (long)side * M * CAPC;
+        const int slot = (int)(j / M);
+        row = (int)(j % M);
+        have = slot < ccount[2 * (size_t)row + side];
+        col = have ? (int)cidx[((size_t)row * 2 + side) * CAPC + slot] : 0;
     }
     if (__ballot(have) == 0ull) return;                  // nothing in this wave
     const double u = exact_element_wave<false>(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
-    if (have) atomicMax(&amax_bits[row], (unsigned long long)__double_as_longlong(fabs(u)));
+    if (have) {
+        if constexpr (ASYM) atomicMax(&amax_bits[2 * (size_t)row + side], okey(side == 0 ? u : -u));
+        else atomicMax(&amax_bits[2 * (size_t)row], (unsigned long long)__double_as_longlong(fabs(u)));
+    }
 }
 
-// ---- codes from u~ with the exact amax; the elements the bound leaves undecided go to the row's list (one wave per row)
+// ---- codes from u~ with the exact amax (zero-point form: the exact maximum and minimum); the elements the bound leaves
+// undecided go to the row's list (one wave per row)
+template <bool ASYM>
 __global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __restrict__ Ut, int M, int K, double qmax,
                                                                const double* __restrict__ eps,
                                                                const unsigned long long* __restrict__ amax_bits,
                                                                int8_t* __restrict__ q, float* __restrict__ scale,
-                                                               int* __restrict__ fcount, uint16_t* __restrict__ fidx, int capf,
-                                                               int* __restrict__ mode) {
+                                                               int32_t* __restrict__ zero, int* __restrict__ fcount,
+                                                               uint16_t* __restrict__ fidx, int capf, int* __restrict__ mode) {
     extern __shared__ int lds_cnt[];            // one counter per wave
     const int wv = threadIdx.x / kWave, lane = threadIdx.x % kWave, row = blockIdx.x * 4 + wv;
     if (lane == 0) lds_cnt[wv] = 0;
@@ -568,8 +670,8 @@ __global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __re
         if (lane == 0) fcount[row] = 0;
         return;
     }
-    const double amax = __longlong_as_double((long long)amax_bits[row]);
-    const double inv = amax > 0.0 ? qmax / amax : 0.0;
+    const RowQuant rq = row_quant<ASYM>(amax_bits[2 * (size_t)row], amax_bits[2 * (size_t)row + 1], qmax);
+    const double inv = rq.inv;
     const double delta = eps[row] * inv * (1.0 + 1e-6) + 1e-12;
     const double keep = 0.5 - delta;            // |p - rint(p)| below this: the code is settled
     const float4* us = reinterpret_cast<const float4*>(Ut + (size_t)row * K);
@@ -586,7 +688,7 @@ __global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __re
                 const int slot = atomicAdd(&lds_cnt[wv], 1);
                 if (slot < capf) myidx[slot] = (uint16_t)(c * 8 + i);
             }
-            r = fmin(fmax(r, -qmax), qmax);
+            r = ASYM ? fmin(fmax(r - rq.zsub, -(qmax + 1.0)), qmax) : fmin(fmax(r, -qmax), qmax);
             b[i] = (unsigned)__double2loint(r + kMagic) & 0xffu;
         }
         *reinterpret_cast<uint2*>(q + (size_t)row * K + (size_t)c * 8) =
@@ -596,7 +698,8 @@ __global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __re
     __builtin_amdgcn_wave_barrier();
     if (lane == 0) {
         const int n = lds_cnt[wv];
-        scale[row] = (float)(amax / qmax);
+        scale[row] = rq.scale;
+        if (ASYM) zero[row] = rq.izero;
         if (n > capf) {
             mode[row] = 1;
             fcount[row] = 0;
@@ -644,6 +747,7 @@ __global__ __launch_bounds__(1024) void dense_scan_counts_kernel(const int* __re
 }
 
 // ---- undecided elements: exact value, exact code.  Thread i takes list entry i (row found by bisection of offs).
+template <bool ASYM>
 __global__ __launch_bounds__(256) void dense_exact_codes_kernel(const uint16_t* X, const uint16_t* Rt, int M, int K, double qmax,
                                                                 const int* __restrict__ offs, const uint16_t* __restrict__ fidx,
                                                                 int capf, const unsigned long long* __restrict__ amax_bits,
@@ -666,18 +770,20 @@ __global__ __launch_bounds__(256) void dense_exact_codes_kernel(const uint16_t* 
         }
         const double u = exact_element_wave<true>(X, Rt, K, row, col, stage + (threadIdx.x / kWave) * 2 * XE_BUF);
         if (have) {
-            const double amax = __longlong_as_double((long long)amax_bits[row]);
-            const double inv = amax > 0.0 ? qmax / amax : 0.0;
-            q[(size_t)row * K + col] = (int8_t)__double2loint(u * inv + kMagic);
+            const RowQuant rq = row_quant<ASYM>(amax_bits[2 * (size_t)row], amax_bits[2 * (size_t)row + 1], qmax);
+            q[(size_t)row * K + col] = (int8_t)exact_code<ASYM>(u, rq, qmax);
         }
     }
 }
 
 // ---- rows recomputed as a whole (one workgroup per row, rows with mode == 0 leave at once): every column's chain,
-// twice - once for the maximum, once for the codes - with the row of x in LDS; R is read row by row, coalesced.
+// twice - once for the maximum (zero-point form: maximum and minimum), once for the codes - with the row of x in LDS; R
+// is read row by row, coalesced.
+template <bool ASYM>
 __global__ __launch_bounds__(256) void dense_exact_rows_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ R,
                                                                int K, double qmax, const int* __restrict__ mode,
-                                                               int8_t* __restrict__ q, float* __restrict__ scale) {
+                                                               int8_t* __restrict__ q, float* __restrict__ scale,
+                                                               int32_t* __restrict__ zero) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int row = blockIdx.x, t = threadIdx.x;
     if (!mode[row]) return;
@@ -685,25 +791,37 @@ __global__ __launch_bounds__(256) void dense_exact_rows_kernel(const uint16_t* _
     double* red = reinterpret_cast<double*>(lds_raw + (((size_t)K * 2 + 15) & ~(size_t)15));
     for (int k = t; k < K; k += 256) xr[k] = X[(size_t)row * K + k];
     __syncthreads();
-    double inv = 0.0;
+    RowQuant rq = {};
     for (int pass = 0; pass < 2; ++pass) {
-        double mx = 0.0;
+        double mx = ASYM ? -INFINITY : 0.0, mn = -INFINITY;      // mn: maximum of -u
         for (int col = t; col < K; col += 256) {
             const uint16_t* r = R + col;
             double u = 0.0;
             for (int k = 0; k < K; ++k)
                 u = fma((double)__uint_as_float((unsigned)xr[k] << 16), (double)__uint_as_float((unsigned)r[(size_t)k * K] << 16), u);
-            if (pass == 0) mx = fmax(mx, fabs(u));
-            else q[(size_t)row * K + col] = (int8_t)__double2loint(u * inv + kMagic);
+            if (pass == 0) {
+                mx = fmax(mx, ASYM ? u : fabs(u));
+                if (ASYM) mn = fmax(mn, -u);
+            } else {
+                q[(size_t)row * K + col] = (int8_t)exact_code<ASYM>(u, rq, qmax);
+            }
         }
         if (pass == 0) {
 #pragma unroll
-            for (int o = kWave / 2; o > 0; o >>= 1) mx = fmax(mx, __shfl_xor(mx, o, kWave));
-            if (t % kWave == 0) red[t / kWave] = mx;
+            for (int o = kWave / 2; o > 0; o >>= 1) {
+                mx = fmax(mx, __shfl_xor(mx, o, kWave));
+                if (ASYM) mn = fmax(mn, __shfl_xor(mn, o, kWave));
+            }
+            if (t % kWave == 0) { red[t / kWave] = mx; red[4 + t / kWave] = mn; }
             __syncthreads();
-            const double amax = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
-            inv = amax > 0.0 ? qmax / amax : 0.0;
-            if (t == 0) scale[row] = (float)(amax / qmax);
+            const double vmax = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
+            const double nmin = fmax(fmax(red[4], red[5]), fmax(red[6], red[7]));
+            rq = ASYM ? row_quant<true>(okey(vmax), okey(nmin), qmax)
+                      : row_quant<false>((unsigned long long)__double_as_longlong(vmax), 0ull, qmax);
+            if (t == 0) {
+                scale[row] = rq.scale;
+                if (ASYM) zero[row] = rq.izero;
+            }
         }
     }
 }
@@ -719,11 +837,11 @@ DenseFastWs dense_fast_layout(int M, int K) {
     w.rt = take((size_t)K * K * sizeof(uint16_t));          // rt | rowmax | scalars: the layout of dense_prepared_layout
     w.rowmax = take((size_t)K * sizeof(float));
     w.scalars = take(256);
-    w.segmax = take((size_t)M * (K / DT_SEG) * sizeof(float));
+    w.segmax = take((size_t)2 * M * (K / DT_SEG) * sizeof(float));       // max |u~|, or max u~ and max (-u~)
     w.eps = take((size_t)M * sizeof(double));
-    w.amax = take((size_t)M * sizeof(unsigned long long));
-    w.ccount = take((size_t)M * sizeof(int));
-    w.cidx = take((size_t)M * CAPC * sizeof(uint16_t));
+    w.amax = take((size_t)2 * M * sizeof(unsigned long long));     // [M, 2]: maximum and (zero-point form) minimum side
+    w.ccount = take((size_t)2 * M * sizeof(int));
+    w.cidx = take((size_t)2 * M * CAPC * sizeof(uint16_t));
     w.fcount = take((size_t)M * sizeof(int));
     w.fidx = take((size_t)M * w.capf * sizeof(uint16_t));
     w.foffs = take(((size_t)M + 1) * sizeof(int));
@@ -733,7 +851,8 @@ DenseFastWs dense_fast_layout(int M, int K) {
 }
 
 bool dense_fast_applies(int M, int K, bool zero_point, bool prescale) {
-    return !zero_point && !prescale && M > 64 && K % 128 == 0 && K <= 16384 && (size_t)M * K < ((size_t)1 << 31);
+    (void)zero_point;      // both forms of the quantizer are served
+    return !prescale && M > 64 && K % 128 == 0 && K <= 16384 && (size_t)M * K < ((size_t)1 << 31);
 }
 
 // What the fast evaluation derives from R alone: Rt bf16 [K, K] | max_j |R_kj| float [K] | scalars (256 bytes: rho^2).
@@ -763,8 +882,10 @@ hipError_t launch_dense_prepare(hipStream_t st, const uint16_t* R, int K, void* 
     return hipGetLastError();
 }
 
-hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, const void* prepared, int M, int K,
-                                          int act_bits, void* ws, int8_t* q, float* scale) {
+namespace {
+template <bool ASYM>
+hipError_t launch_dense_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, const void* prepared, int M, int K, int act_bits,
+                             void* ws, int8_t* q, float* scale, int32_t* zero) {
     const DenseFastWs L = dense_fast_layout(M, K);
     unsigned char* base = static_cast<unsigned char*>(ws);
     float* Ut = reinterpret_cast<float*>(base + L.ut);
@@ -793,22 +914,30 @@ hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, con
         if (e != hipSuccess) return e;
     }
     const int tiles_m = (M + DT_M - 1) / DT_M, tiles_n = K / DT_N;
-    hipLaunchKernelGGL(dense_rotate_bf16_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, segmax, tiles_m, tiles_n);
+    hipLaunchKernelGGL(dense_rotate_bf16_kernel<ASYM>, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, segmax, tiles_m,
+                       tiles_n);
     if (K <= 4096)
-        hipLaunchKernelGGL(dense_row_candidates_kernel<true>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax, scalars,
-                           err_factor, eps, amax, ccount, cidx, mode);
+        hipLaunchKernelGGL((dense_row_candidates_kernel<true, ASYM>), dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax,
+                           scalars, err_factor, eps, amax, ccount, cidx, mode);
     else
-        hipLaunchKernelGGL(dense_row_candidates_kernel<false>, dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax, scalars,
-                           err_factor, eps, amax, ccount, cidx, mode);
-    hipLaunchKernelGGL(dense_exact_amax_kernel, dim3((unsigned)(((long)M * CAPC + 255) / 256)), dim3(256), 0, st, X, Rt, M, K,
-                       ccount, cidx, amax);
-    hipLaunchKernelGGL(dense_quant_flag_kernel, dim3((M + 3) / 4), dim3(256), 4 * sizeof(int), st, Ut, M, K, qmax, eps, amax, q,
-                       scale, fcount, fidx, L.capf, mode);
+        hipLaunchKernelGGL((dense_row_candidates_kernel<false, ASYM>), dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax,
+                           scalars, err_factor, eps, amax, ccount, cidx, mode);
+    hipLaunchKernelGGL(dense_exact_amax_kernel<ASYM>, dim3((unsigned)(((long)M * CAPC * (ASYM ? 2 : 1) + 255) / 256)), dim3(256), 0, st,
+                       X, Rt, M, K, ccount, cidx, amax);
+    hipLaunchKernelGGL(dense_quant_flag_kernel<ASYM>, dim3((M + 3) / 4), dim3(256), 4 * sizeof(int), st, Ut, M, K, qmax, eps, amax, q,
+                       scale, zero, fcount, fidx, L.capf, mode);
     hipLaunchKernelGGL(dense_scan_counts_kernel, dim3(1), dim3(1024), 0, st, fcount, M, foffs);
-    hipLaunchKernelGGL(dense_exact_codes_kernel, dim3(2048), dim3(256), 0, st, X, Rt, M, K, qmax, foffs, fidx, L.capf, amax, q);
-    const size_t rows_lds = (((size_t)K * 2 + 15) & ~(size_t)15) + 4 * sizeof(double);
-    hipLaunchKernelGGL(dense_exact_rows_kernel, dim3(M), dim3(256), rows_lds, st, X, R, K, qmax, mode, q, scale);
+    hipLaunchKernelGGL(dense_exact_codes_kernel<ASYM>, dim3(2048), dim3(256), 0, st, X, Rt, M, K, qmax, foffs, fidx, L.capf, amax, q);
+    const size_t rows_lds = (((size_t)K * 2 + 15) & ~(size_t)15) + 8 * sizeof(double);
+    hipLaunchKernelGGL(dense_exact_rows_kernel<ASYM>, dim3(M), dim3(256), rows_lds, st, X, R, K, qmax, mode, q, scale, zero);
     return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, const void* prepared, int M, int K,
+                                          int act_bits, void* ws, int8_t* q, float* scale, int32_t* zero) {
+    return zero ? launch_dense_fast<true>(st, X, R, prepared, M, K, act_bits, ws, q, scale, zero)
+                : launch_dense_fast<false>(st, X, R, prepared, M, K, act_bits, ws, q, scale, zero);
 }
 
 }  // namespace lrq

@@ -141,7 +141,7 @@ int run_rotate_quant(hipStream_t st, const void* X, int M, int K, const lrq_rota
         default:
             if (rot->kind == LRQ_ROT_DENSE && lrq::dense_fast_applies(M, K, zero != nullptr, rot->prescale != nullptr))
                 e = lrq::launch_dense_rotate_quant_fast(st, x, static_cast<const uint16_t*>(rot->R), rot->R_prepared, M, K, act_bits,
-                                                        ws, q, scale);
+                                                        ws, q, scale, zero);
             else
                 e = lrq::launch_dense_rotate_quant(st, x, static_cast<const uint16_t*>(rot->R), M, K, act_bits,
                                                    static_cast<double*>(ws), q, scale, zero, rot->prescale);

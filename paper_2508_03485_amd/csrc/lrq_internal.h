@@ -49,7 +49,7 @@ hipError_t launch_dense_rotate_quant(hipStream_t st, const uint16_t* X, const ui
                                      const float* prescale);
 
 // The same rotation + quantizer with the bulk product on the bf16 matrix cores, a certified error bound and exact
-// recomputation of the undecided elements (symmetric quantizer without pre-scale only; dense_fast_applies says when).
+// recomputation of the undecided elements (either form of the quantizer, no pre-scale; dense_fast_applies says when).
 // Bit-identical codes and scales.  ws: dense_fast_layout(M, K).total bytes.
 struct DenseFastWs {
     size_t ut, rt, rowmax, scalars, segmax, eps, amax, ccount, cidx, fcount, fidx, foffs, mode, total;
@@ -59,8 +59,9 @@ DenseFastWs dense_fast_layout(int M, int K);
 bool dense_fast_applies(int M, int K, bool zero_point, bool prescale);
 // prepared: NULL, or dense_prepared_bytes(K) bytes that launch_dense_prepare filled from this R (its transpose and the
 // statistics the error bound needs): then the call skips that preprocessing.
+// zero: NULL (symmetric quantizer) or the per-token zero-points of the zero-point form (then q holds x_q - 2^(b-1)).
 hipError_t launch_dense_rotate_quant_fast(hipStream_t st, const uint16_t* X, const uint16_t* R, const void* prepared, int M, int K,
-                                          int act_bits, void* ws, int8_t* q, float* scale);
+                                          int act_bits, void* ws, int8_t* q, float* scale, int32_t* zero);
 size_t dense_prepared_bytes(int K);
 hipError_t launch_dense_prepare(hipStream_t st, const uint16_t* R, int K, void* prepared);
 

@@ -100,23 +100,24 @@ def test_config_4_weight_codes_in_full(lrq):
     assert np.array_equal(got, oracle.pack_codes(oracle.tlq_encode(W, p), spec.w_bits))
 
 
-@pytest.mark.parametrize("cfg,layer", [(2, 3), (4, 1), (3, 3)])
+@pytest.mark.parametrize("cfg,layer", [(2, 3), (4, 1), (3, 3), (4, 0)])
 def test_zero_point_form_at_full_size(lrq, cfg, layer):
-    """The paper's Eq. 1 quantizer (zero-point per token) through lrq_qlinear_asym at full size, sampled."""
+    """The paper's Eq. 1 quantizer (zero-point per token) through lrq_qlinear_asym at full size, sampled; config 4's first
+    layer takes the dense rotation."""
     import torch
     spec = synth.config_layers(cfg)[layer]
-    print(f"asym layer {spec.name} cfg{cfg} M={spec.M} K={spec.K} N={spec.N} h={spec.had_block}", flush=True)
-    X, W, _, _ = synth.layer_tensors(spec)
+    print(f"asym layer {spec.name} cfg{cfg} M={spec.M} K={spec.K} N={spec.N} {spec.rotation} h={spec.had_block}", flush=True)
+    X, W, R, _ = synth.layer_tensors(spec)
     rows, chans = _sample(spec.M, N_ROWS, spec.key), _sample(spec.N, N_CH, spec.key)
     Xd = bf16_to_dev(X)
-    rot = lrq.Rotation("hadamard", spec.had_block)
+    rot = lrq.Rotation(spec.rotation, spec.had_block, None if R is None else bf16_to_dev(R))
     gd = to_dev(GRID)
     w = lrq.tlq_quantize_pack(to_dev(W), spec.w_bits, 7, gd, gd)
     q, sc, zr = lrq.ars_rotate_quant(Xd, rot, spec.a_bits, asym=True)
     Y = lrq.qlinear(Xd, rot, spec.a_bits, w, out_dtype=torch.bfloat16, asym=True)
     torch.cuda.synchronize()
     ridx, cidx = torch.from_numpy(rows).to(Xd.device), torch.from_numpy(chans).to(Xd.device)
-    q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(X[rows], spec.a_bits, "hadamard", spec.had_block)
+    q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(X[rows], spec.a_bits, spec.rotation, spec.had_block, R)
     assert np.array_equal(q[ridx].cpu().numpy(), q_ref)
     assert np.array_equal(zr[ridx].cpu().numpy(), z_ref)
     assert np.array_equal(sc[ridx].cpu().numpy(), s_ref)

@@ -227,16 +227,18 @@ def test_dense_rotation_random_shapes(lrq, seed):
     the two-stage tail) and bit-widths through the matrix-core evaluation, with and without a prepared R."""
     g = synth.rng_for(919, seed)
     M, K, a_bits = int(g.integers(65, 520)), 128 * int(g.integers(1, 13)), int(g.choice([4, 6, 8]))
-    prepared = bool(g.integers(0, 2))
-    print(f"case dense random seed={seed} M={M} K={K} a={a_bits} prepared={prepared}", flush=True)
+    prepared, asym = bool(g.integers(0, 2)), bool(g.integers(0, 2))
+    print(f"case dense random seed={seed} M={M} K={K} a={a_bits} prepared={prepared} asym={asym}", flush=True)
     X = _acts(M, K, 800 + seed)
+    if asym:                                            # a non-zero mean, so that the zero-points matter
+        X = synth.f32_to_bf16_bits(oracle.bf16_bits_to_f64(X).astype(np.float32) + np.float32(0.5))
     R = synth.make_rotation(K, (919, seed, 1))
-    q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "dense", R_bits=R)
     Rd = bf16_to_dev(R)
     rot = lrq.Rotation("dense", 0, Rd, prepared=lrq.ars_dense_prepare(Rd) if prepared else None)
-    q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits)
-    assert np.array_equal(q.cpu().numpy(), q_ref)
-    assert np.array_equal(s.cpu().numpy(), s_ref)
+    got = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, asym=asym)
+    ref = oracle.ars_rotate_quant_asym(X, a_bits, "dense", 0, R) if asym else oracle.ars_rotate_quant(X, a_bits, "dense", R_bits=R)
+    for a, b in zip(got, ref):
+        assert np.array_equal(a.cpu().numpy(), b)
 
 
 def _blockperm_inputs(lrq, K, B, seed):
@@ -586,6 +588,7 @@ def test_qlinear_end_to_end(lrq, cfg_case):
     (70, 1536, "hadamard", 512, 8), (40, 3072, "hadamard", 1024, 4), (19, 12288, "hadamard", 4096, 8),
     (3, 16384, "hadamard", 16384, 8), (11, 256, "none", 0, 8), (70, 128, "dense", 0, 8), (64, 1152, "dense", 0, 4),
     (100, 1152, "hadamard", 128, 6), (30, 4608, "hadamard", 512, 6),
+    (300, 1152, "dense", 0, 8), (200, 256, "dense", 0, 4), (129, 3072, "dense", 0, 6),      # the matrix-core evaluation
 ])
 def test_zero_point_rotate_quant_bit_exact(lrq, M, K, rotation, h, a_bits):
     print(f"case asym M={M} K={K} {rotation} h={h} a={a_bits}", flush=True)
