@@ -209,13 +209,15 @@ __device__ __forceinline__ void read_fragments(const unsigned char* A, const uns
 // longer than a matrix instruction); fr holds those of step 0 on entry and those of the next stage's step 0 (buffer
 // An / Bn, complete since the previous barrier) on return.
 // The staged registers st (this thread's four 16-byte pieces of the stage that is two ahead) go to LDS one per step, at
-// dst[i], and are reloaded from src[i] + goff (the stage that is four ahead) right away: spread like this the LDS writes of
+// dst[i], and are reloaded from byte offset src[i] + goff_x of x (i < 2) or src[i] + goff_r of Rt (the stage that is four
+// ahead; 32-bit offsets, taken modulo 2^32: both arrays are smaller than 4 GiB) right away: spread like this the LDS writes of
 // the eight waves overlap the matrix work instead of preceding it.
 template <bool FIRST, bool FLUSH>
 __device__ __forceinline__ void multiply_stage(const unsigned char* A, const unsigned char* B, const unsigned char* An,
                                                const unsigned char* Bn, v8s (&fr)[3], v4u (&st)[4], unsigned char* const (&dst)[4],
-                                               const unsigned char* const (&src)[4], size_t goff, double (&wide)[2][16],
-                                               v16f (&group)[2], v16f (&prev)[2]) {
+                                               const unsigned char* xb, const unsigned char* rb, const unsigned (&src)[4],
+                                               unsigned goff_x, unsigned goff_r, double (&wide)[2][16], v16f (&group)[2],
+                                               v16f (&prev)[2]) {
     static_assert(DT_K == 2 * kChunk && kChunk == 32, "two runs of two matrix instructions per stage");
     const v16f zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     v16f ta[2], tb[2];
@@ -226,7 +228,7 @@ __device__ __forceinline__ void multiply_stage(const unsigned char* A, const uns
         else if (s + 1 < DT_K / 16) read_fragments(A, B, s + 1, fr);
         else read_fragments(An, Bn, 0, fr);
         *reinterpret_cast<v4u*>(dst[s]) = st[s];
-        st[s] = *reinterpret_cast<const v4u*>(src[s] + goff);
+        st[s] = *reinterpret_cast<const v4u*>((s < 2 ? xb : rb) + (size_t)(src[s] + (s < 2 ? goff_x : goff_r)));
         asm volatile("" ::: "memory");                   // keeps the load here, ahead of the arithmetic that follows
         __builtin_amdgcn_sched_barrier(0);
         const v8s a = s % 2 == 0 ? fr[0] : fo[0];
@@ -282,6 +284,44 @@ __device__ __forceinline__ float half_wave_max16(float (&vals)[16], int lane) {
     return vals[0];
 }
 
+// Tile order: ids go round-robin over the 8 XCDs; each XCD walks a contiguous range of an order that keeps 8 row tiles
+// together and runs over the column tiles fastest, so that an XCD's L2 sees each x panel and each R panel several times
+// in a row.  id -> first row and first column of the tile.
+struct TileOrigin {
+    int m0, n0;
+};
+__device__ __forceinline__ TileOrigin tile_origin(int id, int tiles_m, int tiles_n) {
+    const int ntiles = tiles_m * tiles_n;
+    const int x = id % 8, i = id / 8;
+    const int base = ntiles / 8, rem = ntiles % 8;
+    const int tile = x * base + (x < rem ? x : rem) + i;
+    constexpr int GM = 8;
+    const int per_group = GM * tiles_n;
+    const int group = tile / per_group, first_m = group * GM;
+    const int gsize = tiles_m - first_m < GM ? tiles_m - first_m : GM;
+    const int r = tile % per_group;
+    TileOrigin o;
+    o.m0 = (first_m + r % gsize) * DT_M;
+    o.n0 = (r / gsize) * DT_N;
+    return o;
+}
+// this thread's four load streams of a tile (rows r0 and r0 + 64 of the x tile and of the R tile)
+// as byte offsets into x (the first two) and Rt (M K < 2^31 and K <= 16384: they fit 32 bits)
+__device__ __forceinline__ void tile_sources(int M, int K, TileOrigin o, int r0, int cc, unsigned (&src)[4]) {
+    int g0 = o.m0 + r0, g1 = o.m0 + r0 + 64;
+    if (g0 >= M) g0 = M - 1;
+    if (g1 >= M) g1 = M - 1;
+    src[0] = ((unsigned)g0 * (unsigned)K) * 2u + cc * 16;
+    src[1] = ((unsigned)g1 * (unsigned)K) * 2u + cc * 16;
+    src[2] = ((unsigned)(o.n0 + r0) * (unsigned)K) * 2u + cc * 16;
+    src[3] = ((unsigned)(o.n0 + r0 + 64) * (unsigned)K) * 2u + cc * 16;
+}
+
+// The workgroups are persistent: workgroup b takes the tiles b, b + gridDim.x, ... (gridDim.x a multiple of 8 whenever a
+// workgroup has more than one tile, so that it stays on its XCD's range).  The operand pipeline does not drain between
+// tiles: the loads that would run past the end of a tile's K fetch the first four stages of the workgroup's next tile, so
+// that tile starts with two stages in LDS and two in registers, as the prologue leaves the first one (K >= 256; a tile
+// of two stages runs the prologue again).
 // ASYM (zero-point form of the quantizer): the segment values are max u~ and, in the second half of segmax, max (-u~)
 // instead of max |u~|.
 template <bool ASYM>
@@ -289,139 +329,151 @@ __global__ __launch_bounds__(512, 2) void dense_rotate_bf16_kernel(const uint16_
                                                                     float* segmax, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) unsigned char As[3 * DT_BUF];
     __shared__ __attribute__((aligned(16))) unsigned char Bs[3 * DT_BUF];
-    // tile order: workgroup ids go round-robin over the 8 XCDs; each XCD walks a contiguous range of an order that keeps
-    // 8 row tiles together and runs over the column tiles fastest, so that an XCD's L2 sees each x panel and each R
-    // panel several times in a row
     const int ntiles = tiles_m * tiles_n;
-    int tile;
-    {
-        const int x = blockIdx.x % 8, i = blockIdx.x / 8;
-        const int base = ntiles / 8, rem = ntiles % 8;
-        tile = x * base + (x < rem ? x : rem) + i;
-    }
-    int tm, tn;
-    {
-        constexpr int GM = 8;
-        const int per_group = GM * tiles_n;
-        const int group = tile / per_group, first_m = group * GM;
-        const int gsize = tiles_m - first_m < GM ? tiles_m - first_m : GM;
-        const int r = tile % per_group;
-        tm = first_m + r % gsize;
-        tn = r / gsize;
-    }
-    const int m0 = tm * DT_M, n0 = tn * DT_N;
     const int t = threadIdx.x, lane = t % kWave, wv = t / kWave;
     const int wm = wv / 2, wn = wv % 2;
-
     // loader: 1024 16-byte pieces per operand tile and stage, two per thread and operand (rows r0 and r0 + 64)
     const int r0 = t / 8, cc = t % 8;
-    int g0 = m0 + r0, g1 = m0 + r0 + 64;
-    if (g0 >= M) g0 = M - 1;
-    if (g1 >= M) g1 = M - 1;
-    const unsigned char* src[4] = {reinterpret_cast<const unsigned char*>(X + (size_t)g0 * K) + cc * 16,
-                                   reinterpret_cast<const unsigned char*>(X + (size_t)g1 * K) + cc * 16,
-                                   reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0) * K) + cc * 16,
-                                   reinterpret_cast<const unsigned char*>(Rt + (size_t)(n0 + r0 + 64) * K) + cc * 16};
     const int d0 = r0 * DT_ROW + cc * 16, d1 = d0 + 64 * DT_ROW;
     const int nk = K / DT_K;
-    auto goff = [nk](int kb) { return (size_t)(kb < nk ? kb : nk - 1) * DT_K * 2; };   // past the end: a harmless re-read
-
-    double wide[2][16];
-    v16f group[2], prev[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            wide[j][r] = 0.0;
-            group[j][r] = 0.0f;
-            prev[j][r] = 0.0f;
-        }
+    const bool chained = nk >= 4;                        // the next tile's first stages ride in this tile's pipeline
     const int a_off = (wm * 32 + lane % 32) * DT_ROW + (lane / 32) * 16;
     const int b_off = (wn * 64 + lane % 32) * DT_ROW + (lane / 32) * 16;
 
-    // prologue: stages 0, 1 in LDS buffers 0, 1; stages 2 (even) and 3 (odd) in registers
+    int id = blockIdx.x;
+    TileOrigin cur = tile_origin(id, tiles_m, tiles_n);
+    const unsigned char* xb = reinterpret_cast<const unsigned char*>(X);
+    const unsigned char* rb = reinterpret_cast<const unsigned char*>(Rt);
+    unsigned src[4];
+    tile_sources(M, K, cur, r0, cc, src);
     v4u ev[4], od[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        ev[i] = *reinterpret_cast<const v4u*>(src[i] + goff(0));
-        od[i] = *reinterpret_cast<const v4u*>(src[i] + goff(1));
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        unsigned char* base = i < 2 ? As : Bs;
-        const int d = i % 2 == 0 ? d0 : d1;
-        *reinterpret_cast<v4u*>(&base[d]) = ev[i];
-        *reinterpret_cast<v4u*>(&base[DT_BUF + d]) = od[i];
-        ev[i] = *reinterpret_cast<const v4u*>(src[i] + goff(2));
-        od[i] = *reinterpret_cast<const v4u*>(src[i] + goff(3));
-    }
-    __syncthreads();
     v8s fr[3];
-    read_fragments(&As[a_off], &Bs[b_off], 0, fr);
     int b0 = 0, b1 = 1, b2 = 2;                          // LDS buffers of stages kb, kb + 1, kb + 2
-    // A group is the eight runs of four stages: stage 4 i opens group i with its first run (FIRST) and, before that, adds
-    // the last run of stage 4 i - 1 to group i - 1 and flushes it (FLUSH).  Stage 0 has nothing to flush: it "flushes" the
-    // zero-initialised tiles, which changes nothing.
-    static_assert(kGroup == 8 && 2 * kChunk == DT_K, "the loop body below is written out for groups of four stages");
-    // two stages: the first multiplies from b0 and refills b2 from the even registers (stage KB + 2, loaded two iterations
-    // ago; they then take stage KB + 4), the second multiplies from b1 and refills b0, the buffer that stage KB just
-    // left, from the odd ones (a macro, not a lambda: captured register arrays would be spilled to scratch memory)
-#define LRQ_DENSE_STAGE_PAIR(FIRST_A, FLUSH_A, FIRST_B, FLUSH_B, KB)                                                     \
-    {                                                                                                                     \
-        unsigned char* const dst_a[4] = {&As[b2 * DT_BUF + d0], &As[b2 * DT_BUF + d1], &Bs[b2 * DT_BUF + d0],             \
-                                         &Bs[b2 * DT_BUF + d1]};                                                          \
-        multiply_stage<FIRST_A, FLUSH_A>(&As[b0 * DT_BUF + a_off], &Bs[b0 * DT_BUF + b_off], &As[b1 * DT_BUF + a_off],    \
-                                         &Bs[b1 * DT_BUF + b_off], fr, ev, dst_a, src, goff((KB) + 4), wide, group, prev); \
-        __builtin_amdgcn_sched_barrier(0);                                                                                \
-        __syncthreads();                                                                                                  \
-        unsigned char* const dst_b[4] = {&As[b0 * DT_BUF + d0], &As[b0 * DT_BUF + d1], &Bs[b0 * DT_BUF + d0],             \
-                                         &Bs[b0 * DT_BUF + d1]};                                                          \
-        multiply_stage<FIRST_B, FLUSH_B>(&As[b1 * DT_BUF + a_off], &Bs[b1 * DT_BUF + b_off], &As[b2 * DT_BUF + a_off],    \
-                                         &Bs[b2 * DT_BUF + b_off], fr, od, dst_b, src, goff((KB) + 5), wide, group, prev); \
-        __builtin_amdgcn_sched_barrier(0);                                                                                \
-        __syncthreads();                                                                                                  \
-        const int f = b0;                                /* stages KB + 2, KB + 3, KB + 4 live in b2, b0, b1 */           \
-        b0 = b2;                                                                                                          \
-        b2 = b1;                                                                                                          \
-        b1 = f;                                                                                                           \
-    }
-    int kb = 0;
-    for (; kb + 3 < nk; kb += 4) {
-        LRQ_DENSE_STAGE_PAIR(true, true, false, false, kb)
-        LRQ_DENSE_STAGE_PAIR(false, false, false, false, kb + 2)
-    }
-    if (kb < nk) LRQ_DENSE_STAGE_PAIR(true, true, false, false, kb)      // K % 256 == 128: two more stages
-#undef LRQ_DENSE_STAGE_PAIR
-    // the last run, and what its group holds
+    bool primed = false;                                 // stages 0, 1 in LDS, 2, 3 in registers, fragments of stage 0 read
+    for (;;) {
+        const bool has_next = id + (int)gridDim.x < ntiles;
+        const TileOrigin nto = tile_origin(has_next ? id + (int)gridDim.x : id, tiles_m, tiles_n);
+        // the next tile's streams are this tile's shifted by a uniform amount (modulo 2^32) unless one of the two tiles is cut
+        // by the end of the matrix (clamped rows): such a transition is not chained, the next tile runs the prologue
+        const bool link = chained && has_next && cur.m0 + DT_M <= M && nto.m0 + DT_M <= M;
+        const unsigned to_next_x = (unsigned)(nto.m0 - cur.m0) * (unsigned)K * 2u, to_next_r = (unsigned)(nto.n0 - cur.n0) * (unsigned)K * 2u;
+        // offsets of the stages past this tile's end (selected by masks, not branches: the loop body stays one block);
+        // a transition that is not chained re-reads this tile's last stage, which is harmless
+        const unsigned next_x = link ? to_next_x : (unsigned)(nk - 1) * DT_K * 2, next_r = link ? to_next_r : (unsigned)(nk - 1) * DT_K * 2;
+        const unsigned next_step = link ? DT_K * 2 : 0;
+        if (!primed) {
+            // prologue: stages 0, 1 in LDS buffers b0, b1; stages 2 (even) and 3 (odd) in registers (a tile of two stages
+            // re-reads its last one: harmless, never multiplied)
+            const unsigned o1 = (unsigned)(nk > 1 ? 1 : 0) * DT_K * 2, o2 = (unsigned)(nk > 2 ? 2 : nk - 1) * DT_K * 2,
+                           o3 = (unsigned)(nk > 3 ? 3 : nk - 1) * DT_K * 2;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+            for (int i = 0; i < 4; ++i) {
+                ev[i] = *reinterpret_cast<const v4u*>((i < 2 ? xb : rb) + (size_t)src[i]);
+                od[i] = *reinterpret_cast<const v4u*>((i < 2 ? xb : rb) + (size_t)(src[i] + o1));
+            }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) wide[j][r] += (double)(group[j][r] + prev[j][r]);
+            for (int i = 0; i < 4; ++i) {
+                unsigned char* base = i < 2 ? As : Bs;
+                const int d = i % 2 == 0 ? d0 : d1;
+                *reinterpret_cast<v4u*>(&base[b0 * DT_BUF + d]) = ev[i];
+                *reinterpret_cast<v4u*>(&base[b1 * DT_BUF + d]) = od[i];
+                ev[i] = *reinterpret_cast<const v4u*>((i < 2 ? xb : rb) + (size_t)(src[i] + o2));
+                od[i] = *reinterpret_cast<const v4u*>((i < 2 ? xb : rb) + (size_t)(src[i] + o3));
+            }
+            __syncthreads();
+            read_fragments(&As[b0 * DT_BUF + a_off], &Bs[b0 * DT_BUF + b_off], 0, fr);
+        }
 
-    // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
-    float vals[16], neg[16];                             // per row that this lane touches: max over its two columns
+        double wide[2][16];
+        v16f group[2], prev[2];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-        const float u0 = (float)wide[0][r], u1 = (float)wide[1][r];
-        if (row < M) {
-            float* dst = Ut + (size_t)row * K + n0 + wn * 64 + lane % 32;
-            dst[0] = u0;
-            dst[32] = u1;
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                wide[j][r] = 0.0;
+                group[j][r] = 0.0f;
+                prev[j][r] = 0.0f;
+            }
+        // A group is the eight runs of four stages: stage 4 i opens group i with its first run (FIRST) and, before that,
+        // adds the last run of stage 4 i - 1 to group i - 1 and flushes it (FLUSH).  Stage 0 has nothing to flush: it
+        // "flushes" the zero-initialised tiles, which changes nothing.
+        static_assert(kGroup == 8 && 2 * kChunk == DT_K, "the loop body below is written out for groups of four stages");
+        // Two stages: the first multiplies from b0 and refills b2 from the even registers (stage KB + 2, loaded two
+        // iterations ago; they then take stage KB + 4), the second multiplies from b1 and refills b0, the buffer that stage
+        // KB just left, from the odd ones.  Stage s >= nk is stage s - nk of the next tile (a transition that is not chained:
+        // a harmless re-read of this tile's last stage).  (A macro, not a lambda: captured register arrays would be spilled to
+        // scratch memory.)
+#define LRQ_DENSE_LOAD_FROM(S, OX, OR)                                                                                    \
+        const unsigned past_##OX = 0u - (unsigned)((S) >= nk);             /* all ones: the stage belongs to the next tile */ \
+        const unsigned in_##OX = (unsigned)(S) * DT_K * 2, step_##OX = (unsigned)((S) - nk) * next_step;                   \
+        const unsigned OX = (in_##OX & ~past_##OX) | ((next_x + step_##OX) & past_##OX);                                   \
+        const unsigned OR = (in_##OX & ~past_##OX) | ((next_r + step_##OX) & past_##OX);
+#define LRQ_DENSE_STAGE_PAIR(FIRST_A, FLUSH_A, FIRST_B, FLUSH_B, KB)                                                     \
+        {                                                                                                                 \
+            unsigned char* const dst_a[4] = {&As[b2 * DT_BUF + d0], &As[b2 * DT_BUF + d1], &Bs[b2 * DT_BUF + d0],         \
+                                             &Bs[b2 * DT_BUF + d1]};                                                      \
+            LRQ_DENSE_LOAD_FROM((KB) + 4, oax, oar)                                                                       \
+            multiply_stage<FIRST_A, FLUSH_A>(&As[b0 * DT_BUF + a_off], &Bs[b0 * DT_BUF + b_off], &As[b1 * DT_BUF + a_off], \
+                                             &Bs[b1 * DT_BUF + b_off], fr, ev, dst_a, xb, rb, src, oax, oar, wide, group, prev); \
+            __builtin_amdgcn_sched_barrier(0);                                                                            \
+            __syncthreads();                                                                                              \
+            unsigned char* const dst_b[4] = {&As[b0 * DT_BUF + d0], &As[b0 * DT_BUF + d1], &Bs[b0 * DT_BUF + d0],         \
+                                             &Bs[b0 * DT_BUF + d1]};                                                      \
+            LRQ_DENSE_LOAD_FROM((KB) + 5, obx, obr)                                                                       \
+            multiply_stage<FIRST_B, FLUSH_B>(&As[b1 * DT_BUF + a_off], &Bs[b1 * DT_BUF + b_off], &As[b2 * DT_BUF + a_off], \
+                                             &Bs[b2 * DT_BUF + b_off], fr, od, dst_b, xb, rb, src, obx, obr, wide, group, prev); \
+            __builtin_amdgcn_sched_barrier(0);                                                                            \
+            __syncthreads();                                                                                              \
+            const int f = b0;                            /* stages KB + 2, KB + 3, KB + 4 live in b2, b0, b1 */           \
+            b0 = b2;                                                                                                      \
+            b2 = b1;                                                                                                      \
+            b1 = f;                                                                                                       \
         }
-        vals[r] = ASYM ? fmaxf(u0, u1) : fmaxf(fabsf(u0), fabsf(u1));
-        neg[r] = ASYM ? fmaxf(-u0, -u1) : 0.0f;
-    }
-    const float hi = half_wave_max16(vals, lane);
-    const float lo = ASYM ? half_wave_max16(neg, lane) : 0.0f;
-    if ((lane & 16) == 0) {
-        const int r = lane % 16;
-        const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
-        if (row < M) {
-            const size_t at = (size_t)row * (K / DT_SEG) + (n0 + wn * 64) / DT_SEG;
-            segmax[at] = hi;
-            if (ASYM) segmax[(size_t)M * (K / DT_SEG) + at] = lo;
+        int kb = 0;
+        for (; kb + 3 < nk; kb += 4) {
+            LRQ_DENSE_STAGE_PAIR(true, true, false, false, kb)
+            LRQ_DENSE_STAGE_PAIR(false, false, false, false, kb + 2)
         }
+        if (kb < nk) LRQ_DENSE_STAGE_PAIR(true, true, false, false, kb)      // K % 256 == 128: two more stages
+#undef LRQ_DENSE_STAGE_PAIR
+#undef LRQ_DENSE_LOAD_FROM
+        // the last run, and what its group holds
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) wide[j][r] += (double)(group[j][r] + prev[j][r]);
+
+        // lane holds column (lane % 32) and rows 8 (r / 4) + 4 (lane / 32) + r % 4 of each 32 x 32 accumulator tile
+        const int m0 = cur.m0, n0 = cur.n0;
+        float vals[16], neg[16];                         // per row that this lane touches: max over its two columns
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+            const float u0 = (float)wide[0][r], u1 = (float)wide[1][r];
+            if (row < M) {
+                float* dst = Ut + (size_t)row * K + n0 + wn * 64 + lane % 32;
+                dst[0] = u0;
+                dst[32] = u1;
+            }
+            vals[r] = ASYM ? fmaxf(u0, u1) : fmaxf(fabsf(u0), fabsf(u1));
+            neg[r] = ASYM ? fmaxf(-u0, -u1) : 0.0f;
+        }
+        const float hi = half_wave_max16(vals, lane);
+        const float lo = ASYM ? half_wave_max16(neg, lane) : 0.0f;
+        if ((lane & 16) == 0) {
+            const int r = lane % 16;
+            const int row = m0 + wm * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+            if (row < M) {
+                const size_t at = (size_t)row * (K / DT_SEG) + (n0 + wn * 64) / DT_SEG;
+                segmax[at] = hi;
+                if (ASYM) segmax[(size_t)M * (K / DT_SEG) + at] = lo;
+            }
+        }
+        if (!has_next) break;
+        id += (int)gridDim.x;
+        cur = nto;
+        tile_sources(M, K, cur, r0, cc, src);
+        primed = link;           // chained: the pipeline already holds the next tile's first four stages
     }
 }
 
@@ -914,8 +966,10 @@ hipError_t launch_dense_fast(hipStream_t st, const uint16_t* X, const uint16_t* 
         if (e != hipSuccess) return e;
     }
     const int tiles_m = (M + DT_M - 1) / DT_M, tiles_n = K / DT_N;
-    hipLaunchKernelGGL(dense_rotate_bf16_kernel<ASYM>, dim3(tiles_m * tiles_n), dim3(512), 0, st, X, Rt, M, K, Ut, segmax, tiles_m,
-                       tiles_n);
+    // one workgroup fits a CU (LDS): 256 persistent workgroups when there are more tiles than that
+    const int ntiles = tiles_m * tiles_n;
+    hipLaunchKernelGGL(dense_rotate_bf16_kernel<ASYM>, dim3(ntiles > 256 ? 256 : ntiles), dim3(512), 0, st, X, Rt, M, K, Ut, segmax,
+                       tiles_m, tiles_n);
     if (K <= 4096)
         hipLaunchKernelGGL((dense_row_candidates_kernel<true, ASYM>), dim3((M + 3) / 4), dim3(256), 0, st, X, Ut, segmax, M, K, rowmax,
                            scalars, err_factor, eps, amax, ccount, cidx, mode);

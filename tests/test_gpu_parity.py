@@ -71,7 +71,8 @@ def test_no_rotation_quant(lrq):
 @pytest.mark.parametrize("M,K,a_bits", [(70, 128, 8), (130, 256, 4), (64, 1152, 8), (200, 192, 8),
                                         (2, 1152, 4), (8, 192, 8), (1, 3072, 8), (64, 384, 8), (65, 384, 8),      # up to 64 rows: the column-per-thread kernel
                                         (300, 1152, 8), (129, 3072, 6), (257, 2048, 4),
-                                        (140, 4224, 8)])            # K > 4096: the row of x no longer stays in registers
+                                        (140, 4224, 8),             # K > 4096: the row of x no longer stays in registers
+                                        (16420, 256, 8), (11013, 384, 4)])      # more tiles than workgroups: chained tiles, a cut last row tile
 def test_dense_rotate_quant_bit_exact(lrq, M, K, a_bits):
     print(f"case dense M={M} K={K} a={a_bits}", flush=True)
     X = _acts(M, K, 3 + K)
