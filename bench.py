@@ -402,7 +402,7 @@ def main():
                               "fp64 totals, error bound, exact recomputation of undecided elements)", achieved=round(tf, 2),
                               peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=round(tf / BF16_MFMA_PEAK_TFLOPS, 4), traffic=None,
                               avg_launch_ms=round(t / len(dense), 4),
-                              note="time of the whole call (ten kernels), flops of the product alone")
+                              note="time of the whole call (seven kernels with R prepared offline, ten without), flops of the product alone")
         # what the error bound left undecided in the first such layer's last call, and how far the approximate product
         # really is from the fp64 evaluation (LRQ_ROT_DENSE_F64 leaves u in fp64 at the head of its workspace)
         l0 = dense[0][1]
