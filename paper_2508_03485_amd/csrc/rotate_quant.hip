@@ -335,14 +335,16 @@ __global__ __launch_bounds__(640) void hadamard_quant_e32_kernel(const uint16_t*
 // 32 contiguous bytes.  LDS rows: 16 doubles + 2 of padding per pass-1 lane and 4 more per 32 lanes (the byte
 // buffer: 16 bytes per 32 lanes), which keeps the 16-byte writes of pass 1 and the quad-strided accesses of
 // pass 2 on distinct banks.  With PERSIST (used for h = 4096) a workgroup walks over row groups and loads the next
-// group's bf16 data while it transforms the current one.
+// group's bf16 data while it transforms the current one; where LDS has room for it (ONE) the exchange then runs in a single
+// round of 32 element offsets (34 doubles per pass-1 lane) with the code bytes in a region of their own, which leaves three
+// workgroup barriers per row group instead of six.
 // PAD doubles after every 32 pass-1 lanes: the Q lanes of a pass-2 pair / quad read rows 32 apart in one instruction,
 // next to 32 / Q element offsets of other lanes, so 32 / Q doubles of padding put all of them on distinct banks.
-template <int PAD>
-__device__ __forceinline__ int lds_row(int slot) { return 18 * slot + PAD * (slot >> 5); }
+template <int PAD, int STRIDE = 18>
+__device__ __forceinline__ int lds_row(int slot) { return STRIDE * slot + PAD * (slot >> 5); }
 constexpr int lds_pad(int log2h) { return log2h == 12 ? 8 : (log2h == 11 ? 16 : 4); }
 
-template <int LOG2H, bool PERSIST, bool ASYM, bool PRE>
+template <int LOG2H, bool PERSIST, bool ASYM, bool PRE, bool ONE = false>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(PERSIST || PRE ? 2 : 3, PERSIST || PRE ? 2 : 3)))
 void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
                                                                    int rows_per_wg, QuantSpec qs,
@@ -354,8 +356,12 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
     extern __shared__ __attribute__((aligned(16))) double lds[];
     __shared__ unsigned long long amax_bits[2][2][32];       // [parity][max |u| or key of max u / key of max -u][row]
     const int lpr = K / E32;
+    static_assert(!ONE || PERSIST, "the single-round exchange is a form of the persistent kernel");
     constexpr int PAD = lds_pad(LOG2H);
-    const int rs = lds_row<PAD>(lpr) + 8;          // doubles per row buffer
+    constexpr int NR = ONE ? 1 : 2;                // exchange rounds
+    constexpr int EPR = 32 / NR;                   // element offsets per round
+    constexpr int STRIDE = EPR + 2;                // doubles per pass-1 lane in LDS
+    const int rs = lds_row<PAD, STRIDE>(lpr) + 8;  // doubles per row buffer
     const int t = threadIdx.x;
     const int rw = t / lpr, slot = t % lpr;
     const bool inwg = rw < rows_per_wg;
@@ -363,7 +369,7 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
     // pass 2 role of this thread: lane j of block b, element offsets e0 .. e0 + EPL - 1, quad position gq
     const int b = slot / G, j = slot % G;
     const int e0 = (j / Q) * EPL, gq = j % Q;
-    const int my_round = e0 >> 4;
+    const int my_round = ONE ? 0 : e0 >> 4;
     const int ngroups = (M + rows_per_wg - 1) / rows_per_wg;
     if (t < 128) amax_bits[t / 64][(t / 32) % 2][t % 32] = 0ull;
 
@@ -395,19 +401,22 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
         }
         butterflies<E32>(v, 5);
 #pragma unroll
-        for (int round = 0; round < 2; ++round) {
-            if (PERSIST || round == 1) __syncthreads();   // earlier readers of the buffer (first half / previous group) are done
+        for (int round = 0; round < NR; ++round) {
+            // earlier readers of the buffer (first half / previous group) are done; the single-round form needs no such
+            // barrier: the previous group's last reads of this buffer precede its barrier after the maxima, and its codes
+            // went through a buffer of their own
+            if (!ONE && (PERSIST || round == 1)) __syncthreads();
             if (inwg) {
-                double2* dst = reinterpret_cast<double2*>(rowbuf + lds_row<PAD>(slot));
+                double2* dst = reinterpret_cast<double2*>(rowbuf + lds_row<PAD, STRIDE>(slot));
 #pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = make_double2(v[16 * round + 2 * i], v[16 * round + 2 * i + 1]);
+                for (int i = 0; i < EPR / 2; ++i) dst[i] = make_double2(v[EPR * round + 2 * i], v[EPR * round + 2 * i + 1]);
             }
             if (PERSIST && round == 0 && t < 64) amax_bits[par ^ 1][t / 32][t % 32] = 0ull;   // the other parity's slots, for the next group
             __syncthreads();
             if (my_round == round) {
 #pragma unroll
                 for (int r = 0; r < NG; ++r) {
-                    const double* p = rowbuf + lds_row<PAD>(b * G + r + 32 * gq) + (e0 - 16 * round);
+                    const double* p = rowbuf + lds_row<PAD, STRIDE>(b * G + r + 32 * gq) + (e0 - EPR * round);
                     if constexpr (EPL == 4) {
                         const double2 a = *reinterpret_cast<const double2*>(p), c = *reinterpret_cast<const double2*>(p + 2);
                         w[r * 4 + 0] = a.x; w[r * 4 + 1] = a.y; w[r * 4 + 2] = c.x; w[r * 4 + 3] = c.y;
@@ -472,7 +481,11 @@ void hadamard_quant_2pass_kernel(const uint16_t* __restrict__ X, int M, int K,
             }
         }
         // byte buffer: 32 bytes per pass-1 lane, 16 bytes of padding per 32 lanes
-        unsigned char* cbuf = reinterpret_cast<unsigned char*>(rowbuf) + (size_t)b * (G * 32 + (G >> 5) * 16);
+        // (single-round form: a region of its own behind the row buffers, so that the next group's pass 1 may overwrite the
+        // row buffer while slower waves still collect this group's codes)
+        unsigned char* cbuf = (ONE ? reinterpret_cast<unsigned char*>(lds + (size_t)rows_per_wg * rs) +
+                                         (size_t)(inwg ? rw : 0) * (lpr * 32 + (lpr >> 5) * 16)
+                                   : reinterpret_cast<unsigned char*>(rowbuf)) + (size_t)b * (G * 32 + (G >> 5) * 16);
         if (inwg) {
 #pragma unroll
             for (int r = 0; r < NG; ++r) {
@@ -1009,7 +1022,12 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         if (R < 1) R = 1;
         if (R > 32) R = 32;
         const int nt = ((lpr * R + kWave - 1) / kWave) * kWave;
-        const size_t ldsb = (size_t)R * (18 * lpr + lds_pad(ilog2(h)) * (lpr >> 5) + 8) * sizeof(double);
+        const int pad = lds_pad(ilog2(h));
+        const size_t ldsb_two = (size_t)R * (18 * lpr + pad * (lpr >> 5) + 8) * sizeof(double);
+        // single-round form of the persistent kernel: 34 doubles per pass-1 lane, code bytes behind the row buffers
+        const size_t ldsb_one = (size_t)R * ((34 * lpr + pad * (lpr >> 5) + 8) * sizeof(double) + lpr * 32 + (lpr >> 5) * 16);
+        bool one = h >= 4096 && ldsb_one <= 150 * 1024;
+        size_t ldsb = one ? ldsb_one : ldsb_two;
         // resident workgroups per CU: two waves per SIMD by registers, LDS permitting
         const int groups = (M + R - 1) / R;
         int per_cu = (int)((160 * 1024 - 2048) / (ldsb + 512));
@@ -1019,31 +1037,35 @@ hipError_t launch_hadamard_quant(hipStream_t st, const uint16_t* X, int M, int K
         // the largest block runs as persistent workgroups that load the next row group while transforming the current
         // one (measured: 566 vs 690 us at 35100 x 12288; at h = 2048 the plain form is the faster one, 208 vs 288 us)
         const bool persist = h >= 4096 && groups > 256 * per_cu;
+        if (!persist) {
+            one = false;
+            ldsb = ldsb_two;
+        }
         const dim3 grid(persist ? 256 * per_cu : groups), block(nt);
-#define LRQ_ATTR(L, P, A, S) { hipError_t e = allow_large_lds(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A, S>), 158 * 1024); if (e != hipSuccess) return e; }
-#define LRQ_ATTR2(L, P) { if (qs.asym && qs.prescale) LRQ_ATTR(L, P, true, true) else if (qs.asym) LRQ_ATTR(L, P, true, false) else if (qs.prescale) LRQ_ATTR(L, P, false, true) else LRQ_ATTR(L, P, false, false) }
+#define LRQ_ATTR(L, P, A, S, O) { hipError_t e = allow_large_lds(reinterpret_cast<const void*>(hadamard_quant_2pass_kernel<L, P, A, S, O>), 158 * 1024); if (e != hipSuccess) return e; }
+#define LRQ_ATTR2(L, P, O) { if (qs.asym && qs.prescale) LRQ_ATTR(L, P, true, true, O) else if (qs.asym) LRQ_ATTR(L, P, true, false, O) else if (qs.prescale) LRQ_ATTR(L, P, false, true, O) else LRQ_ATTR(L, P, false, false, O) }
         switch (ilog2(h)) {
-            case 8: LRQ_ATTR2(8, false) break;
-            case 9: LRQ_ATTR2(9, false) break;
-            case 10: LRQ_ATTR2(10, false) break;
-            case 11: LRQ_ATTR2(11, false) break;
-            case 12: if (persist) LRQ_ATTR2(12, true) else LRQ_ATTR2(12, false) break;
+            case 8: LRQ_ATTR2(8, false, false) break;
+            case 9: LRQ_ATTR2(9, false, false) break;
+            case 10: LRQ_ATTR2(10, false, false) break;
+            case 11: LRQ_ATTR2(11, false, false) break;
+            case 12: if (one) LRQ_ATTR2(12, true, true) else if (persist) LRQ_ATTR2(12, true, false) else LRQ_ATTR2(12, false, false) break;
         }
 #undef LRQ_ATTR2
 #undef LRQ_ATTR
-#define LRQ_GO(L, P)                                                                                                      \
+#define LRQ_GO(L, P, O)                                                                                                   \
     {                                                                                                                     \
-        if (qs.asym && qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
-        else if (qs.asym) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, false>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);       \
-        else if (qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false, true>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
-        else hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false, false>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);                   \
+        if (qs.asym && qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, true, O>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
+        else if (qs.asym) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, true, false, O>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);       \
+        else if (qs.prescale) hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false, true, O>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);   \
+        else hipLaunchKernelGGL((hadamard_quant_2pass_kernel<L, P, false, false, O>), grid, block, ldsb, st, X, M, K, R, qs, q, scale);                   \
     }
         switch (ilog2(h)) {
-            case 8: LRQ_GO(8, false) break;
-            case 9: LRQ_GO(9, false) break;
-            case 10: LRQ_GO(10, false) break;
-            case 11: LRQ_GO(11, false) break;
-            case 12: if (persist) LRQ_GO(12, true) else LRQ_GO(12, false) break;
+            case 8: LRQ_GO(8, false, false) break;
+            case 9: LRQ_GO(9, false, false) break;
+            case 10: LRQ_GO(10, false, false) break;
+            case 11: LRQ_GO(11, false, false) break;
+            case 12: if (one) LRQ_GO(12, true, true) else if (persist) LRQ_GO(12, true, false) else LRQ_GO(12, false, false) break;
         }
 #undef LRQ_GO
         return hipGetLastError();

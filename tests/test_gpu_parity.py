@@ -44,6 +44,34 @@ def test_hadamard_rotate_quant_bit_exact(lrq, M, K, h, a_bits):
     assert np.array_equal(s.cpu().numpy(), s_ref)
 
 
+@pytest.mark.parametrize("M,K,a_bits,asym", [
+    (600, 12288, 8, False),       # one row per workgroup, 256 workgroups: two or three row groups each, single-round exchange
+    (1100, 4096, 4, False),       # two rows per workgroup, two workgroups per CU
+    (300, 16384, 8, False),       # LDS has no room for the single round: the two-round persistent form
+    (560, 12288, 6, True),        # zero-point form
+])
+def test_hadamard_4096_persistent_workgroups(lrq, M, K, a_bits, asym):
+    """h = 4096 with more row groups than resident workgroups: the kernel walks over row groups, loads the next group's
+    data early and (LDS permitting) exchanges the block in a single round with three barriers per group.  Every code and
+    scale against the oracle."""
+    print(f"case persistent hadamard M={M} K={K} a={a_bits} asym={asym}", flush=True)
+    X = _acts(M, K, K + M)
+    rot = lrq.Rotation("hadamard", 4096)
+    if asym:
+        q_ref, s_ref, z_ref = oracle.ars_rotate_quant_asym(X, a_bits, "hadamard", 4096)
+        q, s, z = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits, asym=True)
+        assert np.array_equal(z.cpu().numpy(), z_ref)
+    else:
+        q_ref, s_ref = oracle.ars_rotate_quant(X, a_bits, "hadamard", 4096)
+        q, s = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy(), s_ref)
+    # a second call on the same buffers (stale LDS state must not leak between launches or groups)
+    if not asym:
+        q2, s2 = lrq.ars_rotate_quant(bf16_to_dev(X), rot, a_bits)
+        assert np.array_equal(q2.cpu().numpy(), q_ref) and np.array_equal(s2.cpu().numpy(), s_ref)
+
+
 def test_rotate_quant_edge_rows(lrq):
     K, h = 1152, 128
     X = oracle.bf16_bits_to_f64(_acts(6, K, 1)).astype(np.float32)
