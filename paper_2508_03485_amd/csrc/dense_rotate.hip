@@ -762,11 +762,12 @@ __global__ __launch_bounds__(256) void dense_quant_flag_kernel(const float* __re
 }
 
 // ---- exclusive prefix sum of the per-row counts, offs[0 .. M] (one workgroup of 1024 threads; 16384 counts per pass
-// through LDS so that global reads and writes are coalesced)
+// through LDS so that global reads and writes are coalesced; a thread sums its 16 counts, the sums are scanned inside
+// each wave with lane shifts and the 16 wave totals by every thread itself: three barriers per pass)
 __global__ __launch_bounds__(1024) void dense_scan_counts_kernel(const int* __restrict__ cnt, int M, int* __restrict__ offs) {
     __shared__ int buf[16384];
-    __shared__ int part[1024];
-    const int t = threadIdx.x;
+    __shared__ int wave_total[16];
+    const int t = threadIdx.x, lane = t % kWave, wv = t / kWave;
     int carry = 0;
     for (int base = 0; base < M; base += 16384) {
         for (int i = t; i < 16384; i += 1024) buf[i] = base + i < M ? cnt[base + i] : 0;
@@ -774,26 +775,32 @@ __global__ __launch_bounds__(1024) void dense_scan_counts_kernel(const int* __re
         int s = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s += buf[t * 16 + i];
-        part[t] = s;
-        __syncthreads();
-        for (int o = 1; o < 1024; o <<= 1) {
-            const int v = t >= o ? part[t - o] : 0;
-            __syncthreads();
-            part[t] += v;
-            __syncthreads();
+        int incl = s;                                   // inclusive scan of s over the wave
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int v = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += v;
         }
-        int run = carry + part[t] - s;
+        if (lane == kWave - 1) wave_total[wv] = incl;
+        __syncthreads();
+        int before = 0, all = 0;                        // totals of the waves before this one, and of all 16
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int v = wave_total[w];
+            if (w < wv) before += v;
+            all += v;
+        }
+        int run = carry + before + incl - s;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int c = buf[t * 16 + i];
             buf[t * 16 + i] = run;
             run += c;
         }
-        carry += part[1023];
+        carry += all;
         __syncthreads();
         for (int i = t; i < 16384; i += 1024)
             if (base + i < M) offs[base + i] = buf[i];
-        __syncthreads();
     }
     if (t == 0) offs[M] = carry;
 }

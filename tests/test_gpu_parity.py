@@ -374,7 +374,8 @@ def test_smoothing_factor(lrq, alpha):
 
 @pytest.mark.parametrize("M,K,kind,h", [(70, 1152, "hadamard", 128), (130, 4608, "hadamard", 512), (33, 192, "hadamard", 64),
                                         (50, 4096, "hadamard", 4096), (64, 256, "none", 0), (90, 256, "dense", 0),
-                                        (75, 192, "dense", 0), (3, 1152, "dense", 0), (140, 384, "blockperm", 128)])
+                                        (75, 192, "dense", 0), (3, 1152, "dense", 0), (140, 384, "blockperm", 128),
+                                        (530, 12288, "hadamard", 4096)])      # persistent workgroups, single-round exchange
 def test_prescaled_rotate_quant_bit_exact(lrq, M, K, kind, h):
     """The reciprocal smoothing factor multiplied into x ahead of every rotation kind."""
     print(f"case prescale M={M} K={K} {kind} h={h}", flush=True)
