@@ -101,12 +101,21 @@ hipError_t launch_qgemm_levels(hipStream_t st, const int8_t* q, const float* sca
 hipError_t allow_large_lds(const void* kernel, int bytes);
 
 // ---- private GEMM weight layout ----
-// Channels are grouped in tiles of 32, K in blocks of 64.  One (channel tile, K block) unit holds, for
-// each of the 64 lanes of a wave, the codes that lane feeds to two consecutive 32x32x32 int8 MFMAs:
-// lane l owns channel (l % 32) of the tile and k = 32*s + 16*(l / 32) + [0, 16) for step s = 0, 1.
-// Units are stored [channel tile][K block][lane], 16 bytes (4-bit) or 12 bytes (3-bit) per lane.
+// Channels are grouped in tiles of 32, K in blocks of 64.  One (channel tile, K block) unit is 64 slots of 16 bytes:
+// slot (c, kq), c = 0..15, kq = 0..3, at byte (16 kq + c) * 16 of the unit, holds the codes of k = 16 kq + [0, 16) of
+// the block for channel c of the tile (first 8 bytes) and channel 16 + c (last 8 bytes); one nibble per code, byte j
+// of a dword = code[k + j] | code[k + 4 + j] << 4 (k = 0 / 8 for the two dwords of a channel).  Lane 16 kq + c of a
+// wave that loads slot (c, kq) thus holds the B operands of two v_mfma_i32_16x16x64_i8 (column c of two neighbouring
+// 16-column tiles, the lane group's 16 k).  A 32-column matrix instruction (lane = channel l % 32, k half l / 32)
+// reads its channel's 8-byte halves of the slots kq = l / 32 and kq = 2 + l / 32.
+// Units are stored [channel tile][K block].
 constexpr int kGemmTileN = 32;
 constexpr int kGemmBlockK = 64;
+
+// byte offset, inside a unit, of the first of the two 8-byte pieces that lane l of a 32-column matrix instruction
+// reads (k = 16 (l / 32) + [0, 16)); the second (k = 32 + 16 (l / 32) + [0, 16)) lies kGemmPiece32Step bytes further
+__host__ __device__ inline int gemm_piece32_offset(int l) { return ((l / 32) * 16 + l % 16) * 16 + ((l % 32) / 16) * 8; }
+constexpr int kGemmPiece32Step = 2 * 16 * 16;
 
 inline size_t gemm_codes_bytes(int N, int K, int bits) {
     size_t tiles = (size_t)(N + kGemmTileN - 1) / kGemmTileN;

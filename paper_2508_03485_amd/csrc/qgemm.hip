@@ -35,8 +35,8 @@ struct BRaw {
 template <int BITS>
 __device__ __forceinline__ BRaw<BITS> load_braw(const uint8_t* __restrict__ p) {
     BRaw<BITS> r;
-    const uint4 v = *reinterpret_cast<const uint4*>(p);
-    r.d[0] = v.x; r.d[1] = v.y; r.d[2] = v.z; r.d[3] = v.w;
+    const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + kGemmPiece32Step);
+    r.d[0] = lo.x; r.d[1] = lo.y; r.d[2] = hi.x; r.d[3] = hi.y;
     return r;
 }
 
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         if (n >= N) n = N - 1;
         const uint4 lv = *reinterpret_cast<const uint4*>(lut + (size_t)n * 16);
         L[j][0] = lv.x; L[j][1] = lv.y; L[j][2] = lv.z; L[j][3] = lv.w;
-        bptr[j] = gcodes + (size_t)tl * KB * UNIT + (size_t)lane * (UNIT / 64);
+        bptr[j] = gcodes + (size_t)tl * KB * UNIT + gemm_piece32_offset(lane);
     }
 
     // A tile loader: BM*4 chunks of 16 bytes; chunk id -> (row, 16-byte column)

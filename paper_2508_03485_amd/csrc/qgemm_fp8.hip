@@ -27,6 +27,12 @@ constexpr int UNIT = 64 * 16;                   // bytes of one (32-column tile,
 
 __device__ __forceinline__ unsigned perm(unsigned hi, unsigned lo, unsigned sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
 
+// the lane's codes of one K block: its channel's two 8-byte pieces of the unit (k = 16 (l / 32) + [0, 16) and 32 more)
+__device__ __forceinline__ uint4 load_pieces32(const uint8_t* p) {
+    const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + kGemmPiece32Step);
+    return make_uint4(lo.x, lo.y, hi.x, hi.y);
+}
+
 // Raw dword (8 codes: byte j = code[j] | code[4 + j] << 4) -> the table bytes of codes 0..3 (lo) and 4..7 (hi).
 template <int BITS>
 __device__ __forceinline__ void decode8(unsigned w, const unsigned T[4], unsigned C, unsigned& lo, unsigned& hi) {
@@ -90,7 +96,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_fp8_kernel(const uint8_t* __rest
         if (n >= N) n = N - 1;
         const uint4 lv = *reinterpret_cast<const uint4*>(lut + (size_t)n * 16);
         T[j][0] = lv.x; T[j][1] = lv.y; T[j][2] = lv.z; T[j][3] = lv.w;
-        bptr[j] = gcodes + (size_t)tl * KB * UNIT + (size_t)lane * 16;
+        bptr[j] = gcodes + (size_t)tl * KB * UNIT + gemm_piece32_offset(lane);
     }
     unsigned C = 0x03020100u;
     asm volatile("" : "+v"(C));
@@ -121,7 +127,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_fp8_kernel(const uint8_t* __rest
 #pragma unroll
     for (int i = 0; i < 2; ++i) *reinterpret_cast<v4i*>(&smem[aoff[i]]) = *reinterpret_cast<const v4i*>(aptr[i]);
 #pragma unroll
-    for (int j = 0; j < NTW; ++j) bC[j] = *reinterpret_cast<const uint4*>(bptr[j]);
+    for (int j = 0; j < NTW; ++j) bC[j] = load_pieces32(bptr[j]);
     __syncthreads();
 
     const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
@@ -131,7 +137,7 @@ __global__ __launch_bounds__(256, 2) void qgemm_fp8_kernel(const uint8_t* __rest
 #pragma unroll
         for (int i = 0; i < 2; ++i) aN[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)kn * BK);
 #pragma unroll
-        for (int j = 0; j < NTW; ++j) bN[j] = *reinterpret_cast<const uint4*>(bptr[j] + (size_t)kn * UNIT);
+        for (int j = 0; j < NTW; ++j) bN[j] = load_pieces32(bptr[j] + (size_t)kn * UNIT);
         v8i b[NTW];
 #pragma unroll
         for (int j = 0; j < NTW; ++j) {

@@ -38,6 +38,12 @@ __device__ __forceinline__ unsigned perm(unsigned hi, unsigned lo, unsigned sel)
     return __builtin_amdgcn_perm(hi, lo, sel);
 }
 
+// the lane's codes of one K block: its channel's two 8-byte pieces of the unit (k = 16 (l / 32) + [0, 16) and 32 more)
+__device__ __forceinline__ uint4 load_pieces32(const uint8_t* p) {
+    const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + kGemmPiece32Step);
+    return make_uint4(lo.x, lo.y, hi.x, hi.y);
+}
+
 // Four int8 codes (one dword) -> four bf16 values (two dwords).  q + 128 is an unsigned byte; the byte -> float
 // conversions and the subtraction of 128 are exact, and the float of an integer below 256 has a zero low half.
 __device__ __forceinline__ void widen4(unsigned w, unsigned& lo, unsigned& hi) {
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(256, NTW == 1 ? 3 : 2) void qgemm_levels_kernel(con
             L[j][i] = perm(e[2 * i + 1], e[2 * i], 0x06040200u);
             H[j][i] = perm(e[2 * i + 1], e[2 * i], 0x07050301u);
         }
-        bptr[j] = gcodes + (size_t)tl * KB * UNIT + (size_t)lane * 16;
+        bptr[j] = gcodes + (size_t)tl * KB * UNIT + gemm_piece32_offset(lane);
     }
     unsigned C = 0x03020100u;
     asm volatile("" : "+v"(C));
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(256, NTW == 1 ? 3 : 2) void qgemm_levels_kernel(con
 #pragma unroll
     for (int i = 0; i < 2; ++i) aN[i] = *reinterpret_cast<const v4i*>(aptr[i]);
 #pragma unroll
-    for (int j = 0; j < NTW; ++j) bC[j] = *reinterpret_cast<const uint4*>(bptr[j]);
+    for (int j = 0; j < NTW; ++j) bC[j] = load_pieces32(bptr[j]);
     stage(0, aN);
     __syncthreads();
 
@@ -192,7 +198,7 @@ __global__ __launch_bounds__(256, NTW == 1 ? 3 : 2) void qgemm_levels_kernel(con
 #pragma unroll
         for (int i = 0; i < 2; ++i) aN[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)kn * BK);
 #pragma unroll
-        for (int j = 0; j < NTW; ++j) bN[j] = *reinterpret_cast<const uint4*>(bptr[j] + (size_t)kn * UNIT);
+        for (int j = 0; j < NTW; ++j) bN[j] = load_pieces32(bptr[j] + (size_t)kn * UNIT);
         const unsigned char* A = smem + cur * ABUF;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

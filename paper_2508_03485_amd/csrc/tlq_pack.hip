@@ -279,9 +279,10 @@ __global__ __launch_bounds__(NT) void tlq_quantize_pack_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             tiled |= (((unsigned)code[g * 8 + j] & mask) | (((unsigned)code[g * 8 + 4 + j] & mask) << 4)) << (8 * j);
-        const int kb = g / 8, r = g % 8, s2 = r / 4, hl = (r / 2) % 2, d = r % 2;
+        // slot (n % 16, 16-k group kq) of the unit; the channel's half of its 32-tile picks the slot's 8-byte half
+        const int kb = g / 8, r = g % 8, kq = r / 2, d = r % 2;
         const size_t unit = (size_t)(n / kGemmTileN) * (K / kGemmBlockK) + kb;
-        const size_t off = (unit * 64 + (n % kGemmTileN) + 32 * hl) * 16 + (s2 * 2 + d) * 4;
+        const size_t off = (unit * 64 + (n % 16) + 16 * kq) * 16 + (((n % kGemmTileN) / 16) * 2 + d) * 4;
         *reinterpret_cast<uint32_t*>(gemm_codes + off) = tiled;
     }
 }
