@@ -2,9 +2,12 @@
 //   Y[t,n] = scale_t * wscale_n * sum_k q[t,k] * lut_n[code[n,k]]  (+ bias_n)
 // Activation codes q (int8, [M,K]) are staged through LDS (three rotating buffers) and shared by the four
 // waves of a workgroup; every wave owns its own 64 output channels, streams the packed 3/4-bit TLQ codes of
-// those channels straight from global memory into registers and decodes them there with a per-lane
-// level table (byte permutes), so decoded weights never touch LDS.  v_mfma_i32_32x32x32_i8 does the
-// contraction with int32 accumulation ("SpeedUp and Latency": INT8 x INT8, higher-precision accumulate).
+// those channels straight from global memory into registers and decodes them there with per-lane
+// level tables (byte permutes), so decoded weights never touch LDS.  v_mfma_i32_16x16x64_i8 does the
+// contraction with int32 accumulation ("SpeedUp and Latency": INT8 x INT8, higher-precision accumulate): one
+// instruction per 16 x 16 output tile and K block of 64.  (On pseudo-random operands the chip sustains 3.9 POP/s with
+// this instruction and 3.3 POP/s with v_mfma_i32_32x32x32_i8: the matrix pipe is power-limited and this shape draws
+// less per operation.)
 // The epilogue rescales in fp32 and goes through LDS so that every lane stores 16 contiguous bytes.
 #include "lrq_internal.h"
 
@@ -12,7 +15,6 @@ namespace lrq {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WAVES = 4;
 constexpr int BK = kGemmBlockK;     // 64
@@ -26,7 +28,9 @@ __device__ __forceinline__ unsigned perm(unsigned hi, unsigned lo, unsigned sel)
     return __builtin_amdgcn_perm(hi, lo, sel);
 }
 
-// Raw operand codes of one lane for one K block: 32 codes, one nibble each (16 bytes), either bit-width.
+// Raw operand codes of one lane for one K block and one 32-channel tile: its 16-byte slot of the code tiling, i.e. the
+// 16 codes (k = 16 (lane / 16) + [0, 16) of the block) of channel lane % 16 of the tile in dwords 0, 1 and those of channel
+// 16 + lane % 16 in dwords 2, 3; one nibble each, either bit-width.
 template <int BITS>
 struct BRaw {
     unsigned d[4];
@@ -35,12 +39,12 @@ struct BRaw {
 template <int BITS>
 __device__ __forceinline__ BRaw<BITS> load_braw(const uint8_t* __restrict__ p) {
     BRaw<BITS> r;
-    const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + kGemmPiece32Step);
-    r.d[0] = lo.x; r.d[1] = lo.y; r.d[2] = hi.x; r.d[3] = hi.y;
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    r.d[0] = v.x; r.d[1] = v.y; r.d[2] = v.z; r.d[3] = v.w;
     return r;
 }
 
-// Decode the 4 codes of operand dword g (0..3) of MFMA step s (0 | 1) of a K block.  Raw dword 2s + g/2 holds 8
+// Decode the 4 codes of operand dword g (0..3) of the slot's channel s (0 | 1).  Raw dword 2s + g/2 holds 8
 // codes, byte j = code[j] | code[4+j] << 4.
 // 4-bit: the level table has 16 entries (L[0..1] codes 0..7, L[2..3] codes 8..15 = negative twin): two 8-entry byte
 // permutes and a third that picks per byte by the code's sign bit.  C = 0x03020100 must live in a VGPR so that the
@@ -86,9 +90,9 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 // (tile kb), stages tile kb+2 (held in aS, which is then reloaded with tile kb+4) into `st`, and - because tile kb+1
 // in `nx` has been complete since the previous barrier - reads the first A fragments of block kb+1 before its own
 // closing barrier, so that the next block starts on the matrix cores without waiting for LDS.
-// bCur holds B block kb (its MFMA step 0 already decoded in bd0; reloaded with block kb+2 once step 1 is decoded),
-// bNxt holds block kb+1 whose step 0 is decoded into bd0 while step 1 multiplies.
-// Decode work is spread evenly between the MFMAs so that it issues in their shadow.
+// bdCur holds the decoded B operands of block kb (one per 16-column tile); bRaw holds the raw codes of block kb+1, which
+// are decoded into bdNxt between the matrix instructions of this block (so that the decode issues in their shadow) and
+// then reloaded with block kb+3 (the other raw set, block kb+2, is in flight meanwhile).
 // Packed 4-bit activation codes (A4P): a 16-byte chunk holds 32 codes, eight per dword, byte j of a dword = code[j] + 8 in
 // the low nibble and code[4 + j] + 8 in the high nibble.  It is widened on its way into LDS to two 16-byte chunks of
 // bytes in [1, 15]; the constant offset 8 leaves through the epilogue as a zero-point of -8 (times the channel's level sum).
@@ -110,66 +114,55 @@ __device__ __forceinline__ void stage_a(unsigned char* dst, v4i a) {
     }
 }
 
-template <int BITS, int MT, int NTW, int ALOADS, bool A4P>
+template <int BITS, int RT, int NTW, int ALOADS, bool A4P>
 __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int nx, v4i (&aS)[ALOADS],
-                                       BRaw<BITS> (&bCur)[NTW], const BRaw<BITS> (&bNxt)[NTW], int kb, int KB,
+                                       BRaw<BITS> (&bRaw)[NTW], int kb, int KB,
                                        const int8_t* const (&aptr)[ALOADS], const int (&aoff)[ALOADS],
-                                       const uint8_t* const (&bptr)[NTW], const unsigned (&L)[NTW][4], unsigned C,
-                                       v4i (&bd0)[NTW], v16i (&acc)[MT][NTW], int rd_off, v4i (&afp)[AF_DIST]) {
+                                       const uint8_t* const (&bptr)[NTW], const unsigned (&L)[2 * NTW][4], unsigned C,
+                                       const v4i (&bdCur)[2 * NTW], v4i (&bdNxt)[2 * NTW], v4i (&acc)[RT][2 * NTW], int rd_off,
+                                       v4i (&afp)[AF_DIST]) {
     constexpr int UNIT = 64 * 16;
+    constexpr int CT = 2 * NTW;                     // 16-column tiles of a wave
     constexpr int ABK = A4P ? BK / 2 : BK;          // bytes of a token row per K block
     const unsigned char* Acur = smem + cur;
 #pragma unroll
     for (int i = 0; i < ALOADS; ++i) stage_a<A4P>(&smem[st + aoff[i]], aS[i]);
     const int ka = kb + 4 < KB ? kb + 4 : KB - 1;
-    const int kbn = kb + 2 < KB ? kb + 2 : KB - 1;
+    const int kbn = kb + 3 < KB ? kb + 3 : KB - 1;
 #pragma unroll
     for (int i = 0; i < ALOADS; ++i) aS[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)ka * ABK);
-    v4i af[2 * MT], bd1[NTW];
-    constexpr int DPB = (NTW * 4 + MT - 1) / MT;       // operand dwords decoded per MFMA row tile
-    constexpr int DIST = AF_DIST;                   // A fragments are read this many MFMA groups ahead
+    v4i af[RT];
+    constexpr int DPB = (CT * 4 + RT - 1) / RT;     // operand dwords decoded per row tile
+    constexpr int DIST = AF_DIST;                   // A fragments are read this many row tiles ahead
 #pragma unroll
     for (int p = 0; p < DIST; ++p) af[p] = afp[p];
 #pragma unroll
-    for (int p = 0; p < 2 * MT; ++p) {
-        const int s = p / MT, i = p % MT;
-        if (p == 2 * MT - 2) {      // next block's first fragments, early enough to land before the closing barrier
+    for (int p = 0; p < RT; ++p) {
+        if (p == RT - 2) {          // next block's first fragments, early enough to land before the closing barrier
 #pragma unroll
             for (int pp = 0; pp < DIST; ++pp)
-                afp[pp] = *reinterpret_cast<const v4i*>(&smem[nx + ((pp % MT) * 4 + (pp / MT) * 2) * PLANE + rd_off]);
+                afp[pp] = *reinterpret_cast<const v4i*>(&smem[nx + (pp / 2) * 4 * PLANE + (pp % 2) * 256 + rd_off]);
         }
-        if (p + DIST < 2 * MT) {
-            const int s2 = (p + DIST) / MT, i2 = (p + DIST) % MT;
-            af[p + DIST] = *reinterpret_cast<const v4i*>(&Acur[(i2 * 4 + s2 * 2) * PLANE + rd_off]);
-        }
-        if (s == 0) {
+        if (p + DIST < RT)
+            af[p + DIST] = *reinterpret_cast<const v4i*>(&Acur[((p + DIST) / 2) * 4 * PLANE + ((p + DIST) % 2) * 256 + rd_off]);
 #pragma unroll
-            for (int d = 0; d < DPB; ++d) {
-                const int dd = i * DPB + d;
-                if (dd < NTW * 4) bd1[dd / 4][dd % 4] = (int)decode_dword<BITS>(bCur[dd / 4], L[dd / 4], 1, dd % 4, C);
-            }
+        for (int d = 0; d < DPB; ++d) {
+            const int dd = p * DPB + d, ct = dd / 4;
+            if (dd < CT * 4) bdNxt[ct][dd % 4] = (int)decode_dword<BITS>(bRaw[ct / 2], L[ct], ct % 2, dd % 4, C);
         }
 #pragma unroll
-        for (int j = 0; j < NTW; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[p], s == 0 ? bd0[j] : bd1[j], acc[i][j], 0, 0, 0);
-        if (s == 1) {
-            // step 0 of the next block: bd0 is free now (step 1 multiplies with bd1)
+        for (int ct = 0; ct < CT; ++ct)
+            acc[p][ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[p], bdCur[ct], acc[p][ct], 0, 0, 0);
+        if (p == RT - 1) {
 #pragma unroll
-            for (int d = 0; d < DPB; ++d) {
-                const int dd = i * DPB + d;
-                if (dd < NTW * 4) bd0[dd / 4][dd % 4] = (int)decode_dword<BITS>(bNxt[dd / 4], L[dd / 4], 0, dd % 4, C);
-            }
-        }
-        if (p == MT - 1) {
-#pragma unroll
-            for (int j = 0; j < NTW; ++j) bCur[j] = load_braw<BITS>(bptr[j] + (size_t)kbn * UNIT);
+            for (int j = 0; j < NTW; ++j) bRaw[j] = load_braw<BITS>(bptr[j] + (size_t)kbn * UNIT);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
 }
 
-// BM rows x (4 waves x NTW x 32) columns per workgroup; MT = BM / 32 MFMA row tiles per wave.  Shapes in use
+// BM rows x (4 waves x NTW x 32) columns per workgroup; RT = BM / 16 row tiles and 2 NTW column tiles of 16 per wave.  Shapes in use
 // (launch_qgemm picks): 128 x 256 (NTW = 2, 128 accumulator registers per lane, two workgroups per CU), 128 x 128
 // (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens (a 256 x 128 shape - half the decode
 // work per MFMA, twice the LDS reads per MFMA - measured slower on every workload).  ZP: zero-point form (epilogue term).
@@ -180,9 +173,9 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     const float* __restrict__ bias, int out_fp32, void* __restrict__ Y, int tiles_m, int tiles_n,
     const int32_t* __restrict__ zero, const int32_t* __restrict__ colsum, int const_zero) {
     static_assert(!A4P || ZP, "the packed form needs the zero-point term of the epilogue");
-    constexpr int MT = BM / 32;
+    constexpr int RT = BM / 16, CT = 2 * NTW;
     constexpr int WN = 32 * NTW, BN = WAVES * WN;
-    constexpr int ABUF = MT * 4 * PLANE;
+    constexpr int ABUF = (BM / 32) * 4 * PLANE;
     constexpr int ACHUNKS = A4P ? BM * 2 : BM * 4;                 // 16-byte chunks of the A tile in global memory
     constexpr int ALOADS = ACHUNKS >= 256 ? ACHUNKS / 256 : 1;      // per thread (fewer chunks than threads: some are fetched twice)
     constexpr int ABK = A4P ? BK / 2 : BK;
@@ -219,17 +212,22 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
     const int ntile32 = (N + 31) / 32;
     constexpr int UNIT = 64 * 16;
 
-    unsigned L[NTW][4];
+    // level tables of the lane's channel (lane % 16) in each of the wave's 16-column tiles, and the lane's slot of every
+    // 32-channel tile
+    unsigned L[CT][4];
     const uint8_t* bptr[NTW];
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
         int tl = (n0 + wv * WN) / 32 + j;
         if (tl >= ntile32) tl = ntile32 - 1;
-        int n = tl * 32 + lane % 32;
-        if (n >= N) n = N - 1;
-        const uint4 lv = *reinterpret_cast<const uint4*>(lut + (size_t)n * 16);
-        L[j][0] = lv.x; L[j][1] = lv.y; L[j][2] = lv.z; L[j][3] = lv.w;
-        bptr[j] = gcodes + (size_t)tl * KB * UNIT + gemm_piece32_offset(lane);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int n = tl * 32 + h * 16 + lane % 16;
+            if (n >= N) n = N - 1;
+            const uint4 lv = *reinterpret_cast<const uint4*>(lut + (size_t)n * 16);
+            L[2 * j + h][0] = lv.x; L[2 * j + h][1] = lv.y; L[2 * j + h][2] = lv.z; L[2 * j + h][3] = lv.w;
+        }
+        bptr[j] = gcodes + (size_t)tl * KB * UNIT + (size_t)lane * (UNIT / 64);
     }
 
     // A tile loader: BM*4 chunks of 16 bytes; chunk id -> (row, 16-byte column)
@@ -250,23 +248,27 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         zr[t] = (ZP && r < M) ? (zero ? zero[r] : const_zero) : 0;
     }
 
-    v16i acc[MT][NTW];
+    v4i acc[RT][CT];
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int j = 0; j < NTW; ++j)
+        for (int j = 0; j < CT; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
 
-    // ---- prologue: A tiles 0, 1 -> LDS buffers 0, 1; A tiles 2 (aO), 3 (aE) and B blocks 0 (bE), 1 (bO) in registers
+    // ---- prologue: A tiles 0, 1 -> LDS buffers 0, 1; A tiles 2 (aO), 3 (aE) in registers; B block 0 decoded (bdA), raw
+    // codes of blocks 1 (bO) and 2 (bE) in registers
     unsigned C = 0x03020100u;
     asm volatile("" : "+v"(C));
     v4i aO[ALOADS], aE[ALOADS];
     BRaw<BITS> bE[NTW], bO[NTW];
-    v4i bd0[NTW];
+    v4i bdA[CT], bdB[CT];
     {
         v4i a0[ALOADS], a1[ALOADS];
+        BRaw<BITS> b0[NTW];
         const int k1 = KB > 1 ? 1 : 0, k2 = KB > 2 ? 2 : KB - 1, k3 = KB > 3 ? 3 : KB - 1;
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) b0[j] = load_braw<BITS>(bptr[j]);
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
             a0[i] = *reinterpret_cast<const v4i*>(aptr[i]);
@@ -277,60 +279,62 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) aO[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k2 * ABK);
 #pragma unroll
-        for (int j = 0; j < NTW; ++j) bE[j] = load_braw<BITS>(bptr[j]);
+        for (int j = 0; j < NTW; ++j) bO[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) aE[i] = *reinterpret_cast<const v4i*>(aptr[i] + (size_t)k3 * ABK);
 #pragma unroll
-        for (int j = 0; j < NTW; ++j) bO[j] = load_braw<BITS>(bptr[j] + (size_t)k1 * UNIT);
+        for (int j = 0; j < NTW; ++j) bE[j] = load_braw<BITS>(bptr[j] + (size_t)k2 * UNIT);
 #pragma unroll
         for (int i = 0; i < ALOADS; ++i) {
             stage_a<A4P>(&smem[aoff[i]], a0[i]);
             stage_a<A4P>(&smem[ABUF + aoff[i]], a1[i]);
         }
 #pragma unroll
-        for (int j = 0; j < NTW; ++j)
+        for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) bd0[j][g] = (int)decode_dword<BITS>(bE[j], L[j], 0, g, C);
+            for (int g = 0; g < 4; ++g) bdA[ct][g] = (int)decode_dword<BITS>(b0[ct / 2], L[ct], ct % 2, g, C);
     }
     __syncthreads();
 
-    const int rd_off = (lane / 32) * PLANE + (lane % 32) * 16;
+    // fragment of row tile i (16 rows) of a buffer: + (i / 2) * 4 * PLANE + (i % 2) * 256; the lane's row lane % 16 and
+    // its 16-byte k chunk lane / 16
+    const int rd_off = (lane / 16) * PLANE + (lane % 16) * 16;
     v4i afp[AF_DIST];
 #pragma unroll
     for (int p = 0; p < AF_DIST; ++p)
-        afp[p] = *reinterpret_cast<const v4i*>(&smem[((p % MT) * 4 + (p / MT) * 2) * PLANE + rd_off]);
+        afp[p] = *reinterpret_cast<const v4i*>(&smem[(p / 2) * 4 * PLANE + (p % 2) * 256 + rd_off]);
 
     int o0 = 0, o1 = ABUF, o2 = 2 * ABUF;       // LDS buffers of tiles kb, kb+1, kb+2
     int kb = 0;
     // two K blocks per trip with no branch in between: with a conditional second block the compiler has to assume the
     // shorter path at the loop head and drains the whole load queue there (s_waitcnt vmcnt(0)) on every trip
     for (; kb + 1 < KB; kb += 2) {
-        kblock<BITS, MT, NTW, ALOADS, A4P>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
-        kblock<BITS, MT, NTW, ALOADS, A4P>(smem, o1, o0, o2, aE, bO, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        kblock<BITS, RT, NTW, ALOADS, A4P>(smem, o0, o2, o1, aO, bO, kb, KB, aptr, aoff, bptr, L, C, bdA, bdB, acc, rd_off, afp);
+        kblock<BITS, RT, NTW, ALOADS, A4P>(smem, o1, o0, o2, aE, bE, kb + 1, KB, aptr, aoff, bptr, L, C, bdB, bdA, acc, rd_off, afp);
         const int t0 = o0;      // two blocks done: tiles kb+2, kb+3, kb+4 live in o2, o0, o1
         o0 = o2;
         o2 = o1;
         o1 = t0;
     }
     if (kb < KB)                // odd number of K blocks
-        kblock<BITS, MT, NTW, ALOADS, A4P>(smem, o0, o2, o1, aO, bE, bO, kb, KB, aptr, aoff, bptr, L, C, bd0, acc, rd_off, afp);
+        kblock<BITS, RT, NTW, ALOADS, A4P>(smem, o0, o2, o1, aO, bO, kb, KB, aptr, aoff, bptr, L, C, bdA, bdB, acc, rd_off, afp);
 
-    // ---- epilogue: rescale in fp32.  Lane holds column (lane % 32) and rows 8 g + 4 (lane / 32) + (0..3), g = 0..3, of
-    // every 32 x 32 accumulator tile (four consecutive rows per group of four accumulator registers).
-    float wsc[NTW], bs[NTW];
-    int csum[NTW];
+    // ---- epilogue: rescale in fp32.  Lane holds column (lane % 16) and rows 4 (lane / 16) + (0..3) of every 16 x 16
+    // accumulator tile.
+    float wsc[CT], bs[CT];
+    int csum[CT];
 #pragma unroll
-    for (int j = 0; j < NTW; ++j) {
-        int n = n0 + wv * WN + j * 32 + lane % 32;
+    for (int ct = 0; ct < CT; ++ct) {
+        int n = n0 + wv * WN + ct * 16 + lane % 16;
         if (n >= N) n = N - 1;
-        wsc[j] = wscale[n];
-        bs[j] = bias ? bias[n] : 0.0f;
-        csum[j] = ZP ? colsum[n] : 0;
+        wsc[ct] = wscale[n];
+        bs[ct] = bias ? bias[n] : 0.0f;
+        csum[ct] = ZP ? colsum[n] : 0;
     }
-    // y of accumulator register 4 g + x of tile (i, j); the zero-point form adds zero_t * colsum_n to the integer sum
+    // y of accumulator register x of tile (i, ct); the zero-point form adds zero_t * colsum_n to the integer sum
     // (64-bit: the product can exceed 32 bits)
-    auto rescale4 = [&](int i, int j, int g, float (&y)[4]) {
-        const int lr0 = i * 32 + 8 * g + 4 * (lane / 32);
+    auto rescale4 = [&](int i, int ct, float (&y)[4]) {
+        const int lr0 = i * 16 + 4 * (lane / 16);
         const float4 s4 = *reinterpret_cast<const float4*>(&sc[lr0]);
         const float sv[4] = {s4.x, s4.y, s4.z, s4.w};
         int zv[4] = {0, 0, 0, 0};
@@ -340,30 +344,31 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
         }
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const int a = acc[i][j][4 * g + x];
-            const float tot = ZP ? (float)((long long)a + (long long)zv[x] * (long long)csum[j]) : (float)a;
-            y[x] = (tot * sv[x]) * wsc[j] + bs[j];
+            const int a = acc[i][ct][x];
+            const float tot = ZP ? (float)((long long)a + (long long)zv[x] * (long long)csum[ct]) : (float)a;
+            y[x] = (tot * sv[x]) * wsc[ct] + bs[ct];
         }
     };
     const int ncol0 = n0 + wv * WN;                 // first column of this wave
     unsigned char* slab = smem + wv * EPI_WAVE;
     if (!out_fp32) {
-        // bf16: one 32-row slab per wave staged in LDS (wave-private, so only wave-level ordering is needed after the
-        // K loop's final barrier); every lane then stores 16 contiguous bytes, a row segment of the wave is WN * 2 bytes
+        // bf16: one 32-row slab (two row tiles) per wave staged in LDS (wave-private, so only wave-level ordering is needed
+        // after the K loop's final barrier); every lane then stores 16 contiguous bytes, a row segment of the wave is
+        // WN * 2 bytes
         uint16_t* Yh = reinterpret_cast<uint16_t*>(Y);
         const bool vec = N % 8 == 0;                // rows of Y are 16-byte aligned
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
+        for (int i2 = 0; i2 < RT / 2; ++i2) {
 #pragma unroll
-            for (int j = 0; j < NTW; ++j)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
+                for (int ct = 0; ct < CT; ++ct) {
                     float y[4];
-                    rescale4(i, j, g, y);
+                    rescale4(2 * i2 + h, ct, y);
                     const unsigned d[2] = {pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
 #pragma unroll
                     for (int x = 0; x < 4; ++x)
-                        *reinterpret_cast<uint16_t*>(&slab[(8 * g + 4 * (lane / 32) + x) * EPI_ROW + (j * 32 + lane % 32) * 2]) =
+                        *reinterpret_cast<uint16_t*>(&slab[(16 * h + 4 * (lane / 16) + x) * EPI_ROW + (ct * 16 + lane % 16) * 2]) =
                             (uint16_t)(d[x / 2] >> (16 * (x % 2)));
                 }
             wave_sync();
@@ -373,7 +378,7 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
             for (int p = 0; p < 32 / RPP; ++p) {
                 const int lr = p * RPP + lane / LPR, cb = (lane % LPR) * 8;   // 8 bf16 per lane
                 const uint4 v = *reinterpret_cast<const uint4*>(&slab[lr * EPI_ROW + cb * 2]);
-                const int row = m0 + i * 32 + lr, col = ncol0 + cb;
+                const int row = m0 + i2 * 32 + lr, col = ncol0 + cb;
                 if (row < M) {
                     if (vec && col + 8 <= N) {
                         *reinterpret_cast<uint4*>(&Yh[(size_t)row * N + col]) = v;
@@ -388,27 +393,29 @@ __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1
             wave_sync();
         }
     } else {
-        // fp32: the same staging, one 32 x 32 tile at a time
+        // fp32: the same staging, 32 rows x 32 columns at a time
         float* Yf = reinterpret_cast<float*>(Y);
         const bool vec = N % 4 == 0;
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
+        for (int i2 = 0; i2 < RT / 2; ++i2)
 #pragma unroll
             for (int j = 0; j < NTW; ++j) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    float y[4];
-                    rescale4(i, j, g, y);
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        *reinterpret_cast<float*>(&slab[(8 * g + 4 * (lane / 32) + x) * EPI_ROW + (lane % 32) * 4]) = y[x];
-                }
+                    for (int c = 0; c < 2; ++c) {
+                        float y[4];
+                        rescale4(2 * i2 + h, 2 * j + c, y);
+#pragma unroll
+                        for (int x = 0; x < 4; ++x)
+                            *reinterpret_cast<float*>(&slab[(16 * h + 4 * (lane / 16) + x) * EPI_ROW + (c * 16 + lane % 16) * 4]) = y[x];
+                    }
                 wave_sync();
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     const int lr = p * 8 + lane / 8, cb = (lane % 8) * 4;    // 4 floats per lane
                     const uint4 v = *reinterpret_cast<const uint4*>(&slab[lr * EPI_ROW + cb * 4]);
-                    const int row = m0 + i * 32 + lr, col = ncol0 + j * 32 + cb;
+                    const int row = m0 + i2 * 32 + lr, col = ncol0 + j * 32 + cb;
                     if (row < M) {
                         if (vec && col + 4 <= N) {
                             *reinterpret_cast<uint4*>(&Yf[(size_t)row * N + col]) = v;
