@@ -49,7 +49,8 @@ class Probes:
         assert rc == 0
 
     def mfma_i8_tops(self, pattern=1, blocks=2048, iters=4096, reps=5):
-        """Sustained int8 MFMA rate in TOP/s; pattern 0 = constant operands, 1 = pseudo-random operands."""
+        """Sustained int8 MFMA rate in TOP/s; pattern 0 = constant operands, 1 = pseudo-random operands (16x16x64, the
+        GEMM's instruction); 2, 3 = the same with the 32x32x32 instruction."""
         import ctypes
         import torch
         out = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -154,7 +155,8 @@ def main():
     if args.probes_only:
         print(json.dumps(dict(copy_gbs=round(probes.copy_gbs(1 << 30, 5), 1), copy_bytes_per_launch=1 << 30,
                               mfma_i8_tops_constant_operands=round(probes.mfma_i8_tops(0), 1),
-                              mfma_i8_tops_random_operands=round(probes.mfma_i8_tops(1), 1))))
+                              mfma_i8_tops_random_operands=round(probes.mfma_i8_tops(1), 1),
+                              mfma_i8_32x32x32_tops_random_operands=round(probes.mfma_i8_tops(3), 1))))
         return
     cfg = int(args.workload[1])
     specs = synth.config_layers(cfg)
@@ -456,9 +458,11 @@ def main():
     # what this device sustains on a pure int8 MFMA loop and on a plain copy kernel (context for the published peaks)
     out["measured_ceilings"] = dict(mfma_i8_tops_constant_operands=round(probes.mfma_i8_tops(0), 1),
                                     mfma_i8_tops_random_operands=round(probes.mfma_i8_tops(1), 1),
+                                    mfma_i8_32x32x32_tops_random_operands=round(probes.mfma_i8_tops(3), 1),
                                     copy_gbs=round(probes.copy_gbs(1 << 30, 5), 1),
-                                    note="pure 32x32x32 int8 MFMA loops (operand toggling lowers the sustained clock); "
-                                         "1 GiB device copy, read + written bytes")
+                                    note="pure int8 MFMA loops, v_mfma_i32_16x16x64_i8 (the GEMM's instruction) unless named "
+                                         "otherwise: operand toggling lowers the sustained clock, and the 32x32x32 shape "
+                                         "sustains less; 1 GiB device copy, read + written bytes")
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         tr = json.load(open(traffic_file)).get(args.workload)
@@ -489,8 +493,9 @@ def sustained_clocks(lrq, probes, layer, dev):
     scratch = torch.zeros(64, dtype=torch.int32, device=dev)
     cases = [("qgemm, the layer's own codes", lambda: lrq.qgemm(q, sc, w, out=Y)),
              ("qgemm, all-zero activation codes", lambda: lrq.qgemm(qz, sc, w, out=Y)),
-             ("int8 MFMA loop, pseudo-random operands", lambda: probes.launch_mfma(4096, 2048, 1, scratch)),
-             ("int8 MFMA loop, constant operands", lambda: probes.launch_mfma(4096, 2048, 0, scratch)),
+             ("int8 MFMA loop (16x16x64), pseudo-random operands", lambda: probes.launch_mfma(4096, 2048, 1, scratch)),
+             ("int8 MFMA loop (32x32x32), pseudo-random operands", lambda: probes.launch_mfma(4096, 2048, 3, scratch)),
+             ("int8 MFMA loop (16x16x64), constant operands", lambda: probes.launch_mfma(4096, 2048, 0, scratch)),
              ("rotate + quantize", lambda: lrq.ars_rotate_quant(X, rot, s.a_bits, q=q, scale=sc))]
 
     def sclk():

@@ -16,33 +16,51 @@ __device__ __forceinline__ unsigned mix(unsigned x) {
     return x;
 }
 
-// Every wave issues iters x 8 independent 32x32x32 int8 MFMAs; nothing else competes for the pipe.
-// pattern 0: every operand byte is 1 (no data toggling); pattern 1: pseudo-random operand bytes, four
-// different A and four different B register sets in rotation (the matrix pipe's power draw, and with it
-// the sustained clock, depends on how many operand bits toggle).
-__global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(int iters, int pattern, int* __restrict__ out) {
-    v16i acc[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+// Every wave issues iters x 65536 x 8 int8 multiply-accumulates as independent matrix instructions - 16 of
+// v_mfma_i32_16x16x64_i8 per trip (WIDE = false: the GEMM's instruction) or 8 of v_mfma_i32_32x32x32_i8 (WIDE = true);
+// nothing else competes for the pipe.
+// random = 0: every operand byte is 1 (no data toggling); 1: pseudo-random operand bytes, four different A and four
+// different B register sets in rotation (the matrix pipe's power draw, and with it the sustained clock, depends on
+// how many operand bits toggle - and on the instruction: the 16 x 16 x 64 shape sustains the higher rate).
+template <bool WIDE>
+__global__ __launch_bounds__(256, 2) void mfma_i8_probe_kernel(int iters, int random, int* __restrict__ out) {
     v4i a[4], b[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const unsigned seed = (threadIdx.x * 16u + i * 4u + c) * 2654435761u + blockIdx.x;
-            a[i][c] = pattern ? (int)mix(seed) : 0x01010101;
-            b[i][c] = pattern ? (int)mix(seed ^ 0x9e3779b9u) : 0x01010101;
+            a[i][c] = random ? (int)mix(seed) : 0x01010101;
+            b[i][c] = random ? (int)mix(seed ^ 0x9e3779b9u) : 0x01010101;
         }
-    for (int it = 0; it < iters; ++it) {
+    int s = 0;
+    if constexpr (WIDE) {
+        v16i acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i % 4], b[(i / 2) % 4], acc[i], 0, 0, 0);
-    }
-    int s = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
+            for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i % 4], b[(i / 2) % 4], acc[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
+    } else {
+        v4i acc[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][r] = 0;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i % 4], b[(i / 2) % 4], acc[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][3];
+    }
     if (s == 0x7fffffff) out[0] = s;   // keeps the loop alive; practically never taken
 }
 
@@ -59,14 +77,18 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const v4u* __restrict__
 
 extern "C" {
 
-// `blocks` workgroups of 4 waves, each wave issuing iters x 8 independent v_mfma_i32_32x32x32_i8; pattern 0 = all operand
-// bytes 1, pattern 1 = pseudo-random operand bytes.  *ops_per_launch (host, may be NULL) receives the int8 operations one
-// launch performs (2 per multiply-accumulate).  out: int[1] device scratch.  Returns 0 or -1.
+// `blocks` workgroups of 4 waves, each wave issuing iters x 8 x 65536 int8 operations; pattern 0 = all operand bytes 1,
+// 1 = pseudo-random operand bytes, both with v_mfma_i32_16x16x64_i8; 2 and 3 = the same two with v_mfma_i32_32x32x32_i8.
+// *ops_per_launch (host, may be NULL) receives the int8 operations one launch performs (2 per multiply-accumulate).
+// out: int[1] device scratch.  Returns 0 or -1.
 __attribute__((visibility("default"))) int bench_probe_mfma_i8(void* stream, int blocks, int iters, int pattern, int* out,
                                                                 double* ops_per_launch) {
-    if (blocks <= 0 || iters <= 0 || !out || (pattern != 0 && pattern != 1)) return -1;
+    if (blocks <= 0 || iters <= 0 || !out || pattern < 0 || pattern > 3) return -1;
     if (ops_per_launch) *ops_per_launch = 2.0 * 32 * 32 * 32 * 8.0 * iters * 4.0 * blocks;
-    hipLaunchKernelGGL(mfma_i8_probe_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, pattern, out);
+    if (pattern < 2)
+        hipLaunchKernelGGL(mfma_i8_probe_kernel<false>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, pattern, out);
+    else
+        hipLaunchKernelGGL(mfma_i8_probe_kernel<true>, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream), iters, pattern - 2, out);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
