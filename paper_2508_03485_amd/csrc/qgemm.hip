@@ -19,7 +19,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int WAVES = 4;
 constexpr int BK = kGemmBlockK;     // 64
 constexpr int PLANE_PAD = 32;          // padding of a plane (swept 0 / 16 / 32 / 48: 32 leaves the fewest bank conflicts)
-constexpr int AF_DIST = 2;             // A fragments are read this many MFMA groups ahead of their use (swept 1 - 3)
+constexpr int AF_DIST = 2;             // A fragments are read this many row tiles (four MFMAs each) ahead of their use (swept 2 - 4: no difference)
 constexpr int PLANE = 32 * 16 + PLANE_PAD;     // bytes of one (row tile, 16-byte k chunk) plane in LDS, padded
 constexpr int EPI_ROW = 64 * 2 + 16;   // bytes of one staged output row of a wave (up to 64 bf16 / 32 fp32) + pad
 constexpr int EPI_WAVE = 32 * EPI_ROW; // one 32-row slab per wave
@@ -164,8 +164,8 @@ __device__ __forceinline__ void kblock(unsigned char* smem, int cur, int st, int
 
 // BM rows x (4 waves x NTW x 32) columns per workgroup; RT = BM / 16 row tiles and 2 NTW column tiles of 16 per wave.  Shapes in use
 // (launch_qgemm picks): 128 x 256 (NTW = 2, 128 accumulator registers per lane, two workgroups per CU), 128 x 128
-// (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens (a 256 x 128 shape - half the decode
-// work per MFMA, twice the LDS reads per MFMA - measured slower on every workload).  ZP: zero-point form (epilogue term).
+// (NTW = 1, 64 accumulator registers, three per CU) and 64 x 128 for a few tokens (256-row shapes - half the decode
+// work per MFMA - measured no faster, or slower, on every workload).  ZP: zero-point form (epilogue term).
 template <int BITS, int BM, int NTW, bool ZP, bool A4P = false>
 __global__ __launch_bounds__(256, BM * NTW <= 128 ? 3 : (BM * NTW <= 256 ? 2 : 1)) void qgemm_kernel(
     const int8_t* __restrict__ q, const float* __restrict__ scale, int M, int K, int N,

@@ -12,8 +12,8 @@
 // codes go from global memory into registers (same tiling as the int8 GEMM reads) and are decoded there through a
 // per-lane 16-entry table of bf16 levels, held as a high-byte and a low-byte table for byte permutes.
 //
-// K order inside a 64-wide K block: the code tiling gives lane half hh (lane / 32) the k offsets
-// 32 s + 16 hh + [0, 16) for s = 0, 1.  MFMA step u = 2 s + p therefore contracts the sixteen k
+// K order inside a 64-wide K block: the lane's two 8-byte pieces of the code tiling give lane half hh (lane / 32) the
+// k offsets 32 s + 16 hh + [0, 16) for s = 0, 1.  MFMA step u = 2 s + p therefore contracts the sixteen k
 //   { 32 s + 16 hh + 8 p + i : hh = 0, 1; i = 0..7 }
 // (an MFMA only needs both operands to agree on which k a lane holds), and a lane reads its eight activation values
 // of a step as one 16-byte chunk: chunk index 4 s + 2 hh + p of the row.
