@@ -452,6 +452,27 @@ def test_tlq_lower_clip_bit_exact(lrq, N, K, bits):
     assert torch_equal(w0.codes, w1.codes) and torch_equal(w0.lut, w1.lut) and torch_equal(w0.s_pos, w1.s_pos)
 
 
+@pytest.mark.parametrize("N,K,bits", [(70, 192, 4), (48, 128, 3), (33, 64, 4)])
+def test_gemm_code_tiling_matches_its_description(lrq, N, K, bits):
+    """The GEMM's private copy of the weight codes: units of (32 channels x 64 k) stored [channel tile][K block], 64 slots
+    of 16 bytes each; slot 16 kq + c holds k = 16 kq + [0, 16) of channel c (first 8 bytes) and of channel 16 + c (last 8
+    bytes) of the tile, one nibble per code, byte j of a dword = code[k + j] | code[k + 4 + j] << 4.  Channels beyond N
+    stay zero.  Built here from the oracle's codes."""
+    W = synth.make_weights(N, K, (915, N, K))
+    codes = oracle.tlq_encode(W, oracle.tlq_calibrate(W, bits, GRID, GRID)).astype(np.int64) & (2 ** bits - 1)
+    w = lrq.tlq_quantize_pack(to_dev(W), bits, 7, to_dev(GRID), to_dev(GRID))
+    tiles, kblocks = (N + 31) // 32, K // 64
+    want = np.zeros((tiles, kblocks, 64, 16), dtype=np.uint8)
+    for n in range(N):
+        for k0 in range(0, K, 8):                       # one dword: 8 codes
+            kb, kq, d = k0 // 64, (k0 % 64) // 16, (k0 % 16) // 8
+            for j in range(4):
+                want[n // 32, kb, 16 * kq + n % 16, ((n % 32) // 16) * 8 + d * 4 + j] = codes[n, k0 + j] | (codes[n, k0 + 4 + j] << 4)
+    got = w.gemm_codes.cpu().numpy()
+    assert got.size == want.size == lrq.lib().lrq_tlq_gemm_codes_bytes(N, K, bits)
+    assert np.array_equal(got.reshape(want.shape), want)
+
+
 def torch_equal(a, b):
     import torch
     return torch.equal(a, b)
